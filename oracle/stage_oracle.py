@@ -1,0 +1,380 @@
+"""CPU oracle for one pipeline stage's F / B / W compute.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, obviously-correct
+definition that the HIP path is checked against.  Only tests, the smoke check
+and the benchmark's cpu_baseline leg may import it; the product path never
+does, and this file imports nothing from the product package.
+
+What it defines (paper section 3.1, "Computation Blocks", and Appendix B,
+"Weight Gradient Separation"): the backward of a model chunk is split into an
+input-gradient block (the paper's D; called B here) and a weight-gradient block
+(W), so that a schedule may run F, B and W of every microbatch as separate ops
+in any legal order.  For a linear map Y = X W this means B computes
+dX = dY W^T and W computes dW = X^T dY.  Section 3.2 fixes the activation
+lifetime: cached in F, released after B and W.  The split is a re-bracketing
+of ordinary backpropagation, so the oracle is the textbook definition written
+out in NumPy, in fp64 unless a dtype is passed, with the full s-by-s attention
+matrix materialised and no blocking or fusion.
+
+The paper does not itemise the layer ("Llama-style Transformer layers",
+section 7).  The reading used here: pre-norm decoder layer, no biases, no
+rotary embedding, no dropout, exact-erf GELU, eps = 1e-5, biased variance,
+gradients summed (not averaged) over microbatches, norm-parameter gradients
+produced by B.
+
+    n1 = Norm1(x);  [q|k|v] = n1 Wqkv;  o = Attention(q, k, v)
+    x1 = x + o Wo;  n2 = Norm2(x1)
+    GELU:   u = n2 Win;        a = gelu(u)
+    SwiGLU: [g|u] = n2 Win;    a = silu(g) * u
+    y  = x1 + a Wout
+
+Parity pins (tests/test_oracle_*.py): central finite differences in fp64,
+B-then-W == fused backward, schedule-order invariance, sum over microbatches
+== full-batch gradient, closed-form special cases, and PyTorch CPU autograd as
+a second opinion.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from typing import Dict, List, Sequence, Tuple
+
+import numpy as np
+from scipy.special import erf
+
+F, B, W = 0, 1, 2  # op kinds of a per-stage ordered schedule (paper Alg. 1, "S_d")
+
+
+@dataclass(frozen=True)
+class Shape:
+    n_layers: int
+    hidden: int
+    n_heads: int
+    n_kv_heads: int
+    ffn: int
+    seq: int
+    mb_size: int
+    norm: str = "layernorm"   # "layernorm" | "rmsnorm"
+    act: str = "gelu"         # "gelu" | "swiglu"
+    causal: bool = True
+    eps: float = 1e-5
+
+    @property
+    def head_dim(self) -> int:
+        return self.hidden // self.n_heads
+
+    @property
+    def kv_dim(self) -> int:
+        return self.n_kv_heads * self.head_dim
+
+
+Params = List[Dict[str, np.ndarray]]
+# per layer: g1, (b1), wqkv [d, d+2*dkv], wo [d, d], g2, (b2),
+#            win [d, f] or [d, 2f] (gate | up), wout [f, d]
+
+
+# --------------------------------------------------------------------------
+# building blocks, forward
+# --------------------------------------------------------------------------
+
+def norm_forward(kind: str, x, gamma, beta, eps):
+    """Row-wise normalisation over the last axis.  Returns (out, stats)."""
+    if kind == "layernorm":
+        mu = x.mean(axis=-1, keepdims=True)
+        var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)      # biased
+        rstd = 1.0 / np.sqrt(var + eps)
+        xhat = (x - mu) * rstd
+        return xhat * gamma + beta, (xhat, rstd)
+    if kind == "rmsnorm":
+        ms = (x * x).mean(axis=-1, keepdims=True)
+        rstd = 1.0 / np.sqrt(ms + eps)
+        xhat = x * rstd
+        return xhat * gamma, (xhat, rstd)
+    raise ValueError(kind)
+
+
+def head_probs(sh: Shape, qh, kh):
+    """softmax_rows(qh kh^T / sqrt(hd) + causal mask) for one head: [s,s]."""
+    s, hd = qh.shape
+    S = (qh @ kh.T) * (1.0 / math.sqrt(hd))
+    if sh.causal:
+        S = np.where(np.tril(np.ones((s, s), dtype=bool)), S, -np.inf)
+    S = S - S.max(axis=-1, keepdims=True)
+    e = np.exp(S)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def attention_forward(sh: Shape, q, k, v):
+    """q [b,s,h,hd], k,v [b,s,hkv,hd] -> o [b,s,h,hd].  Query head j reads
+    KV head j // (h / hkv).  Sequences of a microbatch do not interact."""
+    b, s, h, hd = q.shape
+    group = h // sh.n_kv_heads
+    o = np.zeros_like(q)
+    for ib in range(b):
+        for j in range(h):
+            g = j // group
+            o[ib, :, j, :] = head_probs(sh, q[ib, :, j, :], k[ib, :, g, :]) @ v[ib, :, g, :]
+    return o
+
+
+def gelu(u):
+    return 0.5 * u * (1.0 + erf(u / math.sqrt(2.0)))
+
+
+def gelu_grad(u):
+    return 0.5 * (1.0 + erf(u / math.sqrt(2.0))) + u * np.exp(-0.5 * u * u) / math.sqrt(2.0 * math.pi)
+
+
+def sigmoid(g):
+    return 1.0 / (1.0 + np.exp(-g))
+
+
+def layer_forward(sh: Shape, p: Dict[str, np.ndarray], x):
+    """x [b,s,d] -> (y [b,s,d], cache)."""
+    b, s, d = x.shape
+    h, hkv, hd, dkv, f = sh.n_heads, sh.n_kv_heads, sh.head_dim, sh.kv_dim, sh.ffn
+    c = {"x": x}
+    n1, c["norm1"] = norm_forward(sh.norm, x, p["g1"], p.get("b1", 0.0), sh.eps)
+    c["n1"] = n1
+    qkv = n1 @ p["wqkv"]
+    q = qkv[..., :d].reshape(b, s, h, hd)
+    k = qkv[..., d:d + dkv].reshape(b, s, hkv, hd)
+    v = qkv[..., d + dkv:].reshape(b, s, hkv, hd)
+    c["q"], c["k"], c["v"] = q, k, v
+    o = attention_forward(sh, q, k, v)
+    o = o.reshape(b, s, d)
+    c["o"] = o
+    x1 = x + o @ p["wo"]
+    c["x1"] = x1
+    n2, c["norm2"] = norm_forward(sh.norm, x1, p["g2"], p.get("b2", 0.0), sh.eps)
+    c["n2"] = n2
+    z = n2 @ p["win"]
+    c["z"] = z
+    if sh.act == "gelu":
+        a = gelu(z)
+    elif sh.act == "swiglu":
+        g, u = z[..., :f], z[..., f:]
+        a = g * sigmoid(g) * u
+    else:
+        raise ValueError(sh.act)
+    c["a"] = a
+    y = x1 + a @ p["wout"]
+    return y, c
+
+
+# --------------------------------------------------------------------------
+# building blocks, backward
+# --------------------------------------------------------------------------
+
+def norm_backward(kind: str, stats, gamma, dout):
+    """Returns (dx, dgamma, dbeta-or-None) for out = xhat*gamma (+beta)."""
+    xhat, rstd = stats
+    dxhat = dout * gamma
+    red = tuple(range(dout.ndim - 1))
+    dgamma = (dout * xhat).sum(axis=red)
+    if kind == "layernorm":
+        dbeta = dout.sum(axis=red)
+        m1 = dxhat.mean(axis=-1, keepdims=True)
+        m2 = (dxhat * xhat).mean(axis=-1, keepdims=True)
+        dx = (dxhat - m1 - xhat * m2) * rstd
+        return dx, dgamma, dbeta
+    m2 = (dxhat * xhat).mean(axis=-1, keepdims=True)
+    dx = (dxhat - xhat * m2) * rstd
+    return dx, dgamma, None
+
+
+def attention_backward(sh: Shape, q, k, v, do):
+    """Gradients of o = softmax(q k^T / sqrt(hd) + mask) v.  do [b,s,h,hd].
+    The probabilities are recomputed from q, k (same definition as forward)
+    instead of being cached, to keep the s-by-s matrices transient."""
+    b, s, h, hd = q.shape
+    group = h // sh.n_kv_heads
+    scale = 1.0 / math.sqrt(hd)
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    for ib in range(b):
+        for j in range(h):
+            g = j // group
+            p = head_probs(sh, q[ib, :, j, :], k[ib, :, g, :])
+            doj = do[ib, :, j, :]
+            dv[ib, :, g, :] += p.T @ doj
+            dp = doj @ v[ib, :, g, :].T
+            ds = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
+            dq[ib, :, j, :] = (ds @ k[ib, :, g, :]) * scale
+            dk[ib, :, g, :] += (ds.T @ q[ib, :, j, :]) * scale
+    return dq, dk, dv
+
+
+def act_backward(sh: Shape, z, da):
+    if sh.act == "gelu":
+        return da * gelu_grad(z)
+    f = sh.ffn
+    g, u = z[..., :f], z[..., f:]
+    sg = sigmoid(g)
+    dg = da * u * (sg + g * sg * (1.0 - sg))
+    du = da * g * sg
+    return np.concatenate([dg, du], axis=-1)
+
+
+def _flat(t):
+    return t.reshape(-1, t.shape[-1])
+
+
+def layer_backward_input(sh: Shape, p, c, dy):
+    """The B op of one layer: dx, the dZ tensors W will need, and norm grads."""
+    b, s, d = dy.shape
+    dkv = sh.kv_dim
+    saved = {"dz_out": dy}
+    da = dy @ p["wout"].T
+    dz_in = act_backward(sh, c["z"], da)
+    saved["dz_in"] = dz_in
+    dn2 = dz_in @ p["win"].T
+    dx1_n, dg2, db2 = norm_backward(sh.norm, c["norm2"], p["g2"], dn2)
+    dx1 = dy + dx1_n
+    saved["dz_o"] = dx1
+    do = dx1 @ p["wo"].T
+    dq, dk, dv = attention_backward(sh, c["q"], c["k"], c["v"],
+                                    do.reshape(b, s, sh.n_heads, sh.head_dim))
+    dz_qkv = np.concatenate([dq.reshape(b, s, d), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
+    saved["dz_qkv"] = dz_qkv
+    dn1 = dz_qkv @ p["wqkv"].T
+    dx_n, dg1, db1 = norm_backward(sh.norm, c["norm1"], p["g1"], dn1)
+    dx = dx1 + dx_n
+    ng = {"g1": dg1, "g2": dg2}
+    if sh.norm == "layernorm":
+        ng["b1"], ng["b2"] = db1, db2
+    return dx, saved, ng
+
+
+def layer_backward_weight(sh: Shape, c, saved):
+    """The W op of one layer: dW = A^T dZ for the four linear maps."""
+    return {
+        "wout": _flat(c["a"]).T @ _flat(saved["dz_out"]),
+        "win": _flat(c["n2"]).T @ _flat(saved["dz_in"]),
+        "wo": _flat(c["o"]).T @ _flat(saved["dz_o"]),
+        "wqkv": _flat(c["n1"]).T @ _flat(saved["dz_qkv"]),
+    }
+
+
+def layer_backward_full(sh: Shape, p, c, dy):
+    """Classic fused backward: every linear yields its input and weight
+    gradient at the same point of the reverse sweep.  Written separately from
+    the split pair above so that comparing them is a real check."""
+    b, s, d = dy.shape
+    dkv = sh.kv_dim
+    gr = {}
+    A = _flat(c["a"]); G = _flat(dy)
+    gr["wout"] = A.T @ G
+    da = (G @ p["wout"].T).reshape(c["a"].shape)
+    dz = act_backward(sh, c["z"], da)
+    gr["win"] = _flat(c["n2"]).T @ _flat(dz)
+    dn2 = dz @ p["win"].T
+    t, gr["g2"], db2 = norm_backward(sh.norm, c["norm2"], p["g2"], dn2)
+    dx1 = dy + t
+    gr["wo"] = _flat(c["o"]).T @ _flat(dx1)
+    do = dx1 @ p["wo"].T
+    dq, dk, dv = attention_backward(sh, c["q"], c["k"], c["v"],
+                                    do.reshape(b, s, sh.n_heads, sh.head_dim))
+    dqkv = np.concatenate([dq.reshape(b, s, d), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
+    gr["wqkv"] = _flat(c["n1"]).T @ _flat(dqkv)
+    dn1 = dqkv @ p["wqkv"].T
+    t, gr["g1"], db1 = norm_backward(sh.norm, c["norm1"], p["g1"], dn1)
+    if sh.norm == "layernorm":
+        gr["b1"], gr["b2"] = db1, db2
+    return dx1 + t, gr
+
+
+# --------------------------------------------------------------------------
+# the stage: F / B / W ops per microbatch, run in schedule order
+# --------------------------------------------------------------------------
+
+class OracleStage:
+    """State: params, accumulated grads, and per-microbatch caches that live
+    from F(m) to W(m) (section 3.2).  Gradients are *summed* over microbatches."""
+
+    def __init__(self, sh: Shape, params: Params, dtype=np.float64):
+        self.sh = sh
+        self.dtype = dtype
+        self.params = [{k: np.asarray(v, dtype=dtype) for k, v in lp.items()} for lp in params]
+        self.zero_grads()
+        self._cache: Dict[int, list] = {}
+        self._saved: Dict[int, list] = {}
+
+    def zero_grads(self):
+        self.grads = [{k: np.zeros_like(v) for k, v in lp.items()} for lp in self.params]
+
+    def _x(self, t):
+        sh = self.sh
+        return np.asarray(t, dtype=self.dtype).reshape(sh.mb_size, sh.seq, sh.hidden)
+
+    def forward(self, mb: int, x):
+        assert mb not in self._cache, "F twice"
+        caches = []
+        y = self._x(x)
+        for lp in self.params:
+            y, c = layer_forward(self.sh, lp, y)
+            caches.append(c)
+        self._cache[mb] = caches
+        return y
+
+    def backward_input(self, mb: int, dy):
+        assert mb in self._cache and mb not in self._saved, "B needs F once"
+        d = self._x(dy)
+        saved = [None] * len(self.params)
+        for li in reversed(range(len(self.params))):
+            d, saved[li], ng = layer_backward_input(self.sh, self.params[li], self._cache[mb][li], d)
+            for k, v in ng.items():
+                self.grads[li][k] += v
+        self._saved[mb] = saved
+        return d
+
+    def backward_weight(self, mb: int):
+        assert mb in self._saved, "W needs B"
+        for li in range(len(self.params)):
+            for k, v in layer_backward_weight(self.sh, self._cache[mb][li], self._saved[mb][li]).items():
+                self.grads[li][k] += v
+        del self._cache[mb], self._saved[mb]
+
+    def backward_full(self, mb: int, dy):
+        """Fused B+W (the paper's undivided backward block)."""
+        assert mb in self._cache and mb not in self._saved
+        d = self._x(dy)
+        for li in reversed(range(len(self.params))):
+            d, gr = layer_backward_full(self.sh, self.params[li], self._cache[mb][li], d)
+            for k, v in gr.items():
+                self.grads[li][k] += v
+        del self._cache[mb]
+        return d
+
+    @property
+    def live(self) -> int:
+        return len(self._cache)
+
+    def run_schedule(self, ops: Sequence[Tuple[int, int]], X, dY):
+        """ops: (kind, mb) pairs.  X, dY: [n_mb, b, s, d].  Returns (Y, dX, peak_live)."""
+        Y = np.zeros(np.shape(X), dtype=self.dtype)
+        dX = np.zeros(np.shape(X), dtype=self.dtype)
+        peak = self.live
+        for kind, mb in ops:
+            if kind == F:
+                Y[mb] = self.forward(mb, X[mb])
+            elif kind == B:
+                dX[mb] = self.backward_input(mb, dY[mb])
+            elif kind == W:
+                self.backward_weight(mb)
+            else:
+                raise ValueError(kind)
+            peak = max(peak, self.live)
+        return Y, dX, peak
+
+
+def max_rel_err(got, ref) -> float:
+    """max_i |got_i - ref_i| / max_j |ref_j|  (the per-tensor reading of
+    "max relative error"; element-wise relative error is unbounded near 0)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.abs(ref).max()
+    if den == 0.0:
+        return float(np.abs(got).max())
+    return float(np.abs(got - ref).max() / den)

@@ -1,0 +1,247 @@
+"""Pins for the CPU oracle: things the mathematics fixes, independent of the
+oracle's own code (finite differences, invariants the paper's F/B/W split must
+satisfy, closed forms, and PyTorch CPU autograd as a second opinion)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import stage_oracle as so
+from paper_2507_00217_amd import synth
+
+F, B, W = so.F, so.B, so.W
+
+
+def tiny_cfg(norm="layernorm", act="gelu", n_kv=2, causal=True, L=2, b=1, n_mb=3):
+    return dict(n_layers=L, hidden=16, n_heads=2, n_kv_heads=n_kv, ffn=32, seq=8, mb_size=b,
+                n_microbatches=n_mb, norm=norm, act=act, dtype="fp32", causal=causal)
+
+
+def shape_of(cfg):
+    return so.Shape(cfg["n_layers"], cfg["hidden"], cfg["n_heads"], cfg["n_kv_heads"], cfg["ffn"],
+                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], cfg.get("causal", True))
+
+
+def setup(cfg, seed=11, wstd_boost=10.0):
+    params = synth.make_weights(cfg, seed)
+    # larger linear weights than N(0,0.02) so every path carries signal in fp64 checks
+    for lp in params:
+        for k in ("wqkv", "wo", "win", "wout"):
+            lp[k] = lp[k].astype(np.float64) * wstd_boost
+    X = synth.make_boundary(cfg, seed + 1).astype(np.float64)
+    G = synth.make_boundary(cfg, seed + 2).astype(np.float64)
+    return shape_of(cfg), params, X, G
+
+
+VARIANTS = [("layernorm", "gelu", 2, True), ("rmsnorm", "swiglu", 1, True),
+            ("rmsnorm", "swiglu", 2, False), ("layernorm", "swiglu", 1, True), ("rmsnorm", "gelu", 2, True)]
+
+
+def loss(sh, params, X, G):
+    st = so.OracleStage(sh, params)
+    return sum(float((st.forward(m, X[m]) * G[m]).sum()) for m in range(X.shape[0]))
+
+
+@pytest.mark.parametrize("norm,act,n_kv,causal", VARIANTS)
+def test_finite_differences(norm, act, n_kv, causal):
+    cfg = tiny_cfg(norm, act, n_kv, causal, n_mb=2)
+    sh, params, X, G = setup(cfg)
+    st = so.OracleStage(sh, params)
+    ops = synth.schedule_1f1b(2, 1)
+    _, dX, _ = st.run_schedule(ops, X, G)
+    rng = np.random.default_rng(5)
+    h = 1e-5
+    # every parameter tensor of every layer, a few random entries each
+    for li in range(sh.n_layers):
+        for name, w in params[li].items():
+            for _ in range(3):
+                idx = tuple(rng.integers(0, n) for n in w.shape)
+                orig = float(w[idx])
+                pp = [{k: v.astype(np.float64).copy() for k, v in lp.items()} for lp in params]
+                pp[li][name][idx] = orig + h
+                lp_ = loss(sh, pp, X, G)
+                pp[li][name][idx] = orig - h
+                lm_ = loss(sh, pp, X, G)
+                fd = (lp_ - lm_) / (2 * h)
+                an = st.grads[li][name][idx]
+                assert abs(fd - an) <= 1e-6 * max(1.0, abs(fd)), (li, name, idx, fd, an)
+    for _ in range(8):
+        idx = tuple(rng.integers(0, n) for n in X.shape)
+        Xp = X.copy(); Xp[idx] += h
+        Xm = X.copy(); Xm[idx] -= h
+        fd = (loss(sh, params, Xp, G) - loss(sh, params, Xm, G)) / (2 * h)
+        assert abs(fd - dX[idx]) <= 1e-6 * max(1.0, abs(fd)), (idx, fd, dX[idx])
+
+
+@pytest.mark.parametrize("norm,act,n_kv,causal", VARIANTS)
+def test_b_then_w_equals_fused_backward(norm, act, n_kv, causal):
+    cfg = tiny_cfg(norm, act, n_kv, causal)
+    sh, params, X, G = setup(cfg)
+    a = so.OracleStage(sh, params)
+    b = so.OracleStage(sh, params)
+    for m in range(X.shape[0]):
+        a.forward(m, X[m]); b.forward(m, X[m])
+        dxa = a.backward_input(m, G[m]); a.backward_weight(m)
+        dxb = b.backward_full(m, G[m])
+        assert so.max_rel_err(dxa, dxb) <= 1e-12
+    for la, lb in zip(a.grads, b.grads):
+        for k in la:
+            assert np.abs(la[k]).max() > 0
+            assert so.max_rel_err(la[k], lb[k]) <= 1e-12, k
+
+
+def test_schedule_order_invariance():
+    cfg = tiny_cfg("rmsnorm", "swiglu", 1, n_mb=6)
+    sh, params, X, G = setup(cfg)
+    res = []
+    for ops in (synth.schedule_1f1b(6, 2), synth.schedule_w_deferred(6, 2, 3), synth.schedule_w_lag1(6, 2),
+                synth.schedule_greedy(6, 2), synth.schedule_random(6, 3, 42)):
+        st = so.OracleStage(sh, params)
+        Y, dX, _ = st.run_schedule(ops, X, G)
+        assert st.live == 0
+        res.append((ops, Y, dX, st.grads))
+    ops0, Y0, dX0, g0 = res[0]
+    for ops, Y, dX, g in res[1:]:
+        assert np.array_equal(Y, Y0) and np.array_equal(dX, dX0)
+        w_sorted = [m for k, m in ops if k == W] == sorted(m for k, m in ops if k == W)
+        b_sorted = [m for k, m in ops if k == B] == sorted(m for k, m in ops if k == B)
+        for la, lb in zip(g, g0):
+            for k in la:
+                if w_sorted and b_sorted:
+                    assert np.array_equal(la[k], lb[k]), k      # same summation order: bitwise
+                else:
+                    assert so.max_rel_err(la[k], lb[k]) <= 1e-12, k
+
+
+def test_sum_over_microbatches_equals_full_batch():
+    cfg = tiny_cfg("layernorm", "gelu", 2, n_mb=4)
+    sh, params, X, G = setup(cfg)
+    st = so.OracleStage(sh, params)
+    st.run_schedule(synth.schedule_1f1b(4, 2), X, G)
+    big = so.Shape(sh.n_layers, sh.hidden, sh.n_heads, sh.n_kv_heads, sh.ffn, sh.seq, 4 * sh.mb_size,
+                   sh.norm, sh.act, sh.causal)
+    sb = so.OracleStage(big, params)
+    Yb = sb.forward(0, X.reshape(4, sh.seq, sh.hidden))
+    sb.backward_input(0, G.reshape(4, sh.seq, sh.hidden)); sb.backward_weight(0)
+    for la, lb in zip(st.grads, sb.grads):
+        for k in la:
+            assert so.max_rel_err(la[k], lb[k]) <= 1e-12, k
+
+
+@pytest.mark.parametrize("norm,act,n_kv,causal", VARIANTS)
+def test_against_torch_autograd(norm, act, n_kv, causal):
+    """Second opinion from a library: the same layer stack composed from
+    PyTorch CPU primitives, differentiated by autograd, in fp64."""
+    torch = pytest.importorskip("torch")
+    cfg = tiny_cfg(norm, act, n_kv, causal, b=2, n_mb=2)
+    sh, params, X, G = setup(cfg)
+    st = so.OracleStage(sh, params)
+    Y, dX, _ = st.run_schedule(synth.schedule_1f1b(2, 1), X, G)
+
+    tp = [{k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in lp.items()} for lp in params]
+    tX = torch.tensor(X, requires_grad=True)
+    d, h, hkv, hd, f = sh.hidden, sh.n_heads, sh.n_kv_heads, sh.head_dim, sh.ffn
+
+    def tnorm(x, g, b_):
+        if norm == "layernorm":
+            return torch.nn.functional.layer_norm(x, (d,), g, b_, 1e-5)
+        return x * torch.rsqrt((x * x).mean(-1, keepdim=True) + 1e-5) * g
+
+    def tlayer(x, p):
+        bsz, s, _ = x.shape
+        qkv = tnorm(x, p["g1"], p.get("b1")) @ p["wqkv"]
+        q = qkv[..., :d].reshape(bsz, s, h, hd).transpose(1, 2)
+        k = qkv[..., d:d + hkv * hd].reshape(bsz, s, hkv, hd).transpose(1, 2).repeat_interleave(h // hkv, dim=1)
+        v = qkv[..., d + hkv * hd:].reshape(bsz, s, hkv, hd).transpose(1, 2).repeat_interleave(h // hkv, dim=1)
+        o = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=causal)
+        x1 = x + o.transpose(1, 2).reshape(bsz, s, d) @ p["wo"]
+        z = tnorm(x1, p["g2"], p.get("b2")) @ p["win"]
+        a = torch.nn.functional.gelu(z) if act == "gelu" else torch.nn.functional.silu(z[..., :f]) * z[..., f:]
+        return x1 + a @ p["wout"]
+
+    total = 0
+    for m in range(2):
+        y = tX[m]
+        for p in tp:
+            y = tlayer(y, p)
+        assert so.max_rel_err(Y[m], y.detach().numpy()) <= 1e-12
+        total = total + (y * torch.tensor(G[m])).sum()
+    total.backward()
+    assert so.max_rel_err(dX, tX.grad.numpy()) <= 1e-11
+    for li in range(sh.n_layers):
+        for k in params[li]:
+            assert so.max_rel_err(st.grads[li][k], tp[li][k].grad.numpy()) <= 1e-11, (li, k)
+
+
+def test_closed_forms():
+    cfg = tiny_cfg("layernorm", "gelu", 2)
+    sh, params, X, G = setup(cfg)
+    # zero output projections: the layer is the identity; upstream weights get zero gradient
+    pz = [{k: (np.zeros_like(v) if k in ("wo", "wout") else v) for k, v in lp.items()} for lp in params]
+    st = so.OracleStage(sh, pz)
+    Y, dX, _ = st.run_schedule(synth.schedule_1f1b(3, 1), X, G)
+    assert np.array_equal(Y, X) and np.array_equal(dX, G)
+    for lg in st.grads:
+        assert not lg["wqkv"].any() and not lg["win"].any() and lg["wo"].any() and lg["wout"].any()
+    # LayerNorm rows with unit scale: mean 0, variance var/(var+eps)
+    x = X[0, 0]
+    out, _ = so.norm_forward("layernorm", x, 1.0, 0.0, 1e-5)
+    var = x.var(axis=-1)
+    assert np.allclose(out.mean(-1), 0, atol=1e-14) and np.allclose(out.var(-1), var / (var + 1e-5), rtol=1e-12)
+    out, _ = so.norm_forward("rmsnorm", x, 1.0, 0.0, 0.0)
+    assert np.allclose((out * out).mean(-1), 1.0, rtol=1e-12)
+    # softmax rows sum to one; causal rows see only the past; s = 1 returns v
+    q = X[0, 0].reshape(8, 2, 8)[:, 0]; k = X[1, 0].reshape(8, 2, 8)[:, 1]
+    p = so.head_probs(sh, q, k)
+    assert np.allclose(p.sum(-1), 1.0, rtol=1e-14) and not np.triu(p, 1).any()
+    assert p[0, 0] == 1.0
+    s1 = so.Shape(1, 16, 2, 1, 32, 1, 1)
+    q1 = X[0, 0, :1].reshape(1, 1, 2, 8); kv1 = X[1, 0, :1, :8].reshape(1, 1, 1, 8)
+    o1 = so.attention_forward(s1, q1, kv1, kv1 * 3)
+    assert np.allclose(o1[0, 0, 0], kv1[0, 0, 0] * 3) and np.allclose(o1[0, 0, 1], kv1[0, 0, 0] * 3)
+    # gelu at known points; swiglu with unit "up" half is silu
+    assert so.gelu(np.array(0.0)) == 0.0 and abs(so.gelu(np.array(1.0)) - 0.8413447460685429) < 1e-15
+    assert abs(so.gelu_grad(np.array(0.0)) - 0.5) < 1e-15
+
+
+def test_causality_and_linearity():
+    cfg = tiny_cfg("rmsnorm", "swiglu", 1)
+    sh, params, X, G = setup(cfg)
+    st = so.OracleStage(sh, params)
+    y0 = st.forward(0, X[0])
+    Xp = X[0].copy(); Xp[0, 5] += 1.0
+    y1 = so.OracleStage(sh, params).forward(0, Xp)
+    assert np.array_equal(y0[0, :5], y1[0, :5]) and not np.array_equal(y0[0, 5:], y1[0, 5:])
+    # dX and grads are linear in the output gradient
+    a = so.OracleStage(sh, params); b = so.OracleStage(sh, params)
+    a.forward(0, X[0]); b.forward(0, X[0])
+    da = a.backward_input(0, G[0]); a.backward_weight(0)
+    db = b.backward_input(0, 3.0 * G[0]); b.backward_weight(0)
+    assert so.max_rel_err(db, 3.0 * da) <= 1e-13
+    for la, lb in zip(a.grads, b.grads):
+        for k in la:
+            assert so.max_rel_err(lb[k], 3.0 * la[k]) <= 1e-13
+
+
+def test_gqa_with_all_kv_heads_is_mha():
+    """n_kv_heads == n_heads through the grouped path equals plain per-head attention."""
+    rng = np.random.default_rng(0)
+    sh = so.Shape(1, 16, 4, 4, 32, 6, 1)
+    q = rng.standard_normal((1, 6, 4, 4)); k = rng.standard_normal((1, 6, 4, 4)); v = rng.standard_normal((1, 6, 4, 4))
+    o = so.attention_forward(sh, q, k, v)
+    for j in range(4):
+        S = q[0, :, j] @ k[0, :, j].T / 2.0
+        S[np.triu_indices(6, 1)] = -np.inf
+        P = np.exp(S - S.max(-1, keepdims=True)); P /= P.sum(-1, keepdims=True)
+        assert np.allclose(o[0, :, j], P @ v[0, :, j], rtol=1e-13)
+    # grouped: 2 kv heads shared by 4 query heads == MHA with the kv heads repeated
+    sg = so.Shape(1, 16, 4, 2, 32, 6, 1)
+    og = so.attention_forward(sg, q, k[:, :, :2], v[:, :, :2])
+    om = so.attention_forward(sh, q, np.repeat(k[:, :, :2], 2, axis=2), np.repeat(v[:, :, :2], 2, axis=2))
+    assert np.array_equal(og, om)
+    do = rng.standard_normal(q.shape)
+    dqg, dkg, dvg = so.attention_backward(sg, q, k[:, :, :2], v[:, :, :2], do)
+    dqm, dkm, dvm = so.attention_backward(sh, q, np.repeat(k[:, :, :2], 2, axis=2), np.repeat(v[:, :, :2], 2, axis=2), do)
+    assert np.allclose(dqg, dqm, rtol=1e-13)
+    assert np.allclose(dkg, dkm.reshape(1, 6, 2, 2, 4).sum(3), rtol=1e-12)
+    assert np.allclose(dvg, dvm.reshape(1, 6, 2, 2, 4).sum(3), rtol=1e-12)
