@@ -1,0 +1,157 @@
+/*
+ * stage.h -- C ABI of the MI355X pipeline-stage F/B/W engine.
+ *
+ * One pipeline stage = a stack of identical pre-norm transformer decoder
+ * layers living on one GPU.  Following the paper's block decomposition
+ * (section 3.1 "Computation Blocks"; Appendix B "Weight Gradient Separation"),
+ * the work of a microbatch is exposed as three separately schedulable ops:
+ *
+ *   F  forward,                          stashes activations
+ *   B  input-gradient backward (the paper's D / DGrad: dX = dY W^T per linear)
+ *   W  weight-gradient backward (WGrad: dW += X^T dY per linear), frees the stash
+ *
+ * and a schedule is a per-stage ordered list of such ops (the "per-stage
+ * schedule S_d" that the paper's generators emit, Alg. 1; section 3.3 "schedule
+ * dependencies").  Activations are cached in F and released after B and W
+ * (section 3.2); the number of microbatches whose stash is live is bounded by
+ * `stash_cap`, the on-device memory constraint of section 4.1.  With
+ * `enforce_mb_order` the list must also satisfy the paper's "Microbatch Order
+ * within Stage and Type" constraint (section 4.1), which makes accumulated
+ * gradients bit-reproducible across schedules.
+ *
+ * Conventions
+ *   - Every pointer named *_dev is DEVICE memory owned by the caller; the
+ *     library never allocates or frees device memory.  `ops`, config structs
+ *     and all out-parameters are HOST memory.
+ *   - All device work is enqueued on the HIP stream given to stage_init and the
+ *     calls return without synchronising.  The caller synchronises that stream
+ *     before reading y / dx / gradients.  x and dy are copied into the stash
+ *     when their op is enqueued (stream order), so they may be reused after
+ *     the op's position in the stream has been reached.
+ *   - Row-major everywhere.  A boundary tensor of one microbatch is
+ *     [mb_size, seq, hidden] contiguous in the compute dtype (fp32 or bf16).
+ *   - Return value: 0 on success, a negative STAGE_E_* code otherwise.  A call
+ *     that returns STAGE_E_INVAL / _ORDER / _STASH_FULL has enqueued nothing
+ *     and changed no state.  STAGE_E_HIP (a failed launch) is sticky.
+ */
+#ifndef PAPER_2507_00217_STAGE_H
+#define PAPER_2507_00217_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct stage stage_t; /* opaque */
+
+enum { STAGE_F = 0, STAGE_B = 1, STAGE_W = 2 };                 /* op kinds */
+enum { STAGE_NORM_LAYERNORM = 0, STAGE_NORM_RMSNORM = 1 };
+enum { STAGE_ACT_GELU = 0, STAGE_ACT_SWIGLU = 1 };               /* GELU is the exact erf form */
+enum { STAGE_DTYPE_FP32 = 0, STAGE_DTYPE_BF16 = 1 };
+
+enum {
+  STAGE_OK = 0,
+  STAGE_E_INVAL = -1,      /* null pointer, bad shape, unsupported head_dim, mb out of range */
+  STAGE_E_ORDER = -2,      /* F twice, B before F or twice, W before B or twice, mb-order violation */
+  STAGE_E_STASH_FULL = -3, /* F while stash_cap microbatches are live */
+  STAGE_E_HIP = -4         /* a kernel launch or runtime call failed */
+};
+
+/* Parameter ids of one layer, in storage order. */
+enum {
+  STAGE_P_NORM1_GAMMA = 0, STAGE_P_NORM1_BETA = 1, STAGE_P_WQKV = 2, STAGE_P_WO = 3,
+  STAGE_P_NORM2_GAMMA = 4, STAGE_P_NORM2_BETA = 5, STAGE_P_WIN = 6, STAGE_P_WOUT = 7,
+  STAGE_P_COUNT = 8
+};
+
+/* One op of a per-stage schedule: (type, microbatch) -- the paper's compute-op
+ * id (stage, chunk, type, microbatch) reduced to one stage and one chunk. */
+typedef struct { int32_t kind; int32_t mb; } stage_op_t;
+
+typedef struct {
+  int32_t n_layers;
+  int32_t hidden;          /* d; multiple of 64 */
+  int32_t n_heads;         /* h; head_dim = d / h must be 64 or 128 */
+  int32_t n_kv_heads;      /* divides n_heads (grouped-query attention when smaller) */
+  int32_t ffn;             /* f; multiple of 64 */
+  int32_t seq;             /* s */
+  int32_t mb_size;         /* b sequences per microbatch; attention never mixes them */
+  int32_t n_microbatches;
+  int32_t norm;            /* STAGE_NORM_* */
+  int32_t act;             /* STAGE_ACT_*  */
+  int32_t causal;          /* 1: token t attends to tokens <= t of its own sequence */
+  int32_t dtype;           /* STAGE_DTYPE_*; weight-gradient accumulators are fp32 in both */
+  int32_t stash_cap;       /* max microbatches live (F started, W not finished); 0 = n_microbatches */
+  int32_t enforce_mb_order;/* 1: ops of one kind must come in increasing microbatch index */
+  float   norm_eps;        /* e.g. 1e-5 */
+} stage_config_t;
+
+typedef struct { size_t weights, grads, stash, workspace; } stage_sizes_t; /* bytes */
+
+/* Host only (no GPU needed). Bytes the caller must allocate for stage_init.
+ * stash = stash_cap slots of equal size. */
+int stage_query_sizes(const stage_config_t* cfg, stage_sizes_t* out);
+
+/* Host only. Checks an op list against the microbatch state machine
+ *   EMPTY --F--> FWD --B--> BWD --W--> EMPTY
+ * starting from all-EMPTY, the stash cap and (if enabled) the microbatch-order
+ * rule.  On failure *first_bad_index is the offending position.  *peak_live is
+ * the largest number of live microbatches reached by the legal prefix.
+ * The list need not be complete. Either out-pointer may be NULL. */
+int stage_validate_schedule(const stage_config_t* cfg, const stage_op_t* ops, int n_ops,
+                            int* first_bad_index, int* peak_live);
+
+/* Host only. Where parameter `param_id` of `layer` lives inside the flat
+ * weights buffer (compute dtype) and the flat grads buffer (fp32): same element
+ * offset in both.  Linear weights are stored [in, out] row-major so that
+ * forward is A.W:  WQKV [d, d+2*d_kv] (columns q | k | v),  WO [d, d],
+ * WIN [d, f] (GELU) or [d, 2f] (SwiGLU, columns gate | up),  WOUT [f, d];
+ * norm vectors have rows = 1, cols = d.  A parameter the config does not have
+ * (beta under RMSNorm) reports rows = cols = 0. */
+int stage_param_layout(const stage_config_t* cfg, int layer, int param_id,
+                       size_t* offset_elems, int64_t* rows, int64_t* cols);
+
+/* Creates a stage over caller-allocated device buffers of at least the
+ * queried sizes (256-byte aligned) and a caller-owned hipStream_t (may be
+ * NULL for the default stream).  Weights must already be in weights_dev (or be
+ * written there, in stream order, before the first op).  Zeroes grads_dev. */
+int stage_init(const stage_config_t* cfg, void* weights_dev, void* grads_dev, void* stash_dev,
+               void* workspace_dev, void* hip_stream, stage_t** out);
+
+/* F(mb): y = layers(x); stashes what B and W need. x_dev, y_dev: [mb_size, seq, hidden]. */
+int stage_forward(stage_t* st, int mb, const void* x_dev, void* y_dev);
+/* B(mb): dx = d<y,dy>/dx; accumulates norm-parameter gradients; keeps the dZ
+ * tensors W needs inside the stash slot. */
+int stage_backward_input(stage_t* st, int mb, const void* dy_dev, void* dx_dev);
+/* W(mb): grads += A^T dZ for the four linear maps of every layer; releases the slot. */
+int stage_backward_weight(stage_t* st, int mb);
+
+/* Runs an ordered op list.  The whole list is validated against the current
+ * state before anything is enqueued.  *_all: [n_microbatches, mb_size, seq,
+ * hidden]; op (kind, mb) uses slice mb.  Leftover live microbatches carry over
+ * to the next call, so an iteration may be fed in pieces. */
+int stage_run_schedule(stage_t* st, const stage_op_t* ops, int n_ops,
+                       const void* x_all_dev, const void* dy_all_dev, void* y_all_dev, void* dx_all_dev);
+
+/* Borrowed pointer to the fp32 gradient buffer (== grads_dev) and its length.
+ * After a full iteration it holds the SUM over microbatches of d<Y_m,dY_m>/dtheta. */
+int stage_grads(stage_t* st, float** grads_dev, size_t* n_elems);
+int stage_zero_grads(stage_t* st);
+
+/* Counters: live microbatches now, their peak since init, peak stash bytes in use. */
+int stage_stats(stage_t* st, int* live, int* peak_live, size_t* peak_stash_bytes);
+
+/* Kernel selection for debugging and A/B measurements: 0 = tuned gfx950 kernels
+ * (MFMA GEMM / fused attention where the dtype has them), 1 = plain reference
+ * HIP kernels for every step.  Both run on the GPU. */
+int stage_set_kernel_set(stage_t* st, int which);
+
+void stage_destroy(stage_t* st);
+const char* stage_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

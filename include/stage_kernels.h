@@ -1,0 +1,58 @@
+/*
+ * stage_kernels.h -- kernel-level entry points of the stage engine.
+ *
+ * The same HIP kernels that stage_forward / stage_backward_input /
+ * stage_backward_weight launch, callable one at a time so that each step of
+ * the F / B / W path (paper section 3.1, Appendix B) can be checked against
+ * its definition and timed against its roofline in isolation.
+ *
+ * All data pointers are DEVICE memory owned by the caller; nothing is
+ * allocated, work is enqueued on `hip_stream` (hipStream_t, NULL = default
+ * stream) without synchronising.  dtype / norm / act codes are the STAGE_*
+ * enums of stage.h.  kernel_set: 0 = tuned gfx950 kernels where one exists for
+ * the shape, 1 = plain reference HIP kernels.  Return: 0, or STAGE_E_INVAL for
+ * a shape the kernel does not take, STAGE_E_HIP for a failed launch.
+ */
+#ifndef PAPER_2507_00217_STAGE_KERNELS_H
+#define PAPER_2507_00217_STAGE_KERNELS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* mode 0 (forward,  A.W):    C[m,n] = sum_k A[m*lda+k] * B[k*ldb+n] (+ R[m*ldr+n])
+ * mode 1 (dgrad,   dZ.W^T):  C[m,n] = sum_k A[m*lda+k] * B[n*ldb+k]
+ * mode 2 (wgrad,   A^T.dZ):  C[m,n] += sum_k A[k*lda+m] * B[k*ldb+n], C fp32 (acc_f32 must be 1)
+ * A, B, R and (unless acc_f32) C are in the compute dtype; R may be NULL. */
+int stage_kernel_gemm(int dtype, int mode, int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
+                      void* C, int64_t ldc, const void* R, int64_t ldr, int acc_f32, int kernel_set, void* hip_stream);
+
+/* qkv: [b*s, (h + 2*hkv)*hd] rows of q | k | v;  o: [b*s, h*hd];  lse: [b, h, s] fp32. */
+int stage_kernel_attention_fwd(int dtype, int b, int s, int h, int hkv, int hd, int causal, const void* qkv, void* o,
+                               float* lse, int kernel_set, void* hip_stream);
+/* dqkv laid out like qkv; delta: [b, h, s] fp32 scratch. */
+int stage_kernel_attention_bwd(int dtype, int b, int s, int h, int hkv, int hd, int causal, const void* qkv,
+                               const void* o, const float* lse, const void* dout, void* dqkv, float* delta,
+                               int kernel_set, void* hip_stream);
+
+/* stats: [rows, 2] fp32 (mean, rstd). beta ignored for RMSNorm. */
+int stage_kernel_norm_fwd(int dtype, int norm, int rows, int d, float eps, const void* x, const void* gamma,
+                          const void* beta, void* out, float* stats, void* hip_stream);
+/* dx = resid + norm'(dout) (resid may be NULL; dx may alias x); dgamma/dbeta fp32 += ;
+ * partial: scratch of stage_kernel_norm_partial_bytes(d) bytes. */
+int stage_kernel_norm_bwd(int dtype, int norm, int rows, int d, const void* x, const float* stats, const void* gamma,
+                          const void* dout, const void* resid, void* dx, float* dgamma, float* dbeta, float* partial,
+                          void* hip_stream);
+size_t stage_kernel_norm_partial_bytes(int d);
+
+/* GELU: z [rows, f]; SwiGLU: z [rows, 2f] (gate | up).  a, da: [rows, f].  Backward overwrites z with dz. */
+int stage_kernel_act_fwd(int dtype, int act, int rows, int f, const void* z, void* a, void* hip_stream);
+int stage_kernel_act_bwd(int dtype, int act, int rows, int f, void* z, const void* da, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

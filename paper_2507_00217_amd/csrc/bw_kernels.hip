@@ -1,0 +1,335 @@
+// Bandwidth-bound kernels of the stage: LayerNorm / RMSNorm forward and backward
+// (wavefront reductions, rows held in registers so HBM is read once), GELU /
+// SwiGLU forward and backward, fill and copy.  All accesses are 16-byte vectors.
+// Norm-parameter gradients are produced here, at B time, through per-workgroup
+// partial sums reduced in a fixed order (no atomics), so results do not depend
+// on scheduling.
+#include "common.h"
+
+namespace stg {
+
+template <typename T> struct Vec {
+  static constexpr int N = 16 / sizeof(T);
+  union { uint4 raw; T v[16 / sizeof(T)]; };
+};
+
+template <typename T> __device__ __forceinline__ Vec<T> ldv(const T* p) {
+  Vec<T> r; r.raw = *reinterpret_cast<const uint4*>(p); return r;
+}
+template <typename T> __device__ __forceinline__ void stv(T* p, const Vec<T>& r) {
+  *reinterpret_cast<uint4*>(p) = r.raw;
+}
+
+constexpr int NORM_THREADS = 256;
+constexpr int NORM_MAXCH = 4;          // 16-byte chunks per thread: d <= 256*4*(16/sizeof(T))
+constexpr int NORM_PARTIAL_ROWS = 256;
+int norm_partial_rows() { return NORM_PARTIAL_ROWS; }
+
+__device__ __forceinline__ float wg_sum(float v, float* red) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+// out = (x - mean) * rstd * gamma + beta   |   out = x * rstd * gamma
+template <typename T, int KIND>
+__global__ __launch_bounds__(NORM_THREADS) void norm_fwd_kernel(NormArgs n) {
+  constexpr int V = Vec<T>::N;
+  __shared__ float red[4];
+  const int row = blockIdx.x;
+  const T* x = (const T*)n.x + (int64_t)row * n.d;
+  T* out = (T*)n.out + (int64_t)row * n.d;
+  const int nvec = n.d / V;
+  float xv[NORM_MAXCH][V];
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < NORM_MAXCH; ++c) {
+    const int vi = threadIdx.x + c * NORM_THREADS;
+    if (vi < nvec) {
+      Vec<T> t = ldv(x + vi * V);
+#pragma unroll
+      for (int e = 0; e < V; ++e) { xv[c][e] = to_f32(t.v[e]); s += (KIND == 0) ? xv[c][e] : xv[c][e] * xv[c][e]; }
+    }
+  }
+  float mean = 0.f, rstd;
+  const float inv_d = 1.f / (float)n.d;
+  if (KIND == 0) {
+    mean = wg_sum(s, red) * inv_d;
+    float q = 0.f;
+#pragma unroll
+    for (int c = 0; c < NORM_MAXCH; ++c)
+      if (threadIdx.x + c * NORM_THREADS < nvec)
+#pragma unroll
+        for (int e = 0; e < V; ++e) { float t = xv[c][e] - mean; q += t * t; }
+    rstd = rsqrtf(wg_sum(q, red) * inv_d + n.eps);
+  } else {
+    rstd = rsqrtf(wg_sum(s, red) * inv_d + n.eps);
+  }
+  if (threadIdx.x == 0) { n.stats[2 * row] = mean; n.stats[2 * row + 1] = rstd; }
+#pragma unroll
+  for (int c = 0; c < NORM_MAXCH; ++c) {
+    const int vi = threadIdx.x + c * NORM_THREADS;
+    if (vi < nvec) {
+      Vec<T> g = ldv((const T*)n.gamma + vi * V), b, o;
+      if (KIND == 0) b = ldv((const T*)n.beta + vi * V);
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        float y = (xv[c][e] - mean) * rstd * to_f32(g.v[e]);
+        if (KIND == 0) y += to_f32(b.v[e]);
+        o.v[e] = from_f32<T>(y);
+      }
+      stv(out + vi * V, o);
+    }
+  }
+}
+
+// dx = resid + rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)),  dxhat = dout * gamma
+// (the mean(dxhat) term is absent for RMSNorm); per-workgroup partial sums of
+// dgamma = sum_rows dout * xhat and dbeta = sum_rows dout go to n.partial.
+template <typename T, int KIND>
+__global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(NormArgs n) {
+  constexpr int V = Vec<T>::N;
+  __shared__ float red[4];
+  const int nvec = n.d / V;
+  float gam[NORM_MAXCH][V], dg[NORM_MAXCH][V], db[NORM_MAXCH][V];
+#pragma unroll
+  for (int c = 0; c < NORM_MAXCH; ++c) {
+    const int vi = threadIdx.x + c * NORM_THREADS;
+    Vec<T> g;
+    if (vi < nvec) g = ldv((const T*)n.gamma + vi * V);
+#pragma unroll
+    for (int e = 0; e < V; ++e) { gam[c][e] = vi < nvec ? to_f32(g.v[e]) : 0.f; dg[c][e] = 0.f; db[c][e] = 0.f; }
+  }
+  const float inv_d = 1.f / (float)n.d;
+  for (int row = blockIdx.x; row < n.rows; row += gridDim.x) {
+    const T* x = (const T*)n.x + (int64_t)row * n.d;
+    const T* dout = (const T*)n.dout + (int64_t)row * n.d;
+    const T* resid = n.resid ? (const T*)n.resid + (int64_t)row * n.d : nullptr;
+    T* dx = (T*)n.out + (int64_t)row * n.d;
+    const float mean = n.stats[2 * row], rstd = n.stats[2 * row + 1];
+    float xh[NORM_MAXCH][V], dxh[NORM_MAXCH][V];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NORM_MAXCH; ++c) {
+      const int vi = threadIdx.x + c * NORM_THREADS;
+      if (vi < nvec) {
+        Vec<T> tx = ldv(x + vi * V), td = ldv(dout + vi * V);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          const float xhat = (to_f32(tx.v[e]) - mean) * rstd;
+          const float dv = to_f32(td.v[e]);
+          xh[c][e] = xhat;
+          dxh[c][e] = dv * gam[c][e];
+          dg[c][e] += dv * xhat;
+          if (KIND == 0) db[c][e] += dv;
+          s1 += dxh[c][e];
+          s2 += dxh[c][e] * xhat;
+        }
+      }
+    }
+    float m1 = 0.f;
+    if (KIND == 0) m1 = wg_sum(s1, red) * inv_d;
+    const float m2 = wg_sum(s2, red) * inv_d;
+#pragma unroll
+    for (int c = 0; c < NORM_MAXCH; ++c) {
+      const int vi = threadIdx.x + c * NORM_THREADS;
+      if (vi < nvec) {
+        Vec<T> r, o;
+        if (resid) r = ldv(resid + vi * V);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          float v = (dxh[c][e] - m1 - xh[c][e] * m2) * rstd;
+          if (resid) v += to_f32(r.v[e]);
+          o.v[e] = from_f32<T>(v);
+        }
+        stv(dx + vi * V, o);
+      }
+    }
+  }
+  float* pg = n.partial + (int64_t)blockIdx.x * 2 * n.d;
+  float* pb = pg + n.d;
+#pragma unroll
+  for (int c = 0; c < NORM_MAXCH; ++c) {
+    const int vi = threadIdx.x + c * NORM_THREADS;
+    if (vi < nvec)
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        pg[vi * V + e] = dg[c][e];
+        if (KIND == 0) pb[vi * V + e] = db[c][e];
+      }
+  }
+}
+
+// grads += sum over workgroup partials, in workgroup order
+template <int KIND>
+__global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(NormArgs n, int nparts) {
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= n.d) return;
+  float g = 0.f, b = 0.f;
+  for (int p = 0; p < nparts; ++p) {
+    g += n.partial[(int64_t)p * 2 * n.d + col];
+    if (KIND == 0) b += n.partial[(int64_t)p * 2 * n.d + n.d + col];
+  }
+  n.dgamma[col] += g;
+  if (KIND == 0) n.dbeta[col] += b;
+}
+
+template <typename T>
+static bool norm_shape_ok(const NormArgs& n) {
+  constexpr int V = 16 / sizeof(T);
+  return n.d % V == 0 && n.d / V <= NORM_THREADS * NORM_MAXCH && n.rows > 0;
+}
+
+template <typename T>
+static hipError_t norm_fwd_t(const NormArgs& n, hipStream_t s) {
+  if (!norm_shape_ok<T>(n)) return hipErrorInvalidValue;
+  if (n.kind == 0) hipLaunchKernelGGL((norm_fwd_kernel<T, 0>), dim3(n.rows), dim3(NORM_THREADS), 0, s, n);
+  else hipLaunchKernelGGL((norm_fwd_kernel<T, 1>), dim3(n.rows), dim3(NORM_THREADS), 0, s, n);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t norm_bwd_t(const NormArgs& n, hipStream_t s) {
+  if (!norm_shape_ok<T>(n)) return hipErrorInvalidValue;
+  const int parts = NORM_PARTIAL_ROWS;
+  const int fb = (n.d + 255) / 256;
+  if (n.kind == 0) {
+    hipLaunchKernelGGL((norm_bwd_kernel<T, 0>), dim3(parts), dim3(NORM_THREADS), 0, s, n);
+    hipLaunchKernelGGL((norm_bwd_finalize_kernel<0>), dim3(fb), dim3(256), 0, s, n, parts);
+  } else {
+    hipLaunchKernelGGL((norm_bwd_kernel<T, 1>), dim3(parts), dim3(NORM_THREADS), 0, s, n);
+    hipLaunchKernelGGL((norm_bwd_finalize_kernel<1>), dim3(fb), dim3(256), 0, s, n, parts);
+  }
+  return hipGetLastError();
+}
+
+hipError_t norm_fwd(DType dt, const NormArgs& n, hipStream_t s) {
+  return dt == DT_F32 ? norm_fwd_t<float>(n, s) : norm_fwd_t<bf16>(n, s);
+}
+hipError_t norm_bwd(DType dt, const NormArgs& n, hipStream_t s) {
+  return dt == DT_F32 ? norm_bwd_t<float>(n, s) : norm_bwd_t<bf16>(n, s);
+}
+
+// ---------------------------------------------------------------------------
+// activations
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_df(float u) {
+  return 0.5f * (1.f + erff(u * 0.70710678118654752f)) + u * 0.39894228040143268f * __expf(-0.5f * u * u);
+}
+__device__ __forceinline__ float sigmoid_f(float g) { return 1.f / (1.f + __expf(-g)); }
+
+// GELU: a = gelu(z).  SwiGLU: a = silu(z[:, :f]) * z[:, f:]
+template <typename T, int KIND>
+__global__ __launch_bounds__(256) void act_fwd_kernel(ActArgs a) {
+  constexpr int V = Vec<T>::N;
+  const int fv = a.f / V;
+  const int64_t total = (int64_t)a.rows * fv;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / fv; const int c = (int)(i % fv) * V;
+    Vec<T> o;
+    if (KIND == 0) {
+      Vec<T> u = ldv((const T*)a.z + r * a.f + c);
+#pragma unroll
+      for (int e = 0; e < V; ++e) o.v[e] = from_f32<T>(gelu_f(to_f32(u.v[e])));
+    } else {
+      Vec<T> g = ldv((const T*)a.z + r * 2 * a.f + c), u = ldv((const T*)a.z + r * 2 * a.f + a.f + c);
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        const float gv = to_f32(g.v[e]);
+        o.v[e] = from_f32<T>(gv * sigmoid_f(gv) * to_f32(u.v[e]));
+      }
+    }
+    stv((T*)a.a + r * a.f + c, o);
+  }
+}
+
+// GELU: z := da * gelu'(z).  SwiGLU: z[:, :f] := da*u*(sg + g*sg*(1-sg)),  z[:, f:] := da*g*sg
+template <typename T, int KIND>
+__global__ __launch_bounds__(256) void act_bwd_kernel(ActArgs a) {
+  constexpr int V = Vec<T>::N;
+  const int fv = a.f / V;
+  const int64_t total = (int64_t)a.rows * fv;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / fv; const int c = (int)(i % fv) * V;
+    Vec<T> da = ldv((const T*)a.da + r * a.f + c);
+    if (KIND == 0) {
+      T* zp = (T*)a.z + r * a.f + c;
+      Vec<T> u = ldv(zp), o;
+#pragma unroll
+      for (int e = 0; e < V; ++e) o.v[e] = from_f32<T>(to_f32(da.v[e]) * gelu_df(to_f32(u.v[e])));
+      stv(zp, o);
+    } else {
+      T* gp = (T*)a.z + r * 2 * a.f + c; T* up = gp + a.f;
+      Vec<T> g = ldv(gp), u = ldv(up), og, ou;
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        const float gv = to_f32(g.v[e]), uv = to_f32(u.v[e]), d = to_f32(da.v[e]);
+        const float sg = sigmoid_f(gv);
+        og.v[e] = from_f32<T>(d * uv * (sg + gv * sg * (1.f - sg)));
+        ou.v[e] = from_f32<T>(d * gv * sg);
+      }
+      stv(gp, og); stv(up, ou);
+    }
+  }
+}
+
+template <typename T>
+static hipError_t act_t(const ActArgs& a, bool bwd, hipStream_t s) {
+  constexpr int V = 16 / sizeof(T);
+  if (a.f % V != 0 || a.rows <= 0) return hipErrorInvalidValue;
+  const int64_t total = (int64_t)a.rows * (a.f / V);
+  const int grid = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
+  if (!bwd) {
+    if (a.kind == 0) hipLaunchKernelGGL((act_fwd_kernel<T, 0>), dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((act_fwd_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a);
+  } else {
+    if (a.kind == 0) hipLaunchKernelGGL((act_bwd_kernel<T, 0>), dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((act_bwd_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t act_fwd(DType dt, const ActArgs& a, hipStream_t s) {
+  return dt == DT_F32 ? act_t<float>(a, false, s) : act_t<bf16>(a, false, s);
+}
+hipError_t act_bwd(DType dt, const ActArgs& a, hipStream_t s) {
+  return dt == DT_F32 ? act_t<float>(a, true, s) : act_t<bf16>(a, true, s);
+}
+
+// ---------------------------------------------------------------------------
+// fill / copy (kernels rather than memset/memcpy nodes, so that a caller may
+// capture a schedule into a HIP graph)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* p, size_t nvec, float* tail, size_t ntail) {
+  const uint4 z = {0, 0, 0, 0};
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (size_t)gridDim.x * 256) p[i] = z;
+  if (blockIdx.x == 0 && threadIdx.x < ntail) tail[threadIdx.x] = 0.f;
+}
+
+hipError_t fill_zero_f32(float* p, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const size_t nvec = n / 4;
+  const size_t want = (nvec + 255) / 256;
+  const int grid = (int)(want < 1 ? 1 : (want > 16384 ? 16384 : want));
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, s, (uint4*)p, nvec, p + nvec * 4, n - nvec * 4);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(uint4* dst, const uint4* src, size_t nvec) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  if (bytes % 16) return hipErrorInvalidValue;
+  const size_t nvec = bytes / 16;
+  const size_t want = (nvec + 255) / 256;
+  const int grid = (int)(want > 16384 ? 16384 : want);
+  hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, nvec);
+  return hipGetLastError();
+}
+
+}  // namespace stg

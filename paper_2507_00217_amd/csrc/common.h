@@ -1,0 +1,90 @@
+// Internal declarations shared by the stage executor and its gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace stg {
+
+typedef __bf16 bf16;
+
+enum DType { DT_F32 = 0, DT_BF16 = 1 };
+enum GemmMode {
+  GEMM_NN = 0,  // C[m,n] = sum_k A[m*lda+k] * B[k*ldb+n]          (forward: A.W)
+  GEMM_NT = 1,  // C[m,n] = sum_k A[m*lda+k] * B[n*ldb+k]          (dgrad:  dZ.W^T)
+  GEMM_TN = 2   // C[m,n] = sum_k A[k*lda+m] * B[k*ldb+n]          (wgrad:  A^T.dZ)
+};
+
+struct GemmArgs {
+  int mode;
+  int M, N, K;
+  const void* A; int64_t lda;
+  const void* B; int64_t ldb;
+  void* C; int64_t ldc;          // compute dtype, or fp32 when acc_f32
+  const void* R; int64_t ldr;    // optional residual added in the epilogue (compute dtype), or null
+  int acc_f32;                   // 1: C is fp32 and the product is added to it (C += A^T.B)
+};
+
+struct AttnArgs {
+  int b, s, h, hkv, hd, causal;
+  const void* qkv; int64_t ld;   // [b*s, d + 2*dkv], columns q | k | v
+  void* o;                       // [b*s, d]
+  float* lse;                    // [b, h, s]  log-sum-exp of the scaled, masked scores
+  // backward only
+  const void* dout;              // [b*s, d]
+  void* dqkv;                    // [b*s, d + 2*dkv]
+  float* delta;                  // [b, h, s] scratch: rowsum(dout * o)
+};
+
+struct NormArgs {
+  int kind;                      // 0 LayerNorm, 1 RMSNorm
+  int rows, d;
+  float eps;
+  const void* x;                 // [rows, d]
+  const void* gamma; const void* beta;
+  void* out;                     // forward: normalised output; backward: dx (may alias x)
+  float* stats;                  // [rows, 2]: mean, rstd (mean unused for RMSNorm)
+  // backward only
+  const void* dout;              // gradient w.r.t. the normalised output
+  const void* resid;             // gradient arriving over the residual branch, added to dx
+  float* dgamma; float* dbeta;   // fp32 accumulators (+=)
+  float* partial;                // scratch [norm_partial_rows(), 2, d] fp32
+};
+
+struct ActArgs {
+  int kind;                      // 0 GELU (erf), 1 SwiGLU
+  int rows, f;
+  void* z;                       // [rows, f] (GELU) or [rows, 2f] (gate | up); backward overwrites it with dz
+  void* a;                       // forward out [rows, f]
+  const void* da;                // backward in  [rows, f]
+};
+
+int norm_partial_rows();
+
+// plain reference kernels (any dtype); one kernel per mathematical step
+hipError_t gemm_ref(DType dt, const GemmArgs& g, hipStream_t s);
+hipError_t attn_fwd_ref(DType dt, const AttnArgs& a, hipStream_t s);
+hipError_t attn_bwd_ref(DType dt, const AttnArgs& a, hipStream_t s);
+
+// bandwidth-bound kernels (wavefront reductions, 16-byte accesses)
+hipError_t norm_fwd(DType dt, const NormArgs& n, hipStream_t s);
+hipError_t norm_bwd(DType dt, const NormArgs& n, hipStream_t s);
+hipError_t act_fwd(DType dt, const ActArgs& a, hipStream_t s);
+hipError_t act_bwd(DType dt, const ActArgs& a, hipStream_t s);
+hipError_t fill_zero_f32(float* p, size_t n, hipStream_t s);
+hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
+
+// tuned gfx950 kernels (bf16 MFMA)
+bool gemm_mfma_supported(const GemmArgs& g);
+hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s);
+bool attn_mfma_supported(const AttnArgs& a);
+hipError_t attn_fwd_mfma(const AttnArgs& a, hipStream_t s);
+hipError_t attn_bwd_mfma(const AttnArgs& a, hipStream_t s);
+
+// scalar conversions
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // round to nearest even
+
+}  // namespace stg

@@ -1,0 +1,530 @@
+// Host side of the pipeline-stage engine: configuration checks, parameter and
+// stash layout, the microbatch state machine / schedule validator, the stash
+// slot allocator with its cap, and the executor that turns F / B / W ops into
+// kernel launches on one stream (no host synchronisation inside a schedule).
+//
+// Block decomposition: paper section 3.1 and Appendix B.  Stash lifetime
+// (cached in F, released after B and W): section 3.2.  Cap on live stashes:
+// the on-device memory constraint of section 4.1.
+#include "../../include/stage.h"
+#include "common.h"
+
+#include <new>
+#include <vector>
+
+using namespace stg;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Dims {
+  int L, d, h, hkv, hd, dkv, dq, f, fin, s, b, T, n_mb, cap;
+  size_t es;  // bytes per element of the compute dtype
+};
+
+bool make_dims(const stage_config_t* c, Dims* o) {
+  if (!c) return false;
+  if (c->n_layers < 1 || c->hidden < 64 || c->n_heads < 1 || c->n_kv_heads < 1 || c->ffn < 64 || c->seq < 1 ||
+      c->mb_size < 1 || c->n_microbatches < 1)
+    return false;
+  if (c->hidden % 64 || c->ffn % 64 || c->hidden % c->n_heads || c->n_heads % c->n_kv_heads) return false;
+  const int hd = c->hidden / c->n_heads;
+  if (hd != 64 && hd != 128) return false;
+  if (c->norm != STAGE_NORM_LAYERNORM && c->norm != STAGE_NORM_RMSNORM) return false;
+  if (c->act != STAGE_ACT_GELU && c->act != STAGE_ACT_SWIGLU) return false;
+  if (c->dtype != STAGE_DTYPE_FP32 && c->dtype != STAGE_DTYPE_BF16) return false;
+  if (c->causal != 0 && c->causal != 1) return false;
+  if (c->stash_cap < 0 || c->stash_cap > c->n_microbatches) return false;
+  if (!(c->norm_eps >= 0.f)) return false;
+  const size_t es = c->dtype == STAGE_DTYPE_FP32 ? 4 : 2;
+  if (c->hidden > 256 * 4 * (int)(16 / es)) return false;  // one norm row must fit a workgroup's registers
+  if ((int64_t)c->seq * c->mb_size > (1 << 20) || c->seq > 65536) return false;
+  o->L = c->n_layers; o->d = c->hidden; o->h = c->n_heads; o->hkv = c->n_kv_heads; o->hd = hd;
+  o->dkv = c->n_kv_heads * hd; o->dq = o->d + 2 * o->dkv; o->f = c->ffn;
+  o->fin = c->act == STAGE_ACT_SWIGLU ? 2 * c->ffn : c->ffn;
+  o->s = c->seq; o->b = c->mb_size; o->T = c->seq * c->mb_size; o->n_mb = c->n_microbatches;
+  o->cap = c->stash_cap ? c->stash_cap : c->n_microbatches;
+  o->es = es;
+  return true;
+}
+
+// --- parameter layout (elements) -------------------------------------------
+void param_dims(const Dims& D, int norm, int pid, int64_t* rows, int64_t* cols) {
+  switch (pid) {
+    case STAGE_P_NORM1_GAMMA: case STAGE_P_NORM2_GAMMA: *rows = 1; *cols = D.d; break;
+    case STAGE_P_NORM1_BETA: case STAGE_P_NORM2_BETA:
+      if (norm == STAGE_NORM_LAYERNORM) { *rows = 1; *cols = D.d; } else { *rows = 0; *cols = 0; }
+      break;
+    case STAGE_P_WQKV: *rows = D.d; *cols = D.dq; break;
+    case STAGE_P_WO: *rows = D.d; *cols = D.d; break;
+    case STAGE_P_WIN: *rows = D.d; *cols = D.fin; break;
+    case STAGE_P_WOUT: *rows = D.f; *cols = D.d; break;
+    default: *rows = 0; *cols = 0;
+  }
+}
+
+size_t layer_param_elems(const Dims& D, int norm) {
+  size_t n = 0;
+  for (int p = 0; p < STAGE_P_COUNT; ++p) { int64_t r, c; param_dims(D, norm, p, &r, &c); n += (size_t)(r * c); }
+  return n;
+}
+
+size_t param_offset(const Dims& D, int norm, int layer, int pid) {
+  size_t off = (size_t)layer * layer_param_elems(D, norm);
+  for (int p = 0; p < pid; ++p) { int64_t r, c; param_dims(D, norm, p, &r, &c); off += (size_t)(r * c); }
+  return off;
+}
+
+// --- stash slot layout (bytes) ----------------------------------------------
+struct LayerOff { size_t x, n1, qkv, dqkv, o, x1, n2, z, a, st1, st2, lse, end; };
+
+LayerOff layer_off(const Dims& D, size_t base) {
+  LayerOff o; size_t p = base;
+  const size_t T = D.T;
+  auto take = [&](size_t bytes) { size_t r = p; p += up(bytes); return r; };
+  o.x = take(T * D.d * D.es);
+  o.n1 = take(T * D.d * D.es);
+  o.qkv = take(T * D.dq * D.es);
+  o.dqkv = take(T * D.dq * D.es);
+  o.o = take(T * D.d * D.es);
+  o.x1 = take(T * D.d * D.es);
+  o.n2 = take(T * D.d * D.es);
+  o.z = take(T * D.fin * D.es);
+  o.a = take(T * D.f * D.es);
+  o.st1 = take(T * 2 * sizeof(float));
+  o.st2 = take(T * 2 * sizeof(float));
+  o.lse = take((size_t)D.b * D.h * D.s * sizeof(float));
+  o.end = p;
+  return o;
+}
+
+size_t slot_bytes(const Dims& D) {
+  const size_t per_layer = layer_off(D, 0).end;
+  return per_layer * D.L + up((size_t)D.T * D.d * D.es);  // + gradient arriving at the stage output
+}
+
+struct WsOff { size_t da, dn, delta, partial, end; };
+WsOff ws_off(const Dims& D) {
+  WsOff w; size_t p = 0;
+  auto take = [&](size_t bytes) { size_t r = p; p += up(bytes); return r; };
+  w.da = take((size_t)D.T * D.f * D.es);
+  w.dn = take((size_t)D.T * D.d * D.es);
+  w.delta = take((size_t)D.b * D.h * D.s * sizeof(float));
+  w.partial = take((size_t)norm_partial_rows() * 2 * D.d * sizeof(float));
+  w.end = p;
+  return w;
+}
+
+// --- microbatch state machine ------------------------------------------------
+enum MbState : int8_t { MB_EMPTY = 0, MB_FWD = 1, MB_BWD = 2 };
+
+struct Tracker {
+  std::vector<int8_t> state;
+  int live = 0, peak = 0;
+  int last[3] = {-1, -1, -1};
+  int cap = 0, enforce = 0;
+
+  // Returns STAGE_OK and applies the op, or an error and leaves state unchanged.
+  int step(int kind, int mb) {
+    if (kind < STAGE_F || kind > STAGE_W || mb < 0 || mb >= (int)state.size()) return STAGE_E_INVAL;
+    if ((int)state[mb] != kind) return STAGE_E_ORDER;   // F needs EMPTY(0), B needs FWD(1), W needs BWD(2)
+    if (enforce && mb <= last[kind]) return STAGE_E_ORDER;
+    if (kind == STAGE_F && live >= cap) return STAGE_E_STASH_FULL;
+    state[mb] = (int8_t)((kind + 1) % 3);
+    last[kind] = mb;
+    if (kind == STAGE_F) { ++live; if (live > peak) peak = live; }
+    if (kind == STAGE_W) { --live; if (live == 0) last[0] = last[1] = last[2] = -1; }  // iteration boundary
+    return STAGE_OK;
+  }
+};
+
+}  // namespace
+
+struct stage {
+  stage_config_t cfg;
+  Dims D;
+  DType dt;
+  char* weights; float* grads; char* stash; char* ws;
+  hipStream_t stream;
+  size_t slot_sz, n_param_elems;
+  Tracker tr;
+  std::vector<int> slot_of;      // microbatch -> slot index, -1 if none
+  std::vector<int> free_slots;
+  int sticky = STAGE_OK;
+  int kernel_set = 0;
+};
+
+namespace {
+
+struct LayerW { const char *g1, *b1, *wqkv, *wo, *g2, *b2, *win, *wout; float *G[STAGE_P_COUNT]; };
+
+LayerW layer_weights(const stage* st, int l) {
+  LayerW w;
+  const char** slots[STAGE_P_COUNT] = {&w.g1, &w.b1, &w.wqkv, &w.wo, &w.g2, &w.b2, &w.win, &w.wout};
+  for (int p = 0; p < STAGE_P_COUNT; ++p) {
+    int64_t r, c; param_dims(st->D, st->cfg.norm, p, &r, &c);
+    const size_t off = param_offset(st->D, st->cfg.norm, l, p);
+    *slots[p] = (r * c) ? st->weights + off * st->D.es : nullptr;
+    w.G[p] = (r * c) ? st->grads + off : nullptr;
+  }
+  return w;
+}
+
+#define HIPCHK(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) { st->sticky = STAGE_E_HIP; return STAGE_E_HIP; } } while (0)
+
+int do_gemm(stage* st, int mode, int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
+            void* C, int64_t ldc, const void* R, int64_t ldr, int acc) {
+  GemmArgs g{mode, M, N, K, A, lda, B, ldb, C, ldc, R, ldr, acc};
+  if (st->kernel_set == 0 && st->dt == DT_BF16 && gemm_mfma_supported(g)) HIPCHK(gemm_mfma(g, st->stream));
+  else HIPCHK(gemm_ref(st->dt, g, st->stream));
+  return STAGE_OK;
+}
+
+AttnArgs attn_args(const stage* st, const LayerOff& o, char* slot, const void* dout, const WsOff& w) {
+  const Dims& D = st->D;
+  AttnArgs a{};
+  a.b = D.b; a.s = D.s; a.h = D.h; a.hkv = D.hkv; a.hd = D.hd; a.causal = st->cfg.causal;
+  a.qkv = slot + o.qkv; a.ld = D.dq; a.o = slot + o.o; a.lse = (float*)(slot + o.lse);
+  a.dout = dout; a.dqkv = slot + o.dqkv; a.delta = (float*)(st->ws + w.delta);
+  return a;
+}
+
+int exec_forward(stage* st, int slot_idx, const void* x, void* y) {
+  const Dims& D = st->D;
+  char* slot = st->stash + (size_t)slot_idx * st->slot_sz;
+  const size_t per_layer = layer_off(D, 0).end;
+  const WsOff w = ws_off(D);
+  const size_t act_bytes = (size_t)D.T * D.d * D.es;
+  HIPCHK(copy_bytes(slot + layer_off(D, 0).x, x, act_bytes, st->stream));
+  for (int l = 0; l < D.L; ++l) {
+    const LayerOff o = layer_off(D, per_layer * l);
+    const LayerW W = layer_weights(st, l);
+    void* y_l = (l + 1 < D.L) ? (void*)(slot + layer_off(D, per_layer * (l + 1)).x) : y;
+    NormArgs n{}; n.kind = st->cfg.norm; n.rows = D.T; n.d = D.d; n.eps = st->cfg.norm_eps;
+    n.x = slot + o.x; n.gamma = W.g1; n.beta = W.b1; n.out = slot + o.n1; n.stats = (float*)(slot + o.st1);
+    HIPCHK(norm_fwd(st->dt, n, st->stream));
+    int rc = do_gemm(st, GEMM_NN, D.T, D.dq, D.d, slot + o.n1, D.d, W.wqkv, D.dq, slot + o.qkv, D.dq, nullptr, 0, 0);
+    if (rc) return rc;
+    AttnArgs a = attn_args(st, o, slot, nullptr, w);
+    if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_fwd_mfma(a, st->stream));
+    else HIPCHK(attn_fwd_ref(st->dt, a, st->stream));
+    rc = do_gemm(st, GEMM_NN, D.T, D.d, D.d, slot + o.o, D.d, W.wo, D.d, slot + o.x1, D.d, slot + o.x, D.d, 0);
+    if (rc) return rc;
+    n.x = slot + o.x1; n.gamma = W.g2; n.beta = W.b2; n.out = slot + o.n2; n.stats = (float*)(slot + o.st2);
+    HIPCHK(norm_fwd(st->dt, n, st->stream));
+    rc = do_gemm(st, GEMM_NN, D.T, D.fin, D.d, slot + o.n2, D.d, W.win, D.fin, slot + o.z, D.fin, nullptr, 0, 0);
+    if (rc) return rc;
+    ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = slot + o.z; ac.a = slot + o.a;
+    HIPCHK(act_fwd(st->dt, ac, st->stream));
+    rc = do_gemm(st, GEMM_NN, D.T, D.d, D.f, slot + o.a, D.f, W.wout, D.d, y_l, D.d, slot + o.x1, D.d, 0);
+    if (rc) return rc;
+  }
+  return STAGE_OK;
+}
+
+int exec_backward_input(stage* st, int slot_idx, const void* dy, void* dx) {
+  const Dims& D = st->D;
+  char* slot = st->stash + (size_t)slot_idx * st->slot_sz;
+  const size_t per_layer = layer_off(D, 0).end;
+  const WsOff w = ws_off(D);
+  const size_t act_bytes = (size_t)D.T * D.d * D.es;
+  char* dy_top = slot + per_layer * D.L;
+  HIPCHK(copy_bytes(dy_top, dy, act_bytes, st->stream));
+  void* da = st->ws + w.da;
+  void* dn = st->ws + w.dn;
+  for (int l = D.L - 1; l >= 0; --l) {
+    const LayerOff o = layer_off(D, per_layer * l);
+    const LayerW W = layer_weights(st, l);
+    const void* dy_l = (l + 1 < D.L) ? (const void*)(slot + layer_off(D, per_layer * (l + 1)).x) : (const void*)dy_top;
+    // FFN: da = dy.Wout^T ; dz = act'(z) * da (in place over z) ; dn2 = dz.Win^T
+    int rc = do_gemm(st, GEMM_NT, D.T, D.f, D.d, dy_l, D.d, W.wout, D.d, da, D.f, nullptr, 0, 0);
+    if (rc) return rc;
+    ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = slot + o.z; ac.da = da;
+    HIPCHK(act_bwd(st->dt, ac, st->stream));
+    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.fin, slot + o.z, D.fin, W.win, D.fin, dn, D.d, nullptr, 0, 0);
+    if (rc) return rc;
+    // dx1 = dy + norm2'(dn2), in place over x1
+    NormArgs n{}; n.kind = st->cfg.norm; n.rows = D.T; n.d = D.d; n.eps = st->cfg.norm_eps;
+    n.x = slot + o.x1; n.gamma = W.g2; n.out = slot + o.x1; n.stats = (float*)(slot + o.st2);
+    n.dout = dn; n.resid = dy_l; n.dgamma = W.G[STAGE_P_NORM2_GAMMA]; n.dbeta = W.G[STAGE_P_NORM2_BETA];
+    n.partial = (float*)(st->ws + w.partial);
+    HIPCHK(norm_bwd(st->dt, n, st->stream));
+    // attention: do = dx1.Wo^T ; (dq,dk,dv) ; dn1 = dqkv.Wqkv^T
+    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.d, slot + o.x1, D.d, W.wo, D.d, dn, D.d, nullptr, 0, 0);
+    if (rc) return rc;
+    AttnArgs a = attn_args(st, o, slot, dn, w);
+    if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_bwd_mfma(a, st->stream));
+    else HIPCHK(attn_bwd_ref(st->dt, a, st->stream));
+    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.dq, slot + o.dqkv, D.dq, W.wqkv, D.dq, dn, D.d, nullptr, 0, 0);
+    if (rc) return rc;
+    // dx = dx1 + norm1'(dn1): in place over x (the layer below reads it as its dy), or to the caller for layer 0
+    n.x = slot + o.x; n.gamma = W.g1; n.out = (l == 0) ? dx : (void*)(slot + o.x); n.stats = (float*)(slot + o.st1);
+    n.dout = dn; n.resid = slot + o.x1; n.dgamma = W.G[STAGE_P_NORM1_GAMMA]; n.dbeta = W.G[STAGE_P_NORM1_BETA];
+    HIPCHK(norm_bwd(st->dt, n, st->stream));
+  }
+  return STAGE_OK;
+}
+
+int exec_backward_weight(stage* st, int slot_idx) {
+  const Dims& D = st->D;
+  char* slot = st->stash + (size_t)slot_idx * st->slot_sz;
+  const size_t per_layer = layer_off(D, 0).end;
+  for (int l = 0; l < D.L; ++l) {
+    const LayerOff o = layer_off(D, per_layer * l);
+    const LayerW W = layer_weights(st, l);
+    const void* dy_l = slot + ((l + 1 < D.L) ? layer_off(D, per_layer * (l + 1)).x : per_layer * D.L);
+    int rc;
+    if ((rc = do_gemm(st, GEMM_TN, D.d, D.dq, D.T, slot + o.n1, D.d, slot + o.dqkv, D.dq, W.G[STAGE_P_WQKV], D.dq, nullptr, 0, 1))) return rc;
+    if ((rc = do_gemm(st, GEMM_TN, D.d, D.d, D.T, slot + o.o, D.d, slot + o.x1, D.d, W.G[STAGE_P_WO], D.d, nullptr, 0, 1))) return rc;
+    if ((rc = do_gemm(st, GEMM_TN, D.d, D.fin, D.T, slot + o.n2, D.d, slot + o.z, D.fin, W.G[STAGE_P_WIN], D.fin, nullptr, 0, 1))) return rc;
+    if ((rc = do_gemm(st, GEMM_TN, D.f, D.d, D.T, slot + o.a, D.f, dy_l, D.d, W.G[STAGE_P_WOUT], D.d, nullptr, 0, 1))) return rc;
+  }
+  return STAGE_OK;
+}
+
+// Applies one already-validated op: allocator bookkeeping + launches.
+int apply_op(stage* st, int kind, int mb, const void* in, void* out) {
+  int rc = STAGE_OK;
+  if (kind == STAGE_F) {
+    const int slot = st->free_slots.back();
+    st->free_slots.pop_back();
+    st->slot_of[mb] = slot;
+    rc = exec_forward(st, slot, in, out);
+  } else if (kind == STAGE_B) {
+    rc = exec_backward_input(st, st->slot_of[mb], in, out);
+  } else {
+    rc = exec_backward_weight(st, st->slot_of[mb]);
+    st->free_slots.push_back(st->slot_of[mb]);
+    st->slot_of[mb] = -1;
+  }
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int stage_query_sizes(const stage_config_t* cfg, stage_sizes_t* out) {
+  Dims D;
+  if (!out || !make_dims(cfg, &D)) return STAGE_E_INVAL;
+  const size_t n = layer_param_elems(D, cfg->norm) * D.L;
+  out->weights = up(n * D.es);
+  out->grads = up(n * sizeof(float));
+  out->stash = slot_bytes(D) * D.cap;
+  out->workspace = ws_off(D).end;
+  return STAGE_OK;
+}
+
+int stage_validate_schedule(const stage_config_t* cfg, const stage_op_t* ops, int n_ops, int* first_bad_index,
+                            int* peak_live) {
+  Dims D;
+  if (first_bad_index) *first_bad_index = -1;
+  if (peak_live) *peak_live = 0;
+  if (!make_dims(cfg, &D) || n_ops < 0 || (n_ops > 0 && !ops)) return STAGE_E_INVAL;
+  Tracker t; t.state.assign(D.n_mb, MB_EMPTY); t.cap = D.cap; t.enforce = cfg->enforce_mb_order;
+  for (int i = 0; i < n_ops; ++i) {
+    const int rc = t.step(ops[i].kind, ops[i].mb);
+    if (rc != STAGE_OK) {
+      if (first_bad_index) *first_bad_index = i;
+      if (peak_live) *peak_live = t.peak;
+      return rc;
+    }
+  }
+  if (peak_live) *peak_live = t.peak;
+  return STAGE_OK;
+}
+
+int stage_param_layout(const stage_config_t* cfg, int layer, int param_id, size_t* offset_elems, int64_t* rows,
+                       int64_t* cols) {
+  Dims D;
+  if (!make_dims(cfg, &D) || layer < 0 || layer >= D.L || param_id < 0 || param_id >= STAGE_P_COUNT || !offset_elems ||
+      !rows || !cols)
+    return STAGE_E_INVAL;
+  param_dims(D, cfg->norm, param_id, rows, cols);
+  *offset_elems = param_offset(D, cfg->norm, layer, param_id);
+  return STAGE_OK;
+}
+
+int stage_init(const stage_config_t* cfg, void* weights_dev, void* grads_dev, void* stash_dev, void* workspace_dev,
+               void* hip_stream, stage_t** out) {
+  Dims D;
+  if (!out) return STAGE_E_INVAL;
+  *out = nullptr;
+  if (!make_dims(cfg, &D) || !weights_dev || !grads_dev || !stash_dev || !workspace_dev) return STAGE_E_INVAL;
+  if (((uintptr_t)weights_dev | (uintptr_t)grads_dev | (uintptr_t)stash_dev | (uintptr_t)workspace_dev) % ALIGN)
+    return STAGE_E_INVAL;
+  stage* st = new (std::nothrow) stage();
+  if (!st) return STAGE_E_INVAL;
+  st->cfg = *cfg; st->D = D; st->dt = cfg->dtype == STAGE_DTYPE_FP32 ? DT_F32 : DT_BF16;
+  st->weights = (char*)weights_dev; st->grads = (float*)grads_dev; st->stash = (char*)stash_dev; st->ws = (char*)workspace_dev;
+  st->stream = (hipStream_t)hip_stream;
+  st->slot_sz = slot_bytes(D);
+  st->n_param_elems = layer_param_elems(D, cfg->norm) * D.L;
+  st->tr.state.assign(D.n_mb, MB_EMPTY); st->tr.cap = D.cap; st->tr.enforce = cfg->enforce_mb_order;
+  st->slot_of.assign(D.n_mb, -1);
+  for (int i = D.cap - 1; i >= 0; --i) st->free_slots.push_back(i);
+  if (fill_zero_f32(st->grads, st->n_param_elems, st->stream) != hipSuccess) { delete st; return STAGE_E_HIP; }
+  *out = st;
+  return STAGE_OK;
+}
+
+static int single_op(stage_t* st, int kind, int mb, const void* in, void* out) {
+  if (!st) return STAGE_E_INVAL;
+  if (st->sticky) return st->sticky;
+  if (kind != STAGE_W && (!in || !out)) return STAGE_E_INVAL;
+  const int rc = st->tr.step(kind, mb);
+  if (rc != STAGE_OK) return rc;
+  return apply_op(st, kind, mb, in, out);
+}
+
+int stage_forward(stage_t* st, int mb, const void* x_dev, void* y_dev) { return single_op(st, STAGE_F, mb, x_dev, y_dev); }
+int stage_backward_input(stage_t* st, int mb, const void* dy_dev, void* dx_dev) { return single_op(st, STAGE_B, mb, dy_dev, dx_dev); }
+int stage_backward_weight(stage_t* st, int mb) { return single_op(st, STAGE_W, mb, nullptr, nullptr); }
+
+int stage_run_schedule(stage_t* st, const stage_op_t* ops, int n_ops, const void* x_all_dev, const void* dy_all_dev,
+                       void* y_all_dev, void* dx_all_dev) {
+  if (!st || n_ops < 0 || (n_ops > 0 && !ops)) return STAGE_E_INVAL;
+  if (st->sticky) return st->sticky;
+  // validate the whole list on a copy of the tracker before enqueuing anything
+  Tracker probe = st->tr;
+  for (int i = 0; i < n_ops; ++i) {
+    if (ops[i].kind == STAGE_F && (!x_all_dev || !y_all_dev)) return STAGE_E_INVAL;
+    if (ops[i].kind == STAGE_B && (!dy_all_dev || !dx_all_dev)) return STAGE_E_INVAL;
+    const int rc = probe.step(ops[i].kind, ops[i].mb);
+    if (rc != STAGE_OK) return rc;
+  }
+  const size_t mb_bytes = (size_t)st->D.T * st->D.d * st->D.es;
+  for (int i = 0; i < n_ops; ++i) {
+    const int kind = ops[i].kind, mb = ops[i].mb;
+    st->tr.step(kind, mb);
+    const void* in = kind == STAGE_F ? (const char*)x_all_dev + mb_bytes * mb
+                   : kind == STAGE_B ? (const char*)dy_all_dev + mb_bytes * mb : nullptr;
+    void* out = kind == STAGE_F ? (char*)y_all_dev + mb_bytes * mb : kind == STAGE_B ? (char*)dx_all_dev + mb_bytes * mb : nullptr;
+    const int rc = apply_op(st, kind, mb, in, out);
+    if (rc != STAGE_OK) return rc;
+  }
+  return STAGE_OK;
+}
+
+int stage_grads(stage_t* st, float** grads_dev, size_t* n_elems) {
+  if (!st || !grads_dev || !n_elems) return STAGE_E_INVAL;
+  *grads_dev = st->grads; *n_elems = st->n_param_elems;
+  return STAGE_OK;
+}
+
+int stage_zero_grads(stage_t* st) {
+  if (!st) return STAGE_E_INVAL;
+  if (st->sticky) return st->sticky;
+  HIPCHK(fill_zero_f32(st->grads, st->n_param_elems, st->stream));
+  return STAGE_OK;
+}
+
+int stage_stats(stage_t* st, int* live, int* peak_live, size_t* peak_stash_bytes) {
+  if (!st) return STAGE_E_INVAL;
+  if (live) *live = st->tr.live;
+  if (peak_live) *peak_live = st->tr.peak;
+  if (peak_stash_bytes) *peak_stash_bytes = (size_t)st->tr.peak * st->slot_sz;
+  return STAGE_OK;
+}
+
+int stage_set_kernel_set(stage_t* st, int which) {
+  if (!st || (which != 0 && which != 1)) return STAGE_E_INVAL;
+  st->kernel_set = which;
+  return STAGE_OK;
+}
+
+void stage_destroy(stage_t* st) { delete st; }
+
+const char* stage_strerror(int code) {
+  switch (code) {
+    case STAGE_OK: return "ok";
+    case STAGE_E_INVAL: return "invalid argument (null pointer, bad shape, unsupported head_dim, or microbatch out of range)";
+    case STAGE_E_ORDER: return "op order violates the microbatch state machine EMPTY-F->FWD-B->BWD-W->EMPTY or the microbatch-order rule";
+    case STAGE_E_STASH_FULL: return "forward refused: stash_cap microbatches are already live";
+    case STAGE_E_HIP: return "a HIP launch or runtime call failed";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------
+// kernel-level entry points (include/stage_kernels.h)
+// ---------------------------------------------------------------------------
+#include "../../include/stage_kernels.h"
+
+extern "C" {
+
+static int hip_rc(hipError_t e) { return e == hipSuccess ? STAGE_OK : (e == hipErrorInvalidValue ? STAGE_E_INVAL : STAGE_E_HIP); }
+static bool dtype_ok(int dt) { return dt == STAGE_DTYPE_FP32 || dt == STAGE_DTYPE_BF16; }
+
+int stage_kernel_gemm(int dtype, int mode, int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
+                      void* C, int64_t ldc, const void* R, int64_t ldr, int acc_f32, int kernel_set, void* hip_stream) {
+  if (!dtype_ok(dtype) || mode < 0 || mode > 2 || M < 0 || N < 0 || K < 0 || !A || !B || !C) return STAGE_E_INVAL;
+  if ((mode == GEMM_TN) != (acc_f32 != 0) || (acc_f32 && R)) return STAGE_E_INVAL;
+  GemmArgs g{mode, M, N, K, A, lda, B, ldb, C, ldc, R, ldr, acc_f32};
+  if (kernel_set == 0 && dtype == STAGE_DTYPE_BF16 && gemm_mfma_supported(g)) return hip_rc(gemm_mfma(g, (hipStream_t)hip_stream));
+  return hip_rc(gemm_ref((DType)dtype, g, (hipStream_t)hip_stream));
+}
+
+static bool attn_shape(int dtype, int b, int s, int h, int hkv, int hd, int causal) {
+  return dtype_ok(dtype) && b > 0 && s > 0 && s <= 65536 && h > 0 && hkv > 0 && h % hkv == 0 && (hd == 64 || hd == 128) &&
+         (causal == 0 || causal == 1);
+}
+
+int stage_kernel_attention_fwd(int dtype, int b, int s, int h, int hkv, int hd, int causal, const void* qkv, void* o,
+                               float* lse, int kernel_set, void* hip_stream) {
+  if (!attn_shape(dtype, b, s, h, hkv, hd, causal) || !qkv || !o || !lse) return STAGE_E_INVAL;
+  AttnArgs a{}; a.b = b; a.s = s; a.h = h; a.hkv = hkv; a.hd = hd; a.causal = causal;
+  a.qkv = qkv; a.ld = (int64_t)(h + 2 * hkv) * hd; a.o = o; a.lse = lse;
+  if (kernel_set == 0 && dtype == STAGE_DTYPE_BF16 && attn_mfma_supported(a)) return hip_rc(attn_fwd_mfma(a, (hipStream_t)hip_stream));
+  return hip_rc(attn_fwd_ref((DType)dtype, a, (hipStream_t)hip_stream));
+}
+
+int stage_kernel_attention_bwd(int dtype, int b, int s, int h, int hkv, int hd, int causal, const void* qkv,
+                               const void* o, const float* lse, const void* dout, void* dqkv, float* delta,
+                               int kernel_set, void* hip_stream) {
+  if (!attn_shape(dtype, b, s, h, hkv, hd, causal) || !qkv || !o || !lse || !dout || !dqkv || !delta) return STAGE_E_INVAL;
+  AttnArgs a{}; a.b = b; a.s = s; a.h = h; a.hkv = hkv; a.hd = hd; a.causal = causal;
+  a.qkv = qkv; a.ld = (int64_t)(h + 2 * hkv) * hd; a.o = (void*)o; a.lse = (float*)lse;
+  a.dout = dout; a.dqkv = dqkv; a.delta = delta;
+  if (kernel_set == 0 && dtype == STAGE_DTYPE_BF16 && attn_mfma_supported(a)) return hip_rc(attn_bwd_mfma(a, (hipStream_t)hip_stream));
+  return hip_rc(attn_bwd_ref((DType)dtype, a, (hipStream_t)hip_stream));
+}
+
+int stage_kernel_norm_fwd(int dtype, int norm, int rows, int d, float eps, const void* x, const void* gamma,
+                          const void* beta, void* out, float* stats, void* hip_stream) {
+  if (!dtype_ok(dtype) || (norm != 0 && norm != 1) || rows <= 0 || d <= 0 || !x || !gamma || (norm == 0 && !beta) || !out || !stats)
+    return STAGE_E_INVAL;
+  NormArgs n{}; n.kind = norm; n.rows = rows; n.d = d; n.eps = eps; n.x = x; n.gamma = gamma; n.beta = beta; n.out = out; n.stats = stats;
+  return hip_rc(norm_fwd((DType)dtype, n, (hipStream_t)hip_stream));
+}
+
+int stage_kernel_norm_bwd(int dtype, int norm, int rows, int d, const void* x, const float* stats, const void* gamma,
+                          const void* dout, const void* resid, void* dx, float* dgamma, float* dbeta, float* partial,
+                          void* hip_stream) {
+  if (!dtype_ok(dtype) || (norm != 0 && norm != 1) || rows <= 0 || d <= 0 || !x || !stats || !gamma || !dout || !dx || !dgamma ||
+      (norm == 0 && !dbeta) || !partial)
+    return STAGE_E_INVAL;
+  NormArgs n{}; n.kind = norm; n.rows = rows; n.d = d; n.x = x; n.stats = (float*)stats; n.gamma = gamma; n.dout = dout;
+  n.resid = resid; n.out = dx; n.dgamma = dgamma; n.dbeta = dbeta; n.partial = partial;
+  return hip_rc(norm_bwd((DType)dtype, n, (hipStream_t)hip_stream));
+}
+
+size_t stage_kernel_norm_partial_bytes(int d) { return d > 0 ? (size_t)norm_partial_rows() * 2 * d * sizeof(float) : 0; }
+
+int stage_kernel_act_fwd(int dtype, int act, int rows, int f, const void* z, void* a, void* hip_stream) {
+  if (!dtype_ok(dtype) || (act != 0 && act != 1) || rows <= 0 || f <= 0 || !z || !a) return STAGE_E_INVAL;
+  ActArgs ac{}; ac.kind = act; ac.rows = rows; ac.f = f; ac.z = (void*)z; ac.a = a;
+  return hip_rc(act_fwd((DType)dtype, ac, (hipStream_t)hip_stream));
+}
+
+int stage_kernel_act_bwd(int dtype, int act, int rows, int f, void* z, const void* da, void* hip_stream) {
+  if (!dtype_ok(dtype) || (act != 0 && act != 1) || rows <= 0 || f <= 0 || !z || !da) return STAGE_E_INVAL;
+  ActArgs ac{}; ac.kind = act; ac.rows = rows; ac.f = f; ac.z = z; ac.da = da;
+  return hip_rc(act_bwd((DType)dtype, ac, (hipStream_t)hip_stream));
+}
+
+}  // extern "C"

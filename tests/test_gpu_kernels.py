@@ -1,0 +1,175 @@
+"""Each step of the path, called alone through the C ABI, against the oracle's
+building block for that step."""
+import ctypes as C
+import math
+
+import numpy as np
+import pytest
+
+from oracle import stage_oracle as so
+from paper_2507_00217_amd import synth
+from tests.gpu_util import rnd, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+DT = {"fp32": 0, "bf16": 1}
+KTOL = {"fp32": 2e-5, "bf16": 1e-2}
+
+
+def L():
+    from paper_2507_00217_amd import stage as S
+    lib = S.lib()
+    if not hasattr(lib, "_ksig"):
+        vp, i, i64, fl = C.c_void_p, C.c_int, C.c_int64, C.c_float
+        lib.stage_kernel_gemm.argtypes = [i, i, i, i, i, vp, i64, vp, i64, vp, i64, vp, i64, i, i, vp]
+        lib.stage_kernel_attention_fwd.argtypes = [i] * 7 + [vp, vp, vp, i, vp]
+        lib.stage_kernel_attention_bwd.argtypes = [i] * 7 + [vp] * 6 + [i, vp]
+        lib.stage_kernel_norm_fwd.argtypes = [i, i, i, i, fl, vp, vp, vp, vp, vp, vp]
+        lib.stage_kernel_norm_bwd.argtypes = [i, i, i, i] + [vp] * 10
+        lib.stage_kernel_norm_partial_bytes.restype = C.c_size_t
+        lib.stage_kernel_act_fwd.argtypes = [i, i, i, i, vp, vp, vp]
+        lib.stage_kernel_act_bwd.argtypes = [i, i, i, i, vp, vp, vp]
+        lib._ksig = True
+    return lib
+
+
+def P(t):
+    return None if t is None else t.data_ptr()
+
+
+GEMM_SHAPES = [(128, 256, 768), (200, 192, 136), (328, 1088, 512), (512, 512, 2048), (257, 320, 72), (1024, 768, 264)]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("kernel_set", [0, 1])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm(dtype, mode, kernel_set, M, N, K):
+    import torch
+    a_shape = (K, M) if mode == 2 else (M, K)
+    b_shape = (N, K) if mode == 1 else (K, N)
+    A = rnd(synth.normal(1, 1, a_shape), dtype); Bm = rnd(synth.normal(1, 2, b_shape), dtype)
+    R = rnd(synth.normal(1, 3, (M, N)), dtype)
+    C0 = synth.normal(1, 4, (M, N))
+    Ad, Bd, Rd = to_dev(A, dtype), to_dev(Bm, dtype), to_dev(R, dtype)
+    A64, B64 = A.astype(np.float64), Bm.astype(np.float64)
+    prod = (A64.T if mode == 2 else A64) @ (B64.T if mode == 1 else B64)
+    if mode == 2:
+        Cd = to_dev(C0, "fp32")
+        ref = C0.astype(np.float64) + prod
+        rc = L().stage_kernel_gemm(DT[dtype], mode, M, N, K, P(Ad), M, P(Bd), N, P(Cd), N, None, 0, 1, kernel_set, None)
+    else:
+        use_r = mode == 0
+        Cd = torch.zeros((M, N), dtype=Ad.dtype, device="cuda:0")
+        ref = prod + (R if use_r else 0)
+        rc = L().stage_kernel_gemm(DT[dtype], mode, M, N, K, P(Ad), K, P(Bd), K if mode == 1 else N, P(Cd), N,
+                                   P(Rd) if use_r else None, N, 0, kernel_set, None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert so.max_rel_err(to_np(Cd), ref) <= (KTOL[dtype] if mode != 2 else 2e-5 if dtype == "fp32" else 1e-5 * math.sqrt(K))
+
+
+def test_gemm_rejects_bad_arguments():
+    import torch
+    t = torch.zeros(64, 64, device="cuda:0")
+    assert L().stage_kernel_gemm(0, 2, 64, 64, 64, P(t), 64, P(t), 64, P(t), 64, None, 0, 0, 0, None) == -1   # wgrad needs acc
+    assert L().stage_kernel_gemm(0, 0, 64, 64, 64, None, 64, P(t), 64, P(t), 64, None, 0, 0, 0, None) == -1
+    assert L().stage_kernel_gemm(7, 0, 64, 64, 64, P(t), 64, P(t), 64, P(t), 64, None, 0, 0, 0, None) == -1
+
+
+ATT_SHAPES = [(1, 128, 4, 4, 64), (2, 200, 5, 5, 128), (1, 392, 8, 1, 128), (1, 448, 4, 2, 128), (1, 1, 2, 1, 64), (1, 640, 2, 2, 64)]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("kernel_set", [0, 1])
+@pytest.mark.parametrize("causal", [1, 0])
+@pytest.mark.parametrize("b,s,h,hkv,hd", ATT_SHAPES)
+def test_attention(dtype, kernel_set, causal, b, s, h, hkv, hd):
+    import torch
+    d, dkv = h * hd, hkv * hd
+    qkv = rnd(synth.normal(2, 1, (b, s, d + 2 * dkv)), dtype)
+    do = rnd(synth.normal(2, 2, (b, s, d)), dtype)
+    sh = so.Shape(1, d, h, hkv, 64, s, b, causal=bool(causal))
+    q = qkv[..., :d].astype(np.float64).reshape(b, s, h, hd)
+    k = qkv[..., d:d + dkv].astype(np.float64).reshape(b, s, hkv, hd)
+    v = qkv[..., d + dkv:].astype(np.float64).reshape(b, s, hkv, hd)
+    o_ref = so.attention_forward(sh, q, k, v)
+    qd = to_dev(qkv, dtype)
+    od = torch.zeros((b, s, d), dtype=qd.dtype, device="cuda:0")
+    lse = torch.zeros((b, h, s), dtype=torch.float32, device="cuda:0")
+    assert L().stage_kernel_attention_fwd(DT[dtype], b, s, h, hkv, hd, causal, P(qd), P(od), P(lse), kernel_set, None) == 0
+    torch.cuda.synchronize()
+    tol = KTOL[dtype] if dtype == "bf16" else 5e-5
+    assert so.max_rel_err(to_np(od), o_ref.reshape(b, s, d)) <= tol
+    # log-sum-exp of the scaled masked scores, from its definition
+    j = h - 1
+    S = q[0, :, j] @ k[0, :, j // (h // hkv)].T / math.sqrt(hd)
+    if causal:
+        S = np.where(np.tril(np.ones((s, s), bool)), S, -np.inf)
+    lse_ref = np.log(np.exp(S - S.max(-1, keepdims=True)).sum(-1)) + S.max(-1)
+    assert np.abs(to_np(lse[0, j]) - lse_ref).max() <= (1e-4 if dtype == "fp32" else 2e-2)
+    # backward consumes the device's own o / lse, like the stage does
+    dod = to_dev(do, dtype)
+    dqkv = torch.zeros_like(qd)
+    delta = torch.zeros((b, h, s), dtype=torch.float32, device="cuda:0")
+    assert L().stage_kernel_attention_bwd(DT[dtype], b, s, h, hkv, hd, causal, P(qd), P(od), P(lse), P(dod), P(dqkv),
+                                          P(delta), kernel_set, None) == 0
+    torch.cuda.synchronize()
+    dq, dk, dv = so.attention_backward(sh, q, k, v, do.astype(np.float64).reshape(b, s, h, hd))
+    got = to_np(dqkv)
+    assert so.max_rel_err(got[..., :d], dq.reshape(b, s, d)) <= tol
+    assert so.max_rel_err(got[..., d:d + dkv], dk.reshape(b, s, dkv)) <= tol
+    assert so.max_rel_err(got[..., d + dkv:], dv.reshape(b, s, dkv)) <= tol
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("norm", ["layernorm", "rmsnorm"])
+@pytest.mark.parametrize("rows,d", [(128, 256), (333, 1024), (64, 4096), (1000, 640), (3, 8192)])
+def test_norm(dtype, norm, rows, d):
+    import torch
+    if dtype == "fp32" and d > 4096:
+        pytest.skip("fp32 rows above 4096 elements are outside the kernel's register budget (rejected at init)")
+    kind = {"layernorm": 0, "rmsnorm": 1}[norm]
+    x = rnd(synth.normal(3, 1, (rows, d), mean=0.3, std=2.0), dtype)
+    gamma = rnd(synth.normal(3, 2, (d,), mean=1.0, std=0.1), dtype); beta = rnd(synth.normal(3, 3, (d,), std=0.1), dtype)
+    dout = rnd(synth.normal(3, 4, (rows, d)), dtype); resid = rnd(synth.normal(3, 5, (rows, d)), dtype)
+    out_ref, stats = so.norm_forward(norm, x.astype(np.float64), gamma.astype(np.float64), beta.astype(np.float64), 1e-5)
+    dx_ref, dg_ref, db_ref = so.norm_backward(norm, stats, gamma.astype(np.float64), dout.astype(np.float64))
+    xd, gd, bd = to_dev(x, dtype), to_dev(gamma, dtype), to_dev(beta, dtype)
+    outd = torch.zeros_like(xd); st = torch.zeros((rows, 2), dtype=torch.float32, device="cuda:0")
+    assert L().stage_kernel_norm_fwd(DT[dtype], kind, rows, d, 1e-5, P(xd), P(gd), P(bd), P(outd), P(st), None) == 0
+    torch.cuda.synchronize()
+    assert so.max_rel_err(to_np(outd), out_ref) <= KTOL[dtype]
+    assert so.max_rel_err(to_np(st[:, 1]), stats[1][:, 0]) <= 1e-5
+    dg0 = synth.normal(3, 6, (d,)); db0 = synth.normal(3, 7, (d,))
+    dgd, dbd = to_dev(dg0, "fp32"), to_dev(db0, "fp32")
+    part = torch.zeros(L().stage_kernel_norm_partial_bytes(d) // 4, dtype=torch.float32, device="cuda:0")
+    dxd = xd.clone()     # in place over x, as the stage uses it
+    assert L().stage_kernel_norm_bwd(DT[dtype], kind, rows, d, P(dxd), P(st), P(gd), P(to_dev(dout, dtype)),
+                                     P(to_dev(resid, dtype)), P(dxd), P(dgd), P(dbd), P(part), None) == 0
+    torch.cuda.synchronize()
+    assert so.max_rel_err(to_np(dxd), dx_ref + resid) <= KTOL[dtype]
+    assert so.max_rel_err(to_np(dgd) - dg0, dg_ref) <= (1e-5 if dtype == "fp32" else 2e-3)
+    if norm == "layernorm":
+        assert so.max_rel_err(to_np(dbd) - db0, db_ref) <= 1e-5
+    else:
+        assert np.array_equal(to_np(dbd), db0.astype(np.float64))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+@pytest.mark.parametrize("rows,f", [(128, 1024), (77, 1408), (5, 64)])
+def test_activation(dtype, act, rows, f):
+    import torch
+    kind = {"gelu": 0, "swiglu": 1}[act]
+    fin = 2 * f if act == "swiglu" else f
+    z = rnd(synth.normal(4, 1, (rows, fin), std=2.0), dtype); da = rnd(synth.normal(4, 2, (rows, f)), dtype)
+    sh = so.Shape(1, 64, 1, 1, f, 1, 1, act=act)
+    z64 = z.astype(np.float64)
+    a_ref = so.gelu(z64) if act == "gelu" else z64[:, :f] * so.sigmoid(z64[:, :f]) * z64[:, f:]
+    dz_ref = so.act_backward(sh, z64, da.astype(np.float64))
+    zd = to_dev(z, dtype); ad = torch.zeros((rows, f), dtype=zd.dtype, device="cuda:0")
+    assert L().stage_kernel_act_fwd(DT[dtype], kind, rows, f, P(zd), P(ad), None) == 0
+    assert L().stage_kernel_act_bwd(DT[dtype], kind, rows, f, P(zd), P(to_dev(da, dtype)), None) == 0
+    torch.cuda.synchronize()
+    assert so.max_rel_err(to_np(ad), a_ref) <= KTOL[dtype]
+    assert so.max_rel_err(to_np(zd), dz_ref) <= KTOL[dtype]

@@ -1,0 +1,143 @@
+"""Parity of the HIP stage (through the C ABI) against the CPU oracle, element
+by element, on seeded inputs; plus the invariants the F/B/W split must keep."""
+import numpy as np
+import pytest
+
+from oracle import stage_oracle as so
+from paper_2507_00217_amd import synth
+from tests.gpu_util import SMALL, TOL, shape_of, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+F, B, W = 0, 1, 2
+
+
+def run_gpu(cfg, params, X, G, ops, kernel_set=0, pieces=1):
+    import torch
+    from paper_2507_00217_amd import stage as S
+    st = S.Stage(cfg)
+    st.set_kernel_set(kernel_set)
+    st.load_weights(params)
+    Xd, Gd = to_dev(X, cfg["dtype"]), to_dev(G, cfg["dtype"])
+    Y, dX = torch.zeros_like(Xd), torch.zeros_like(Xd)
+    step = (len(ops) + pieces - 1) // pieces
+    for i in range(0, len(ops), step):
+        st.run_schedule(ops[i:i + step], Xd, Gd, Y, dX)
+    torch.cuda.synchronize()
+    out = to_np(Y), to_np(dX), st.grads(), st.stats()
+    st.close()
+    return out
+
+
+def run_oracle(cfg, params, X, G, ops):
+    st = so.OracleStage(shape_of(cfg), params)
+    Y, dX, peak = st.run_schedule(ops, X.astype(np.float64), G.astype(np.float64))
+    return Y, dX, st.grads, peak
+
+
+def compare(cfg, got, ref, tol):
+    Yg, dXg, gg, stats = got
+    Yr, dXr, gr, peak = ref
+    errs = {"Y": so.max_rel_err(Yg, Yr), "dX": so.max_rel_err(dXg, dXr)}
+    for li, (lg, lr) in enumerate(zip(gg, gr)):
+        assert set(lg) == set(lr)
+        for k in lr:
+            errs[f"L{li}.{k}"] = so.max_rel_err(lg[k], lr[k])
+    worst = max(errs, key=errs.get)
+    print(f"worst {worst} = {errs[worst]:.3e} (tol {tol:g})", flush=True)
+    assert errs[worst] <= tol, errs
+    assert stats["peak_live"] == peak and stats["live"] == 0
+    return errs
+
+
+def inputs(cfg, base_seed):
+    return (synth.make_weights(cfg, base_seed), synth.make_boundary(cfg, base_seed + 1), synth.make_boundary(cfg, base_seed + 2))
+
+
+@pytest.mark.parametrize("kernel_set", [0, 1])
+def test_cfg1_full_fp32(kernel_set):
+    cfg = synth.CONFIGS["cfg1"]
+    params, X, G = inputs(cfg, 1000)
+    ops = synth.make_schedule(cfg)
+    compare(cfg, run_gpu(cfg, params, X, G, ops, kernel_set), run_oracle(cfg, params, X, G, ops), TOL["fp32"])
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("kernel_set", [0, 1])
+def test_small_variants_bf16(name, kernel_set):
+    cfg = SMALL[name]
+    params, X, G = inputs(cfg, 2000 + int(name[3]))
+    ops = synth.make_schedule(cfg)
+    compare(cfg, run_gpu(cfg, params, X, G, ops, kernel_set), run_oracle(cfg, params, X, G, ops), TOL["bf16"])
+
+
+@pytest.mark.parametrize("name", ["cfg3s", "cfg4s"])
+def test_small_variants_fp32_storage(name):
+    """Same shapes in fp32: isolates arithmetic from bf16 storage rounding."""
+    cfg = dict(SMALL[name], dtype="fp32")
+    params, X, G = inputs(cfg, 2100)
+    ops = synth.make_schedule(cfg)
+    compare(cfg, run_gpu(cfg, params, X, G, ops), run_oracle(cfg, params, X, G, ops), TOL["fp32"])
+
+
+def test_order_invariance_bitwise_and_pieces():
+    """Accumulated gradients do not depend on the schedule: bitwise when every
+    kind of op comes in microbatch order, to 1e-5 for a random legal order; an
+    iteration fed in pieces equals one call."""
+    cfg = dict(SMALL["cfg5s"], enforce_mb_order=0)
+    params, X, G = inputs(cfg, 2205)
+    n = cfg["n_microbatches"]
+    base = run_gpu(cfg, params, X, G, synth.schedule_1f1b(n, 3))
+    for ops, pieces in ((synth.schedule_w_deferred(n, 3, 3), 1), (synth.schedule_greedy(n, 3), 4)):
+        other = run_gpu(cfg, params, X, G, ops, pieces=pieces)
+        assert np.array_equal(base[0], other[0]) and np.array_equal(base[1], other[1])
+        for la, lb in zip(base[2], other[2]):
+            for k in la:
+                assert np.array_equal(la[k], lb[k]), k
+    rnd_ops = synth.schedule_random(n, 4, 5003)
+    other = run_gpu(cfg, params, X, G, rnd_ops)
+    assert np.array_equal(base[0], other[0]) and np.array_equal(base[1], other[1])
+    for la, lb in zip(base[2], other[2]):
+        for k in la:
+            assert so.max_rel_err(lb[k], la[k]) <= 1e-5, k
+
+
+def test_error_paths_leave_state_untouched():
+    import torch
+    from paper_2507_00217_amd import stage as S
+    cfg = dict(synth.CONFIGS["cfg1"], stash_cap=2, enforce_mb_order=1)
+    params, X, G = inputs(cfg, 1000)
+    st = S.Stage(cfg)
+    st.load_weights(params)
+    Xd, Gd = to_dev(X, "fp32"), to_dev(G, "fp32")
+    Y, dX = torch.zeros_like(Xd), torch.zeros_like(Xd)
+
+    def code(fn, *a):
+        with pytest.raises(S.StageError) as e:
+            fn(*a)
+        return e.value.code
+
+    assert code(st.backward_input, 0, Gd[0], dX[0]) == S.E_ORDER
+    assert code(st.backward_weight, 0) == S.E_ORDER
+    assert code(st.forward, 4, Xd[0], Y[0]) == S.E_INVAL
+    st.forward(0, Xd[0], Y[0])
+    assert code(st.forward, 0, Xd[0], Y[0]) == S.E_ORDER
+    st.forward(1, Xd[1], Y[1])
+    assert code(st.forward, 2, Xd[2], Y[2]) == S.E_STASH_FULL
+    assert code(st.backward_input, 1, Gd[1], dX[1]) in (S.E_ORDER,)          # microbatch order enforced: B0 first
+    # a list that fails at its last op enqueues nothing
+    assert code(st.run_schedule, [(B, 0), (W, 0), (F, 2), (F, 3)], Xd, Gd, Y, dX) == S.E_STASH_FULL
+    assert st.stats()["live"] == 2
+    st.run_schedule([(B, 0), (W, 0), (F, 2), (B, 1), (W, 1), (F, 3), (B, 2), (W, 2), (B, 3), (W, 3)], Xd, Gd, Y, dX)
+    torch.cuda.synchronize()
+    assert st.stats() == {"live": 0, "peak_live": 2, "peak_stash_bytes": 2 * (st.sizes["stash"] // 2)}
+    ref = run_oracle(cfg, params, X, G, synth.schedule_1f1b(4, 2))
+    compare(cfg, (to_np(Y), to_np(dX), st.grads(), dict(st.stats(), peak_live=ref[3])), ref, TOL["fp32"])
+    # zero_grads, then a second iteration gives the same gradients again (slots are reused cleanly)
+    g1 = st.grads()
+    st.zero_grads()
+    st.run_schedule(synth.schedule_1f1b(4, 2), Xd, Gd, Y, dX)
+    g2 = st.grads()
+    for la, lb in zip(g1, g2):
+        for k in la:
+            assert np.array_equal(la[k], lb[k])
+    st.close()
