@@ -1,6 +1,235 @@
-// placeholder until the MFMA GEMM lands
+// bf16 MFMA GEMM for gfx950, the three operand layouts of a linear layer's
+// forward, input-gradient and weight-gradient products (paper Appendix B):
+//
+//   NN  C[M,N]  = A[M,K] . B[K,N] (+ R)        forward,  A.W
+//   NT  C[M,N]  = A[M,K] . B[N,K]^T            dgrad,    dZ.W^T
+//   TN  C[M,N] += A[K,M]^T . B[K,N]   (fp32)   wgrad,    A^T.dZ
+//
+// Design: 256x256x64 macro tile per workgroup, 4 wavefronts (2x2), each owning
+// a 128x128 sub-tile as 4x4 v_mfma_f32_32x32x16_bf16 accumulators (256 fp32
+// registers per lane).  Global -> register -> LDS with register prefetch of the
+// next K tile and two LDS buffers (one barrier per K step).  An operand whose
+// reduction index is contiguous in memory sits in LDS as [row][k] (padded to
+// 72 elements: conflict-free 16-byte fragment reads); an operand whose
+// reduction index is the slow one sits as [k][row] (padded to 288) and is read
+// with ds_read_b64_tr_b16, the LDS transpose load, so no layout needs a
+// transposing copy.  The MFMA is issued with the operands swapped (computes the
+// transposed 32x32 block), which leaves every lane with 4 consecutive columns
+// of one row: 8-byte bf16 / 16-byte fp32 epilogue accesses.  Workgroup ids are
+// remapped so that each XCD (own L2) works on a compact band of tiles.
 #include "common.h"
+
 namespace stg {
-bool gemm_mfma_supported(const GemmArgs&) { return false; }
-hipError_t gemm_mfma(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int KPAD = BK + 8;      // [row][k] layout: 144-byte rows
+constexpr int MPAD = BM + 32;     // [k][row] layout: 576-byte rows
+constexpr int TILE_ELEMS = BM * KPAD;                      // == BK * MPAD == 18432
+static_assert(BM * KPAD == BK * MPAD, "both layouts use the same LDS footprint");
+constexpr int THREADS = 256;
+constexpr int CHUNKS = BM * BK / 8 / THREADS;              // 16-byte chunks per thread per operand tile = 8
+constexpr size_t LDS_BYTES = (size_t)4 * TILE_ELEMS * sizeof(bf16);   // A,B x 2 buffers = 147456
+
+enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_ACC32 = 2 };
+
+// one operand tile: global -> registers.  KC: reduction index contiguous in memory.
+template <bool KC>
+__device__ __forceinline__ void g2r(uint4 (&r)[CHUNKS], const bf16* __restrict__ base, int64_t ld, int row0, int rows,
+                                    int k0, int K, int tid) {
+#pragma unroll
+  for (int j = 0; j < CHUNKS; ++j) {
+    const int c = tid + THREADS * j;
+    int row, k;
+    if (KC) { row = c >> 3; k = (c & 7) * 8; } else { k = c >> 5; row = (c & 31) * 8; }
+    const int gr = row0 + row, gk = k0 + k;
+    uint4 v = {0, 0, 0, 0};
+    if (gr < rows && gk < K) {
+      const bf16* p = KC ? base + (int64_t)gr * ld + gk : base + (int64_t)gk * ld + gr;
+      v = *reinterpret_cast<const uint4*>(p);
+    }
+    r[j] = v;
+  }
 }
+
+template <bool KC>
+__device__ __forceinline__ void r2s(const uint4 (&r)[CHUNKS], bf16* tile, int tid) {
+#pragma unroll
+  for (int j = 0; j < CHUNKS; ++j) {
+    const int c = tid + THREADS * j;
+    int off;
+    if (KC) off = (c >> 3) * KPAD + (c & 7) * 8; else off = (c >> 5) * MPAD + (c & 31) * 8;
+    *reinterpret_cast<uint4*>(tile + off) = r[j];
+  }
+}
+
+// 32(row) x 16(k) MFMA operand fragment: lane l holds row l%32, k = (l/32)*8 .. +7
+template <bool KC>
+__device__ __forceinline__ bf16x8 frag(const bf16* tile, int row0, int kk, int lane) {
+  if (KC) {
+    const bf16* p = tile + (row0 + (lane & 31)) * KPAD + kk + (lane >> 5) * 8;
+    return *reinterpret_cast<const bf16x8*>(p);
+  } else {
+    // transpose load: in a 16-lane group, lane i addresses row (i/4) of a 4(k) x 16(row) block at
+    // column 4*(i%4) and receives column i of the block, i.e. 4 consecutive k for its own row
+    const int g = lane >> 4, li = lane & 15;
+    const bf16* p = tile + (kk + (g >> 1) * 8 + (li >> 2)) * MPAD + row0 + (g & 1) * 16 + (li & 3) * 4;
+    typedef s16x4 __attribute__((address_space(3))) * lds_p;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * MPAD));
+    union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+    u.s.a = lo; u.s.b = hi;
+    return u.v;
+  }
+}
+
+template <bool AKC, bool BKC, int EPI>
+__global__ __launch_bounds__(THREADS) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+
+  // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give XCD x the
+  // x-th contiguous band of the tile sequence; inside it walk groups of 8 tile rows column by column.
+  int bid = blockIdx.x;
+  const int nb = tiles_m * tiles_n;
+  {
+    const int per = nb >> 3, main = per << 3;
+    if (bid < main) bid = (bid & 7) * per + (bid >> 3);
+  }
+  constexpr int GROUP = 8;
+  const int in_group = GROUP * tiles_n;
+  const int gid = bid / in_group;
+  const int first_m = gid * GROUP;
+  const int gsz = min(tiles_m - first_m, GROUP);
+  const int tile_m = first_m + (bid % in_group) % gsz;
+  const int tile_n = (bid % in_group) / gsz;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const bf16* A = (const bf16*)g.A;
+  const bf16* B = (const bf16*)g.B;
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  uint4 ra[CHUNKS], rb[CHUNKS];
+  const int nk = (g.K + BK - 1) / BK;
+  g2r<AKC>(ra, A, g.lda, m0, g.M, 0, g.K, tid);
+  g2r<BKC>(rb, B, g.ldb, n0, g.N, 0, g.K, tid);
+  r2s<AKC>(ra, smem, tid);
+  r2s<BKC>(rb, smem + TILE_ELEMS, tid);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const bf16* sa = smem + (kt & 1) * 2 * TILE_ELEMS;
+    const bf16* sb = sa + TILE_ELEMS;
+    if (kt + 1 < nk) {
+      g2r<AKC>(ra, A, g.lda, m0, g.M, (kt + 1) * BK, g.K, tid);
+      g2r<BKC>(rb, B, g.ldb, n0, g.N, (kt + 1) * BK, g.K, tid);
+    }
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8 fa[4], fb[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[i] = frag<AKC>(sa, wm + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) fb[j] = frag<BKC>(sb, wn + j * 32, kk, lane);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) {
+      bf16* da = smem + ((kt + 1) & 1) * 2 * TILE_ELEMS;
+      r2s<AKC>(ra, da, tid);
+      r2s<BKC>(rb, da + TILE_ELEMS, tid);
+    }
+    __syncthreads();
+  }
+
+  // epilogue: acc[i][j][e] = C[m][n],  m = m0+wm+i*32 + lane%32,  n = n0+wn+j*32 + (e/4)*8 + (lane/32)*4 + e%4
+  const int row_l = lane & 31, col_l = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + wm + i * 32 + row_l;
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn + j * 32 + q * 8 + col_l;
+        if (n >= g.N) continue;          // N % 8 == 0 and n % 4 == 0: the 4 columns are in or out together
+        f32x4 v = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+        if (EPI == EPI_ACC32) {
+          float* c = (float*)g.C + (int64_t)m * g.ldc + n;
+          f32x4 old = *reinterpret_cast<f32x4*>(c);
+          *reinterpret_cast<f32x4*>(c) = old + v;
+        } else {
+          if (EPI == EPI_RESID) {
+            bf16x4 r = *reinterpret_cast<const bf16x4*>((const bf16*)g.R + (int64_t)m * g.ldr + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
+          }
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+          *reinterpret_cast<bf16x4*>((bf16*)g.C + (int64_t)m * g.ldc + n) = o;
+        }
+      }
+    }
+  }
+}
+
+template <bool AKC, bool BKC, int EPI>
+hipError_t launch(const GemmArgs& g, hipStream_t s) {
+  static bool attr_set = false;
+  auto kern = gemm_mfma_kernel<AKC, BKC, EPI>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(THREADS), LDS_BYTES, s, g, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool gemm_mfma_supported(const GemmArgs& g) {
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return false;
+  auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  if (!al16(g.A) || !al16(g.B) || !al16(g.C) || (g.R && !al16(g.R))) return false;
+  if (g.lda % 8 || g.ldb % 8 || g.ldc % 4 || (g.R && g.ldr % 4) || g.N % 8) return false;
+  switch (g.mode) {
+    case GEMM_NN: return g.K % 8 == 0 && !g.acc_f32;
+    case GEMM_NT: return g.K % 8 == 0 && !g.acc_f32 && !g.R;
+    case GEMM_TN: return g.M % 8 == 0 && g.acc_f32 && !g.R;
+  }
+  return false;
+}
+
+hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s) {
+  switch (g.mode) {
+    case GEMM_NN: return g.R ? launch<true, false, EPI_RESID>(g, s) : launch<true, false, EPI_STORE>(g, s);
+    case GEMM_NT: return launch<true, true, EPI_STORE>(g, s);
+    case GEMM_TN: return launch<false, false, EPI_ACC32>(g, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace stg

@@ -130,7 +130,12 @@ struct Tracker {
   int step(int kind, int mb) {
     if (kind < STAGE_F || kind > STAGE_W || mb < 0 || mb >= (int)state.size()) return STAGE_E_INVAL;
     if ((int)state[mb] != kind) return STAGE_E_ORDER;   // F needs EMPTY(0), B needs FWD(1), W needs BWD(2)
-    if (enforce && mb <= last[kind]) return STAGE_E_ORDER;
+    if (enforce) {   // same-kind ops in increasing microbatch index: none skipped, none repeated out of order
+      if (mb <= last[kind]) return STAGE_E_ORDER;
+      if (kind != STAGE_F)
+        for (int m = 0; m < mb; ++m)
+          if ((int)state[m] == kind) return STAGE_E_ORDER;   // a smaller microbatch still waits for this op
+    }
     if (kind == STAGE_F && live >= cap) return STAGE_E_STASH_FULL;
     state[mb] = (int8_t)((kind + 1) % 3);
     last[kind] = mb;

@@ -35,3 +35,5 @@ SMALL = {
     "cfg4s": dict(synth.CONFIGS["cfg4"], n_layers=2, hidden=640, n_heads=5, n_kv_heads=5, ffn=1728, seq=200, n_microbatches=5, stash_cap=3, warmup=2),
     "cfg5s": dict(synth.CONFIGS["cfg5"], n_layers=2, hidden=1024, n_heads=8, n_kv_heads=1, ffn=1792, seq=392, n_microbatches=6, stash_cap=4, warmup=3),
 }
+for _c in SMALL.values():          # cap = the schedule's own peak of live microbatches
+    _c["stash_cap"] = synth.peak_live(synth.make_schedule(_c))

@@ -135,7 +135,7 @@ def test_error_paths_leave_state_untouched():
     # zero_grads, then a second iteration gives the same gradients again (slots are reused cleanly)
     g1 = st.grads()
     st.zero_grads()
-    st.run_schedule(synth.schedule_1f1b(4, 2), Xd, Gd, Y, dX)
+    st.run_schedule(synth.schedule_1f1b(4, 1), Xd, Gd, Y, dX)
     g2 = st.grads()
     for la, lb in zip(g1, g2):
         for k in la:

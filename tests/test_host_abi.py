@@ -82,7 +82,7 @@ def ref_validate(ops, n_mb, cap, enforce):
     for i, (k, m) in enumerate(ops):
         if not (0 <= k <= 2 and 0 <= m < n_mb):
             return S.E_INVAL, i, peak
-        if state[m] != k or (enforce and m <= last[k]):
+        if state[m] != k or (enforce and (m <= last[k] or (k != F and k in state[:m]))):
             return S.E_ORDER, i, peak
         if k == F and live >= cap:
             return S.E_STASH_FULL, i, peak
