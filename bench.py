@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the pipeline-stage F/B/W engine on one MI355X.
+
+A "step" is one full schedule iteration of the workload: every F, B and W op of
+all its microbatches, in the workload's op order, through stage_run_schedule.
+Inputs (weights, boundary activations and gradients) are resident in HBM before
+the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3]
+
+FLOP convention (algorithmic work only): GEMM 2*M*N*K; causal attention forward
+2*b*s^2*d (half the dense 4*b*s^2*d), backward 2.5x forward; norm / activation
+arithmetic not counted.  F = GEMMs + attention forward, B = GEMMs + attention
+backward, W = GEMMs.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def flops_per_layer_mb(cfg):
+    d, f, h = cfg["hidden"], cfg["ffn"], cfg["n_heads"]
+    dkv = cfg["n_kv_heads"] * (d // h)
+    T = cfg["seq"] * cfg["mb_size"]
+    fin = 2 * f if cfg["act"] == "swiglu" else f
+    gemm = 2.0 * T * (d * (d + 2 * dkv) + d * d + d * fin + f * d)
+    attn = (2.0 if cfg.get("causal", True) else 4.0) * cfg["mb_size"] * cfg["seq"] ** 2 * d
+    return {"F": gemm + attn, "B": gemm + 2.5 * attn, "W": gemm, "gemm": gemm, "attn_fwd": attn}
+
+
+def cpu_baseline(cfg, budget_s=30.0):
+    """Times the CPU oracle (as it stands) on one layer / one microbatch of the
+    same shapes: F, B and W, fp64."""
+    import numpy as np
+    from oracle import stage_oracle as so
+    from paper_2507_00217_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    one = dict(cfg, n_layers=1, n_microbatches=1)
+    fl = flops_per_layer_mb(one)
+    # bound the sample: shorten the sequence until the estimate fits the budget (assume ~25 GFLOP/s/core fp64)
+    est = lambda c: sum(flops_per_layer_mb(c)[k] for k in "FBW") / (25e9 * cores)
+    while est(one) > budget_s and one["seq"] > 256:
+        one["seq"] //= 2
+    fl = flops_per_layer_mb(one)
+    params = synth.make_weights(one, 1)
+    X = synth.make_boundary(one, 2).astype(np.float64)
+    G = synth.make_boundary(one, 3).astype(np.float64)
+    sh = so.Shape(1, one["hidden"], one["n_heads"], one["n_kv_heads"], one["ffn"], one["seq"], one["mb_size"],
+                  one["norm"], one["act"], True)
+    st = so.OracleStage(sh, params)
+    t0 = time.perf_counter(); st.forward(0, X[0]); t1 = time.perf_counter()
+    st.backward_input(0, G[0]); t2 = time.perf_counter()
+    st.backward_weight(0); t3 = time.perf_counter()
+    total = fl["F"] + fl["B"] + fl["W"]
+    return {"value": total / (t3 - t0) / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"1 layer x 1 microbatch of the workload's shapes at seq {one['seq']} (F {t1 - t0:.1f}s, B {t2 - t1:.1f}s, "
+                      f"W {t3 - t2:.1f}s, fp64 NumPy)",
+            "seconds": t3 - t0}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--kernel-set", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_00217_amd import stage as S
+    from paper_2507_00217_amd import synth
+
+    cfg = dict(synth.CONFIGS[args.config], enforce_mb_order=1)
+    ops = synth.make_schedule(cfg)
+    n_mb, L = cfg["n_microbatches"], cfg["n_layers"]
+    tdt = torch.float32 if cfg["dtype"] == "fp32" else torch.bfloat16
+    seed = 1000 * int(args.config[3])
+    st = S.Stage(cfg)
+    st.set_kernel_set(args.kernel_set)
+    st.load_weights(synth.make_weights(cfg, seed))
+    X = torch.from_numpy(synth.make_boundary(cfg, seed + 1)).to("cuda:0", tdt)
+    dY = torch.from_numpy(synth.make_boundary(cfg, seed + 2)).to("cuda:0", tdt)
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+    ops_c = S.make_ops(ops)
+    fl = flops_per_layer_mb(cfg)
+    iter_flops = n_mb * L * (fl["F"] + fl["B"] + fl["W"])
+
+    for _ in range(args.warmup):
+        st.run_schedule(ops, X, dY, Y, dX, ops_c)
+    st.zero_grads()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st.run_schedule(ops, X, dY, Y, dX, ops_c)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tflops = iter_flops / (dt / args.steps) / 1e12
+
+    # per-op timing (events on the stage's stream) over one more iteration, op by op
+    op_ms = {S.F: 0.0, S.B: 0.0, S.W: 0.0}
+    evs = []
+    for kind, mb in ops:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        if kind == S.F:
+            st.forward(mb, X[mb], Y[mb])
+        elif kind == S.B:
+            st.backward_input(mb, dY[mb], dX[mb])
+        else:
+            st.backward_weight(mb)
+        e1.record()
+        evs.append((kind, e0, e1))
+    torch.cuda.synchronize()
+    for kind, e0, e1 in evs:
+        op_ms[kind] += e0.elapsed_time(e1)
+    per_op = {}
+    for kind, name in ((S.F, "F"), (S.B, "B"), (S.W, "W")):
+        ms = op_ms[kind] / n_mb
+        per_op[name] = {"ms": round(ms, 4), "tflops": round(L * fl[name] / ms / 1e9, 1),
+                        "frac_peak": round(L * fl[name] / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+
+    # per-kernel-class timing, live, with HIP events around every launch of one more iteration
+    st.profile(True)
+    st.run_schedule(ops, X, dY, Y, dX, ops_c)
+    prof = st.profile_read()
+    st.profile(False)
+    kernels = {}
+    for name, r in prof.items():
+        if not r["launches"]:
+            continue
+        rate = r["work"] / (r["ms"] * 1e-3)
+        is_flop = name.startswith(("gemm", "attn"))
+        kernels[name] = {"launches": r["launches"], "avg_ms": round(r["ms"] / r["launches"], 5),
+                         ("tflops" if is_flop else "gbs"): round(rate / (1e12 if is_flop else 1e9), 1)}
+    gemm_ms = sum(prof[k]["ms"] for k in ("gemm_nn", "gemm_nt", "gemm_tn"))
+    gemm_work = sum(prof[k]["work"] for k in ("gemm_nn", "gemm_nt", "gemm_tn"))
+    gemm_n = sum(prof[k]["launches"] for k in ("gemm_nn", "gemm_nt", "gemm_tn"))
+    peak = PEAK_BF16_TFLOPS if cfg["dtype"] == "bf16" else PEAK_FP32_TFLOPS
+    achieved = gemm_work / (gemm_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma" if cfg["dtype"] == "bf16" else "alu", "kernel": "gemm_mfma_kernel (NN+NT+TN launches of one iteration)",
+                "achieved": round(achieved, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "flops_per_launch": gemm_work / gemm_n, "avg_launch_ms": round(gemm_ms / gemm_n, 5), "traffic": None}
+    stats = st.stats()
+    out = {
+        "metric": "stage TFLOP/s per schedule iteration (F+B+W of all microbatches; % of bf16 MFMA peak in frac_peak)",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": f"{args.config}: {L} layers, hidden {cfg['hidden']}, heads {cfg['n_heads']}/{cfg['n_kv_heads']}, "
+                               f"ffn {cfg['ffn']}, {cfg['norm']}+{cfg['act']}, seq {cfg['seq']}, mb_size {cfg['mb_size']}, "
+                               f"{n_mb} microbatches, schedule {cfg['schedule']}, stash cap {cfg['stash_cap'] or n_mb}",
+                   "ops": len(ops), "peak_live": stats["peak_live"], "peak_stash_GiB": round(stats["peak_stash_bytes"] / 2 ** 30, 2),
+                   "kernel_set": args.kernel_set},
+        "frac_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "iter_tflop": round(iter_flops / 1e12, 2),
+        "per_op": per_op, "kernels": kernels, "roofline": roofline,
+    }
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

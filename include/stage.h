@@ -148,6 +148,22 @@ int stage_stats(stage_t* st, int* live, int* peak_live, size_t* peak_stash_bytes
  * HIP kernels for every step.  Both run on the GPU. */
 int stage_set_kernel_set(stage_t* st, int which);
 
+/* Per-launch timing by kernel class, with HIP events recorded on the stage's
+ * stream around every launch while enabled (costs two event records per launch,
+ * so use a separate, untimed pass).  stage_profile(st, 1) clears earlier records
+ * and starts; stage_profile(st, 0) stops and clears.  stage_profile_read
+ * synchronises the stream and returns, for one class, the summed duration in
+ * ms, the number of launches, and the summed algorithmic work: FLOPs (2MNK per
+ * GEMM; 2*b*s^2*d causal / 4*b*s^2*d full per attention forward, 2.5x that for
+ * backward) for classes 0-4, bytes moved by definition for classes 5-9. */
+enum {
+  STAGE_K_GEMM_NN = 0, STAGE_K_GEMM_NT = 1, STAGE_K_GEMM_TN = 2, STAGE_K_ATTN_FWD = 3, STAGE_K_ATTN_BWD = 4,
+  STAGE_K_NORM_FWD = 5, STAGE_K_NORM_BWD = 6, STAGE_K_ACT_FWD = 7, STAGE_K_ACT_BWD = 8, STAGE_K_COPY = 9,
+  STAGE_K_COUNT = 10
+};
+int stage_profile(stage_t* st, int enable);
+int stage_profile_read(stage_t* st, int kernel_class, double* total_ms, int64_t* launches, double* work);
+
 void stage_destroy(stage_t* st);
 const char* stage_strerror(int code);
 

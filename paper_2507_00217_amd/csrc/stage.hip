@@ -159,6 +159,11 @@ struct stage {
   std::vector<int> free_slots;
   int sticky = STAGE_OK;
   int kernel_set = 0;
+  // optional per-launch timing (HIP events on the stage's stream), by kernel class
+  struct ProfRec { int cls; hipEvent_t t0, t1; double work; };
+  bool profiling = false;
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> event_pool;
 };
 
 namespace {
@@ -177,11 +182,34 @@ LayerW layer_weights(const stage* st, int l) {
   return w;
 }
 
+struct ProfScope {
+  stage* st; size_t idx; bool on;
+  ProfScope(stage* s, int cls, double work) : st(s), idx(0), on(s->profiling) {
+    if (!on) return;
+    auto get = [&]() { hipEvent_t e; if (st->event_pool.empty()) { if (hipEventCreate(&e) != hipSuccess) e = nullptr; } else { e = st->event_pool.back(); st->event_pool.pop_back(); } return e; };
+    stage::ProfRec r{cls, get(), get(), work};
+    if (!r.t0 || !r.t1) { on = false; return; }
+    (void)hipEventRecord(r.t0, st->stream);
+    idx = st->prof.size();
+    st->prof.push_back(r);
+  }
+  ~ProfScope() { if (on) (void)hipEventRecord(st->prof[idx].t1, st->stream); }
+};
+
 #define HIPCHK(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) { st->sticky = STAGE_E_HIP; return STAGE_E_HIP; } } while (0)
+
+double act_bytes_fwd(const stage* st) { return (double)st->D.T * (st->D.fin + st->D.f) * st->D.es; }
+double norm_bytes(const stage* st, int n_streams) { return (double)st->D.T * st->D.d * st->D.es * n_streams; }
+double attn_flops(const stage* st, bool bwd) {
+  const Dims& D = st->D;
+  const double dense = 4.0 * D.b * (double)D.s * D.s * D.d;
+  return (st->cfg.causal ? 0.5 : 1.0) * dense * (bwd ? 2.5 : 1.0);
+}
 
 int do_gemm(stage* st, int mode, int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
             void* C, int64_t ldc, const void* R, int64_t ldr, int acc) {
   GemmArgs g{mode, M, N, K, A, lda, B, ldb, C, ldc, R, ldr, acc};
+  ProfScope ps(st, STAGE_K_GEMM_NN + mode, 2.0 * M * N * K);
   if (st->kernel_set == 0 && st->dt == DT_BF16 && gemm_mfma_supported(g)) HIPCHK(gemm_mfma(g, st->stream));
   else HIPCHK(gemm_ref(st->dt, g, st->stream));
   return STAGE_OK;
@@ -202,27 +230,30 @@ int exec_forward(stage* st, int slot_idx, const void* x, void* y) {
   const size_t per_layer = layer_off(D, 0).end;
   const WsOff w = ws_off(D);
   const size_t act_bytes = (size_t)D.T * D.d * D.es;
-  HIPCHK(copy_bytes(slot + layer_off(D, 0).x, x, act_bytes, st->stream));
+  { ProfScope ps(st, STAGE_K_COPY, 2.0 * act_bytes); HIPCHK(copy_bytes(slot + layer_off(D, 0).x, x, act_bytes, st->stream)); }
   for (int l = 0; l < D.L; ++l) {
     const LayerOff o = layer_off(D, per_layer * l);
     const LayerW W = layer_weights(st, l);
     void* y_l = (l + 1 < D.L) ? (void*)(slot + layer_off(D, per_layer * (l + 1)).x) : y;
     NormArgs n{}; n.kind = st->cfg.norm; n.rows = D.T; n.d = D.d; n.eps = st->cfg.norm_eps;
     n.x = slot + o.x; n.gamma = W.g1; n.beta = W.b1; n.out = slot + o.n1; n.stats = (float*)(slot + o.st1);
-    HIPCHK(norm_fwd(st->dt, n, st->stream));
+    { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 2)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
     int rc = do_gemm(st, GEMM_NN, D.T, D.dq, D.d, slot + o.n1, D.d, W.wqkv, D.dq, slot + o.qkv, D.dq, nullptr, 0, 0);
     if (rc) return rc;
     AttnArgs a = attn_args(st, o, slot, nullptr, w);
-    if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_fwd_mfma(a, st->stream));
-    else HIPCHK(attn_fwd_ref(st->dt, a, st->stream));
+    {
+      ProfScope ps(st, STAGE_K_ATTN_FWD, attn_flops(st, false));
+      if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_fwd_mfma(a, st->stream));
+      else HIPCHK(attn_fwd_ref(st->dt, a, st->stream));
+    }
     rc = do_gemm(st, GEMM_NN, D.T, D.d, D.d, slot + o.o, D.d, W.wo, D.d, slot + o.x1, D.d, slot + o.x, D.d, 0);
     if (rc) return rc;
     n.x = slot + o.x1; n.gamma = W.g2; n.beta = W.b2; n.out = slot + o.n2; n.stats = (float*)(slot + o.st2);
-    HIPCHK(norm_fwd(st->dt, n, st->stream));
+    { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 2)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
     rc = do_gemm(st, GEMM_NN, D.T, D.fin, D.d, slot + o.n2, D.d, W.win, D.fin, slot + o.z, D.fin, nullptr, 0, 0);
     if (rc) return rc;
     ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = slot + o.z; ac.a = slot + o.a;
-    HIPCHK(act_fwd(st->dt, ac, st->stream));
+    { ProfScope ps(st, STAGE_K_ACT_FWD, act_bytes_fwd(st)); HIPCHK(act_fwd(st->dt, ac, st->stream)); }
     rc = do_gemm(st, GEMM_NN, D.T, D.d, D.f, slot + o.a, D.f, W.wout, D.d, y_l, D.d, slot + o.x1, D.d, 0);
     if (rc) return rc;
   }
@@ -236,7 +267,7 @@ int exec_backward_input(stage* st, int slot_idx, const void* dy, void* dx) {
   const WsOff w = ws_off(D);
   const size_t act_bytes = (size_t)D.T * D.d * D.es;
   char* dy_top = slot + per_layer * D.L;
-  HIPCHK(copy_bytes(dy_top, dy, act_bytes, st->stream));
+  { ProfScope ps(st, STAGE_K_COPY, 2.0 * act_bytes); HIPCHK(copy_bytes(dy_top, dy, act_bytes, st->stream)); }
   void* da = st->ws + w.da;
   void* dn = st->ws + w.dn;
   for (int l = D.L - 1; l >= 0; --l) {
@@ -247,7 +278,7 @@ int exec_backward_input(stage* st, int slot_idx, const void* dy, void* dx) {
     int rc = do_gemm(st, GEMM_NT, D.T, D.f, D.d, dy_l, D.d, W.wout, D.d, da, D.f, nullptr, 0, 0);
     if (rc) return rc;
     ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = slot + o.z; ac.da = da;
-    HIPCHK(act_bwd(st->dt, ac, st->stream));
+    { ProfScope ps(st, STAGE_K_ACT_BWD, (double)st->D.T * (2.0 * st->D.fin + st->D.f) * st->D.es); HIPCHK(act_bwd(st->dt, ac, st->stream)); }
     rc = do_gemm(st, GEMM_NT, D.T, D.d, D.fin, slot + o.z, D.fin, W.win, D.fin, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
     // dx1 = dy + norm2'(dn2), in place over x1
@@ -255,19 +286,22 @@ int exec_backward_input(stage* st, int slot_idx, const void* dy, void* dx) {
     n.x = slot + o.x1; n.gamma = W.g2; n.out = slot + o.x1; n.stats = (float*)(slot + o.st2);
     n.dout = dn; n.resid = dy_l; n.dgamma = W.G[STAGE_P_NORM2_GAMMA]; n.dbeta = W.G[STAGE_P_NORM2_BETA];
     n.partial = (float*)(st->ws + w.partial);
-    HIPCHK(norm_bwd(st->dt, n, st->stream));
+    { ProfScope ps(st, STAGE_K_NORM_BWD, norm_bytes(st, 4)); HIPCHK(norm_bwd(st->dt, n, st->stream)); }
     // attention: do = dx1.Wo^T ; (dq,dk,dv) ; dn1 = dqkv.Wqkv^T
     rc = do_gemm(st, GEMM_NT, D.T, D.d, D.d, slot + o.x1, D.d, W.wo, D.d, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
     AttnArgs a = attn_args(st, o, slot, dn, w);
-    if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_bwd_mfma(a, st->stream));
-    else HIPCHK(attn_bwd_ref(st->dt, a, st->stream));
+    {
+      ProfScope ps(st, STAGE_K_ATTN_BWD, attn_flops(st, true));
+      if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_bwd_mfma(a, st->stream));
+      else HIPCHK(attn_bwd_ref(st->dt, a, st->stream));
+    }
     rc = do_gemm(st, GEMM_NT, D.T, D.d, D.dq, slot + o.dqkv, D.dq, W.wqkv, D.dq, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
     // dx = dx1 + norm1'(dn1): in place over x (the layer below reads it as its dy), or to the caller for layer 0
     n.x = slot + o.x; n.gamma = W.g1; n.out = (l == 0) ? dx : (void*)(slot + o.x); n.stats = (float*)(slot + o.st1);
     n.dout = dn; n.resid = slot + o.x1; n.dgamma = W.G[STAGE_P_NORM1_GAMMA]; n.dbeta = W.G[STAGE_P_NORM1_BETA];
-    HIPCHK(norm_bwd(st->dt, n, st->stream));
+    { ProfScope ps(st, STAGE_K_NORM_BWD, norm_bytes(st, 4)); HIPCHK(norm_bwd(st->dt, n, st->stream)); }
   }
   return STAGE_OK;
 }
@@ -440,7 +474,34 @@ int stage_set_kernel_set(stage_t* st, int which) {
   return STAGE_OK;
 }
 
-void stage_destroy(stage_t* st) { delete st; }
+int stage_profile(stage_t* st, int enable) {
+  if (!st) return STAGE_E_INVAL;
+  for (auto& r : st->prof) { st->event_pool.push_back(r.t0); st->event_pool.push_back(r.t1); }
+  st->prof.clear();
+  st->profiling = enable != 0;
+  return STAGE_OK;
+}
+
+int stage_profile_read(stage_t* st, int kernel_class, double* total_ms, int64_t* launches, double* work) {
+  if (!st || kernel_class < 0 || kernel_class >= STAGE_K_COUNT || !total_ms || !launches || !work) return STAGE_E_INVAL;
+  if (hipStreamSynchronize(st->stream) != hipSuccess) { st->sticky = STAGE_E_HIP; return STAGE_E_HIP; }
+  double ms = 0.0, w = 0.0; int64_t n = 0;
+  for (auto& r : st->prof) {
+    if (r.cls != kernel_class) continue;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, r.t0, r.t1) != hipSuccess) return STAGE_E_HIP;
+    ms += t; w += r.work; ++n;
+  }
+  *total_ms = ms; *launches = n; *work = w;
+  return STAGE_OK;
+}
+
+void stage_destroy(stage_t* st) {
+  if (!st) return;
+  for (auto& r : st->prof) { (void)hipEventDestroy(r.t0); (void)hipEventDestroy(r.t1); }
+  for (auto e : st->event_pool) (void)hipEventDestroy(e);
+  delete st;
+}
 
 const char* stage_strerror(int code) {
   switch (code) {

@@ -21,6 +21,7 @@ NORM = {"layernorm": 0, "rmsnorm": 1}
 ACT = {"gelu": 0, "swiglu": 1}
 DTYPE = {"fp32": 0, "bf16": 1}
 PARAM_IDS = {"g1": 0, "b1": 1, "wqkv": 2, "wo": 3, "g2": 4, "b2": 5, "win": 6, "wout": 7}
+KERNEL_CLASSES = ("gemm_nn", "gemm_nt", "gemm_tn", "attn_fwd", "attn_bwd", "norm_fwd", "norm_bwd", "act_fwd", "act_bwd", "copy")
 OK, E_INVAL, E_ORDER, E_STASH_FULL, E_HIP = 0, -1, -2, -3, -4
 
 
@@ -52,6 +53,9 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2507_00217_amd.build`")
+        # PyTorch ships its own HIP runtime; it must be the one already loaded when libstage.so resolves
+        # libamdhip64, or the process ends up with two runtimes and launches on torch's streams fail.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, ip = C.c_void_p, C.POINTER(C.c_int)
         cfgp, opp = C.POINTER(StageConfig), C.POINTER(StageOp)
@@ -69,6 +73,8 @@ def lib() -> C.CDLL:
             "stage_zero_grads": (C.c_int, [vp]),
             "stage_stats": (C.c_int, [vp, ip, ip, C.POINTER(C.c_size_t)]),
             "stage_set_kernel_set": (C.c_int, [vp, C.c_int]),
+            "stage_profile": (C.c_int, [vp, C.c_int]),
+            "stage_profile_read": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
             "stage_destroy": (None, [vp]),
             "stage_strerror": (C.c_char_p, [C.c_int]),
         }
@@ -209,6 +215,17 @@ class Stage:
 
     def set_kernel_set(self, which: int):
         self._chk(lib().stage_set_kernel_set(self.h, which), "stage_set_kernel_set")
+
+    def profile(self, enable: bool):
+        self._chk(lib().stage_profile(self.h, int(enable)), "stage_profile")
+
+    def profile_read(self) -> Dict[str, Dict[str, float]]:
+        out = {}
+        for cls, name in enumerate(KERNEL_CLASSES):
+            ms, n, w = C.c_double(), C.c_int64(), C.c_double()
+            self._chk(lib().stage_profile_read(self.h, cls, C.byref(ms), C.byref(n), C.byref(w)), "stage_profile_read")
+            out[name] = {"ms": ms.value, "launches": n.value, "work": w.value}
+        return out
 
     def close(self):
         if getattr(self, "h", None):
