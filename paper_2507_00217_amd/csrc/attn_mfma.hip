@@ -34,33 +34,35 @@ constexpr int PADE = 40;          // row padding (elements): 16-byte row reads a
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-template <int HD> struct Cfg {
+template <int HD, int NTHR = THREADS> struct Cfg {
   static constexpr int LD = HD + PADE;           // LDS row stride (elements)
   static constexpr int NKK = HD / 16;            // k-steps of a product reducing over head_dim
   static constexpr int NHB = HD / 32;            // 32-wide head_dim blocks of an output
   static constexpr int TILE = TK * LD;           // elements per LDS tile
-  static constexpr int CH = TK * HD / 8 / THREADS;  // 16-byte chunks per thread per tile
+  static constexpr int CH = TK * HD / 8 / NTHR;    // 16-byte chunks per thread per tile
 };
+
+template <int HD, int NTHR> using TileRegs = uint4[Cfg<HD, NTHR>::CH];
 
 // ---- tile movement ----------------------------------------------------------
 // rows [row0, row0+TK) of a [*, ld] matrix (HD columns from col0) -> registers; rows >= nrows read as zero
-template <int HD>
-__device__ __forceinline__ void tile_g2r(uint4 (&r)[Cfg<HD>::CH], const bf16* __restrict__ base, int64_t ld, int row0,
+template <int HD, int NTHR = THREADS>
+__device__ __forceinline__ void tile_g2r(TileRegs<HD, NTHR>& r, const bf16* __restrict__ base, int64_t ld, int row0,
                                          int nrows, int tid) {
 #pragma unroll
-  for (int j = 0; j < Cfg<HD>::CH; ++j) {
-    const int c = tid + THREADS * j;
+  for (int j = 0; j < Cfg<HD, NTHR>::CH; ++j) {
+    const int c = tid + NTHR * j;
     const int row = c / (HD / 8), col = (c % (HD / 8)) * 8;
     uint4 v = {0, 0, 0, 0};
     if (row0 + row < nrows) v = *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + row) * ld + col);
     r[j] = v;
   }
 }
-template <int HD>
-__device__ __forceinline__ void tile_r2s(const uint4 (&r)[Cfg<HD>::CH], bf16* tile, int tid) {
+template <int HD, int NTHR = THREADS>
+__device__ __forceinline__ void tile_r2s(const TileRegs<HD, NTHR>& r, bf16* tile, int tid) {
 #pragma unroll
-  for (int j = 0; j < Cfg<HD>::CH; ++j) {
-    const int c = tid + THREADS * j;
+  for (int j = 0; j < Cfg<HD, NTHR>::CH; ++j) {
+    const int c = tid + NTHR * j;
     *reinterpret_cast<uint4*>(tile + (c / (HD / 8)) * Cfg<HD>::LD + (c % (HD / 8)) * 8) = r[j];
   }
 }
@@ -111,133 +113,122 @@ __device__ __forceinline__ void zero(f32x16& a) {
 __device__ __forceinline__ int acc_row(int e, int hf) { return (e >> 2) * 8 + hf * 4 + (e & 3); }
 
 // ---------------------------------------------------------------------------
-// forward: one workgroup = 4 wavefronts x QB*32 queries of one (sequence, head)
+// forward: one workgroup = 8 wavefronts x 32 queries of one (sequence, head).  Two wavefronts share a SIMD, so
+// one can run its softmax (VALU, exp) while the other runs MFMAs.
 // ---------------------------------------------------------------------------
-template <int HD, int QB>
-__global__ __launch_bounds__(THREADS) void attn_fwd_kernel(AttnArgs a) {
-  using C = Cfg<HD>;
+constexpr int FWD_THREADS = 512;
+constexpr int FWD_BQ = (FWD_THREADS / 64) * 32;
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; -inf -> 0
+
+template <int HD>
+__global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
+  using C = Cfg<HD, FWD_THREADS>;
   __shared__ __attribute__((aligned(16))) bf16 sK[C::TILE];
   __shared__ __attribute__((aligned(16))) bf16 sV[C::TILE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
-  constexpr int BQ = 4 * QB * 32;
+  constexpr int BQ = FWD_BQ;
   const int nqt = (a.s + BQ - 1) / BQ;
-  const int qt = nqt - 1 - blockIdx.x;              // heaviest (latest) query tiles first
-  const int j = blockIdx.y, ib = blockIdx.z;
+  const int qt = nqt - 1 - blockIdx.y;              // slow grid index: heaviest (latest) query tiles are dispatched first
+  const int j = blockIdx.x, ib = blockIdx.z;
   const int d = a.h * HD, dkv = a.hkv * HD, g = j / (a.h / a.hkv);
   const bf16* base = (const bf16*)a.qkv + (int64_t)ib * a.s * a.ld;
   const bf16* qp = base + j * HD;
   const bf16* kp = base + d + g * HD;
   const bf16* vp = base + d + dkv + g * HD;
-  const int q0b = qt * BQ, q0w = q0b + wave * QB * 32;
+  const int q0b = qt * BQ, q0w = q0b + wave * 32;
+  const int q = q0w + (lane & 31);
   const float sl2 = rsqrtf((float)HD) * LOG2E;
 
-  bf16x8 qf[QB][C::NKK];
+  bf16x8 qf[C::NKK];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-    for (int kk = 0; kk < C::NKK; ++kk) qf[qb][kk] = frag_rows_global(qp, a.ld, q0w + qb * 32, a.s, kk * 16, lane);
+  for (int kk = 0; kk < C::NKK; ++kk) qf[kk] = frag_rows_global(qp, a.ld, q0w, a.s, kk * 16, lane);
 
-  f32x16 o[QB][C::NHB];
-  float m[QB], l[QB];
+  f32x16 o[C::NHB];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m[qb] = -1e30f; l[qb] = 0.f;
-#pragma unroll
-    for (int hb = 0; hb < C::NHB; ++hb) zero(o[qb][hb]);
-  }
+  for (int hb = 0; hb < C::NHB; ++hb) zero(o[hb]);
+  float m = -1e30f, l = 0.f;                       // running max (in log2 units, scaled) and sum of the lane's query
 
   const int last_q = min(q0b + BQ, a.s) - 1;
   const int ntiles = a.causal ? last_q / TK + 1 : (a.s + TK - 1) / TK;
   uint4 rk[C::CH], rv[C::CH];
-  tile_g2r<HD>(rk, kp, a.ld, 0, a.s, tid);
-  tile_g2r<HD>(rv, vp, a.ld, 0, a.s, tid);
-  tile_r2s<HD>(rk, sK, tid);
-  tile_r2s<HD>(rv, sV, tid);
+  tile_g2r<HD, FWD_THREADS>(rk, kp, a.ld, 0, a.s, tid);
+  tile_g2r<HD, FWD_THREADS>(rv, vp, a.ld, 0, a.s, tid);
+  tile_r2s<HD, FWD_THREADS>(rk, sK, tid);
+  tile_r2s<HD, FWD_THREADS>(rv, sV, tid);
   __syncthreads();
 
   for (int t = 0; t < ntiles; ++t) {
     const int kv0 = t * TK;
     if (t + 1 < ntiles) {
-      tile_g2r<HD>(rk, kp, a.ld, kv0 + TK, a.s, tid);
-      tile_g2r<HD>(rv, vp, a.ld, kv0 + TK, a.s, tid);
+      tile_g2r<HD, FWD_THREADS>(rk, kp, a.ld, kv0 + TK, a.s, tid);
+      tile_g2r<HD, FWD_THREADS>(rv, vp, a.ld, kv0 + TK, a.s, tid);
     }
-    const bool active = !a.causal || kv0 <= min(q0w + QB * 32, a.s) - 1;
+    const bool active = !a.causal || kv0 <= min(q0w + 32, a.s) - 1;
     if (active && q0w < a.s) {
       // S^T[key][query] for two 32-key blocks
-      f32x16 sacc[QB][2];
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) { zero(sacc[qb][0]); zero(sacc[qb][1]); }
+      f32x16 sacc[2];
+      zero(sacc[0]); zero(sacc[1]);
 #pragma unroll
       for (int kk = 0; kk < C::NKK; ++kk) {
-        const bf16x8 k0 = frag_rows<C::LD>(sK, 0, kk * 16, lane), k1 = frag_rows<C::LD>(sK, 32, kk * 16, lane);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-          sacc[qb][0] = MFMA(k0, qf[qb][kk], sacc[qb][0]);
-          sacc[qb][1] = MFMA(k1, qf[qb][kk], sacc[qb][1]);
-        }
+        sacc[0] = MFMA(frag_rows<C::LD>(sK, 0, kk * 16, lane), qf[kk], sacc[0]);
+        sacc[1] = MFMA(frag_rows<C::LD>(sK, 32, kk * 16, lane), qf[kk], sacc[1]);
       }
-      bf16x8 pf[QB][2][2];
+      const bool need_mask = (a.causal && kv0 + TK - 1 > q0w) || kv0 + TK > a.s;
+      float p[2][16];
+      float mx = -INFINITY;
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int q = q0w + qb * 32 + (lane & 31);
-        const bool need_mask = (a.causal && kv0 + TK - 1 > q0w + qb * 32) || kv0 + TK > a.s;
-        float p[2][16];
-        float mx = -INFINITY;
+      for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            float x = sacc[qb][c][e] * sl2;
-            if (need_mask) {
-              const int key = kv0 + c * 32 + acc_row(e, hf);
-              if (key >= a.s || (a.causal && key > q)) x = -INFINITY;
-            }
-            p[c][e] = x;
-            mx = fmaxf(mx, x);
+        for (int e = 0; e < 16; ++e) {
+          float x = sacc[c][e] * sl2;
+          if (need_mask) {
+            const int key = kv0 + c * 32 + acc_row(e, hf);
+            if (key >= a.s || (a.causal && key > q)) x = -INFINITY;
           }
-        mx = fmaxf(mx, xhalf(mx));
-        const float mn = fmaxf(m[qb], mx);
-        const float alpha = exp2f(m[qb] - mn);
-        float sum = 0.f;
+          p[c][e] = x;
+          mx = fmaxf(mx, x);
+        }
+      mx = fmaxf(mx, xhalf(mx));
+      const float mn = fmaxf(m, mx);
+      float sum = 0.f;
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+      for (int c = 0; c < 2; ++c)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) { p[c][e] = exp2f(p[c][e] - mn); sum += p[c][e]; }
-        sum += xhalf(sum);
-        l[qb] = l[qb] * alpha + sum;
-        m[qb] = mn;
+        for (int e = 0; e < 16; ++e) { p[c][e] = fast_exp2(p[c][e] - mn); sum += p[c][e]; }
+      sum += xhalf(sum);
+      if (__any(mn != m)) {                          // the running max moved for some query of the wavefront
+        const float alpha = fast_exp2(m - mn);
+        l *= alpha;
 #pragma unroll
         for (int hb = 0; hb < C::NHB; ++hb)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) o[qb][hb][e] *= alpha;
-#pragma unroll
-        for (int c = 0; c < 2; ++c) { pf[qb][c][0] = pack8(&p[c][0]); pf[qb][c][1] = pack8(&p[c][8]); }
+          for (int e = 0; e < 16; ++e) o[hb][e] *= alpha;
       }
+      l += sum;
+      m = mn;
+      bf16x8 pf[2][2];
+#pragma unroll
+      for (int c = 0; c < 2; ++c) { pf[c][0] = pack8(&p[c][0]); pf[c][1] = pack8(&p[c][8]); }
       // O^T[hd][query] += V^T . P^T
 #pragma unroll
       for (int hb = 0; hb < C::NHB; ++hb)
 #pragma unroll
         for (int c = 0; c < 2; ++c)
 #pragma unroll
-          for (int t2 = 0; t2 < 2; ++t2) {
-            const bf16x8 vf = frag_cols_tr<C::LD>(sV, c * 32 + t2 * 16, hb * 32, lane);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) o[qb][hb] = MFMA(vf, pf[qb][c][t2], o[qb][hb]);
-          }
+          for (int t2 = 0; t2 < 2; ++t2)
+            o[hb] = MFMA(frag_cols_tr<C::LD>(sV, c * 32 + t2 * 16, hb * 32, lane), pf[c][t2], o[hb]);
     }
     __syncthreads();
     if (t + 1 < ntiles) {
-      tile_r2s<HD>(rk, sK, tid);
-      tile_r2s<HD>(rv, sV, tid);
+      tile_r2s<HD, FWD_THREADS>(rk, sK, tid);
+      tile_r2s<HD, FWD_THREADS>(rv, sV, tid);
     }
     __syncthreads();
   }
 
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int q = q0w + qb * 32 + (lane & 31);
-    if (q >= a.s) continue;
-    const float inv = 1.f / l[qb];
+  if (q < a.s) {
+    const float inv = 1.f / l;
     bf16* orow = (bf16*)a.o + ((int64_t)ib * a.s + q) * d + j * HD;
 #pragma unroll
     for (int hb = 0; hb < C::NHB; ++hb)
@@ -245,10 +236,10 @@ __global__ __launch_bounds__(THREADS) void attn_fwd_kernel(AttnArgs a) {
       for (int q4 = 0; q4 < 4; ++q4) {
         bf16x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[qb][hb][q4 * 4 + e] * inv);
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[hb][q4 * 4 + e] * inv);
         *reinterpret_cast<bf16x4*>(orow + hb * 32 + q4 * 8 + hf * 4) = v;
       }
-    if (hf == 0) a.lse[((int64_t)ib * a.h + j) * a.s + q] = (m[qb] + log2f(l[qb])) * LN2;
+    if (hf == 0) a.lse[((int64_t)ib * a.h + j) * a.s + q] = (m + log2f(l)) * LN2;
   }
 }
 
@@ -281,18 +272,19 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(AttnArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// dQ: one workgroup = 4 wavefronts x 32 queries of one (sequence, head)
+// dQ: one workgroup = 8 wavefronts x 32 queries of one (sequence, head); two wavefronts per SIMD so that one
+// wavefront's exp / dS arithmetic overlaps the other's MFMAs
 // ---------------------------------------------------------------------------
 template <int HD>
-__global__ __launch_bounds__(THREADS) void attn_dq_kernel(AttnArgs a) {
-  using C = Cfg<HD>;
+__global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
+  using C = Cfg<HD, FWD_THREADS>;
   __shared__ __attribute__((aligned(16))) bf16 sK[C::TILE];
   __shared__ __attribute__((aligned(16))) bf16 sV[C::TILE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
-  constexpr int BQ = 128;
+  constexpr int BQ = FWD_BQ;
   const int nqt = (a.s + BQ - 1) / BQ;
-  const int qt = nqt - 1 - blockIdx.x;
-  const int j = blockIdx.y, ib = blockIdx.z;
+  const int qt = nqt - 1 - blockIdx.y;              // slow grid index: heaviest query tiles first
+  const int j = blockIdx.x, ib = blockIdx.z;
   const int d = a.h * HD, dkv = a.hkv * HD, g = j / (a.h / a.hkv);
   const bf16* base = (const bf16*)a.qkv + (int64_t)ib * a.s * a.ld;
   const bf16* qp = base + j * HD;
@@ -321,59 +313,54 @@ __global__ __launch_bounds__(THREADS) void attn_dq_kernel(AttnArgs a) {
   const int last_q = min(q0b + BQ, a.s) - 1;
   const int ntiles = a.causal ? last_q / TK + 1 : (a.s + TK - 1) / TK;
   uint4 rk[C::CH], rv[C::CH];
-  tile_g2r<HD>(rk, kp, a.ld, 0, a.s, tid);
-  tile_g2r<HD>(rv, vp, a.ld, 0, a.s, tid);
-  tile_r2s<HD>(rk, sK, tid);
-  tile_r2s<HD>(rv, sV, tid);
+  tile_g2r<HD, FWD_THREADS>(rk, kp, a.ld, 0, a.s, tid);
+  tile_g2r<HD, FWD_THREADS>(rv, vp, a.ld, 0, a.s, tid);
+  tile_r2s<HD, FWD_THREADS>(rk, sK, tid);
+  tile_r2s<HD, FWD_THREADS>(rv, sV, tid);
   __syncthreads();
 
   for (int t = 0; t < ntiles; ++t) {
     const int kv0 = t * TK;
     if (t + 1 < ntiles) {
-      tile_g2r<HD>(rk, kp, a.ld, kv0 + TK, a.s, tid);
-      tile_g2r<HD>(rv, vp, a.ld, kv0 + TK, a.s, tid);
+      tile_g2r<HD, FWD_THREADS>(rk, kp, a.ld, kv0 + TK, a.s, tid);
+      tile_g2r<HD, FWD_THREADS>(rv, vp, a.ld, kv0 + TK, a.s, tid);
     }
     const bool active = !a.causal || kv0 <= min(q0w + 32, a.s) - 1;
     if (active && q0w < a.s) {
-      f32x16 sacc[2], pacc[2];
-      zero(sacc[0]); zero(sacc[1]); zero(pacc[0]); zero(pacc[1]);
-#pragma unroll
-      for (int kk = 0; kk < C::NKK; ++kk) {
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          sacc[c] = MFMA(frag_rows<C::LD>(sK, c * 32, kk * 16, lane), qf[kk], sacc[c]);     // S^T  = K . Q^T
-          pacc[c] = MFMA(frag_rows<C::LD>(sV, c * 32, kk * 16, lane), dof[kk], pacc[c]);    // dP^T = V . dO^T
-        }
-      }
       const bool need_mask = (a.causal && kv0 + TK - 1 > q0w) || kv0 + TK > a.s;
-      bf16x8 dsf[2][2];
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
+        if (a.causal && kv0 + c * 32 > q0w + 31) continue;          // the whole 32-key block is in the future
+        f32x16 sacc, pacc;
+        zero(sacc); zero(pacc);
+#pragma unroll
+        for (int kk = 0; kk < C::NKK; ++kk) {
+          sacc = MFMA(frag_rows<C::LD>(sK, c * 32, kk * 16, lane), qf[kk], sacc);     // S^T  = K . Q^T
+          pacc = MFMA(frag_rows<C::LD>(sV, c * 32, kk * 16, lane), dof[kk], pacc);    // dP^T = V . dO^T
+        }
         float ds[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          float p = exp2f(sacc[c][e] * sl2 - lse2);
+          float p = fast_exp2(sacc[e] * sl2 - lse2);
           if (need_mask) {
             const int key = kv0 + c * 32 + acc_row(e, hf);
             if (key >= a.s || (a.causal && key > q)) p = 0.f;
           }
-          ds[e] = p * (pacc[c][e] - dl);
+          ds[e] = p * (pacc[e] - dl);
         }
-        dsf[c][0] = pack8(&ds[0]); dsf[c][1] = pack8(&ds[8]);
+        const bf16x8 ds0 = pack8(&ds[0]), ds1 = pack8(&ds[8]);
+        // dQ^T[hd][query] += K^T . dS^T
+#pragma unroll
+        for (int hb = 0; hb < C::NHB; ++hb) {
+          dq[hb] = MFMA(frag_cols_tr<C::LD>(sK, c * 32, hb * 32, lane), ds0, dq[hb]);
+          dq[hb] = MFMA(frag_cols_tr<C::LD>(sK, c * 32 + 16, hb * 32, lane), ds1, dq[hb]);
+        }
       }
-      // dQ^T[hd][query] += K^T . dS^T
-#pragma unroll
-      for (int hb = 0; hb < C::NHB; ++hb)
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int t2 = 0; t2 < 2; ++t2)
-            dq[hb] = MFMA(frag_cols_tr<C::LD>(sK, c * 32 + t2 * 16, hb * 32, lane), dsf[c][t2], dq[hb]);
     }
     __syncthreads();
     if (t + 1 < ntiles) {
-      tile_r2s<HD>(rk, sK, tid);
-      tile_r2s<HD>(rv, sV, tid);
+      tile_r2s<HD, FWD_THREADS>(rk, sK, tid);
+      tile_r2s<HD, FWD_THREADS>(rv, sV, tid);
     }
     __syncthreads();
   }
@@ -404,8 +391,8 @@ __global__ __launch_bounds__(THREADS) void attn_dkv_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) float sD[TK];     // delta per query of the tile
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
   constexpr int BKEY = 128;
-  const int kt = blockIdx.x;                              // early key tiles see the most queries: first
-  const int g = blockIdx.y, ib = blockIdx.z;
+  const int kt = blockIdx.y;                              // slow grid index: early key tiles see the most queries, first
+  const int g = blockIdx.x, ib = blockIdx.z;
   const int d = a.h * HD, dkv = a.hkv * HD, grp = a.h / a.hkv;
   const bf16* base = (const bf16*)a.qkv + (int64_t)ib * a.s * a.ld;
   const bf16* kp = base + d + g * HD;
@@ -477,7 +464,7 @@ __global__ __launch_bounds__(THREADS) void attn_dkv_kernel(AttnArgs a) {
           const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sD[qc * 32 + e4 * 8 + hf * 4]);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            float pv = exp2f(sacc[e4 * 4 + e] * sl2 - l4[e]);
+            float pv = fast_exp2(sacc[e4 * 4 + e] * sl2 - l4[e]);
             if (need_mask && q0 + qc * 32 + e4 * 8 + hf * 4 + e < key) pv = 0.f;
             p[e4 * 4 + e] = pv;
             ds[e4 * 4 + e] = pv * (pacc[e4 * 4 + e] - d4[e]);
@@ -515,9 +502,8 @@ __global__ __launch_bounds__(THREADS) void attn_dkv_kernel(AttnArgs a) {
 
 template <int HD>
 hipError_t fwd_t(const AttnArgs& a, hipStream_t s) {
-  constexpr int QB = 2;
-  const int nqt = (a.s + 4 * QB * 32 - 1) / (4 * QB * 32);
-  hipLaunchKernelGGL((attn_fwd_kernel<HD, QB>), dim3(nqt, a.h, a.b), dim3(THREADS), 0, s, a);
+  const int nqt = (a.s + FWD_BQ - 1) / FWD_BQ;
+  hipLaunchKernelGGL((attn_fwd_kernel<HD>), dim3(a.h, nqt, a.b), dim3(FWD_THREADS), 0, s, a);
   return hipGetLastError();
 }
 
@@ -525,8 +511,8 @@ template <int HD>
 hipError_t bwd_t(const AttnArgs& a, hipStream_t s) {
   const int64_t lanes = (int64_t)a.b * a.s * a.h * (HD / 8);
   hipLaunchKernelGGL((attn_delta_kernel<HD>), dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, s, a);
-  hipLaunchKernelGGL((attn_dq_kernel<HD>), dim3((a.s + 127) / 128, a.h, a.b), dim3(THREADS), 0, s, a);
-  hipLaunchKernelGGL((attn_dkv_kernel<HD>), dim3((a.s + 127) / 128, a.hkv, a.b), dim3(THREADS), 0, s, a);
+  hipLaunchKernelGGL((attn_dq_kernel<HD>), dim3(a.h, (a.s + FWD_BQ - 1) / FWD_BQ, a.b), dim3(FWD_THREADS), 0, s, a);
+  hipLaunchKernelGGL((attn_dkv_kernel<HD>), dim3(a.hkv, (a.s + 127) / 128, a.b), dim3(THREADS), 0, s, a);
   return hipGetLastError();
 }
 

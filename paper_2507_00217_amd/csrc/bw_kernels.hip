@@ -22,7 +22,7 @@ template <typename T> __device__ __forceinline__ void stv(T* p, const Vec<T>& r)
 
 constexpr int NORM_THREADS = 256;
 constexpr int NORM_MAXCH = 4;          // 16-byte chunks per thread: d <= 256*4*(16/sizeof(T))
-constexpr int NORM_PARTIAL_ROWS = 256;
+constexpr int NORM_PARTIAL_ROWS = 256;   // multiple of 4
 int norm_partial_rows() { return NORM_PARTIAL_ROWS; }
 
 __device__ __forceinline__ float wg_sum(float v, float* red) {
@@ -162,18 +162,28 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(NormArgs n) {
   }
 }
 
-// grads += sum over workgroup partials, in workgroup order
+// grads += sum over workgroup partials, in a fixed order: 64 columns per workgroup, 4 wavefronts each summing a
+// quarter of the partial rows (coalesced 256-byte reads), then wavefront 0 adds the four quarter-sums in order
 template <int KIND>
 __global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(NormArgs n, int nparts) {
-  const int col = blockIdx.x * 256 + threadIdx.x;
-  if (col >= n.d) return;
+  __shared__ float sg[4][64], sb[4][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + lane;
   float g = 0.f, b = 0.f;
-  for (int p = 0; p < nparts; ++p) {
-    g += n.partial[(int64_t)p * 2 * n.d + col];
-    if (KIND == 0) b += n.partial[(int64_t)p * 2 * n.d + n.d + col];
+  if (col < n.d) {
+    const int per = nparts / 4;
+#pragma unroll 8
+    for (int p = w * per; p < (w + 1) * per; ++p) {
+      g += n.partial[(int64_t)p * 2 * n.d + col];
+      if (KIND == 0) b += n.partial[(int64_t)p * 2 * n.d + n.d + col];
+    }
   }
-  n.dgamma[col] += g;
-  if (KIND == 0) n.dbeta[col] += b;
+  sg[w][lane] = g; sb[w][lane] = b;
+  __syncthreads();
+  if (w == 0 && col < n.d) {
+    n.dgamma[col] += ((sg[0][lane] + sg[1][lane]) + sg[2][lane]) + sg[3][lane];
+    if (KIND == 0) n.dbeta[col] += ((sb[0][lane] + sb[1][lane]) + sb[2][lane]) + sb[3][lane];
+  }
 }
 
 template <typename T>
@@ -194,7 +204,7 @@ template <typename T>
 static hipError_t norm_bwd_t(const NormArgs& n, hipStream_t s) {
   if (!norm_shape_ok<T>(n)) return hipErrorInvalidValue;
   const int parts = NORM_PARTIAL_ROWS;
-  const int fb = (n.d + 255) / 256;
+  const int fb = (n.d + 63) / 64;
   if (n.kind == 0) {
     hipLaunchKernelGGL((norm_bwd_kernel<T, 0>), dim3(parts), dim3(NORM_THREADS), 0, s, n);
     hipLaunchKernelGGL((norm_bwd_finalize_kernel<0>), dim3(fb), dim3(256), 0, s, n, parts);

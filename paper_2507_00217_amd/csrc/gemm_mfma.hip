@@ -27,6 +27,10 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+#ifndef GEMM_EXPERIMENT
+#define GEMM_EXPERIMENT 0
+#endif
+
 namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
@@ -40,22 +44,43 @@ constexpr size_t LDS_BYTES = (size_t)4 * TILE_ELEMS * sizeof(bf16);   // A,B x 2
 
 enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_ACC32 = 2 };
 
-// one operand tile: global -> registers.  KC: reduction index contiguous in memory.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+constexpr unsigned OOB = 0x80000000u;   // any offset >= num_records makes a buffer load return zeros
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+
+// Per-thread byte offsets of its CHUNKS 16-byte pieces of one operand tile at k = 0.  Rows past the end of
+// the matrix fall outside the buffer's range by themselves (offset >= rows*ld*2); a piece whose contiguous
+// coordinate is out of range is redirected to OOB.  KC: reduction index contiguous in memory.
 template <bool KC>
-__device__ __forceinline__ void g2r(uint4 (&r)[CHUNKS], const bf16* __restrict__ base, int64_t ld, int row0, int rows,
-                                    int k0, int K, int tid) {
+__device__ __forceinline__ void tile_offsets(unsigned (&off)[CHUNKS], int64_t ld, int row0, int rows, int tid) {
 #pragma unroll
   for (int j = 0; j < CHUNKS; ++j) {
     const int c = tid + THREADS * j;
-    int row, k;
-    if (KC) { row = c >> 3; k = (c & 7) * 8; } else { k = c >> 5; row = (c & 31) * 8; }
-    const int gr = row0 + row, gk = k0 + k;
-    uint4 v = {0, 0, 0, 0};
-    if (gr < rows && gk < K) {
-      const bf16* p = KC ? base + (int64_t)gr * ld + gk : base + (int64_t)gk * ld + gr;
-      v = *reinterpret_cast<const uint4*>(p);
+    if (KC) {
+      const int row = row0 + (c >> 3), k = (c & 7) * 8;
+      off[j] = (unsigned)(((int64_t)row * ld + k) * 2);
+      if (row >= rows) off[j] = OOB;
+    } else {
+      const int k = c >> 5, row = row0 + (c & 31) * 8;
+      off[j] = row < rows ? (unsigned)(((int64_t)k * ld + row) * 2) : OOB;
     }
-    r[j] = v;
+  }
+}
+
+// one operand tile at reduction offset k0 (a multiple of BK; K % BK == 0 for a KC operand): global -> registers,
+// no branches.  OOB + anything below 2 GiB stays out of range; reduction rows >= K of a non-KC operand are past
+// the end of the buffer.
+template <bool KC>
+__device__ __forceinline__ void g2r(uint4 (&r)[CHUNKS], __amdgpu_buffer_rsrc_t rsrc, const unsigned (&off)[CHUNKS],
+                                    int64_t ld, int k0) {
+  const unsigned step = KC ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * ld * 2);
+#pragma unroll
+  for (int j = 0; j < CHUNKS; ++j) {
+    i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(off[j] + step), 0, 0);
+    r[j] = uint4{(unsigned)v[0], (unsigned)v[1], (unsigned)v[2], (unsigned)v[3]};
   }
 }
 
@@ -125,43 +150,105 @@ __global__ __launch_bounds__(THREADS) void gemm_mfma_kernel(GemmArgs g, int tile
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  // buffer descriptors cover exactly the rows that exist: KC operand = [rows, ld], other = [K, ld]
+  const __amdgpu_buffer_rsrc_t rsA = make_rsrc(A, (unsigned)(((int64_t)((AKC ? g.M : g.K) - 1) * g.lda + (AKC ? g.K : g.M)) * 2));
+  const __amdgpu_buffer_rsrc_t rsB = make_rsrc(B, (unsigned)(((int64_t)((BKC ? g.N : g.K) - 1) * g.ldb + (BKC ? g.K : g.N)) * 2));
+  unsigned offa[CHUNKS], offb[CHUNKS];
+  tile_offsets<AKC>(offa, g.lda, m0, g.M, tid);
+  tile_offsets<BKC>(offb, g.ldb, n0, g.N, tid);
+
   uint4 ra[CHUNKS], rb[CHUNKS];
   const int nk = (g.K + BK - 1) / BK;
-  g2r<AKC>(ra, A, g.lda, m0, g.M, 0, g.K, tid);
-  g2r<BKC>(rb, B, g.ldb, n0, g.N, 0, g.K, tid);
+  g2r<AKC>(ra, rsA, offa, g.lda, 0);
+  g2r<BKC>(rb, rsB, offb, g.ldb, 0);
   r2s<AKC>(ra, smem, tid);
   r2s<BKC>(rb, smem + TILE_ELEMS, tid);
+  g2r<AKC>(ra, rsA, offa, g.lda, BK);
+  g2r<BKC>(rb, rsB, offb, g.ldb, BK);
   __syncthreads();
 
+  // Software pipeline, one K tile (4 k-steps of 16) per trip, fragments double-buffered in registers:
+  //   S0  read frags k1 | MFMA k0            S2  read frags k3 | write tile t+1 to the other LDS buffer | MFMA k2
+  //   S1  read frags k2 | MFMA k1            -- barrier --
+  //                                          S3  read frags k0 of tile t+1 | issue global loads of tile t+2 | MFMA k3
+  // Loads past the last K tile return zeros (buffer range check), so the loop needs no branches.
+  constexpr int NREADS = (AKC ? 4 : 8) + (BKC ? 4 : 8);   // LDS read instructions per k-step
+  bf16x8 fa[2][4], fb[2][4];
+#define LOAD_FRAGS(buf, sa_, sb_, kk_)                                              \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) fa[buf][i] = frag<AKC>(sa_, wm + i * 32, kk_, lane); \
+  _Pragma("unroll") for (int j = 0; j < 4; ++j) fb[buf][j] = frag<BKC>(sb_, wn + j * 32, kk_, lane);
+#define MFMA16(buf)                                                                  \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
+  _Pragma("unroll") for (int j = 0; j < 4; ++j)                                      \
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
+  // interleave: NREADS LDS reads spread evenly over the 16 MFMAs of a stage
+#define INTERLEAVE_READS()                                                           \
+  _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                    \
+    __builtin_amdgcn_sched_group_barrier(0x100, NREADS / 4, 0);                      \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);                               \
+  }
+
+  LOAD_FRAGS(0, smem, smem + TILE_ELEMS, 0)
   for (int kt = 0; kt < nk; ++kt) {
     const bf16* sa = smem + (kt & 1) * 2 * TILE_ELEMS;
     const bf16* sb = sa + TILE_ELEMS;
-    if (kt + 1 < nk) {
-      g2r<AKC>(ra, A, g.lda, m0, g.M, (kt + 1) * BK, g.K, tid);
-      g2r<BKC>(rb, B, g.ldb, n0, g.N, (kt + 1) * BK, g.K, tid);
+    bf16* na = smem + ((kt + 1) & 1) * 2 * TILE_ELEMS;
+    bf16* nb = na + TILE_ELEMS;
+    // S0
+    LOAD_FRAGS(1, sa, sb, 16)
+    MFMA16(0)
+    INTERLEAVE_READS()
+    __builtin_amdgcn_sched_barrier(0);
+    // S1
+    LOAD_FRAGS(0, sa, sb, 32)
+    MFMA16(1)
+    INTERLEAVE_READS()
+    __builtin_amdgcn_sched_barrier(0);
+    // S2
+    LOAD_FRAGS(1, sa, sb, 48)
+    r2s<AKC>(ra, na, tid);
+    r2s<BKC>(rb, nb, tid);
+    MFMA16(0)
+    // LDS reads first (the compiler will not move a read below a write it cannot prove disjoint)
+    __builtin_amdgcn_sched_group_barrier(0x100, NREADS / 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, NREADS / 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x200, 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
     }
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 fa[4], fb[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) fa[i] = frag<AKC>(sa, wm + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) fb[j] = frag<BKC>(sb, wn + j * 32, kk, lane);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      bf16* da = smem + ((kt + 1) & 1) * 2 * TILE_ELEMS;
-      r2s<AKC>(ra, da, tid);
-      r2s<BKC>(rb, da + TILE_ELEMS, tid);
-    }
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    // S3
+    LOAD_FRAGS(0, na, nb, 0)
+#if GEMM_EXPERIMENT == 2      // timing experiment only: keep re-reading K tile 0 (cache resident)
+    g2r<AKC>(ra, rsA, offa, g.lda, 0);
+    g2r<BKC>(rb, rsB, offb, g.ldb, 0);
+#else
+    g2r<AKC>(ra, rsA, offa, g.lda, (kt + 2) * BK);
+    g2r<BKC>(rb, rsB, offb, g.ldb, (kt + 2) * BK);
+#endif
+    MFMA16(1)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x100, NREADS / 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
+#undef LOAD_FRAGS
+#undef MFMA16
+#undef INTERLEAVE_READS
 
   // epilogue: acc[i][j][e] = C[m][n],  m = m0+wm+i*32 + lane%32,  n = n0+wn+j*32 + (e/4)*8 + (lane/32)*4 + e%4
+#if GEMM_EXPERIMENT == 3      // timing experiment only: no epilogue stores unless a value is NaN
+  if (!(acc[0][0][0] != acc[0][0][0])) return;
+#endif
   const int row_l = lane & 31, col_l = (lane >> 5) * 4;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -215,9 +302,12 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
   if (!al16(g.A) || !al16(g.B) || !al16(g.C) || (g.R && !al16(g.R))) return false;
   if (g.lda % 8 || g.ldb % 8 || g.ldc % 4 || (g.R && g.ldr % 4) || g.N % 8) return false;
+  const int64_t lim = (int64_t)1 << 30;   // operand byte offsets are 32-bit buffer offsets below 2 GiB
+  const int64_t a_rows = g.mode == GEMM_TN ? g.K : g.M, b_rows = g.mode == GEMM_NT ? g.N : g.K;
+  if (a_rows * g.lda >= lim || b_rows * g.ldb >= lim) return false;
   switch (g.mode) {
-    case GEMM_NN: return g.K % 8 == 0 && !g.acc_f32;
-    case GEMM_NT: return g.K % 8 == 0 && !g.acc_f32 && !g.R;
+    case GEMM_NN: return g.K % BK == 0 && !g.acc_f32;
+    case GEMM_NT: return g.K % BK == 0 && !g.acc_f32 && !g.R;
     case GEMM_TN: return g.M % 8 == 0 && g.acc_f32 && !g.R;
   }
   return false;
