@@ -20,6 +20,35 @@ template <typename T> __device__ __forceinline__ void stv(T* p, const Vec<T>& r)
   *reinterpret_cast<uint4*>(p) = r.raw;
 }
 
+// V consecutive elements starting at element offset `off` of a row that is stored either in T or (wide) in fp32
+template <typename T>
+__device__ __forceinline__ void ld_row(float (&dst)[Vec<T>::N], const void* base, int64_t off, bool wide) {
+  constexpr int V = Vec<T>::N;
+  if (wide && sizeof(T) != 4) {
+    const float4* p = reinterpret_cast<const float4*>((const float*)base + off);
+#pragma unroll
+    for (int q = 0; q < V / 4; ++q) { float4 t = p[q]; dst[4 * q] = t.x; dst[4 * q + 1] = t.y; dst[4 * q + 2] = t.z; dst[4 * q + 3] = t.w; }
+  } else {
+    Vec<T> t = ldv((const T*)base + off);
+#pragma unroll
+    for (int e = 0; e < V; ++e) dst[e] = to_f32(t.v[e]);
+  }
+}
+template <typename T>
+__device__ __forceinline__ void st_row(void* base, int64_t off, const float (&src)[Vec<T>::N], bool wide) {
+  constexpr int V = Vec<T>::N;
+  if (wide && sizeof(T) != 4) {
+    float4* p = reinterpret_cast<float4*>((float*)base + off);
+#pragma unroll
+    for (int q = 0; q < V / 4; ++q) p[q] = make_float4(src[4 * q], src[4 * q + 1], src[4 * q + 2], src[4 * q + 3]);
+  } else {
+    Vec<T> o;
+#pragma unroll
+    for (int e = 0; e < V; ++e) o.v[e] = from_f32<T>(src[e]);
+    stv((T*)base + off, o);
+  }
+}
+
 constexpr int NORM_THREADS = 256;
 constexpr int NORM_MAXCH = 4;          // 16-byte chunks per thread: d <= 256*4*(16/sizeof(T))
 constexpr int NORM_PARTIAL_ROWS = 256;   // multiple of 4
@@ -39,8 +68,8 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_fwd_kernel(NormArgs n) {
   constexpr int V = Vec<T>::N;
   __shared__ float red[4];
   const int row = blockIdx.x;
-  const T* x = (const T*)n.x + (int64_t)row * n.d;
-  T* out = (T*)n.out + (int64_t)row * n.d;
+  const int64_t roff = (int64_t)row * n.d;
+  T* out = (T*)n.out + roff;
   const int nvec = n.d / V;
   float xv[NORM_MAXCH][V];
   float s = 0.f;
@@ -48,9 +77,9 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_fwd_kernel(NormArgs n) {
   for (int c = 0; c < NORM_MAXCH; ++c) {
     const int vi = threadIdx.x + c * NORM_THREADS;
     if (vi < nvec) {
-      Vec<T> t = ldv(x + vi * V);
+      ld_row<T>(xv[c], n.x, roff + vi * V, n.x_f32);
 #pragma unroll
-      for (int e = 0; e < V; ++e) { xv[c][e] = to_f32(t.v[e]); s += (KIND == 0) ? xv[c][e] : xv[c][e] * xv[c][e]; }
+      for (int e = 0; e < V; ++e) s += (KIND == 0) ? xv[c][e] : xv[c][e] * xv[c][e];
     }
   }
   float mean = 0.f, rstd;
@@ -104,10 +133,8 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(NormArgs n) {
   }
   const float inv_d = 1.f / (float)n.d;
   for (int row = blockIdx.x; row < n.rows; row += gridDim.x) {
-    const T* x = (const T*)n.x + (int64_t)row * n.d;
-    const T* dout = (const T*)n.dout + (int64_t)row * n.d;
-    const T* resid = n.resid ? (const T*)n.resid + (int64_t)row * n.d : nullptr;
-    T* dx = (T*)n.out + (int64_t)row * n.d;
+    const int64_t roff = (int64_t)row * n.d;
+    const T* dout = (const T*)n.dout + roff;
     const float mean = n.stats[2 * row], rstd = n.stats[2 * row + 1];
     float xh[NORM_MAXCH][V], dxh[NORM_MAXCH][V];
     float s1 = 0.f, s2 = 0.f;
@@ -115,10 +142,12 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(NormArgs n) {
     for (int c = 0; c < NORM_MAXCH; ++c) {
       const int vi = threadIdx.x + c * NORM_THREADS;
       if (vi < nvec) {
-        Vec<T> tx = ldv(x + vi * V), td = ldv(dout + vi * V);
+        float tx[V];
+        ld_row<T>(tx, n.x, roff + vi * V, n.x_f32);
+        Vec<T> td = ldv(dout + vi * V);
 #pragma unroll
         for (int e = 0; e < V; ++e) {
-          const float xhat = (to_f32(tx.v[e]) - mean) * rstd;
+          const float xhat = (tx[e] - mean) * rstd;
           const float dv = to_f32(td.v[e]);
           xh[c][e] = xhat;
           dxh[c][e] = dv * gam[c][e];
@@ -136,15 +165,16 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(NormArgs n) {
     for (int c = 0; c < NORM_MAXCH; ++c) {
       const int vi = threadIdx.x + c * NORM_THREADS;
       if (vi < nvec) {
-        Vec<T> r, o;
-        if (resid) r = ldv(resid + vi * V);
+        float r[V], o[V];
+        if (n.resid) ld_row<T>(r, n.resid, roff + vi * V, n.resid_f32);
 #pragma unroll
         for (int e = 0; e < V; ++e) {
           float v = (dxh[c][e] - m1 - xh[c][e] * m2) * rstd;
-          if (resid) v += to_f32(r.v[e]);
-          o.v[e] = from_f32<T>(v);
+          if (n.resid) v += r[e];
+          o[e] = v;
         }
-        stv(dx + vi * V, o);
+        st_row<T>(n.out, roff + vi * V, o, n.out_f32);
+        if (n.out_lp) st_row<T>(n.out_lp, roff + vi * V, o, false);
       }
     }
   }
@@ -330,6 +360,27 @@ hipError_t fill_zero_f32(float* p, size_t n, hipStream_t s) {
 
 __global__ __launch_bounds__(256) void copy_kernel(uint4* dst, const uint4* src, size_t nvec) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void widen_kernel(float* dst, const T* src, size_t nvec) {
+  constexpr int V = Vec<T>::N;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (size_t)gridDim.x * 256) {
+    float v[V];
+    ld_row<T>(v, src, (int64_t)i * V, false);
+    st_row<T>(dst, (int64_t)i * V, v, true);
+  }
+}
+
+hipError_t widen_to_f32(DType dt, float* dst, const void* src, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const size_t V = dt == DT_F32 ? 4 : 8;
+  if (n % V) return hipErrorInvalidValue;
+  const size_t nvec = n / V, want = (nvec + 255) / 256;
+  const int grid = (int)(want > 16384 ? 16384 : want);
+  if (dt == DT_F32) hipLaunchKernelGGL((widen_kernel<float>), dim3(grid), dim3(256), 0, s, dst, (const float*)src, nvec);
+  else hipLaunchKernelGGL((widen_kernel<bf16>), dim3(grid), dim3(256), 0, s, dst, (const bf16*)src, nvec);
+  return hipGetLastError();
 }
 
 hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s) {

@@ -22,6 +22,8 @@ struct GemmArgs {
   void* C; int64_t ldc;          // compute dtype, or fp32 when acc_f32
   const void* R; int64_t ldr;    // optional residual added in the epilogue (compute dtype), or null
   int acc_f32;                   // 1: C is fp32 and the product is added to it (C += A^T.B)
+  int r_f32;                     // 1: R is fp32 (the fp32 residual stream) instead of the compute dtype
+  int c_f32;                     // 1: C is stored as fp32 (no accumulate) instead of the compute dtype
 };
 
 struct AttnArgs {
@@ -48,6 +50,11 @@ struct NormArgs {
   const void* resid;             // gradient arriving over the residual branch, added to dx
   float* dgamma; float* dbeta;   // fp32 accumulators (+=)
   float* partial;                // scratch [norm_partial_rows(), 2, d] fp32
+  // storage of the residual stream: these tensors may be fp32 while the compute dtype is bf16
+  int x_f32;                     // x is fp32
+  int resid_f32;                 // resid is fp32
+  int out_f32;                   // backward: dx is stored as fp32
+  void* out_lp;                  // backward, optional: second copy of dx in the compute dtype (a GEMM operand)
 };
 
 struct ActArgs {
@@ -72,6 +79,7 @@ hipError_t act_fwd(DType dt, const ActArgs& a, hipStream_t s);
 hipError_t act_bwd(DType dt, const ActArgs& a, hipStream_t s);
 hipError_t fill_zero_f32(float* p, size_t n, hipStream_t s);
 hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
+hipError_t widen_to_f32(DType dt, float* dst, const void* src, size_t n, hipStream_t s);   // dst[i] = (float)src[i]
 
 // tuned gfx950 kernels (bf16 MFMA)
 bool gemm_mfma_supported(const GemmArgs& g);

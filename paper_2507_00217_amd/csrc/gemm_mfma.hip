@@ -266,15 +266,23 @@ __global__ __launch_bounds__(THREADS) void gemm_mfma_kernel(GemmArgs g, int tile
           f32x4 old = *reinterpret_cast<f32x4*>(c);
           *reinterpret_cast<f32x4*>(c) = old + v;
         } else {
-          if (EPI == EPI_RESID) {
-            bf16x4 r = *reinterpret_cast<const bf16x4*>((const bf16*)g.R + (int64_t)m * g.ldr + n);
+          if (EPI == EPI_RESID && g.R) {
+            if (g.r_f32) {
+              v += *reinterpret_cast<const f32x4*>((const float*)g.R + (int64_t)m * g.ldr + n);
+            } else {
+              bf16x4 r = *reinterpret_cast<const bf16x4*>((const bf16*)g.R + (int64_t)m * g.ldr + n);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
+              for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
+            }
           }
-          bf16x4 o;
+          if (EPI == EPI_RESID && g.c_f32) {
+            *reinterpret_cast<f32x4*>((float*)g.C + (int64_t)m * g.ldc + n) = v;
+          } else {
+            bf16x4 o;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-          *reinterpret_cast<bf16x4*>((bf16*)g.C + (int64_t)m * g.ldc + n) = o;
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+            *reinterpret_cast<bf16x4*>((bf16*)g.C + (int64_t)m * g.ldc + n) = o;
+          }
         }
       }
     }
@@ -307,15 +315,15 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   if (a_rows * g.lda >= lim || b_rows * g.ldb >= lim) return false;
   switch (g.mode) {
     case GEMM_NN: return g.K % BK == 0 && !g.acc_f32;
-    case GEMM_NT: return g.K % BK == 0 && !g.acc_f32 && !g.R;
-    case GEMM_TN: return g.M % 8 == 0 && g.acc_f32 && !g.R;
+    case GEMM_NT: return g.K % BK == 0 && !g.acc_f32 && !g.R && !g.c_f32;
+    case GEMM_TN: return g.M % 8 == 0 && g.acc_f32 && !g.R && !g.c_f32;
   }
   return false;
 }
 
 hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s) {
   switch (g.mode) {
-    case GEMM_NN: return g.R ? launch<true, false, EPI_RESID>(g, s) : launch<true, false, EPI_STORE>(g, s);
+    case GEMM_NN: return (g.R || g.c_f32) ? launch<true, false, EPI_RESID>(g, s) : launch<true, false, EPI_STORE>(g, s);
     case GEMM_NT: return launch<true, true, EPI_STORE>(g, s);
     case GEMM_TN: return launch<false, false, EPI_ACC32>(g, s);
   }

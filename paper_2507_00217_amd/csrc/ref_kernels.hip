@@ -66,8 +66,9 @@ __global__ __launch_bounds__(256) void gemm_ref_kernel(GemmArgs g) {
         C[(int64_t)gm * g.ldc + gn] += acc[i][j];
       } else {
         float v = acc[i][j];
-        if (g.R) v += to_f32(((const T*)g.R)[(int64_t)gm * g.ldr + gn]);
-        ((T*)g.C)[(int64_t)gm * g.ldc + gn] = from_f32<T>(v);
+        if (g.R) v += g.r_f32 ? ((const float*)g.R)[(int64_t)gm * g.ldr + gn] : to_f32(((const T*)g.R)[(int64_t)gm * g.ldr + gn]);
+        if (g.c_f32) ((float*)g.C)[(int64_t)gm * g.ldc + gn] = v;
+        else ((T*)g.C)[(int64_t)gm * g.ldc + gn] = from_f32<T>(v);
       }
     }
   }

@@ -78,21 +78,26 @@ size_t param_offset(const Dims& D, int norm, int layer, int pid) {
 }
 
 // --- stash slot layout (bytes) ----------------------------------------------
-struct LayerOff { size_t x, n1, qkv, dqkv, o, x1, n2, z, a, st1, st2, lse, end; };
+// The residual stream (x, x1 going forward; dx1, dx coming back, written in place over them) is kept in fp32
+// whatever the compute dtype: in bf16 it would be rounded twice per layer in each direction and those roundings
+// dominate the stage's error.  GEMM operands derived from it (dyb, dx1b) are stored in the compute dtype.
+struct LayerOff { size_t x, n1, qkv, dqkv, o, x1, n2, z, a, dyb, dx1b, st1, st2, lse, end; };
 
 LayerOff layer_off(const Dims& D, size_t base) {
   LayerOff o; size_t p = base;
   const size_t T = D.T;
   auto take = [&](size_t bytes) { size_t r = p; p += up(bytes); return r; };
-  o.x = take(T * D.d * D.es);
+  o.x = take(T * D.d * sizeof(float));
   o.n1 = take(T * D.d * D.es);
   o.qkv = take(T * D.dq * D.es);
   o.dqkv = take(T * D.dq * D.es);
   o.o = take(T * D.d * D.es);
-  o.x1 = take(T * D.d * D.es);
+  o.x1 = take(T * D.d * sizeof(float));
   o.n2 = take(T * D.d * D.es);
   o.z = take(T * D.fin * D.es);
   o.a = take(T * D.f * D.es);
+  o.dyb = take(T * D.d * D.es);
+  o.dx1b = take(T * D.d * D.es);
   o.st1 = take(T * 2 * sizeof(float));
   o.st2 = take(T * 2 * sizeof(float));
   o.lse = take((size_t)D.b * D.h * D.s * sizeof(float));
@@ -100,10 +105,7 @@ LayerOff layer_off(const Dims& D, size_t base) {
   return o;
 }
 
-size_t slot_bytes(const Dims& D) {
-  const size_t per_layer = layer_off(D, 0).end;
-  return per_layer * D.L + up((size_t)D.T * D.d * D.es);  // + gradient arriving at the stage output
-}
+size_t slot_bytes(const Dims& D) { return layer_off(D, 0).end * D.L; }
 
 struct WsOff { size_t da, dn, delta, partial, end; };
 WsOff ws_off(const Dims& D) {
@@ -199,7 +201,8 @@ struct ProfScope {
 #define HIPCHK(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) { st->sticky = STAGE_E_HIP; return STAGE_E_HIP; } } while (0)
 
 double act_bytes_fwd(const stage* st) { return (double)st->D.T * (st->D.fin + st->D.f) * st->D.es; }
-double norm_bytes(const stage* st, int n_streams) { return (double)st->D.T * st->D.d * st->D.es * n_streams; }
+// bytes moved by a norm kernel: fp32 (residual-stream) tensors and compute-dtype tensors it reads or writes
+double norm_bytes(const stage* st, int n_f32, int n_lp) { return (double)st->D.T * st->D.d * (4.0 * n_f32 + (double)st->D.es * n_lp); }
 double attn_flops(const stage* st, bool bwd) {
   const Dims& D = st->D;
   const double dense = 4.0 * D.b * (double)D.s * D.s * D.d;
@@ -207,8 +210,8 @@ double attn_flops(const stage* st, bool bwd) {
 }
 
 int do_gemm(stage* st, int mode, int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
-            void* C, int64_t ldc, const void* R, int64_t ldr, int acc) {
-  GemmArgs g{mode, M, N, K, A, lda, B, ldb, C, ldc, R, ldr, acc};
+            void* C, int64_t ldc, const void* R, int64_t ldr, int acc, int r_f32 = 0, int c_f32 = 0) {
+  GemmArgs g{mode, M, N, K, A, lda, B, ldb, C, ldc, R, ldr, acc, r_f32, c_f32};
   ProfScope ps(st, STAGE_K_GEMM_NN + mode, 2.0 * M * N * K);
   if (st->kernel_set == 0 && st->dt == DT_BF16 && gemm_mfma_supported(g)) HIPCHK(gemm_mfma(g, st->stream));
   else HIPCHK(gemm_ref(st->dt, g, st->stream));
@@ -229,15 +232,19 @@ int exec_forward(stage* st, int slot_idx, const void* x, void* y) {
   char* slot = st->stash + (size_t)slot_idx * st->slot_sz;
   const size_t per_layer = layer_off(D, 0).end;
   const WsOff w = ws_off(D);
-  const size_t act_bytes = (size_t)D.T * D.d * D.es;
-  { ProfScope ps(st, STAGE_K_COPY, 2.0 * act_bytes); HIPCHK(copy_bytes(slot + layer_off(D, 0).x, x, act_bytes, st->stream)); }
+  const size_t n_act = (size_t)D.T * D.d;
+  {
+    ProfScope ps(st, STAGE_K_COPY, (double)n_act * (D.es + sizeof(float)));
+    HIPCHK(widen_to_f32(st->dt, (float*)(slot + layer_off(D, 0).x), x, n_act, st->stream));
+  }
   for (int l = 0; l < D.L; ++l) {
     const LayerOff o = layer_off(D, per_layer * l);
     const LayerW W = layer_weights(st, l);
-    void* y_l = (l + 1 < D.L) ? (void*)(slot + layer_off(D, per_layer * (l + 1)).x) : y;
-    NormArgs n{}; n.kind = st->cfg.norm; n.rows = D.T; n.d = D.d; n.eps = st->cfg.norm_eps;
+    const bool last = l + 1 == D.L;
+    void* y_l = last ? y : (void*)(slot + layer_off(D, per_layer * (l + 1)).x);   // next layer's fp32 x, or the caller's Y
+    NormArgs n{}; n.kind = st->cfg.norm; n.rows = D.T; n.d = D.d; n.eps = st->cfg.norm_eps; n.x_f32 = 1;
     n.x = slot + o.x; n.gamma = W.g1; n.beta = W.b1; n.out = slot + o.n1; n.stats = (float*)(slot + o.st1);
-    { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 2)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
+    { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 1, 1)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
     int rc = do_gemm(st, GEMM_NN, D.T, D.dq, D.d, slot + o.n1, D.d, W.wqkv, D.dq, slot + o.qkv, D.dq, nullptr, 0, 0);
     if (rc) return rc;
     AttnArgs a = attn_args(st, o, slot, nullptr, w);
@@ -246,15 +253,15 @@ int exec_forward(stage* st, int slot_idx, const void* x, void* y) {
       if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_fwd_mfma(a, st->stream));
       else HIPCHK(attn_fwd_ref(st->dt, a, st->stream));
     }
-    rc = do_gemm(st, GEMM_NN, D.T, D.d, D.d, slot + o.o, D.d, W.wo, D.d, slot + o.x1, D.d, slot + o.x, D.d, 0);
+    rc = do_gemm(st, GEMM_NN, D.T, D.d, D.d, slot + o.o, D.d, W.wo, D.d, slot + o.x1, D.d, slot + o.x, D.d, 0, 1, 1);
     if (rc) return rc;
     n.x = slot + o.x1; n.gamma = W.g2; n.beta = W.b2; n.out = slot + o.n2; n.stats = (float*)(slot + o.st2);
-    { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 2)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
+    { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 1, 1)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
     rc = do_gemm(st, GEMM_NN, D.T, D.fin, D.d, slot + o.n2, D.d, W.win, D.fin, slot + o.z, D.fin, nullptr, 0, 0);
     if (rc) return rc;
     ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = slot + o.z; ac.a = slot + o.a;
     { ProfScope ps(st, STAGE_K_ACT_FWD, act_bytes_fwd(st)); HIPCHK(act_fwd(st->dt, ac, st->stream)); }
-    rc = do_gemm(st, GEMM_NN, D.T, D.d, D.f, slot + o.a, D.f, W.wout, D.d, y_l, D.d, slot + o.x1, D.d, 0);
+    rc = do_gemm(st, GEMM_NN, D.T, D.d, D.f, slot + o.a, D.f, W.wout, D.d, y_l, D.d, slot + o.x1, D.d, 0, 1, last ? 0 : 1);
     if (rc) return rc;
   }
   return STAGE_OK;
@@ -266,29 +273,35 @@ int exec_backward_input(stage* st, int slot_idx, const void* dy, void* dx) {
   const size_t per_layer = layer_off(D, 0).end;
   const WsOff w = ws_off(D);
   const size_t act_bytes = (size_t)D.T * D.d * D.es;
-  char* dy_top = slot + per_layer * D.L;
-  { ProfScope ps(st, STAGE_K_COPY, 2.0 * act_bytes); HIPCHK(copy_bytes(dy_top, dy, act_bytes, st->stream)); }
+  {
+    ProfScope ps(st, STAGE_K_COPY, 2.0 * act_bytes);
+    HIPCHK(copy_bytes(slot + layer_off(D, per_layer * (D.L - 1)).dyb, dy, act_bytes, st->stream));
+  }
   void* da = st->ws + w.da;
   void* dn = st->ws + w.dn;
   for (int l = D.L - 1; l >= 0; --l) {
     const LayerOff o = layer_off(D, per_layer * l);
     const LayerW W = layer_weights(st, l);
-    const void* dy_l = (l + 1 < D.L) ? (const void*)(slot + layer_off(D, per_layer * (l + 1)).x) : (const void*)dy_top;
+    const bool last = l + 1 == D.L;
+    // gradient arriving at this layer's output: GEMM operand copy in the compute dtype, and the residual-branch
+    // term, which is the fp32 dx the layer above left in its x region (the caller's dY for the last layer)
+    const void* dy_op = slot + o.dyb;
+    const void* dy_res = last ? dy_op : (const void*)(slot + layer_off(D, per_layer * (l + 1)).x);
     // FFN: da = dy.Wout^T ; dz = act'(z) * da (in place over z) ; dn2 = dz.Win^T
-    int rc = do_gemm(st, GEMM_NT, D.T, D.f, D.d, dy_l, D.d, W.wout, D.d, da, D.f, nullptr, 0, 0);
+    int rc = do_gemm(st, GEMM_NT, D.T, D.f, D.d, dy_op, D.d, W.wout, D.d, da, D.f, nullptr, 0, 0);
     if (rc) return rc;
     ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = slot + o.z; ac.da = da;
-    { ProfScope ps(st, STAGE_K_ACT_BWD, (double)st->D.T * (2.0 * st->D.fin + st->D.f) * st->D.es); HIPCHK(act_bwd(st->dt, ac, st->stream)); }
+    { ProfScope ps(st, STAGE_K_ACT_BWD, (double)D.T * (2.0 * D.fin + D.f) * D.es); HIPCHK(act_bwd(st->dt, ac, st->stream)); }
     rc = do_gemm(st, GEMM_NT, D.T, D.d, D.fin, slot + o.z, D.fin, W.win, D.fin, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
-    // dx1 = dy + norm2'(dn2), in place over x1
+    // dx1 = dy + norm2'(dn2): fp32 in place over x1, plus a compute-dtype copy for the two GEMMs that read it
     NormArgs n{}; n.kind = st->cfg.norm; n.rows = D.T; n.d = D.d; n.eps = st->cfg.norm_eps;
-    n.x = slot + o.x1; n.gamma = W.g2; n.out = slot + o.x1; n.stats = (float*)(slot + o.st2);
-    n.dout = dn; n.resid = dy_l; n.dgamma = W.G[STAGE_P_NORM2_GAMMA]; n.dbeta = W.G[STAGE_P_NORM2_BETA];
-    n.partial = (float*)(st->ws + w.partial);
-    { ProfScope ps(st, STAGE_K_NORM_BWD, norm_bytes(st, 4)); HIPCHK(norm_bwd(st->dt, n, st->stream)); }
+    n.x = slot + o.x1; n.x_f32 = 1; n.gamma = W.g2; n.out = slot + o.x1; n.out_f32 = 1; n.out_lp = slot + o.dx1b;
+    n.stats = (float*)(slot + o.st2); n.dout = dn; n.resid = dy_res; n.resid_f32 = last ? 0 : 1;
+    n.dgamma = W.G[STAGE_P_NORM2_GAMMA]; n.dbeta = W.G[STAGE_P_NORM2_BETA]; n.partial = (float*)(st->ws + w.partial);
+    { ProfScope ps(st, STAGE_K_NORM_BWD, norm_bytes(st, last ? 2 : 3, last ? 3 : 2)); HIPCHK(norm_bwd(st->dt, n, st->stream)); }
     // attention: do = dx1.Wo^T ; (dq,dk,dv) ; dn1 = dqkv.Wqkv^T
-    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.d, slot + o.x1, D.d, W.wo, D.d, dn, D.d, nullptr, 0, 0);
+    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.d, slot + o.dx1b, D.d, W.wo, D.d, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
     AttnArgs a = attn_args(st, o, slot, dn, w);
     {
@@ -298,10 +311,13 @@ int exec_backward_input(stage* st, int slot_idx, const void* dy, void* dx) {
     }
     rc = do_gemm(st, GEMM_NT, D.T, D.d, D.dq, slot + o.dqkv, D.dq, W.wqkv, D.dq, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
-    // dx = dx1 + norm1'(dn1): in place over x (the layer below reads it as its dy), or to the caller for layer 0
-    n.x = slot + o.x; n.gamma = W.g1; n.out = (l == 0) ? dx : (void*)(slot + o.x); n.stats = (float*)(slot + o.st1);
-    n.dout = dn; n.resid = slot + o.x1; n.dgamma = W.G[STAGE_P_NORM1_GAMMA]; n.dbeta = W.G[STAGE_P_NORM1_BETA];
-    { ProfScope ps(st, STAGE_K_NORM_BWD, norm_bytes(st, 4)); HIPCHK(norm_bwd(st->dt, n, st->stream)); }
+    // dx = dx1 + norm1'(dn1): layer 0 hands it to the caller; otherwise fp32 in place over x (the residual term of
+    // the layer below) plus the compute-dtype copy the layer below uses as its dy operand
+    n.x = slot + o.x; n.gamma = W.g1; n.stats = (float*)(slot + o.st1); n.dout = dn; n.resid = slot + o.x1; n.resid_f32 = 1;
+    n.dgamma = W.G[STAGE_P_NORM1_GAMMA]; n.dbeta = W.G[STAGE_P_NORM1_BETA];
+    if (l == 0) { n.out = dx; n.out_f32 = 0; n.out_lp = nullptr; }
+    else { n.out = slot + o.x; n.out_f32 = 1; n.out_lp = slot + layer_off(D, per_layer * (l - 1)).dyb; }
+    { ProfScope ps(st, STAGE_K_NORM_BWD, norm_bytes(st, l == 0 ? 2 : 3, 2)); HIPCHK(norm_bwd(st->dt, n, st->stream)); }
   }
   return STAGE_OK;
 }
@@ -313,12 +329,11 @@ int exec_backward_weight(stage* st, int slot_idx) {
   for (int l = 0; l < D.L; ++l) {
     const LayerOff o = layer_off(D, per_layer * l);
     const LayerW W = layer_weights(st, l);
-    const void* dy_l = slot + ((l + 1 < D.L) ? layer_off(D, per_layer * (l + 1)).x : per_layer * D.L);
     int rc;
     if ((rc = do_gemm(st, GEMM_TN, D.d, D.dq, D.T, slot + o.n1, D.d, slot + o.dqkv, D.dq, W.G[STAGE_P_WQKV], D.dq, nullptr, 0, 1))) return rc;
-    if ((rc = do_gemm(st, GEMM_TN, D.d, D.d, D.T, slot + o.o, D.d, slot + o.x1, D.d, W.G[STAGE_P_WO], D.d, nullptr, 0, 1))) return rc;
+    if ((rc = do_gemm(st, GEMM_TN, D.d, D.d, D.T, slot + o.o, D.d, slot + o.dx1b, D.d, W.G[STAGE_P_WO], D.d, nullptr, 0, 1))) return rc;
     if ((rc = do_gemm(st, GEMM_TN, D.d, D.fin, D.T, slot + o.n2, D.d, slot + o.z, D.fin, W.G[STAGE_P_WIN], D.fin, nullptr, 0, 1))) return rc;
-    if ((rc = do_gemm(st, GEMM_TN, D.f, D.d, D.T, slot + o.a, D.f, dy_l, D.d, W.G[STAGE_P_WOUT], D.d, nullptr, 0, 1))) return rc;
+    if ((rc = do_gemm(st, GEMM_TN, D.f, D.d, D.T, slot + o.a, D.f, slot + o.dyb, D.d, W.G[STAGE_P_WOUT], D.d, nullptr, 0, 1))) return rc;
   }
   return STAGE_OK;
 }

@@ -1,0 +1,93 @@
+"""Parity at the workloads' full layer shapes, in the launch configuration the
+benchmark times (tuned kernels, microbatch order enforced).
+
+The oracle cannot run a whole iteration of these workloads in test time, so:
+  * one layer x one microbatch of every bf16 workload's exact shapes is compared
+    element by element (Y, dX and every gradient tensor);
+  * on the benchmark workload itself (cfg3, all layers, all 16 microbatches, its
+    W-deferred op list) the first rows of Y are compared against the oracle run
+    on the truncated sequence -- exact under the causal mask, where position t
+    depends only on positions <= t -- and the accumulated gradients are checked
+    to be bit-identical to those of the plain 1F1B order.
+"""
+import numpy as np
+import pytest
+
+from oracle import stage_oracle as so
+from paper_2507_00217_amd import synth
+from tests.gpu_util import TOL, shape_of, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5"])
+def test_one_layer_one_microbatch_full_shapes(name):
+    import torch
+    from paper_2507_00217_amd import stage as S
+    cfg = dict(synth.CONFIGS[name], n_layers=1, n_microbatches=1, stash_cap=1, enforce_mb_order=1)
+    seed = 3000 + int(name[3])
+    params = synth.make_weights(cfg, seed)
+    X, G = synth.make_boundary(cfg, seed + 1), synth.make_boundary(cfg, seed + 2)
+    st = S.Stage(cfg)
+    st.load_weights(params)
+    Xd, Gd = to_dev(X, "bf16"), to_dev(G, "bf16")
+    Y, dX = torch.zeros_like(Xd), torch.zeros_like(Xd)
+    st.run_schedule([(0, 0), (1, 0), (2, 0)], Xd, Gd, Y, dX)
+    torch.cuda.synchronize()
+    Yg, dXg, gg = to_np(Y), to_np(dX), st.grads()
+    st.close()
+    del st, Xd, Gd, Y, dX
+    torch.cuda.empty_cache()
+    print(f"{name}: GPU done, running the oracle", flush=True)
+    ref = so.OracleStage(shape_of(cfg), params)
+    Yr, dXr, _ = ref.run_schedule([(0, 0), (1, 0), (2, 0)], X.astype(np.float64), G.astype(np.float64))
+    errs = {"Y": so.max_rel_err(Yg, Yr), "dX": so.max_rel_err(dXg, dXr)}
+    for k in ref.grads[0]:
+        errs[k] = so.max_rel_err(gg[0][k], ref.grads[0][k])
+    print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert max(errs.values()) <= TOL["bf16"], errs
+
+
+def test_cfg3_full_iteration_prefix_rows_and_order_invariance():
+    import torch
+    from paper_2507_00217_amd import stage as S
+    cfg = dict(synth.CONFIGS["cfg3"], enforce_mb_order=1)
+    n = cfg["n_microbatches"]
+    params = synth.make_weights(cfg, 3000)
+    X, G = synth.make_boundary(cfg, 3001), synth.make_boundary(cfg, 3002)
+    st = S.Stage(cfg)
+    st.load_weights(params)
+    Xd, Gd = to_dev(X, "bf16"), to_dev(G, "bf16")
+    Y, dX = torch.zeros_like(Xd), torch.zeros_like(Xd)
+    st.run_schedule(synth.make_schedule(cfg), Xd, Gd, Y, dX)
+    torch.cuda.synchronize()
+    assert st.stats()["peak_live"] == 8 and st.stats()["live"] == 0
+    g_def = st.grads_tensor().clone()
+    Y_def, dX_def = Y.clone(), dX.clone()
+    # (1) prefix rows of Y for three microbatches against the oracle on the truncated sequence
+    P = 192
+    short = dict(cfg, seq=P)
+    ref = so.OracleStage(shape_of(short), params)
+    for m in (0, 7, 15):
+        yr = ref.forward(m, X[m][:, :P].astype(np.float64))
+        err = so.max_rel_err(to_np(Y_def[m][:, :P]), yr)
+        print(f"mb {m}: Y[:{P}] max rel err {err:.2e}", flush=True)
+        assert err <= TOL["bf16"]
+    # (2) the same iteration in plain 1F1B order (same cap): bit-identical outputs and gradients
+    st.zero_grads()
+    Y.zero_(); dX.zero_()
+    st.run_schedule(synth.schedule_1f1b(n, 7), Xd, Gd, Y, dX)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y_def) and torch.equal(dX, dX_def)
+    assert torch.equal(st.grads_tensor(), g_def)
+    # (3) linearity in the output gradient (exact for a power of two): dY -> 2 dY doubles dX and the gradients
+    st.zero_grads()
+    st.run_schedule([(0, 0), (1, 0), (2, 0)], Xd, Gd, Y, dX)
+    g1 = st.grads_tensor().clone(); dx1 = dX[0].clone()
+    st.zero_grads()
+    G2 = (Gd.float() * 2).to(torch.bfloat16)
+    st.run_schedule([(0, 0), (1, 0), (2, 0)], Xd, G2, Y, dX)
+    torch.cuda.synchronize()
+    assert so.max_rel_err(to_np(dX[0]), 2 * to_np(dx1)) <= 1e-2
+    assert so.max_rel_err(to_np(st.grads_tensor()), 2 * to_np(g1)) <= 1e-2
+    st.close()

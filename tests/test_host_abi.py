@@ -72,7 +72,7 @@ def test_layout_and_sizes(name):
     fin = 2 * f if cfg["act"] == "swiglu" else f
     need = (6 * d + 2 * dkv + fin + f) * T * es * cfg["n_layers"]
     cap = cfg["stash_cap"] or cfg["n_microbatches"]
-    assert sz["stash"] % cap == 0 and need <= sz["stash"] // cap <= 1.5 * need
+    assert sz["stash"] % cap == 0 and need <= sz["stash"] // cap <= 1.6 * need
     assert sz["stash"] + sz["weights"] + sz["grads"] + sz["workspace"] < 200 * 2 ** 30
 
 
