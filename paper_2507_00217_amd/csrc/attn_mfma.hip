@@ -108,6 +108,11 @@ __device__ __forceinline__ void zero(f32x16& a) {
   for (int e = 0; e < 16; ++e) a[e] = 0.f;
 }
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+// first product of an accumulation chain: C = 0 as an inline constant, so no registers are cleared beforehand
+__device__ __forceinline__ f32x16 mfma0(bf16x8 a, bf16x8 b) {
+  const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, z, 0, 0, 0);
+}
 
 // row index inside a 32-row accumulator block held in register e by a lane of half hf
 __device__ __forceinline__ int acc_row(int e, int hf) { return (e >> 2) * 8 + hf * 4 + (e & 3); }
@@ -168,9 +173,10 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
     if (active && q0w < a.s) {
       // S^T[key][query] for two 32-key blocks
       f32x16 sacc[2];
-      zero(sacc[0]); zero(sacc[1]);
+      sacc[0] = mfma0(frag_rows<C::LD>(sK, 0, 0, lane), qf[0]);
+      sacc[1] = mfma0(frag_rows<C::LD>(sK, 32, 0, lane), qf[0]);
 #pragma unroll
-      for (int kk = 0; kk < C::NKK; ++kk) {
+      for (int kk = 1; kk < C::NKK; ++kk) {
         sacc[0] = MFMA(frag_rows<C::LD>(sK, 0, kk * 16, lane), qf[kk], sacc[0]);
         sacc[1] = MFMA(frag_rows<C::LD>(sK, 32, kk * 16, lane), qf[kk], sacc[1]);
       }
@@ -181,7 +187,7 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
       for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          float x = sacc[c][e] * sl2;
+          float x = sacc[c][e];                       // raw score; sl2 > 0, so the max can be taken before scaling
           if (need_mask) {
             const int key = kv0 + c * 32 + acc_row(e, hf);
             if (key >= a.s || (a.causal && key > q)) x = -INFINITY;
@@ -190,12 +196,12 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
           mx = fmaxf(mx, x);
         }
       mx = fmaxf(mx, xhalf(mx));
-      const float mn = fmaxf(m, mx);
+      const float mn = fmaxf(m, mx * sl2);
       float sum = 0.f;
 #pragma unroll
       for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { p[c][e] = fast_exp2(p[c][e] - mn); sum += p[c][e]; }
+        for (int e = 0; e < 16; ++e) { p[c][e] = fast_exp2(fmaf(p[c][e], sl2, -mn)); sum += p[c][e]; }
       sum += xhalf(sum);
       if (__any(mn != m)) {                          // the running max moved for some query of the wavefront
         const float alpha = fast_exp2(m - mn);
@@ -331,12 +337,12 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         if (a.causal && kv0 + c * 32 > q0w + 31) continue;          // the whole 32-key block is in the future
-        f32x16 sacc, pacc;
-        zero(sacc); zero(pacc);
+        f32x16 sacc = mfma0(frag_rows<C::LD>(sK, c * 32, 0, lane), qf[0]);             // S^T  = K . Q^T
+        f32x16 pacc = mfma0(frag_rows<C::LD>(sV, c * 32, 0, lane), dof[0]);            // dP^T = V . dO^T
 #pragma unroll
-        for (int kk = 0; kk < C::NKK; ++kk) {
-          sacc = MFMA(frag_rows<C::LD>(sK, c * 32, kk * 16, lane), qf[kk], sacc);     // S^T  = K . Q^T
-          pacc = MFMA(frag_rows<C::LD>(sV, c * 32, kk * 16, lane), dof[kk], pacc);    // dP^T = V . dO^T
+        for (int kk = 1; kk < C::NKK; ++kk) {
+          sacc = MFMA(frag_rows<C::LD>(sK, c * 32, kk * 16, lane), qf[kk], sacc);
+          pacc = MFMA(frag_rows<C::LD>(sV, c * 32, kk * 16, lane), dof[kk], pacc);
         }
         float ds[16];
 #pragma unroll
@@ -449,12 +455,12 @@ __global__ __launch_bounds__(THREADS) void attn_dkv_kernel(AttnArgs a) {
 #pragma unroll
       for (int qc = 0; qc < 2; ++qc) {
         if (a.causal && q0 + qc * 32 + 31 < k0w) continue;          // every query of the block precedes every key
-        f32x16 sacc, pacc;
-        zero(sacc); zero(pacc);
+        f32x16 sacc = mfma0(frag_rows<C::LD>(sQ, qc * 32, 0, lane), kf[0]);            // S  = Q . K^T
+        f32x16 pacc = mfma0(frag_rows<C::LD>(sO, qc * 32, 0, lane), vf[0]);            // dP = dO . V^T
 #pragma unroll
-        for (int kk = 0; kk < C::NKK; ++kk) {
-          sacc = MFMA(frag_rows<C::LD>(sQ, qc * 32, kk * 16, lane), kf[kk], sacc);     // S  = Q . K^T
-          pacc = MFMA(frag_rows<C::LD>(sO, qc * 32, kk * 16, lane), vf[kk], pacc);     // dP = dO . V^T
+        for (int kk = 1; kk < C::NKK; ++kk) {
+          sacc = MFMA(frag_rows<C::LD>(sQ, qc * 32, kk * 16, lane), kf[kk], sacc);
+          pacc = MFMA(frag_rows<C::LD>(sO, qc * 32, kk * 16, lane), vf[kk], pacc);
         }
         const bool need_mask = a.causal && q0 + qc * 32 < k0w + 31;
         float p[16], ds[16];
