@@ -27,6 +27,10 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes per GEMM launch (average over the NN/NT/TN launches of one cfg3 iteration), from two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE) scaled by the same counters' reading for the plain copy kernel of known size in
+# the same run; summary and commands in profiles/cfg3_schedule_pmc.md.  Only valid for the cfg3 workload.
+MEASURED_GEMM_TRAFFIC_BYTES = {"cfg3": 870.1e6}
 
 
 def flops_per_layer_mb(cfg):
@@ -160,7 +164,8 @@ def main():
     achieved = gemm_work / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma" if cfg["dtype"] == "bf16" else "alu", "kernel": "gemm_mfma_kernel (NN+NT+TN launches of one iteration)",
                 "achieved": round(achieved, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "flops_per_launch": gemm_work / gemm_n, "avg_launch_ms": round(gemm_ms / gemm_n, 5), "traffic": None}
+                "flops_per_launch": gemm_work / gemm_n, "avg_launch_ms": round(gemm_ms / gemm_n, 5),
+                "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.config) if args.kernel_set == 0 else None}
     stats = st.stats()
     out = {
         "metric": "stage TFLOP/s per schedule iteration (F+B+W of all microbatches; % of bf16 MFMA peak in frac_peak)",
