@@ -386,17 +386,17 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// dK/dV: one workgroup = 4 wavefronts x 32 keys of one (sequence, kv head)
+// dK/dV: one workgroup = NTHR/64 wavefronts x 32 keys of one (sequence, kv head)
 // ---------------------------------------------------------------------------
-template <int HD>
-__global__ __launch_bounds__(THREADS) void attn_dkv_kernel(AttnArgs a) {
-  using C = Cfg<HD>;
+template <int HD, int NTHR>
+__global__ __launch_bounds__(NTHR) void attn_dkv_kernel(AttnArgs a) {
+  using C = Cfg<HD, NTHR>;
   __shared__ __attribute__((aligned(16))) bf16 sQ[C::TILE];
   __shared__ __attribute__((aligned(16))) bf16 sO[C::TILE];
   __shared__ __attribute__((aligned(16))) float sL[TK];     // lse * log2(e) per query of the tile
   __shared__ __attribute__((aligned(16))) float sD[TK];     // delta per query of the tile
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
-  constexpr int BKEY = 128;
+  constexpr int BKEY = (NTHR / 64) * 32;
   const int kt = blockIdx.y;                              // slow grid index: early key tiles see the most queries, first
   const int g = blockIdx.x, ib = blockIdx.z;
   const int d = a.h * HD, dkv = a.hkv * HD, grp = a.h / a.hkv;
@@ -427,8 +427,8 @@ __global__ __launch_bounds__(THREADS) void attn_dkv_kernel(AttnArgs a) {
   auto fetch = [&](int it) {
     const int jj = it / per_head, t = t_first + it % per_head;
     const int j = g * grp + jj;
-    tile_g2r<HD>(rq, base + j * HD, a.ld, t * TK, a.s, tid);
-    tile_g2r<HD>(ro, (const bf16*)a.dout + (int64_t)ib * a.s * d + j * HD, d, t * TK, a.s, tid);
+    tile_g2r<HD, NTHR>(rq, base + j * HD, a.ld, t * TK, a.s, tid);
+    tile_g2r<HD, NTHR>(ro, (const bf16*)a.dout + (int64_t)ib * a.s * d + j * HD, d, t * TK, a.s, tid);
     if (tid < TK) {
       const int qi = t * TK + tid;
       rl = 1e30f; rd = 0.f;
@@ -439,8 +439,8 @@ __global__ __launch_bounds__(THREADS) void attn_dkv_kernel(AttnArgs a) {
     }
   };
   auto stash = [&]() {
-    tile_r2s<HD>(rq, sQ, tid);
-    tile_r2s<HD>(ro, sO, tid);
+    tile_r2s<HD, NTHR>(rq, sQ, tid);
+    tile_r2s<HD, NTHR>(ro, sO, tid);
     if (tid < TK) { sL[tid] = rl; sD[tid] = rd; }
   };
 
@@ -518,7 +518,11 @@ hipError_t bwd_t(const AttnArgs& a, hipStream_t s) {
   const int64_t lanes = (int64_t)a.b * a.s * a.h * (HD / 8);
   hipLaunchKernelGGL((attn_delta_kernel<HD>), dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, s, a);
   hipLaunchKernelGGL((attn_dq_kernel<HD>), dim3(a.h, (a.s + FWD_BQ - 1) / FWD_BQ, a.b), dim3(FWD_THREADS), 0, s, a);
-  hipLaunchKernelGGL((attn_dkv_kernel<HD>), dim3(a.hkv, (a.s + 127) / 128, a.b), dim3(THREADS), 0, s, a);
+    // 256 keys per workgroup (8 wavefronts, two per SIMD) when that still gives two workgroups per CU, else 128
+  if ((int64_t)a.b * a.hkv * ((a.s + 255) / 256) >= 512)
+    hipLaunchKernelGGL((attn_dkv_kernel<HD, 512>), dim3(a.hkv, (a.s + 255) / 256, a.b), dim3(512), 0, s, a);
+  else
+    hipLaunchKernelGGL((attn_dkv_kernel<HD, 256>), dim3(a.hkv, (a.s + 127) / 128, a.b), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
