@@ -146,13 +146,32 @@ __global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int ti
   const bf16* A = (const bf16*)g.A;
   const bf16* B = (const bf16*)g.B;
 
+  // Accumulators start at zero, or -- weight gradients, C += A^T.B -- at the current value of C: the read half of
+  // the read-modify-write then travels together with the first operand tiles instead of stalling the epilogue.
   f32x16 acc[4][TN];
+  if (EPI == EPI_ACC32) {
+    const __amdgpu_buffer_rsrc_t rsC = make_rsrc(g.C, (unsigned)(((int64_t)(g.M - 1) * g.ldc + g.N) * 4));
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i) {
+      const int m = m0 + wm + i * 32 + (lane & 31);
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+        for (int q = 0; q < 4; ++q) {
+          const int n = n0 + wn + j * 32 + q * 8 + (lane >> 5) * 4;
+          const unsigned off = (m < g.M && n < g.N) ? (unsigned)(((int64_t)m * g.ldc + n) * 4) : OOB;
+          const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsC, (int)off, 0, 0));
+          acc[i][j][q * 4] = v[0]; acc[i][j][q * 4 + 1] = v[1]; acc[i][j][q * 4 + 2] = v[2]; acc[i][j][q * 4 + 3] = v[3];
+        }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  }
 
   // buffer descriptors cover exactly the rows that exist: KC operand = [rows, ld], other = [K, ld]
   const __amdgpu_buffer_rsrc_t rsA = make_rsrc(A, (unsigned)(((int64_t)((AKC ? g.M : g.K) - 1) * g.lda + (AKC ? g.K : g.M)) * 2));
@@ -286,9 +305,7 @@ __global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int ti
         if (n >= g.N) continue;          // N % 8 == 0 and n % 4 == 0: the 4 columns are in or out together
         f32x4 v = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
         if (EPI == EPI_ACC32) {
-          float* c = (float*)g.C + (int64_t)m * g.ldc + n;
-          f32x4 old = *reinterpret_cast<f32x4*>(c);
-          *reinterpret_cast<f32x4*>(c) = old + v;
+          *reinterpret_cast<f32x4*>((float*)g.C + (int64_t)m * g.ldc + n) = v;   // acc already holds C + A^T.B
         } else {
           if (EPI == EPI_RESID && g.R) {
             if (g.r_f32) {
@@ -346,6 +363,7 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   const int64_t lim = (int64_t)1 << 30;   // operand byte offsets are 32-bit buffer offsets below 2 GiB
   const int64_t a_rows = g.mode == GEMM_TN ? g.K : g.M, b_rows = g.mode == GEMM_NT ? g.N : g.K;
   if (a_rows * g.lda >= lim || b_rows * g.ldb >= lim) return false;
+  if (g.acc_f32 && (int64_t)g.M * g.ldc >= lim / 2) return false;   // C is read through a 32-bit byte offset too
   switch (g.mode) {
     case GEMM_NN: return g.K % BK == 0 && !g.acc_f32;
     case GEMM_NT: return g.K % BK == 0 && !g.acc_f32 && !g.R && !g.c_f32;
