@@ -24,7 +24,8 @@
  *     library never allocates or frees device memory.  `ops`, config structs
  *     and all out-parameters are HOST memory.
  *   - All device work is enqueued on the HIP stream given to stage_init and the
- *     calls return without synchronising.  The caller synchronises that stream
+ *     calls return without synchronising (no host synchronisation and no device
+ *     allocation inside any call, so a schedule can be captured into a HIP graph).  The caller synchronises that stream
  *     before reading y / dx / gradients.  x and dy are copied into the stash
  *     when their op is enqueued (stream order), so they may be reused after
  *     the op's position in the stream has been reached.
