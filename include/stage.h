@@ -87,6 +87,8 @@ typedef struct {
   int32_t stash_cap;       /* max microbatches live (F started, W not finished); 0 = n_microbatches */
   int32_t enforce_mb_order;/* 1: ops of one kind must come in increasing microbatch index */
   float   norm_eps;        /* e.g. 1e-5 */
+  int32_t n_sub;           /* sub-blocks per op (the paper's n_sub, section 4.2.1): each covers n_layers / n_sub
+                              consecutive layers; 0 or 1 = whole ops only; must divide n_layers; at most 32 */
 } stage_config_t;
 
 typedef struct { size_t weights, grads, stash, workspace; } stage_sizes_t; /* bytes */
@@ -135,6 +137,23 @@ int stage_backward_weight(stage_t* st, int mb);
  * to the next call, so an iteration may be fed in pieces. */
 int stage_run_schedule(stage_t* st, const stage_op_t* ops, int n_ops,
                        const void* x_all_dev, const void* dy_all_dev, void* y_all_dev, void* dx_all_dev);
+
+/* Sub-block ops (paper section 4.2.1: each F / D / W block is cut into n_sub sub-blocks so that a schedule can fill
+ * bubbles at a finer grain).  Sub-block `sub` covers layers [sub, sub+1) * n_layers / n_sub.  Per microbatch:
+ *   F(mb, sub) in the order sub = 0, 1, ...; the first takes a stash slot (STAGE_E_STASH_FULL applies to it);
+ *   B(mb, sub) after every F(mb, .), in the order sub = n_sub-1, ..., 0;
+ *   W(mb, sub) any time after B(mb, sub), each once; the last one releases the slot.
+ * A whole op (stage_forward, ...) equals its sub-blocks issued back to back in that order, bit for bit.
+ * x is read by F(mb, 0) and y written by F(mb, n_sub-1); dy is read by B(mb, n_sub-1) and dx written by B(mb, 0);
+ * the other pointer of a call may be NULL.  With enforce_mb_order the microbatch-order rule applies per (kind, sub). */
+typedef struct { int32_t kind; int32_t mb; int32_t sub; } stage_subop_t;
+int stage_validate_subschedule(const stage_config_t* cfg, const stage_subop_t* ops, int n_ops,
+                               int* first_bad_index, int* peak_live);
+int stage_forward_sub(stage_t* st, int mb, int sub, const void* x_dev, void* y_dev);
+int stage_backward_input_sub(stage_t* st, int mb, int sub, const void* dy_dev, void* dx_dev);
+int stage_backward_weight_sub(stage_t* st, int mb, int sub);
+int stage_run_subschedule(stage_t* st, const stage_subop_t* ops, int n_ops,
+                          const void* x_all_dev, const void* dy_all_dev, void* y_all_dev, void* dx_all_dev);
 
 /* Borrowed pointer to the fp32 gradient buffer (== grads_dev) and its length.
  * After a full iteration it holds the SUM over microbatches of d<Y_m,dY_m>/dtheta. */

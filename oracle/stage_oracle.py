@@ -336,6 +336,78 @@ class OracleStage:
                 self.grads[li][k] += v
         del self._cache[mb], self._saved[mb]
 
+    # -- sub-block ops (paper section 4.2.1): sub-block `sub` of n_sub covers layers [sub, sub+1) * L / n_sub ----
+    def _layers(self, sub: int, n_sub: int):
+        per = len(self.params) // n_sub
+        assert per * n_sub == len(self.params)
+        return range(sub * per, (sub + 1) * per)
+
+    def forward_sub(self, mb: int, sub: int, n_sub: int, x=None):
+        """F of one sub-block; x is given for sub 0, later sub-blocks continue from the previous one's output.
+        Returns the sub-block's output (the stage output for the last sub-block)."""
+        if sub == 0:
+            assert mb not in self._cache
+            self._cache[mb] = []
+            y = self._x(x)
+        else:
+            assert len(self._cache[mb]) == self._layers(sub, n_sub)[0]
+            y = self._carry[mb]
+        for li in self._layers(sub, n_sub):
+            y, c = layer_forward(self.sh, self.params[li], y)
+            self._cache[mb].append(c)
+        if not hasattr(self, "_carry"):
+            self._carry = {}
+        self._carry[mb] = y
+        return y
+
+    def backward_input_sub(self, mb: int, sub: int, n_sub: int, dy=None):
+        """B of one sub-block, from the last sub-block down to 0; dy is given for the last one."""
+        L = len(self.params)
+        if sub == n_sub - 1:
+            assert len(self._cache[mb]) == L and mb not in self._saved
+            self._saved[mb] = [None] * L
+            d = self._x(dy)
+        else:
+            assert self._saved[mb][self._layers(sub, n_sub)[-1] + 1] is not None
+            d = self._carry[mb]
+        for li in reversed(self._layers(sub, n_sub)):
+            d, self._saved[mb][li], ng = layer_backward_input(self.sh, self.params[li], self._cache[mb][li], d)
+            for k, v in ng.items():
+                self.grads[li][k] += v
+        self._carry[mb] = d
+        return d
+
+    def backward_weight_sub(self, mb: int, sub: int, n_sub: int):
+        """W of one sub-block (any order after its B); the microbatch's cache is dropped after the last one."""
+        for li in self._layers(sub, n_sub):
+            assert self._saved[mb][li] is not None and self._saved[mb][li] != "done"
+            for k, v in layer_backward_weight(self.sh, self._cache[mb][li], self._saved[mb][li]).items():
+                self.grads[li][k] += v
+            self._saved[mb][li] = "done"
+        if all(sv == "done" for sv in self._saved[mb]):
+            del self._cache[mb], self._saved[mb], self._carry[mb]
+
+    def run_subschedule(self, ops, n_sub: int, X, dY):
+        """ops: (kind, mb, sub) triples. Returns (Y, dX, peak_live)."""
+        Y = np.zeros(np.shape(X), dtype=self.dtype)
+        dX = np.zeros(np.shape(X), dtype=self.dtype)
+        peak = self.live
+        for kind, mb, sub in ops:
+            if kind == F:
+                y = self.forward_sub(mb, sub, n_sub, X[mb] if sub == 0 else None)
+                if sub == n_sub - 1:
+                    Y[mb] = y
+            elif kind == B:
+                d = self.backward_input_sub(mb, sub, n_sub, dY[mb] if sub == n_sub - 1 else None)
+                if sub == 0:
+                    dX[mb] = d
+            elif kind == W:
+                self.backward_weight_sub(mb, sub, n_sub)
+            else:
+                raise ValueError(kind)
+            peak = max(peak, self.live)
+        return Y, dX, peak
+
     def backward_full(self, mb: int, dy):
         """Fused B+W (the paper's undivided backward block)."""
         assert mb in self._cache and mb not in self._saved

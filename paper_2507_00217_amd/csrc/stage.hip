@@ -20,7 +20,7 @@ constexpr size_t ALIGN = 256;
 inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Dims {
-  int L, d, h, hkv, hd, dkv, dq, f, fin, s, b, T, n_mb, cap;
+  int L, d, h, hkv, hd, dkv, dq, f, fin, s, b, T, n_mb, cap, n_sub;
   size_t es;  // bytes per element of the compute dtype
 };
 
@@ -38,6 +38,7 @@ bool make_dims(const stage_config_t* c, Dims* o) {
   if (c->causal != 0 && c->causal != 1) return false;
   if (c->stash_cap < 0 || c->stash_cap > c->n_microbatches) return false;
   if (!(c->norm_eps >= 0.f)) return false;
+  if (c->n_sub < 0 || c->n_sub > 32 || (c->n_sub > 0 && c->n_layers % c->n_sub)) return false;
   const size_t es = c->dtype == STAGE_DTYPE_FP32 ? 4 : 2;
   if (c->hidden > 256 * 4 * (int)(16 / es)) return false;  // one norm row must fit a workgroup's registers
   if ((int64_t)c->seq * c->mb_size > (1 << 20) || c->seq > 65536) return false;
@@ -46,6 +47,7 @@ bool make_dims(const stage_config_t* c, Dims* o) {
   o->fin = c->act == STAGE_ACT_SWIGLU ? 2 * c->ffn : c->ffn;
   o->s = c->seq; o->b = c->mb_size; o->T = c->seq * c->mb_size; o->n_mb = c->n_microbatches;
   o->cap = c->stash_cap ? c->stash_cap : c->n_microbatches;
+  o->n_sub = c->n_sub > 0 ? c->n_sub : 1;
   o->es = es;
   return true;
 }
@@ -120,31 +122,65 @@ WsOff ws_off(const Dims& D) {
 }
 
 // --- microbatch state machine ------------------------------------------------
-enum MbState : int8_t { MB_EMPTY = 0, MB_FWD = 1, MB_BWD = 2 };
-
 struct Tracker {
-  std::vector<int8_t> state;
+  // per microbatch: forward sub-blocks done (0..n_sub, in layer order), backward-input sub-blocks done (0..n_sub, in
+  // reverse layer order), and a bit per sub-block whose weight gradients are done
+  std::vector<int8_t> nf, nb;
+  std::vector<uint32_t> wmask;
+  int n_sub = 1;
   int live = 0, peak = 0;
-  int last[3] = {-1, -1, -1};
+  std::vector<int> last;          // [kind][sub] -> last microbatch that ran it in this iteration
   int cap = 0, enforce = 0;
 
-  // Returns STAGE_OK and applies the op, or an error and leaves state unchanged.
-  int step(int kind, int mb) {
-    if (kind < STAGE_F || kind > STAGE_W || mb < 0 || mb >= (int)state.size()) return STAGE_E_INVAL;
-    if ((int)state[mb] != kind) return STAGE_E_ORDER;   // F needs EMPTY(0), B needs FWD(1), W needs BWD(2)
-    if (enforce) {   // same-kind ops in increasing microbatch index: none skipped, none repeated out of order
-      if (mb <= last[kind]) return STAGE_E_ORDER;
+  void init(int n_mb, int nsub, int cap_, int enforce_) {
+    nf.assign(n_mb, 0); nb.assign(n_mb, 0); wmask.assign(n_mb, 0);
+    n_sub = nsub; cap = cap_; enforce = enforce_; live = peak = 0;
+    last.assign(3 * nsub, -1);
+  }
+  bool waits(int m, int kind, int sub) const {       // microbatch m could run (kind, sub) right now
+    if (kind == STAGE_B) return nf[m] == n_sub && sub == n_sub - 1 - nb[m];
+    if (kind == STAGE_W) return sub >= n_sub - nb[m] && !(wmask[m] >> sub & 1);
+    return false;
+  }
+  // One sub-block op. Returns STAGE_OK and applies it, or an error and leaves the state unchanged.
+  //   F(mb,s): s-th group of layers, s = 0,1,..  in order; the first one takes a stash slot
+  //   B(mb,s): after every F of mb; s = n_sub-1 down to 0
+  //   W(mb,s): after B(mb,s); any order; the last one releases the slot
+  int step_sub(int kind, int mb, int sub) {
+    if (kind < STAGE_F || kind > STAGE_W || mb < 0 || mb >= (int)nf.size() || sub < 0 || sub >= n_sub) return STAGE_E_INVAL;
+    if (kind == STAGE_F) { if (sub != nf[mb] || nb[mb] != 0 || wmask[mb] != 0) return STAGE_E_ORDER; }
+    else if (!waits(mb, kind, sub)) return STAGE_E_ORDER;
+    if (enforce) {   // same (kind, sub) in increasing microbatch index: none skipped, none out of order
+      if (mb <= last[kind * n_sub + sub]) return STAGE_E_ORDER;
       if (kind != STAGE_F)
         for (int m = 0; m < mb; ++m)
-          if ((int)state[m] == kind) return STAGE_E_ORDER;   // a smaller microbatch still waits for this op
+          if (waits(m, kind, sub)) return STAGE_E_ORDER;
     }
-    if (kind == STAGE_F && live >= cap) return STAGE_E_STASH_FULL;
-    state[mb] = (int8_t)((kind + 1) % 3);
-    last[kind] = mb;
-    if (kind == STAGE_F) { ++live; if (live > peak) peak = live; }
-    if (kind == STAGE_W) { --live; if (live == 0) last[0] = last[1] = last[2] = -1; }  // iteration boundary
+    if (kind == STAGE_F && sub == 0 && live >= cap) return STAGE_E_STASH_FULL;
+    last[kind * n_sub + sub] = mb;
+    if (kind == STAGE_F) { if (sub == 0) { ++live; if (live > peak) peak = live; } ++nf[mb]; }
+    else if (kind == STAGE_B) ++nb[mb];
+    else {
+      wmask[mb] |= 1u << sub;
+      if (wmask[mb] == (n_sub >= 32 ? 0xFFFFFFFFu : (1u << n_sub) - 1)) {          // microbatch complete: back to EMPTY
+        nf[mb] = nb[mb] = 0; wmask[mb] = 0;
+        if (--live == 0) std::fill(last.begin(), last.end(), -1);                    // iteration boundary
+      }
+    }
     return STAGE_OK;
   }
+  // A whole op = its sub-blocks in their natural order, all or nothing.
+  int step(int kind, int mb) {
+    if (n_sub == 1) return step_sub(kind, mb, 0);
+    Tracker t = *this;
+    for (int i = 0; i < n_sub; ++i) {
+      const int rc = t.step_sub(kind, mb, kind == STAGE_B ? n_sub - 1 - i : i);
+      if (rc != STAGE_OK) return rc;
+    }
+    *this = t;
+    return STAGE_OK;
+  }
+  bool slot_held(int mb) const { return nf[mb] > 0; }
 };
 
 }  // namespace
@@ -227,17 +263,18 @@ AttnArgs attn_args(const stage* st, const LayerOff& o, char* slot, const void* d
   return a;
 }
 
-int exec_forward(stage* st, int slot_idx, const void* x, void* y) {
+// layers [l0, l1): x is read when l0 == 0, y is written when l1 == L
+int exec_forward(stage* st, int slot_idx, const void* x, void* y, int l0, int l1) {
   const Dims& D = st->D;
   char* slot = st->stash + (size_t)slot_idx * st->slot_sz;
   const size_t per_layer = layer_off(D, 0).end;
   const WsOff w = ws_off(D);
   const size_t n_act = (size_t)D.T * D.d;
-  {
+  if (l0 == 0) {
     ProfScope ps(st, STAGE_K_COPY, (double)n_act * (D.es + sizeof(float)));
     HIPCHK(widen_to_f32(st->dt, (float*)(slot + layer_off(D, 0).x), x, n_act, st->stream));
   }
-  for (int l = 0; l < D.L; ++l) {
+  for (int l = l0; l < l1; ++l) {
     const LayerOff o = layer_off(D, per_layer * l);
     const LayerW W = layer_weights(st, l);
     const bool last = l + 1 == D.L;
@@ -267,19 +304,20 @@ int exec_forward(stage* st, int slot_idx, const void* x, void* y) {
   return STAGE_OK;
 }
 
-int exec_backward_input(stage* st, int slot_idx, const void* dy, void* dx) {
+// layers [l0, l1) in reverse: dy is read when l1 == L, dx is written when l0 == 0
+int exec_backward_input(stage* st, int slot_idx, const void* dy, void* dx, int l0, int l1) {
   const Dims& D = st->D;
   char* slot = st->stash + (size_t)slot_idx * st->slot_sz;
   const size_t per_layer = layer_off(D, 0).end;
   const WsOff w = ws_off(D);
   const size_t act_bytes = (size_t)D.T * D.d * D.es;
-  {
+  if (l1 == D.L) {
     ProfScope ps(st, STAGE_K_COPY, 2.0 * act_bytes);
     HIPCHK(copy_bytes(slot + layer_off(D, per_layer * (D.L - 1)).dyb, dy, act_bytes, st->stream));
   }
   void* da = st->ws + w.da;
   void* dn = st->ws + w.dn;
-  for (int l = D.L - 1; l >= 0; --l) {
+  for (int l = l1 - 1; l >= l0; --l) {
     const LayerOff o = layer_off(D, per_layer * l);
     const LayerW W = layer_weights(st, l);
     const bool last = l + 1 == D.L;
@@ -322,11 +360,11 @@ int exec_backward_input(stage* st, int slot_idx, const void* dy, void* dx) {
   return STAGE_OK;
 }
 
-int exec_backward_weight(stage* st, int slot_idx) {
+int exec_backward_weight(stage* st, int slot_idx, int l0, int l1) {
   const Dims& D = st->D;
   char* slot = st->stash + (size_t)slot_idx * st->slot_sz;
   const size_t per_layer = layer_off(D, 0).end;
-  for (int l = 0; l < D.L; ++l) {
+  for (int l = l0; l < l1; ++l) {
     const LayerOff o = layer_off(D, per_layer * l);
     const LayerW W = layer_weights(st, l);
     int rc;
@@ -338,22 +376,61 @@ int exec_backward_weight(stage* st, int slot_idx) {
   return STAGE_OK;
 }
 
-// Applies one already-validated op: allocator bookkeeping + launches.
-int apply_op(stage* st, int kind, int mb, const void* in, void* out) {
+// Applies one already-validated op (sub < 0: the whole op, every sub-block): allocator bookkeeping + launches.
+// `had_slot` / `holds_slot`: whether the microbatch held a stash slot before / holds one after the op.
+int apply_op(stage* st, int kind, int mb, int sub, bool had_slot, bool holds_slot, const void* in, void* out) {
+  const int per = st->D.L / st->D.n_sub;
+  const int l0 = sub < 0 ? 0 : sub * per, l1 = sub < 0 ? st->D.L : (sub + 1) * per;
   int rc = STAGE_OK;
   if (kind == STAGE_F) {
-    const int slot = st->free_slots.back();
-    st->free_slots.pop_back();
-    st->slot_of[mb] = slot;
-    rc = exec_forward(st, slot, in, out);
+    if (!had_slot) {
+      st->slot_of[mb] = st->free_slots.back();
+      st->free_slots.pop_back();
+    }
+    rc = exec_forward(st, st->slot_of[mb], in, out, l0, l1);
   } else if (kind == STAGE_B) {
-    rc = exec_backward_input(st, st->slot_of[mb], in, out);
+    rc = exec_backward_input(st, st->slot_of[mb], in, out, l0, l1);
   } else {
-    rc = exec_backward_weight(st, st->slot_of[mb]);
-    st->free_slots.push_back(st->slot_of[mb]);
-    st->slot_of[mb] = -1;
+    rc = exec_backward_weight(st, st->slot_of[mb], l0, l1);
+    if (!holds_slot) {
+      st->free_slots.push_back(st->slot_of[mb]);
+      st->slot_of[mb] = -1;
+    }
   }
   return rc;
+}
+
+// validate + apply one op against the stage's tracker
+int run_one(stage* st, int kind, int mb, int sub, const void* in, void* out) {
+  if (mb < 0 || mb >= st->D.n_mb) return STAGE_E_INVAL;
+  const bool had = st->tr.slot_held(mb);
+  const int rc = sub < 0 ? st->tr.step(kind, mb) : st->tr.step_sub(kind, mb, sub);
+  if (rc != STAGE_OK) return rc;
+  return apply_op(st, kind, mb, sub, had, st->tr.slot_held(mb), in, out);
+}
+
+// shared body of the two schedule runners: op i is (kind(i), mb(i), sub(i)), sub < 0 meaning a whole op
+template <typename GetOp>
+int run_list(stage* st, int n_ops, GetOp get, const void* x_all, const void* dy_all, void* y_all, void* dx_all) {
+  // validate the whole list on a copy of the tracker before enqueuing anything
+  Tracker probe = st->tr;
+  const int ns = st->D.n_sub;
+  for (int i = 0; i < n_ops; ++i) {
+    int kind, mb, sub; get(i, kind, mb, sub);
+    if (kind == STAGE_F && ((sub <= 0 && !x_all) || ((sub < 0 || sub == ns - 1) && !y_all))) return STAGE_E_INVAL;
+    if (kind == STAGE_B && (((sub < 0 || sub == ns - 1) && !dy_all) || (sub <= 0 && !dx_all))) return STAGE_E_INVAL;
+    const int rc = sub < 0 ? probe.step(kind, mb) : probe.step_sub(kind, mb, sub);
+    if (rc != STAGE_OK) return rc;
+  }
+  const size_t mb_bytes = (size_t)st->D.T * st->D.d * st->D.es;
+  for (int i = 0; i < n_ops; ++i) {
+    int kind, mb, sub; get(i, kind, mb, sub);
+    const void* in = kind == STAGE_F ? (const char*)x_all + mb_bytes * mb : kind == STAGE_B ? (const char*)dy_all + mb_bytes * mb : nullptr;
+    void* out = kind == STAGE_F ? (char*)y_all + mb_bytes * mb : kind == STAGE_B ? (char*)dx_all + mb_bytes * mb : nullptr;
+    const int rc = run_one(st, kind, mb, sub, in, out);
+    if (rc != STAGE_OK) return rc;
+  }
+  return STAGE_OK;
 }
 
 }  // namespace
@@ -377,7 +454,7 @@ int stage_validate_schedule(const stage_config_t* cfg, const stage_op_t* ops, in
   if (first_bad_index) *first_bad_index = -1;
   if (peak_live) *peak_live = 0;
   if (!make_dims(cfg, &D) || n_ops < 0 || (n_ops > 0 && !ops)) return STAGE_E_INVAL;
-  Tracker t; t.state.assign(D.n_mb, MB_EMPTY); t.cap = D.cap; t.enforce = cfg->enforce_mb_order;
+  Tracker t; t.init(D.n_mb, D.n_sub, D.cap, cfg->enforce_mb_order);
   for (int i = 0; i < n_ops; ++i) {
     const int rc = t.step(ops[i].kind, ops[i].mb);
     if (rc != STAGE_OK) {
@@ -416,7 +493,7 @@ int stage_init(const stage_config_t* cfg, void* weights_dev, void* grads_dev, vo
   st->stream = (hipStream_t)hip_stream;
   st->slot_sz = slot_bytes(D);
   st->n_param_elems = layer_param_elems(D, cfg->norm) * D.L;
-  st->tr.state.assign(D.n_mb, MB_EMPTY); st->tr.cap = D.cap; st->tr.enforce = cfg->enforce_mb_order;
+  st->tr.init(D.n_mb, D.n_sub, D.cap, cfg->enforce_mb_order);
   st->slot_of.assign(D.n_mb, -1);
   for (int i = D.cap - 1; i >= 0; --i) st->free_slots.push_back(i);
   if (fill_zero_f32(st->grads, st->n_param_elems, st->stream) != hipSuccess) { delete st; return STAGE_E_HIP; }
@@ -424,41 +501,65 @@ int stage_init(const stage_config_t* cfg, void* weights_dev, void* grads_dev, vo
   return STAGE_OK;
 }
 
-static int single_op(stage_t* st, int kind, int mb, const void* in, void* out) {
+static int single_op(stage_t* st, int kind, int mb, int sub, const void* in, void* out) {
   if (!st) return STAGE_E_INVAL;
   if (st->sticky) return st->sticky;
-  if (kind != STAGE_W && (!in || !out)) return STAGE_E_INVAL;
-  const int rc = st->tr.step(kind, mb);
-  if (rc != STAGE_OK) return rc;
-  return apply_op(st, kind, mb, in, out);
+  const int ns = st->D.n_sub;
+  const bool needs_in = kind == STAGE_F ? (sub <= 0) : kind == STAGE_B ? (sub < 0 || sub == ns - 1) : false;
+  const bool needs_out = kind == STAGE_F ? (sub < 0 || sub == ns - 1) : kind == STAGE_B ? (sub <= 0) : false;
+  if ((needs_in && !in) || (needs_out && !out)) return STAGE_E_INVAL;
+  return run_one(st, kind, mb, sub, in, out);
 }
 
-int stage_forward(stage_t* st, int mb, const void* x_dev, void* y_dev) { return single_op(st, STAGE_F, mb, x_dev, y_dev); }
-int stage_backward_input(stage_t* st, int mb, const void* dy_dev, void* dx_dev) { return single_op(st, STAGE_B, mb, dy_dev, dx_dev); }
-int stage_backward_weight(stage_t* st, int mb) { return single_op(st, STAGE_W, mb, nullptr, nullptr); }
+int stage_forward(stage_t* st, int mb, const void* x_dev, void* y_dev) { return single_op(st, STAGE_F, mb, -1, x_dev, y_dev); }
+int stage_backward_input(stage_t* st, int mb, const void* dy_dev, void* dx_dev) { return single_op(st, STAGE_B, mb, -1, dy_dev, dx_dev); }
+int stage_backward_weight(stage_t* st, int mb) { return single_op(st, STAGE_W, mb, -1, nullptr, nullptr); }
+
+static bool sub_ok(const stage_t* st, int sub) { return st && sub >= 0 && sub < st->D.n_sub; }
+int stage_forward_sub(stage_t* st, int mb, int sub, const void* x_dev, void* y_dev) {
+  return sub_ok(st, sub) ? single_op(st, STAGE_F, mb, sub, x_dev, y_dev) : STAGE_E_INVAL;
+}
+int stage_backward_input_sub(stage_t* st, int mb, int sub, const void* dy_dev, void* dx_dev) {
+  return sub_ok(st, sub) ? single_op(st, STAGE_B, mb, sub, dy_dev, dx_dev) : STAGE_E_INVAL;
+}
+int stage_backward_weight_sub(stage_t* st, int mb, int sub) {
+  return sub_ok(st, sub) ? single_op(st, STAGE_W, mb, sub, nullptr, nullptr) : STAGE_E_INVAL;
+}
 
 int stage_run_schedule(stage_t* st, const stage_op_t* ops, int n_ops, const void* x_all_dev, const void* dy_all_dev,
                        void* y_all_dev, void* dx_all_dev) {
   if (!st || n_ops < 0 || (n_ops > 0 && !ops)) return STAGE_E_INVAL;
   if (st->sticky) return st->sticky;
-  // validate the whole list on a copy of the tracker before enqueuing anything
-  Tracker probe = st->tr;
+  return run_list(st, n_ops, [&](int i, int& k, int& m, int& s) { k = ops[i].kind; m = ops[i].mb; s = -1; },
+                  x_all_dev, dy_all_dev, y_all_dev, dx_all_dev);
+}
+
+int stage_run_subschedule(stage_t* st, const stage_subop_t* ops, int n_ops, const void* x_all_dev, const void* dy_all_dev,
+                          void* y_all_dev, void* dx_all_dev) {
+  if (!st || n_ops < 0 || (n_ops > 0 && !ops)) return STAGE_E_INVAL;
+  if (st->sticky) return st->sticky;
+  for (int i = 0; i < n_ops; ++i)
+    if (ops[i].sub < 0 || ops[i].sub >= st->D.n_sub) return STAGE_E_INVAL;
+  return run_list(st, n_ops, [&](int i, int& k, int& m, int& s) { k = ops[i].kind; m = ops[i].mb; s = ops[i].sub; },
+                  x_all_dev, dy_all_dev, y_all_dev, dx_all_dev);
+}
+
+int stage_validate_subschedule(const stage_config_t* cfg, const stage_subop_t* ops, int n_ops, int* first_bad_index,
+                               int* peak_live) {
+  Dims D;
+  if (first_bad_index) *first_bad_index = -1;
+  if (peak_live) *peak_live = 0;
+  if (!make_dims(cfg, &D) || n_ops < 0 || (n_ops > 0 && !ops)) return STAGE_E_INVAL;
+  Tracker t; t.init(D.n_mb, D.n_sub, D.cap, cfg->enforce_mb_order);
   for (int i = 0; i < n_ops; ++i) {
-    if (ops[i].kind == STAGE_F && (!x_all_dev || !y_all_dev)) return STAGE_E_INVAL;
-    if (ops[i].kind == STAGE_B && (!dy_all_dev || !dx_all_dev)) return STAGE_E_INVAL;
-    const int rc = probe.step(ops[i].kind, ops[i].mb);
-    if (rc != STAGE_OK) return rc;
+    const int rc = t.step_sub(ops[i].kind, ops[i].mb, ops[i].sub);
+    if (rc != STAGE_OK) {
+      if (first_bad_index) *first_bad_index = i;
+      if (peak_live) *peak_live = t.peak;
+      return rc;
+    }
   }
-  const size_t mb_bytes = (size_t)st->D.T * st->D.d * st->D.es;
-  for (int i = 0; i < n_ops; ++i) {
-    const int kind = ops[i].kind, mb = ops[i].mb;
-    st->tr.step(kind, mb);
-    const void* in = kind == STAGE_F ? (const char*)x_all_dev + mb_bytes * mb
-                   : kind == STAGE_B ? (const char*)dy_all_dev + mb_bytes * mb : nullptr;
-    void* out = kind == STAGE_F ? (char*)y_all_dev + mb_bytes * mb : kind == STAGE_B ? (char*)dx_all_dev + mb_bytes * mb : nullptr;
-    const int rc = apply_op(st, kind, mb, in, out);
-    if (rc != STAGE_OK) return rc;
-  }
+  if (peak_live) *peak_live = t.peak;
   return STAGE_OK;
 }
 

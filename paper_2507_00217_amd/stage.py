@@ -28,7 +28,11 @@ OK, E_INVAL, E_ORDER, E_STASH_FULL, E_HIP = 0, -1, -2, -3, -4
 class StageConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_heads", "n_kv_heads", "ffn", "seq", "mb_size", "n_microbatches",
-        "norm", "act", "causal", "dtype", "stash_cap", "enforce_mb_order")] + [("norm_eps", C.c_float)]
+        "norm", "act", "causal", "dtype", "stash_cap", "enforce_mb_order")] + [("norm_eps", C.c_float), ("n_sub", C.c_int32)]
+
+
+class StageSubOp(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("mb", C.c_int32), ("sub", C.c_int32)]
 
 
 class StageOp(C.Structure):
@@ -58,7 +62,7 @@ def lib() -> C.CDLL:
         import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, ip = C.c_void_p, C.POINTER(C.c_int)
-        cfgp, opp = C.POINTER(StageConfig), C.POINTER(StageOp)
+        cfgp, opp, sopp = C.POINTER(StageConfig), C.POINTER(StageOp), C.POINTER(StageSubOp)
         sig = {
             "stage_query_sizes": (C.c_int, [cfgp, C.POINTER(StageSizes)]),
             "stage_validate_schedule": (C.c_int, [cfgp, opp, C.c_int, ip, ip]),
@@ -69,6 +73,11 @@ def lib() -> C.CDLL:
             "stage_backward_input": (C.c_int, [vp, C.c_int, vp, vp]),
             "stage_backward_weight": (C.c_int, [vp, C.c_int]),
             "stage_run_schedule": (C.c_int, [vp, opp, C.c_int, vp, vp, vp, vp]),
+            "stage_validate_subschedule": (C.c_int, [cfgp, sopp, C.c_int, ip, ip]),
+            "stage_forward_sub": (C.c_int, [vp, C.c_int, C.c_int, vp, vp]),
+            "stage_backward_input_sub": (C.c_int, [vp, C.c_int, C.c_int, vp, vp]),
+            "stage_backward_weight_sub": (C.c_int, [vp, C.c_int, C.c_int]),
+            "stage_run_subschedule": (C.c_int, [vp, sopp, C.c_int, vp, vp, vp, vp]),
             "stage_grads": (C.c_int, [vp, C.POINTER(vp), C.POINTER(C.c_size_t)]),
             "stage_zero_grads": (C.c_int, [vp]),
             "stage_stats": (C.c_int, [vp, ip, ip, C.POINTER(C.c_size_t)]),
@@ -95,7 +104,7 @@ def make_config(cfg: dict) -> StageConfig:
         ffn=cfg["ffn"], seq=cfg["seq"], mb_size=cfg["mb_size"], n_microbatches=cfg["n_microbatches"],
         norm=NORM[cfg["norm"]], act=ACT[cfg["act"]], causal=int(cfg.get("causal", True)), dtype=DTYPE[cfg["dtype"]],
         stash_cap=cfg.get("stash_cap", 0), enforce_mb_order=int(cfg.get("enforce_mb_order", 0)),
-        norm_eps=cfg.get("norm_eps", 1e-5))
+        norm_eps=cfg.get("norm_eps", 1e-5), n_sub=cfg.get("n_sub", 0))
 
 
 def make_ops(ops: Sequence[Tuple[int, int]]):
@@ -103,6 +112,20 @@ def make_ops(ops: Sequence[Tuple[int, int]]):
     for i, (k, m) in enumerate(ops):
         arr[i].kind, arr[i].mb = k, m
     return arr
+
+
+def make_subops(ops: Sequence[Tuple[int, int, int]]):
+    arr = (StageSubOp * max(1, len(ops)))()
+    for i, (k, m, sb) in enumerate(ops):
+        arr[i].kind, arr[i].mb, arr[i].sub = k, m, sb
+    return arr
+
+
+def stage_validate_subschedule(cfg: dict, ops) -> Tuple[int, int, int]:
+    """Returns (code, first_bad_index, peak_live)."""
+    bad, peak = C.c_int(-1), C.c_int(0)
+    rc = lib().stage_validate_subschedule(C.byref(make_config(cfg)), make_subops(ops), len(ops), C.byref(bad), C.byref(peak))
+    return rc, bad.value, peak.value
 
 
 def stage_query_sizes(cfg: dict) -> Dict[str, int]:
@@ -204,6 +227,22 @@ class Stage:
         arr = ops_c if ops_c is not None else make_ops(ops)
         p = lambda t: t.data_ptr() if t is not None else None
         self._chk(lib().stage_run_schedule(self.h, arr, len(ops), p(X), p(dY), p(Y), p(dX)), "stage_run_schedule")
+
+    def forward_sub(self, mb: int, sub: int, x, y):
+        p = lambda t: t.data_ptr() if t is not None else None
+        self._chk(lib().stage_forward_sub(self.h, mb, sub, p(x), p(y)), "stage_forward_sub")
+
+    def backward_input_sub(self, mb: int, sub: int, dy, dx):
+        p = lambda t: t.data_ptr() if t is not None else None
+        self._chk(lib().stage_backward_input_sub(self.h, mb, sub, p(dy), p(dx)), "stage_backward_input_sub")
+
+    def backward_weight_sub(self, mb: int, sub: int):
+        self._chk(lib().stage_backward_weight_sub(self.h, mb, sub), "stage_backward_weight_sub")
+
+    def run_subschedule(self, ops, X, dY, Y, dX):
+        p = lambda t: t.data_ptr() if t is not None else None
+        self._chk(lib().stage_run_subschedule(self.h, make_subops(ops), len(ops), p(X), p(dY), p(Y), p(dX)),
+                  "stage_run_subschedule")
 
     def zero_grads(self):
         self._chk(lib().stage_zero_grads(self.h), "stage_zero_grads")

@@ -247,6 +247,49 @@ def schedule_random(n_mb: int, cap: int, seed: int) -> List[Tuple[int, int]]:
     return ops
 
 
+def expand_to_subops(ops, n_sub: int) -> List[Tuple[int, int, int]]:
+    """Every whole op replaced by its sub-blocks back to back (F, W ascending; B descending)."""
+    out = []
+    for k, m in ops:
+        subs = range(n_sub - 1, -1, -1) if k == B else range(n_sub)
+        out += [(k, m, sb) for sb in subs]
+    return out
+
+
+def subschedule_interleaved(n_mb: int, n_sub: int, cap: int, seed: int) -> List[Tuple[int, int, int]]:
+    """Seeded random legal order at sub-block grain: F sub-blocks of a microbatch ascending, B descending after all
+    its F, W(mb, sub) any time after B(mb, sub); at most `cap` microbatches live; same (kind, sub) in microbatch order."""
+    rng_vals = _splitmix64(_key(seed, 4) + np.arange(4 * 3 * n_mb * n_sub, dtype=np.uint64) * _GOLD)
+    nf = [0] * n_mb; nb = [0] * n_mb; wdone = [set() for _ in range(n_mb)]
+    nxt = {}
+    ops, step = [], 0
+    live = lambda: sum(1 for m in range(n_mb) if nf[m] > 0 and len(wdone[m]) < n_sub)
+    while len(ops) < 3 * n_mb * n_sub:
+        cand = []
+        for m in range(n_mb):
+            if len(wdone[m]) == n_sub:
+                continue
+            if nf[m] < n_sub and (nf[m] > 0 or live() < cap):
+                cand.append((F, m, nf[m]))
+            if nf[m] == n_sub and nb[m] < n_sub:
+                cand.append((B, m, n_sub - 1 - nb[m]))
+            for sb in range(n_sub - nb[m], n_sub):
+                if sb not in wdone[m]:
+                    cand.append((W, m, sb))
+        cand = [c for c in cand if nxt.get((c[0], c[2]), 0) == c[1]]     # each (kind, sub) visits microbatches in order
+        k, m, sb = cand[int(rng_vals[step] % np.uint64(len(cand)))]
+        step += 1
+        nxt[(k, sb)] = m + 1
+        if k == F:
+            nf[m] += 1
+        elif k == B:
+            nb[m] += 1
+        else:
+            wdone[m].add(sb)
+        ops.append((k, m, sb))
+    return ops
+
+
 def make_schedule(cfg: dict, n_mb: int | None = None) -> List[Tuple[int, int]]:
     n = cfg["n_microbatches"] if n_mb is None else n_mb
     kind = cfg["schedule"]

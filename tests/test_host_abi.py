@@ -138,3 +138,63 @@ def test_random_order_violates_mb_order_only():
     ws = [m for k, m in ops if k == W]
     assert ws != sorted(ws)
     assert S.stage_validate_schedule(dict(cfg, enforce_mb_order=1), ops)[0] == S.E_ORDER
+
+
+def ref_validate_sub(ops, n_mb, n_sub, cap, enforce):
+    """Reference for the sub-block validator."""
+    nf, nb, wd = [0] * n_mb, [0] * n_mb, [set() for _ in range(n_mb)]
+    live = peak = 0
+    last = {}
+    def waits(m, k, s):
+        if k == B:
+            return nf[m] == n_sub and s == n_sub - 1 - nb[m]
+        if k == W:
+            return s >= n_sub - nb[m] and s not in wd[m]
+        return False
+    for i, (k, m, s) in enumerate(ops):
+        if not (0 <= k <= 2 and 0 <= m < n_mb and 0 <= s < n_sub):
+            return S.E_INVAL, i, peak
+        ok = (s == nf[m] and nb[m] == 0 and not wd[m]) if k == F else waits(m, k, s)
+        if not ok:
+            return S.E_ORDER, i, peak
+        if enforce and (m <= last.get((k, s), -1) or (k != F and any(waits(x, k, s) for x in range(m)))):
+            return S.E_ORDER, i, peak
+        if k == F and s == 0 and live >= cap:
+            return S.E_STASH_FULL, i, peak
+        last[(k, s)] = m
+        if k == F:
+            if s == 0:
+                live += 1; peak = max(peak, live)
+            nf[m] += 1
+        elif k == B:
+            nb[m] += 1
+        else:
+            wd[m].add(s)
+            if len(wd[m]) == n_sub:
+                nf[m] = nb[m] = 0; wd[m] = set(); live -= 1
+                if live == 0:
+                    last = {}
+    return 0, -1, peak
+
+
+@pytest.mark.parametrize("enforce", [0, 1])
+def test_sub_block_validator_brute_force(enforce):
+    n_mb, n_sub, cap = 2, 2, 1
+    cfg = dict(synth.CONFIGS["cfg1"], n_microbatches=n_mb, stash_cap=cap, enforce_mb_order=enforce, n_sub=n_sub)
+    alphabet = [(k, m, s) for k in range(3) for m in range(n_mb) for s in range(n_sub)]
+    n_ok = 0
+    for length in range(0, 5):
+        for ops in itertools.product(alphabet, repeat=length):
+            got = S.stage_validate_subschedule(cfg, list(ops))
+            assert got == ref_validate_sub(ops, n_mb, n_sub, cap, enforce), ops
+            n_ok += got[0] == 0
+    assert n_ok > 5
+    cfg = dict(cfg, n_microbatches=4, stash_cap=3, n_sub=2)
+    for seed in range(4):
+        ops = synth.subschedule_interleaved(4, 2, 3, seed)
+        got = S.stage_validate_subschedule(cfg, ops)
+        assert got == ref_validate_sub(ops, 4, 2, 3, enforce) and got[0] == 0
+        assert S.stage_validate_subschedule(dict(cfg, stash_cap=1), ops)[0] in (S.E_STASH_FULL, 0)
+    assert S.stage_validate_subschedule(cfg, [(0, 0, 2)])[0] == S.E_INVAL
+    with pytest.raises(S.StageError):
+        S.stage_query_sizes(dict(cfg, n_sub=3))          # must divide n_layers

@@ -245,3 +245,29 @@ def test_gqa_with_all_kv_heads_is_mha():
     assert np.allclose(dqg, dqm, rtol=1e-13)
     assert np.allclose(dkg, dkm.reshape(1, 6, 2, 2, 4).sum(3), rtol=1e-12)
     assert np.allclose(dvg, dvm.reshape(1, 6, 2, 2, 4).sum(3), rtol=1e-12)
+
+
+@pytest.mark.parametrize("n_sub", [2, 4])
+def test_sub_blocks_in_order_equal_whole_ops(n_sub):
+    """Sub-block ops (n_sub groups of layers per F/B/W op): back to back they are the whole op, bit for bit; in any
+    legal interleaving across microbatches they give the same outputs and (microbatch-ordered) the same gradients."""
+    cfg = tiny_cfg("rmsnorm", "swiglu", 1, L=4, n_mb=4)
+    sh, params, X, G = setup(cfg)
+    whole = so.OracleStage(sh, params)
+    ops = synth.schedule_1f1b(4, 2)
+    Y0, dX0, _ = whole.run_schedule(ops, X, G)
+    a = so.OracleStage(sh, params)
+    Y1, dX1, pk = a.run_subschedule(synth.expand_to_subops(ops, n_sub), n_sub, X, G)
+    assert np.array_equal(Y0, Y1) and np.array_equal(dX0, dX1) and a.live == 0 and pk == 3
+    for la, lb in zip(whole.grads, a.grads):
+        for k in la:
+            assert np.array_equal(la[k], lb[k]), k
+    for seed in range(3):
+        sub_ops = synth.subschedule_interleaved(4, n_sub, 3, seed)
+        assert sub_ops != synth.expand_to_subops(ops, n_sub)
+        b = so.OracleStage(sh, params)
+        Y2, dX2, pk = b.run_subschedule(sub_ops, n_sub, X, G)
+        assert np.array_equal(Y0, Y2) and np.array_equal(dX0, dX2) and b.live == 0 and pk <= 3
+        for la, lb in zip(whole.grads, b.grads):
+            for k in la:
+                assert np.array_equal(la[k], lb[k]), k
