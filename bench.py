@@ -167,6 +167,20 @@ def main():
                 "flops_per_launch": gemm_work / gemm_n, "avg_launch_ms": round(gemm_ms / gemm_n, 5),
                 "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.config) if args.kernel_set == 0 else None}
     stats = st.stats()
+    # what the measured block times mean for a pipeline (the paper's performance model, host code): this stage's
+    # T_F/T_D/T_W replicated over 8 stages in 2 datacenters, 2 x n_PP microbatches, memory of 1F1B, with latency and
+    # bandwidth delays of 2 T_F on the cross-datacenter hop (the paper's hardest setting); seconds per microbatch
+    from paper_2507_00217_amd import sched as SC
+    tf, td, tw = (op_ms[k] / n_mb * 1e-3 for k in (S.F, S.B, S.W))
+    n_pp = 8
+    model = {}
+    for name, (lat, bw) in (("no_delay", (0.0, 0.0)), ("delay_2_2", (2.0 * tf, 2.0 * tf))):
+        a, b = synth.delay_matrices(n_pp, 2, lat, bw)
+        pl, keep = SC.make_params(n_pp, 2 * n_pp, 4, [tf] * n_pp, [td] * n_pp, [tw] * n_pp, m_limit=float(n_pp),
+                                  alpha=a, beta=b, msg_bytes=1.0)
+        _, mk = SC.crosspipe_greedy(pl)
+        rc, _, mk_1f1b = SC.crosspipe_simulate(pl, synth.pipeline_1f1b(n_pp, 2 * n_pp, 4))
+        model[name] = {"greedy_s_per_mb": round(mk / (2 * n_pp), 5), "onef1b_s_per_mb": round(mk_1f1b / (2 * n_pp), 5)}
     out = {
         "metric": "stage TFLOP/s per schedule iteration (F+B+W of all microbatches; % of bf16 MFMA peak in frac_peak)",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -180,6 +194,8 @@ def main():
         "frac_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "iter_tflop": round(iter_flops / 1e12, 2),
         "per_op": per_op, "kernels": kernels, "roofline": roofline,
+        "pipeline_model": dict(model, note="8 stages x this stage's measured T_F/T_D/T_W, 16 microbatches, n_sub 4, memory of "
+                               "1F1B; paper context: -33.6 % vs static at T_bw/T_F = 2 on 8-32 GH200 (M70, TP4 PP8)"),
     }
     st.close()
     del st

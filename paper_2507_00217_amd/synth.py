@@ -314,3 +314,34 @@ def peak_live(ops) -> int:
             live -= 1
         peak = max(peak, live)
     return peak
+
+
+# ---------------------------------------------------------------------------
+# whole-pipeline inputs for the schedule generator / performance model:
+# static per-stage orders (paper section 5.1, table of static schedules) as
+# (kind, mb, sub) lists per stage, kind 1 = the input-gradient block D
+# ---------------------------------------------------------------------------
+
+def pipeline_1f1b(n_pp: int, n_mb: int, n_sub: int = 1) -> List[List[Tuple[int, int, int]]]:
+    """1F1B with the weight gradient combined: stage s warms up with n_pp - s - 1 forwards, then alternates one
+    forward and one backward (D immediately followed by its W)."""
+    out = []
+    for s in range(n_pp):
+        warm = min(n_pp - s - 1, n_mb)
+        ops = [(F, i) for i in range(warm)]
+        for i in range(n_mb):
+            if i + warm < n_mb:
+                ops.append((F, i + warm))
+            ops += [(B, i), (W, i)]
+        out.append(expand_to_subops(ops, n_sub))
+    return out
+
+
+def delay_matrices(n_pp: int, n_dc: int, lat: float, inv_bw: float):
+    """alpha / beta matrices for n_pp stages spread evenly over n_dc datacenters in order: only links that cross a
+    datacenter boundary have latency `lat` and inverse bandwidth `inv_bw`; links inside one are free."""
+    per = n_pp // n_dc
+    dc = [min(i // per, n_dc - 1) for i in range(n_pp)]
+    alpha = [[lat if dc[i] != dc[j] else 0.0 for j in range(n_pp)] for i in range(n_pp)]
+    beta = [[inv_bw if dc[i] != dc[j] else 0.0 for j in range(n_pp)] for i in range(n_pp)]
+    return alpha, beta

@@ -21,7 +21,7 @@ def declared_symbols():
         if fn.endswith(".h"):
             txt = open(os.path.join(ROOT, "include", fn)).read()
             txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
-            names |= set(re.findall(r"\b(stage_\w+)\s*\(", txt))
+            names |= set(re.findall(r"\b((?:stage|crosspipe)_\w+)\s*\(", txt))
     return names
 
 
@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(S.LIB_PATH)
     names = declared_symbols()
     assert {"stage_init", "stage_forward", "stage_backward_input", "stage_backward_weight", "stage_run_schedule",
-            "stage_grads", "stage_kernel_gemm"} <= names
+            "stage_grads", "stage_kernel_gemm", "crosspipe_greedy", "crosspipe_simulate", "crosspipe_stage_ops"} <= names
     for n in names:
         assert hasattr(lib, n), n
 
