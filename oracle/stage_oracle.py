@@ -293,9 +293,13 @@ class OracleStage:
     """State: params, accumulated grads, and per-microbatch caches that live
     from F(m) to W(m) (section 3.2).  Gradients are *summed* over microbatches."""
 
-    def __init__(self, sh: Shape, params: Params, dtype=np.float64):
+    def __init__(self, sh: Shape, params: Params, dtype=np.float64, recompute: bool = False):
+        """recompute: layer-wise activation recomputation (the memory/batch-size trade-off's Case 2, section 7.2):
+        F keeps only every layer's input; B rebuilds a layer's cache by running its forward again just before
+        that layer's backward, and the rebuilt cache then lives until W."""
         self.sh = sh
         self.dtype = dtype
+        self.recompute = recompute
         self.params = [{k: np.asarray(v, dtype=dtype) for k, v in lp.items()} for lp in params]
         self.zero_grads()
         self._cache: Dict[int, list] = {}
@@ -314,16 +318,38 @@ class OracleStage:
         y = self._x(x)
         for lp in self.params:
             y, c = layer_forward(self.sh, lp, y)
-            caches.append(c)
+            caches.append(self._keep(c))
         self._cache[mb] = caches
         return y
+
+    def _keep(self, c):
+        """What F leaves in the stash for one layer."""
+        return {"x": c["x"]} if self.recompute else c
+
+    def _full(self, mb: int, li: int):
+        """The layer's complete cache, rebuilt from its stashed input when only that was kept."""
+        c = self._cache[mb][li]
+        if len(c) == 1:
+            _, c = layer_forward(self.sh, self.params[li], c["x"])
+            self._cache[mb][li] = c
+        return c
+
+    def stash_elems(self, mb: int) -> int:
+        """Array elements held for a microbatch right now (stash footprint in elements)."""
+        def count(v):
+            if isinstance(v, np.ndarray):
+                return v.size
+            if isinstance(v, (tuple, list)):
+                return sum(count(e) for e in v)
+            return 0
+        return sum(count(v) for c in self._cache.get(mb, []) for v in c.values())
 
     def backward_input(self, mb: int, dy):
         assert mb in self._cache and mb not in self._saved, "B needs F once"
         d = self._x(dy)
         saved = [None] * len(self.params)
         for li in reversed(range(len(self.params))):
-            d, saved[li], ng = layer_backward_input(self.sh, self.params[li], self._cache[mb][li], d)
+            d, saved[li], ng = layer_backward_input(self.sh, self.params[li], self._full(mb, li), d)
             for k, v in ng.items():
                 self.grads[li][k] += v
         self._saved[mb] = saved
@@ -354,7 +380,7 @@ class OracleStage:
             y = self._carry[mb]
         for li in self._layers(sub, n_sub):
             y, c = layer_forward(self.sh, self.params[li], y)
-            self._cache[mb].append(c)
+            self._cache[mb].append(self._keep(c))
         if not hasattr(self, "_carry"):
             self._carry = {}
         self._carry[mb] = y
@@ -371,7 +397,7 @@ class OracleStage:
             assert self._saved[mb][self._layers(sub, n_sub)[-1] + 1] is not None
             d = self._carry[mb]
         for li in reversed(self._layers(sub, n_sub)):
-            d, self._saved[mb][li], ng = layer_backward_input(self.sh, self.params[li], self._cache[mb][li], d)
+            d, self._saved[mb][li], ng = layer_backward_input(self.sh, self.params[li], self._full(mb, li), d)
             for k, v in ng.items():
                 self.grads[li][k] += v
         self._carry[mb] = d
@@ -413,7 +439,7 @@ class OracleStage:
         assert mb in self._cache and mb not in self._saved
         d = self._x(dy)
         for li in reversed(range(len(self.params))):
-            d, gr = layer_backward_full(self.sh, self.params[li], self._cache[mb][li], d)
+            d, gr = layer_backward_full(self.sh, self.params[li], self._full(mb, li), d)
             for k, v in gr.items():
                 self.grads[li][k] += v
         del self._cache[mb]

@@ -271,3 +271,40 @@ def test_sub_blocks_in_order_equal_whole_ops(n_sub):
         for la, lb in zip(whole.grads, b.grads):
             for k in la:
                 assert np.array_equal(la[k], lb[k]), k
+
+
+@pytest.mark.parametrize("norm,act,n_kv,causal", VARIANTS[:3])
+def test_recomputation_changes_memory_not_results(norm, act, n_kv, causal):
+    """Layer-wise activation recomputation (section 7.2, Case 2): between F and B only each layer's input is held
+    (L * tokens * hidden elements); B rebuilds the rest; outputs and gradients are bit-identical to the plain path,
+    for whole ops, fused backward and interleaved sub-blocks.  Also against torch autograd through the plain path's
+    own pin (equality carries it over)."""
+    cfg = tiny_cfg(norm, act, n_kv, causal, L=4, n_mb=4)
+    sh, params, X, G = setup(cfg)
+    plain, rec = so.OracleStage(sh, params), so.OracleStage(sh, params, recompute=True)
+    tokens = cfg["mb_size"] * cfg["seq"]
+    for st in (plain, rec):
+        st.forward(0, X[0])
+    assert rec.stash_elems(0) == cfg["n_layers"] * tokens * cfg["hidden"]
+    assert plain.stash_elems(0) > 8 * rec.stash_elems(0)
+    d0, d1 = plain.backward_input(0, G[0]), rec.backward_input(0, G[0])
+    assert np.array_equal(d0, d1)
+    assert rec.stash_elems(0) == plain.stash_elems(0)          # rebuilt caches live from B to W
+    plain.backward_weight(0); rec.backward_weight(0)
+    assert rec.live == 0 and rec.stash_elems(0) == 0
+    ops = synth.schedule_1f1b(4, 2)
+    plain, rec = so.OracleStage(sh, params), so.OracleStage(sh, params, recompute=True)
+    Y0, dX0, _ = plain.run_schedule(ops, X, G)
+    Y1, dX1, _ = rec.run_schedule(ops, X, G)
+    sub = so.OracleStage(sh, params, recompute=True)
+    Y2, dX2, _ = sub.run_subschedule(synth.subschedule_interleaved(4, 2, 3, 5), 2, X, G)
+    fused = so.OracleStage(sh, params, recompute=True)
+    for m in range(4):
+        fused.forward(m, X[m])
+    dX3 = np.stack([fused.backward_full(m, G[m]) for m in range(4)])
+    assert np.array_equal(Y0, Y1) and np.array_equal(dX0, dX1) and np.array_equal(Y0, Y2) and np.array_equal(dX0, dX2)
+    assert np.array_equal(dX0.reshape(dX3.shape), dX3)
+    for la, lb, lc, ld in zip(plain.grads, rec.grads, sub.grads, fused.grads):
+        for k in la:
+            assert np.array_equal(la[k], lb[k]) and np.array_equal(la[k], lc[k]), k
+            np.testing.assert_allclose(ld[k], la[k], rtol=1e-12, atol=1e-12)
