@@ -85,6 +85,10 @@ def main():
     ap.add_argument("--config", default="cfg3")
     ap.add_argument("--kernel-set", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--schedule", default=None, help="override the config's schedule (1f1b, w_deferred, w_lag1, greedy)")
+    ap.add_argument("--recompute", type=int, default=0, metavar="CAP",
+                    help="layer-wise activation recomputation with at most CAP rebuilt stashes (0 = off); the reported "
+                         "TFLOP/s still counts each layer's forward once, so the tax shows as lower throughput")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -95,6 +99,10 @@ def main():
     from paper_2507_00217_amd import synth
 
     cfg = dict(synth.CONFIGS[args.config], enforce_mb_order=1)
+    if args.schedule:
+        cfg["schedule"] = args.schedule
+    if args.recompute:
+        cfg.update(recompute=1, recompute_cap=args.recompute)
     ops = synth.make_schedule(cfg)
     n_mb, L = cfg["n_microbatches"], cfg["n_layers"]
     tdt = torch.float32 if cfg["dtype"] == "fp32" else torch.bfloat16
@@ -188,7 +196,8 @@ def main():
         "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": f"{args.config}: {L} layers, hidden {cfg['hidden']}, heads {cfg['n_heads']}/{cfg['n_kv_heads']}, "
                                f"ffn {cfg['ffn']}, {cfg['norm']}+{cfg['act']}, seq {cfg['seq']}, mb_size {cfg['mb_size']}, "
-                               f"{n_mb} microbatches, schedule {cfg['schedule']}, stash cap {cfg['stash_cap'] or n_mb}",
+                               f"{n_mb} microbatches, schedule {cfg['schedule']}, stash cap {cfg['stash_cap'] or n_mb}"
+                               + (f", recomputation with {args.recompute} rebuilt stashes" if args.recompute else ""),
                    "ops": len(ops), "peak_live": stats["peak_live"], "peak_stash_GiB": round(stats["peak_stash_bytes"] / 2 ** 30, 2),
                    "kernel_set": args.kernel_set},
         "frac_peak": round(tflops / PEAK_BF16_TFLOPS, 4),

@@ -56,7 +56,7 @@ enum {
   STAGE_OK = 0,
   STAGE_E_INVAL = -1,      /* null pointer, bad shape, unsupported head_dim, mb out of range */
   STAGE_E_ORDER = -2,      /* F twice, B before F or twice, W before B or twice, mb-order violation */
-  STAGE_E_STASH_FULL = -3, /* F while stash_cap microbatches are live */
+  STAGE_E_STASH_FULL = -3, /* F while stash_cap microbatches are live; B while recompute_cap hold a rebuilt stash */
   STAGE_E_HIP = -4         /* a kernel launch or runtime call failed */
 };
 
@@ -89,12 +89,20 @@ typedef struct {
   float   norm_eps;        /* e.g. 1e-5 */
   int32_t n_sub;           /* sub-blocks per op (the paper's n_sub, section 4.2.1): each covers n_layers / n_sub
                               consecutive layers; 0 or 1 = whole ops only; must divide n_layers; at most 32 */
+  int32_t recompute;       /* 1: layer-wise activation recomputation (section 7.2, Case 2 of the memory / batch-size
+                              trade-off): F keeps only every layer's fp32 input; B runs a layer's forward again
+                              (minus its last GEMM) right before that layer's backward, into a full-size slot that
+                              the microbatch holds from its first B sub-block to its last W.  Results are bit-identical
+                              to recompute = 0. */
+  int32_t recompute_cap;   /* recompute = 1: max microbatches holding such a full-size slot (B started, W not
+                              finished); 0 = stash_cap; at most stash_cap.  Must be 0 when recompute = 0. */
 } stage_config_t;
 
 typedef struct { size_t weights, grads, stash, workspace; } stage_sizes_t; /* bytes */
 
 /* Host only (no GPU needed). Bytes the caller must allocate for stage_init.
- * stash = stash_cap slots of equal size. */
+ * stash = stash_cap slots of equal size; under recomputation stash_cap small slots (layer inputs) followed by
+ * recompute_cap full-size ones. */
 int stage_query_sizes(const stage_config_t* cfg, stage_sizes_t* out);
 
 /* Host only. Checks an op list against the microbatch state machine
@@ -160,7 +168,7 @@ int stage_run_subschedule(stage_t* st, const stage_subop_t* ops, int n_ops,
 int stage_grads(stage_t* st, float** grads_dev, size_t* n_elems);
 int stage_zero_grads(stage_t* st);
 
-/* Counters: live microbatches now, their peak since init, peak stash bytes in use. */
+/* Counters: live microbatches now, their peak since init, peak stash bytes in use (slots of both kinds). */
 int stage_stats(stage_t* st, int* live, int* peak_live, size_t* peak_stash_bytes);
 
 /* Kernel selection for debugging and A/B measurements: 0 = tuned gfx950 kernels

@@ -21,6 +21,7 @@ inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Dims {
   int L, d, h, hkv, hd, dkv, dq, f, fin, s, b, T, n_mb, cap, n_sub;
+  int recompute, hcap;   // layer-wise recomputation on; cap on microbatches holding a rebuilt stash (B started, W not finished)
   size_t es;  // bytes per element of the compute dtype
 };
 
@@ -39,6 +40,8 @@ bool make_dims(const stage_config_t* c, Dims* o) {
   if (c->stash_cap < 0 || c->stash_cap > c->n_microbatches) return false;
   if (!(c->norm_eps >= 0.f)) return false;
   if (c->n_sub < 0 || c->n_sub > 32 || (c->n_sub > 0 && c->n_layers % c->n_sub)) return false;
+  if ((c->recompute != 0 && c->recompute != 1) || c->recompute_cap < 0 || c->recompute_cap > c->n_microbatches) return false;
+  if (!c->recompute && c->recompute_cap) return false;
   const size_t es = c->dtype == STAGE_DTYPE_FP32 ? 4 : 2;
   if (c->hidden > 256 * 4 * (int)(16 / es)) return false;  // one norm row must fit a workgroup's registers
   if ((int64_t)c->seq * c->mb_size > (1 << 20) || c->seq > 65536) return false;
@@ -48,6 +51,9 @@ bool make_dims(const stage_config_t* c, Dims* o) {
   o->s = c->seq; o->b = c->mb_size; o->T = c->seq * c->mb_size; o->n_mb = c->n_microbatches;
   o->cap = c->stash_cap ? c->stash_cap : c->n_microbatches;
   o->n_sub = c->n_sub > 0 ? c->n_sub : 1;
+  o->recompute = c->recompute;
+  o->hcap = !c->recompute ? 0 : (c->recompute_cap ? c->recompute_cap : o->cap);
+  if (o->hcap > o->cap) return false;   // a microbatch with a rebuilt stash is also live
   o->es = es;
   return true;
 }
@@ -83,13 +89,19 @@ size_t param_offset(const Dims& D, int norm, int layer, int pid) {
 // The residual stream (x, x1 going forward; dx1, dx coming back, written in place over them) is kept in fp32
 // whatever the compute dtype: in bf16 it would be rounded twice per layer in each direction and those roundings
 // dominate the stage's error.  GEMM operands derived from it (dyb, dx1b) are stored in the compute dtype.
+//
+// Without recomputation a slot is L such layer records and lives from F to W.  With layer-wise recomputation
+// (section 7.2, Case 2) the layer inputs x live apart, in a small slot of L fp32 [T, d] tensors held from F to W;
+// everything else is a layer record without x: F runs every layer through one such record in the workspace and
+// keeps nothing of it, B rebuilds it layer by layer (forward again, minus the last GEMM, whose output is the
+// next layer's stashed x) into a big slot that is held from the microbatch's first B sub-block to its last W.
 struct LayerOff { size_t x, n1, qkv, dqkv, o, x1, n2, z, a, dyb, dx1b, st1, st2, lse, end; };
 
-LayerOff layer_off(const Dims& D, size_t base) {
+LayerOff layer_off(const Dims& D, size_t base, bool with_x = true) {
   LayerOff o; size_t p = base;
   const size_t T = D.T;
   auto take = [&](size_t bytes) { size_t r = p; p += up(bytes); return r; };
-  o.x = take(T * D.d * sizeof(float));
+  o.x = take(with_x ? T * D.d * sizeof(float) : 0);
   o.n1 = take(T * D.d * D.es);
   o.qkv = take(T * D.dq * D.es);
   o.dqkv = take(T * D.dq * D.es);
@@ -107,9 +119,14 @@ LayerOff layer_off(const Dims& D, size_t base) {
   return o;
 }
 
-size_t slot_bytes(const Dims& D) { return layer_off(D, 0).end * D.L; }
+size_t x_bytes(const Dims& D) { return up((size_t)D.T * D.d * sizeof(float)); }
+size_t rec_bytes(const Dims& D) { return layer_off(D, 0, !D.recompute).end; }        // one layer record
+// slot held from F to W, and (recomputation only) the slot held from B to W
+size_t slot_bytes(const Dims& D) { return (D.recompute ? x_bytes(D) : rec_bytes(D)) * D.L; }
+size_t big_slot_bytes(const Dims& D) { return D.recompute ? rec_bytes(D) * D.L : 0; }
+size_t stash_bytes(const Dims& D) { return slot_bytes(D) * D.cap + big_slot_bytes(D) * D.hcap; }
 
-struct WsOff { size_t da, dn, delta, partial, end; };
+struct WsOff { size_t da, dn, delta, partial, rec, end; };
 WsOff ws_off(const Dims& D) {
   WsOff w; size_t p = 0;
   auto take = [&](size_t bytes) { size_t r = p; p += up(bytes); return r; };
@@ -117,6 +134,7 @@ WsOff ws_off(const Dims& D) {
   w.dn = take((size_t)D.T * D.d * D.es);
   w.delta = take((size_t)D.b * D.h * D.s * sizeof(float));
   w.partial = take((size_t)norm_partial_rows() * 2 * D.d * sizeof(float));
+  w.rec = take(D.recompute ? rec_bytes(D) : 0);       // the layer record F works in under recomputation
   w.end = p;
   return w;
 }
@@ -129,14 +147,18 @@ struct Tracker {
   std::vector<uint32_t> wmask;
   int n_sub = 1;
   int live = 0, peak = 0;
+  int hlive = 0, hpeak = 0;       // microbatches between their first B sub-block and their last W
   std::vector<int> last;          // [kind][sub] -> last microbatch that ran it in this iteration
-  int cap = 0, enforce = 0;
+  int cap = 0, hcap = 0, enforce = 0;   // hcap 0: no limit on hlive (no recomputation)
+  size_t slot_b = 0, big_b = 0, peak_b = 0;   // bytes per slot of either kind, peak bytes in use
 
-  void init(int n_mb, int nsub, int cap_, int enforce_) {
-    nf.assign(n_mb, 0); nb.assign(n_mb, 0); wmask.assign(n_mb, 0);
-    n_sub = nsub; cap = cap_; enforce = enforce_; live = peak = 0;
-    last.assign(3 * nsub, -1);
+  void init(const Dims& D, int enforce_) {
+    nf.assign(D.n_mb, 0); nb.assign(D.n_mb, 0); wmask.assign(D.n_mb, 0);
+    n_sub = D.n_sub; cap = D.cap; hcap = D.hcap; enforce = enforce_; live = peak = hlive = hpeak = 0;
+    slot_b = slot_bytes(D); big_b = big_slot_bytes(D); peak_b = 0;
+    last.assign(3 * n_sub, -1);
   }
+  void note_bytes() { const size_t b = live * slot_b + hlive * big_b; if (b > peak_b) peak_b = b; }
   bool waits(int m, int kind, int sub) const {       // microbatch m could run (kind, sub) right now
     if (kind == STAGE_B) return nf[m] == n_sub && sub == n_sub - 1 - nb[m];
     if (kind == STAGE_W) return sub >= n_sub - nb[m] && !(wmask[m] >> sub & 1);
@@ -144,7 +166,7 @@ struct Tracker {
   }
   // One sub-block op. Returns STAGE_OK and applies it, or an error and leaves the state unchanged.
   //   F(mb,s): s-th group of layers, s = 0,1,..  in order; the first one takes a stash slot
-  //   B(mb,s): after every F of mb; s = n_sub-1 down to 0
+  //   B(mb,s): after every F of mb; s = n_sub-1 down to 0; under recomputation the first one takes a big slot
   //   W(mb,s): after B(mb,s); any order; the last one releases the slot
   int step_sub(int kind, int mb, int sub) {
     if (kind < STAGE_F || kind > STAGE_W || mb < 0 || mb >= (int)nf.size() || sub < 0 || sub >= n_sub) return STAGE_E_INVAL;
@@ -157,13 +179,15 @@ struct Tracker {
           if (waits(m, kind, sub)) return STAGE_E_ORDER;
     }
     if (kind == STAGE_F && sub == 0 && live >= cap) return STAGE_E_STASH_FULL;
+    if (kind == STAGE_B && nb[mb] == 0 && hcap > 0 && hlive >= hcap) return STAGE_E_STASH_FULL;
     last[kind * n_sub + sub] = mb;
-    if (kind == STAGE_F) { if (sub == 0) { ++live; if (live > peak) peak = live; } ++nf[mb]; }
-    else if (kind == STAGE_B) ++nb[mb];
+    if (kind == STAGE_F) { if (sub == 0) { ++live; if (live > peak) peak = live; note_bytes(); } ++nf[mb]; }
+    else if (kind == STAGE_B) { if (nb[mb] == 0) { ++hlive; if (hlive > hpeak) hpeak = hlive; note_bytes(); } ++nb[mb]; }
     else {
       wmask[mb] |= 1u << sub;
       if (wmask[mb] == (n_sub >= 32 ? 0xFFFFFFFFu : (1u << n_sub) - 1)) {          // microbatch complete: back to EMPTY
         nf[mb] = nb[mb] = 0; wmask[mb] = 0;
+        --hlive;
         if (--live == 0) std::fill(last.begin(), last.end(), -1);                    // iteration boundary
       }
     }
@@ -181,6 +205,7 @@ struct Tracker {
     return STAGE_OK;
   }
   bool slot_held(int mb) const { return nf[mb] > 0; }
+  bool big_held(int mb) const { return nb[mb] > 0; }
 };
 
 }  // namespace
@@ -191,10 +216,10 @@ struct stage {
   DType dt;
   char* weights; float* grads; char* stash; char* ws;
   hipStream_t stream;
-  size_t slot_sz, n_param_elems;
+  size_t slot_sz, big_sz, n_param_elems;
   Tracker tr;
-  std::vector<int> slot_of;      // microbatch -> slot index, -1 if none
-  std::vector<int> free_slots;
+  std::vector<int> slot_of, big_of;      // microbatch -> slot index of either kind, -1 if none
+  std::vector<int> free_slots, free_big;
   int sticky = STAGE_OK;
   int kernel_set = 0;
   // optional per-launch timing (HIP events on the stage's stream), by kernel class
@@ -254,124 +279,155 @@ int do_gemm(stage* st, int mode, int M, int N, int K, const void* A, int64_t lda
   return STAGE_OK;
 }
 
-AttnArgs attn_args(const stage* st, const LayerOff& o, char* slot, const void* dout, const WsOff& w) {
+// Where one layer's tensors of one microbatch live.
+struct LayerBuf { char *x, *n1, *qkv, *dqkv, *o, *x1, *n2, *z, *a, *dyb, *dx1b; float *st1, *st2, *lse; };
+
+enum { REC_SLOT = 0, REC_WORKSPACE = 1 };
+
+// `where`: REC_SLOT = the microbatch's stash (its big slot under recomputation); REC_WORKSPACE = the single
+// layer record in the workspace that F uses under recomputation.  x always comes from the F-to-W slot.
+LayerBuf layer_buf(const stage* st, int mb, int l, int where = REC_SLOT) {
+  const Dims& D = st->D;
+  char* slot = st->stash + (size_t)st->slot_of[mb] * st->slot_sz;
+  char* rec;
+  LayerBuf b;
+  if (!D.recompute) {
+    rec = slot + rec_bytes(D) * l;
+    b.x = rec;
+  } else {
+    b.x = slot + x_bytes(D) * l;
+    rec = where == REC_WORKSPACE ? st->ws + ws_off(D).rec
+                                 : st->stash + st->slot_sz * D.cap + (size_t)st->big_of[mb] * st->big_sz + rec_bytes(D) * l;
+  }
+  const LayerOff o = layer_off(D, 0, !D.recompute);
+  b.n1 = rec + o.n1; b.qkv = rec + o.qkv; b.dqkv = rec + o.dqkv; b.o = rec + o.o; b.x1 = rec + o.x1; b.n2 = rec + o.n2;
+  b.z = rec + o.z; b.a = rec + o.a; b.dyb = rec + o.dyb; b.dx1b = rec + o.dx1b;
+  b.st1 = (float*)(rec + o.st1); b.st2 = (float*)(rec + o.st2); b.lse = (float*)(rec + o.lse);
+  return b;
+}
+
+AttnArgs attn_args(const stage* st, const LayerBuf& o, const void* dout, const WsOff& w) {
   const Dims& D = st->D;
   AttnArgs a{};
   a.b = D.b; a.s = D.s; a.h = D.h; a.hkv = D.hkv; a.hd = D.hd; a.causal = st->cfg.causal;
-  a.qkv = slot + o.qkv; a.ld = D.dq; a.o = slot + o.o; a.lse = (float*)(slot + o.lse);
-  a.dout = dout; a.dqkv = slot + o.dqkv; a.delta = (float*)(st->ws + w.delta);
+  a.qkv = o.qkv; a.ld = D.dq; a.o = o.o; a.lse = o.lse;
+  a.dout = dout; a.dqkv = o.dqkv; a.delta = (float*)(st->ws + w.delta);
   return a;
 }
 
-// layers [l0, l1): x is read when l0 == 0, y is written when l1 == L
-int exec_forward(stage* st, int slot_idx, const void* x, void* y, int l0, int l1) {
+// Forward of layer l through the record `o`.  y_l: where the layer's output goes (fp32 unless `y_lp`); nullptr
+// skips the last GEMM, which is what rebuilding a record for B needs.
+int forward_layer(stage* st, int l, const LayerBuf& o, void* y_l, bool y_lp) {
   const Dims& D = st->D;
-  char* slot = st->stash + (size_t)slot_idx * st->slot_sz;
-  const size_t per_layer = layer_off(D, 0).end;
+  const LayerW W = layer_weights(st, l);
   const WsOff w = ws_off(D);
+  NormArgs n{}; n.kind = st->cfg.norm; n.rows = D.T; n.d = D.d; n.eps = st->cfg.norm_eps; n.x_f32 = 1;
+  n.x = o.x; n.gamma = W.g1; n.beta = W.b1; n.out = o.n1; n.stats = o.st1;
+  { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 1, 1)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
+  int rc = do_gemm(st, GEMM_NN, D.T, D.dq, D.d, o.n1, D.d, W.wqkv, D.dq, o.qkv, D.dq, nullptr, 0, 0);
+  if (rc) return rc;
+  AttnArgs a = attn_args(st, o, nullptr, w);
+  {
+    ProfScope ps(st, STAGE_K_ATTN_FWD, attn_flops(st, false));
+    if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_fwd_mfma(a, st->stream));
+    else HIPCHK(attn_fwd_ref(st->dt, a, st->stream));
+  }
+  rc = do_gemm(st, GEMM_NN, D.T, D.d, D.d, o.o, D.d, W.wo, D.d, o.x1, D.d, o.x, D.d, 0, 1, 1);
+  if (rc) return rc;
+  n.x = o.x1; n.gamma = W.g2; n.beta = W.b2; n.out = o.n2; n.stats = o.st2;
+  { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 1, 1)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
+  rc = do_gemm(st, GEMM_NN, D.T, D.fin, D.d, o.n2, D.d, W.win, D.fin, o.z, D.fin, nullptr, 0, 0);
+  if (rc) return rc;
+  ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = o.z; ac.a = o.a;
+  { ProfScope ps(st, STAGE_K_ACT_FWD, act_bytes_fwd(st)); HIPCHK(act_fwd(st->dt, ac, st->stream)); }
+  if (!y_l) return STAGE_OK;
+  return do_gemm(st, GEMM_NN, D.T, D.d, D.f, o.a, D.f, W.wout, D.d, y_l, D.d, o.x1, D.d, 0, 1, y_lp ? 0 : 1);
+}
+
+// layers [l0, l1): x is read when l0 == 0, y is written when l1 == L
+int exec_forward(stage* st, int mb, const void* x, void* y, int l0, int l1) {
+  const Dims& D = st->D;
   const size_t n_act = (size_t)D.T * D.d;
   if (l0 == 0) {
     ProfScope ps(st, STAGE_K_COPY, (double)n_act * (D.es + sizeof(float)));
-    HIPCHK(widen_to_f32(st->dt, (float*)(slot + layer_off(D, 0).x), x, n_act, st->stream));
+    HIPCHK(widen_to_f32(st->dt, (float*)layer_buf(st, mb, 0, REC_WORKSPACE).x, x, n_act, st->stream));
   }
   for (int l = l0; l < l1; ++l) {
-    const LayerOff o = layer_off(D, per_layer * l);
-    const LayerW W = layer_weights(st, l);
     const bool last = l + 1 == D.L;
-    void* y_l = last ? y : (void*)(slot + layer_off(D, per_layer * (l + 1)).x);   // next layer's fp32 x, or the caller's Y
-    NormArgs n{}; n.kind = st->cfg.norm; n.rows = D.T; n.d = D.d; n.eps = st->cfg.norm_eps; n.x_f32 = 1;
-    n.x = slot + o.x; n.gamma = W.g1; n.beta = W.b1; n.out = slot + o.n1; n.stats = (float*)(slot + o.st1);
-    { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 1, 1)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
-    int rc = do_gemm(st, GEMM_NN, D.T, D.dq, D.d, slot + o.n1, D.d, W.wqkv, D.dq, slot + o.qkv, D.dq, nullptr, 0, 0);
-    if (rc) return rc;
-    AttnArgs a = attn_args(st, o, slot, nullptr, w);
-    {
-      ProfScope ps(st, STAGE_K_ATTN_FWD, attn_flops(st, false));
-      if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_fwd_mfma(a, st->stream));
-      else HIPCHK(attn_fwd_ref(st->dt, a, st->stream));
-    }
-    rc = do_gemm(st, GEMM_NN, D.T, D.d, D.d, slot + o.o, D.d, W.wo, D.d, slot + o.x1, D.d, slot + o.x, D.d, 0, 1, 1);
-    if (rc) return rc;
-    n.x = slot + o.x1; n.gamma = W.g2; n.beta = W.b2; n.out = slot + o.n2; n.stats = (float*)(slot + o.st2);
-    { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 1, 1)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
-    rc = do_gemm(st, GEMM_NN, D.T, D.fin, D.d, slot + o.n2, D.d, W.win, D.fin, slot + o.z, D.fin, nullptr, 0, 0);
-    if (rc) return rc;
-    ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = slot + o.z; ac.a = slot + o.a;
-    { ProfScope ps(st, STAGE_K_ACT_FWD, act_bytes_fwd(st)); HIPCHK(act_fwd(st->dt, ac, st->stream)); }
-    rc = do_gemm(st, GEMM_NN, D.T, D.d, D.f, slot + o.a, D.f, W.wout, D.d, y_l, D.d, slot + o.x1, D.d, 0, 1, last ? 0 : 1);
+    // the output is the next layer's fp32 x, or the caller's Y
+    void* y_l = last ? y : (void*)layer_buf(st, mb, l + 1, REC_WORKSPACE).x;
+    const int rc = forward_layer(st, l, layer_buf(st, mb, l, REC_WORKSPACE), y_l, last);
     if (rc) return rc;
   }
   return STAGE_OK;
 }
 
 // layers [l0, l1) in reverse: dy is read when l1 == L, dx is written when l0 == 0
-int exec_backward_input(stage* st, int slot_idx, const void* dy, void* dx, int l0, int l1) {
+int exec_backward_input(stage* st, int mb, const void* dy, void* dx, int l0, int l1) {
   const Dims& D = st->D;
-  char* slot = st->stash + (size_t)slot_idx * st->slot_sz;
-  const size_t per_layer = layer_off(D, 0).end;
   const WsOff w = ws_off(D);
   const size_t act_bytes = (size_t)D.T * D.d * D.es;
   if (l1 == D.L) {
     ProfScope ps(st, STAGE_K_COPY, 2.0 * act_bytes);
-    HIPCHK(copy_bytes(slot + layer_off(D, per_layer * (D.L - 1)).dyb, dy, act_bytes, st->stream));
+    HIPCHK(copy_bytes(layer_buf(st, mb, D.L - 1).dyb, dy, act_bytes, st->stream));
   }
   void* da = st->ws + w.da;
   void* dn = st->ws + w.dn;
   for (int l = l1 - 1; l >= l0; --l) {
-    const LayerOff o = layer_off(D, per_layer * l);
+    const LayerBuf o = layer_buf(st, mb, l);
     const LayerW W = layer_weights(st, l);
     const bool last = l + 1 == D.L;
+    int rc;
+    if (D.recompute && (rc = forward_layer(st, l, o, nullptr, false))) return rc;
     // gradient arriving at this layer's output: GEMM operand copy in the compute dtype, and the residual-branch
     // term, which is the fp32 dx the layer above left in its x region (the caller's dY for the last layer)
-    const void* dy_op = slot + o.dyb;
-    const void* dy_res = last ? dy_op : (const void*)(slot + layer_off(D, per_layer * (l + 1)).x);
+    const void* dy_op = o.dyb;
+    const void* dy_res = last ? dy_op : (const void*)layer_buf(st, mb, l + 1).x;
     // FFN: da = dy.Wout^T ; dz = act'(z) * da (in place over z) ; dn2 = dz.Win^T
-    int rc = do_gemm(st, GEMM_NT, D.T, D.f, D.d, dy_op, D.d, W.wout, D.d, da, D.f, nullptr, 0, 0);
+    rc = do_gemm(st, GEMM_NT, D.T, D.f, D.d, dy_op, D.d, W.wout, D.d, da, D.f, nullptr, 0, 0);
     if (rc) return rc;
-    ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = slot + o.z; ac.da = da;
+    ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = o.z; ac.da = da;
     { ProfScope ps(st, STAGE_K_ACT_BWD, (double)D.T * (2.0 * D.fin + D.f) * D.es); HIPCHK(act_bwd(st->dt, ac, st->stream)); }
-    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.fin, slot + o.z, D.fin, W.win, D.fin, dn, D.d, nullptr, 0, 0);
+    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.fin, o.z, D.fin, W.win, D.fin, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
     // dx1 = dy + norm2'(dn2): fp32 in place over x1, plus a compute-dtype copy for the two GEMMs that read it
     NormArgs n{}; n.kind = st->cfg.norm; n.rows = D.T; n.d = D.d; n.eps = st->cfg.norm_eps;
-    n.x = slot + o.x1; n.x_f32 = 1; n.gamma = W.g2; n.out = slot + o.x1; n.out_f32 = 1; n.out_lp = slot + o.dx1b;
-    n.stats = (float*)(slot + o.st2); n.dout = dn; n.resid = dy_res; n.resid_f32 = last ? 0 : 1;
+    n.x = o.x1; n.x_f32 = 1; n.gamma = W.g2; n.out = o.x1; n.out_f32 = 1; n.out_lp = o.dx1b;
+    n.stats = o.st2; n.dout = dn; n.resid = dy_res; n.resid_f32 = last ? 0 : 1;
     n.dgamma = W.G[STAGE_P_NORM2_GAMMA]; n.dbeta = W.G[STAGE_P_NORM2_BETA]; n.partial = (float*)(st->ws + w.partial);
     { ProfScope ps(st, STAGE_K_NORM_BWD, norm_bytes(st, last ? 2 : 3, last ? 3 : 2)); HIPCHK(norm_bwd(st->dt, n, st->stream)); }
     // attention: do = dx1.Wo^T ; (dq,dk,dv) ; dn1 = dqkv.Wqkv^T
-    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.d, slot + o.dx1b, D.d, W.wo, D.d, dn, D.d, nullptr, 0, 0);
+    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.d, o.dx1b, D.d, W.wo, D.d, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
-    AttnArgs a = attn_args(st, o, slot, dn, w);
+    AttnArgs a = attn_args(st, o, dn, w);
     {
       ProfScope ps(st, STAGE_K_ATTN_BWD, attn_flops(st, true));
       if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_bwd_mfma(a, st->stream));
       else HIPCHK(attn_bwd_ref(st->dt, a, st->stream));
     }
-    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.dq, slot + o.dqkv, D.dq, W.wqkv, D.dq, dn, D.d, nullptr, 0, 0);
+    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.dq, o.dqkv, D.dq, W.wqkv, D.dq, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
     // dx = dx1 + norm1'(dn1): layer 0 hands it to the caller; otherwise fp32 in place over x (the residual term of
     // the layer below) plus the compute-dtype copy the layer below uses as its dy operand
-    n.x = slot + o.x; n.gamma = W.g1; n.stats = (float*)(slot + o.st1); n.dout = dn; n.resid = slot + o.x1; n.resid_f32 = 1;
+    n.x = o.x; n.gamma = W.g1; n.stats = o.st1; n.dout = dn; n.resid = o.x1; n.resid_f32 = 1;
     n.dgamma = W.G[STAGE_P_NORM1_GAMMA]; n.dbeta = W.G[STAGE_P_NORM1_BETA];
     if (l == 0) { n.out = dx; n.out_f32 = 0; n.out_lp = nullptr; }
-    else { n.out = slot + o.x; n.out_f32 = 1; n.out_lp = slot + layer_off(D, per_layer * (l - 1)).dyb; }
+    else { n.out = o.x; n.out_f32 = 1; n.out_lp = layer_buf(st, mb, l - 1).dyb; }
     { ProfScope ps(st, STAGE_K_NORM_BWD, norm_bytes(st, l == 0 ? 2 : 3, 2)); HIPCHK(norm_bwd(st->dt, n, st->stream)); }
   }
   return STAGE_OK;
 }
 
-int exec_backward_weight(stage* st, int slot_idx, int l0, int l1) {
+int exec_backward_weight(stage* st, int mb, int l0, int l1) {
   const Dims& D = st->D;
-  char* slot = st->stash + (size_t)slot_idx * st->slot_sz;
-  const size_t per_layer = layer_off(D, 0).end;
   for (int l = l0; l < l1; ++l) {
-    const LayerOff o = layer_off(D, per_layer * l);
+    const LayerBuf o = layer_buf(st, mb, l);
     const LayerW W = layer_weights(st, l);
     int rc;
-    if ((rc = do_gemm(st, GEMM_TN, D.d, D.dq, D.T, slot + o.n1, D.d, slot + o.dqkv, D.dq, W.G[STAGE_P_WQKV], D.dq, nullptr, 0, 1))) return rc;
-    if ((rc = do_gemm(st, GEMM_TN, D.d, D.d, D.T, slot + o.o, D.d, slot + o.dx1b, D.d, W.G[STAGE_P_WO], D.d, nullptr, 0, 1))) return rc;
-    if ((rc = do_gemm(st, GEMM_TN, D.d, D.fin, D.T, slot + o.n2, D.d, slot + o.z, D.fin, W.G[STAGE_P_WIN], D.fin, nullptr, 0, 1))) return rc;
-    if ((rc = do_gemm(st, GEMM_TN, D.f, D.d, D.T, slot + o.a, D.f, slot + o.dyb, D.d, W.G[STAGE_P_WOUT], D.d, nullptr, 0, 1))) return rc;
+    if ((rc = do_gemm(st, GEMM_TN, D.d, D.dq, D.T, o.n1, D.d, o.dqkv, D.dq, W.G[STAGE_P_WQKV], D.dq, nullptr, 0, 1))) return rc;
+    if ((rc = do_gemm(st, GEMM_TN, D.d, D.d, D.T, o.o, D.d, o.dx1b, D.d, W.G[STAGE_P_WO], D.d, nullptr, 0, 1))) return rc;
+    if ((rc = do_gemm(st, GEMM_TN, D.d, D.fin, D.T, o.n2, D.d, o.z, D.fin, W.G[STAGE_P_WIN], D.fin, nullptr, 0, 1))) return rc;
+    if ((rc = do_gemm(st, GEMM_TN, D.f, D.d, D.T, o.a, D.f, o.dyb, D.d, W.G[STAGE_P_WOUT], D.d, nullptr, 0, 1))) return rc;
   }
   return STAGE_OK;
 }
@@ -387,14 +443,19 @@ int apply_op(stage* st, int kind, int mb, int sub, bool had_slot, bool holds_slo
       st->slot_of[mb] = st->free_slots.back();
       st->free_slots.pop_back();
     }
-    rc = exec_forward(st, st->slot_of[mb], in, out, l0, l1);
+    rc = exec_forward(st, mb, in, out, l0, l1);
   } else if (kind == STAGE_B) {
-    rc = exec_backward_input(st, st->slot_of[mb], in, out, l0, l1);
+    if (st->D.recompute && st->big_of[mb] < 0) {
+      st->big_of[mb] = st->free_big.back();
+      st->free_big.pop_back();
+    }
+    rc = exec_backward_input(st, mb, in, out, l0, l1);
   } else {
-    rc = exec_backward_weight(st, st->slot_of[mb], l0, l1);
+    rc = exec_backward_weight(st, mb, l0, l1);
     if (!holds_slot) {
       st->free_slots.push_back(st->slot_of[mb]);
       st->slot_of[mb] = -1;
+      if (st->big_of[mb] >= 0) { st->free_big.push_back(st->big_of[mb]); st->big_of[mb] = -1; }
     }
   }
   return rc;
@@ -443,7 +504,7 @@ int stage_query_sizes(const stage_config_t* cfg, stage_sizes_t* out) {
   const size_t n = layer_param_elems(D, cfg->norm) * D.L;
   out->weights = up(n * D.es);
   out->grads = up(n * sizeof(float));
-  out->stash = slot_bytes(D) * D.cap;
+  out->stash = stash_bytes(D);
   out->workspace = ws_off(D).end;
   return STAGE_OK;
 }
@@ -454,7 +515,7 @@ int stage_validate_schedule(const stage_config_t* cfg, const stage_op_t* ops, in
   if (first_bad_index) *first_bad_index = -1;
   if (peak_live) *peak_live = 0;
   if (!make_dims(cfg, &D) || n_ops < 0 || (n_ops > 0 && !ops)) return STAGE_E_INVAL;
-  Tracker t; t.init(D.n_mb, D.n_sub, D.cap, cfg->enforce_mb_order);
+  Tracker t; t.init(D, cfg->enforce_mb_order);
   for (int i = 0; i < n_ops; ++i) {
     const int rc = t.step(ops[i].kind, ops[i].mb);
     if (rc != STAGE_OK) {
@@ -491,11 +552,12 @@ int stage_init(const stage_config_t* cfg, void* weights_dev, void* grads_dev, vo
   st->cfg = *cfg; st->D = D; st->dt = cfg->dtype == STAGE_DTYPE_FP32 ? DT_F32 : DT_BF16;
   st->weights = (char*)weights_dev; st->grads = (float*)grads_dev; st->stash = (char*)stash_dev; st->ws = (char*)workspace_dev;
   st->stream = (hipStream_t)hip_stream;
-  st->slot_sz = slot_bytes(D);
+  st->slot_sz = slot_bytes(D); st->big_sz = big_slot_bytes(D);
   st->n_param_elems = layer_param_elems(D, cfg->norm) * D.L;
-  st->tr.init(D.n_mb, D.n_sub, D.cap, cfg->enforce_mb_order);
-  st->slot_of.assign(D.n_mb, -1);
+  st->tr.init(D, cfg->enforce_mb_order);
+  st->slot_of.assign(D.n_mb, -1); st->big_of.assign(D.n_mb, -1);
   for (int i = D.cap - 1; i >= 0; --i) st->free_slots.push_back(i);
+  for (int i = D.hcap - 1; i >= 0; --i) st->free_big.push_back(i);
   if (fill_zero_f32(st->grads, st->n_param_elems, st->stream) != hipSuccess) { delete st; return STAGE_E_HIP; }
   *out = st;
   return STAGE_OK;
@@ -550,7 +612,7 @@ int stage_validate_subschedule(const stage_config_t* cfg, const stage_subop_t* o
   if (first_bad_index) *first_bad_index = -1;
   if (peak_live) *peak_live = 0;
   if (!make_dims(cfg, &D) || n_ops < 0 || (n_ops > 0 && !ops)) return STAGE_E_INVAL;
-  Tracker t; t.init(D.n_mb, D.n_sub, D.cap, cfg->enforce_mb_order);
+  Tracker t; t.init(D, cfg->enforce_mb_order);
   for (int i = 0; i < n_ops; ++i) {
     const int rc = t.step_sub(ops[i].kind, ops[i].mb, ops[i].sub);
     if (rc != STAGE_OK) {
@@ -580,7 +642,7 @@ int stage_stats(stage_t* st, int* live, int* peak_live, size_t* peak_stash_bytes
   if (!st) return STAGE_E_INVAL;
   if (live) *live = st->tr.live;
   if (peak_live) *peak_live = st->tr.peak;
-  if (peak_stash_bytes) *peak_stash_bytes = (size_t)st->tr.peak * st->slot_sz;
+  if (peak_stash_bytes) *peak_stash_bytes = st->tr.peak_b;
   return STAGE_OK;
 }
 
@@ -624,7 +686,7 @@ const char* stage_strerror(int code) {
     case STAGE_OK: return "ok";
     case STAGE_E_INVAL: return "invalid argument (null pointer, bad shape, unsupported head_dim, or microbatch out of range)";
     case STAGE_E_ORDER: return "op order violates the microbatch state machine EMPTY-F->FWD-B->BWD-W->EMPTY or the microbatch-order rule";
-    case STAGE_E_STASH_FULL: return "forward refused: stash_cap microbatches are already live";
+    case STAGE_E_STASH_FULL: return "refused: stash_cap microbatches are already live (F), or recompute_cap hold a rebuilt stash (B)";
     case STAGE_E_HIP: return "a HIP launch or runtime call failed";
     default: return "unknown error code";
   }

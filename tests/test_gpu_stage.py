@@ -222,3 +222,92 @@ def test_generated_schedule_runs_on_the_stage():
     for (y, dx, g) in outs:
         assert torch.equal(y, Y) and torch.equal(dx, dX) and torch.equal(g, st.grads_tensor())
     st.close()
+
+
+def peak_rebuilt(ops):
+    """Largest number of microbatches between their (first) B and their last W in an op list of pairs or triples."""
+    started, left, cur, peak = set(), {}, 0, 0
+    n_w = {}
+    for op in ops:
+        if op[0] == W:
+            n_w[op[1]] = n_w.get(op[1], 0) + 1
+    for op in ops:
+        k, m = op[0], op[1]
+        if k == B and m not in started:
+            started.add(m); left[m] = n_w[m]; cur += 1; peak = max(peak, cur)
+        elif k == W:
+            left[m] -= 1
+            if left[m] == 0:
+                started.discard(m); cur -= 1
+    return peak
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg3s", "cfg4s", "cfg5s", "cfg2s"])
+def test_recomputation_is_bitwise_the_plain_path(name):
+    """Layer-wise activation recomputation (section 7.2, Case 2): same bits as the plain path for Y, dX and every
+    gradient, within tolerance of the oracle that recomputes, with the smaller stash the sizes promise."""
+    import torch
+    from paper_2507_00217_amd import stage as S
+    base = dict(synth.CONFIGS["cfg1"]) if name == "cfg1" else dict(SMALL[name])
+    ops = synth.make_schedule(base)
+    cap = synth.peak_live(ops)
+    base["stash_cap"] = cap
+    rcap = peak_rebuilt(ops)
+    params, X, G = inputs(base, 2500)
+    plain = run_gpu(base, params, X, G, ops)
+    cfg = dict(base, recompute=1, recompute_cap=rcap)
+    got = run_gpu(cfg, params, X, G, ops)
+    assert np.array_equal(plain[0], got[0]) and np.array_equal(plain[1], got[1])
+    for la, lb in zip(plain[2], got[2]):
+        for k in la:
+            assert np.array_equal(la[k], lb[k]), k
+    ref = so.OracleStage(shape_of(cfg), params, recompute=True)
+    Yr, dXr, peak = ref.run_schedule(ops, X.astype(np.float64), G.astype(np.float64))
+    compare(cfg, got, (Yr, dXr, ref.grads, peak), TOL[cfg["dtype"]])
+    sz_plain, sz = S.stage_query_sizes(base), S.stage_query_sizes(cfg)
+    assert got[3]["peak_stash_bytes"] <= sz["stash"] and plain[3]["peak_stash_bytes"] == sz_plain["stash"]
+    assert rcap == cap or sz["stash"] < sz_plain["stash"]
+    print(f"{name}: cap {cap}, rebuilt cap {rcap}, stash {sz_plain['stash'] >> 20} -> {sz['stash'] >> 20} MiB", flush=True)
+
+
+def test_recomputation_with_sub_blocks_and_cap():
+    """Recomputation under interleaved sub-block ops, and the cap on rebuilt stashes refusing a B without touching
+    the state."""
+    import torch
+    from paper_2507_00217_amd import stage as S
+    n_sub = 2
+    base = dict(SMALL["cfg3s"], n_layers=4, n_sub=n_sub, stash_cap=3, n_microbatches=4, enforce_mb_order=1)
+    params, X, G = inputs(base, 2600)
+    sub_ops = synth.subschedule_interleaved(4, n_sub, 3, 7)
+    rcap = peak_rebuilt(sub_ops)
+    Xd, Gd = to_dev(X, "bf16"), to_dev(G, "bf16")
+    res = []
+    for cfg in (base, dict(base, recompute=1, recompute_cap=rcap)):
+        st = S.Stage(cfg)
+        st.load_weights(params)
+        Y, dX = torch.zeros_like(Xd), torch.zeros_like(Xd)
+        st.run_subschedule(sub_ops, Xd, Gd, Y, dX)
+        torch.cuda.synchronize()
+        assert st.stats()["live"] == 0
+        res.append((Y.clone(), dX.clone(), st.grads_tensor().clone()))
+        st.close()
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+    # cap of one rebuilt stash: the second B is refused, nothing changes, and it goes through after W(0)
+    cfg = dict(base, n_sub=0, recompute=1, recompute_cap=1)
+    st = S.Stage(cfg)
+    st.load_weights(params)
+    Y, dX = torch.zeros_like(Xd), torch.zeros_like(Xd)
+    st.forward(0, Xd[0], Y[0]); st.forward(1, Xd[1], Y[1])
+    st.backward_input(0, Gd[0], dX[0])
+    with pytest.raises(S.StageError) as e:
+        st.backward_input(1, Gd[1], dX[1])
+    assert e.value.code == S.E_STASH_FULL and st.stats()["live"] == 2
+    with pytest.raises(S.StageError) as e:
+        st.run_schedule([(W, 0), (B, 1), (F, 2), (B, 2)], Xd, Gd, Y, dX)       # refused as a whole: B(2) while 1 is rebuilt
+    assert e.value.code == S.E_STASH_FULL and st.stats()["live"] == 2
+    st.run_schedule([(W, 0), (B, 1), (W, 1), (F, 2), (F, 3), (B, 2), (W, 2), (B, 3), (W, 3)], Xd, Gd, Y, dX)
+    torch.cuda.synchronize()
+    assert st.stats()["live"] == 0
+    assert torch.equal(Y, res[0][0]) and torch.equal(dX, res[0][1]) and torch.equal(st.grads_tensor(), res[0][2])
+    st.close()

@@ -198,3 +198,38 @@ def test_sub_block_validator_brute_force(enforce):
     assert S.stage_validate_subschedule(cfg, [(0, 0, 2)])[0] == S.E_INVAL
     with pytest.raises(S.StageError):
         S.stage_query_sizes(dict(cfg, n_sub=3))          # must divide n_layers
+
+
+def test_recomputation_sizes_and_validator():
+    """Layer-wise recomputation (section 7.2, Case 2): the F-to-W slot shrinks to the layer inputs, the full-size
+    record is only held from B to W and is capped separately; the validator refuses the B that would exceed it."""
+    base = dict(synth.CONFIGS["cfg3"])
+    plain = S.stage_query_sizes(base)
+    cap = base["stash_cap"]
+    T, d, L = base["seq"] * base["mb_size"], base["hidden"], base["n_layers"]
+    small = L * T * d * 4
+    for rcap in (1, 2, cap):
+        cfg = dict(base, recompute=1, recompute_cap=rcap)
+        sz = S.stage_query_sizes(cfg)
+        full = plain["stash"] // cap - small               # a full record has no x of its own
+        assert sz["stash"] == cap * small + rcap * full
+        assert sz["workspace"] == plain["workspace"] + full // L
+    assert S.stage_query_sizes(dict(base, recompute=1))["stash"] == S.stage_query_sizes(dict(base, recompute=1, recompute_cap=cap))["stash"]
+    for bad in (dict(recompute=0, recompute_cap=1), dict(recompute=2), dict(recompute=1, recompute_cap=cap + 1),
+                dict(recompute=1, recompute_cap=-1)):
+        with pytest.raises(S.StageError):
+            S.stage_query_sizes(dict(base, **bad))
+    cfg = dict(base, n_microbatches=4, stash_cap=4, recompute=1, recompute_cap=1)
+    f4 = [(F, m) for m in range(4)]
+    rc, bad, peak = S.stage_validate_schedule(cfg, f4 + [(B, 0), (B, 1)])
+    assert (rc, bad, peak) == (S.E_STASH_FULL, 5, 4)
+    rc, bad, peak = S.stage_validate_schedule(cfg, f4 + [(B, 0), (W, 0), (B, 1), (W, 1), (B, 2), (W, 2), (B, 3), (W, 3)])
+    assert (rc, bad, peak) == (0, -1, 4)
+    rc, bad, _ = S.stage_validate_schedule(dict(cfg, recompute_cap=2), f4 + [(B, 0), (B, 1), (W, 0), (B, 2), (B, 3)])
+    assert (rc, bad) == (S.E_STASH_FULL, 8)
+    sub = dict(cfg, n_sub=2)
+    rc, bad, _ = S.stage_validate_subschedule(sub, [(F, 0, 0), (F, 0, 1), (F, 1, 0), (F, 1, 1), (B, 0, 1), (B, 1, 1)])
+    assert (rc, bad) == (S.E_STASH_FULL, 5)
+    rc, bad, _ = S.stage_validate_subschedule(sub, [(F, 0, 0), (F, 0, 1), (F, 1, 0), (F, 1, 1), (B, 0, 1), (B, 0, 0), (W, 0, 1),
+                                                    (W, 0, 0), (B, 1, 1)])
+    assert (rc, bad) == (0, -1)
