@@ -7,18 +7,22 @@
 //
 // Design: 256x256x64 macro tile per workgroup, 8 wavefronts (2x4, two per SIMD),
 // each owning a 128x64 sub-tile as 4x2 v_mfma_f32_32x32x16_bf16 accumulators
-// (128 fp32 registers per lane).  Global -> register -> LDS through buffer loads
-// (hardware range check, no branches) with the next-but-one K tile in flight,
-// two LDS buffers and one barrier per K tile; fragments are double-buffered in
-// registers and the loop body is an explicit 4-stage software pipeline.  An operand whose
-// reduction index is contiguous in memory sits in LDS as [row][k] (padded to
-// 72 elements: conflict-free 16-byte fragment reads); an operand whose
-// reduction index is the slow one sits as [k][row] (padded to 288) and is read
-// with ds_read_b64_tr_b16, the LDS transpose load, so no layout needs a
-// transposing copy.  The MFMA is issued with the operands swapped (computes the
-// transposed 32x32 block), which leaves every lane with 4 consecutive columns
-// of one row: 8-byte bf16 / 16-byte fp32 epilogue accesses.  Workgroup ids are
-// remapped so that each XCD (own L2) works on a compact band of tiles.
+// (128 fp32 registers per lane).  Operand tiles travel global -> LDS directly
+// (buffer loads with the LDS bit: no staging registers, no ds_write instructions,
+// hardware range check gives the zero fill at the edges), two LDS buffers, one
+// barrier per K tile, the next-but-one tile in flight; fragments are
+// double-buffered in registers and the loop body is an explicit 4-stage software
+// pipeline.  Such a load writes each wavefront's 64 x 16 bytes to consecutive
+// LDS addresses, so the tiles are unpadded and bank conflicts are avoided by
+// choosing WHICH 16-byte piece each lane fetches (an XOR swizzle of the piece
+// index).  An operand whose reduction index is contiguous in memory sits in LDS
+// as [row][k] and is read with 16-byte loads; an operand whose reduction index is
+// the slow one sits as [k][row] and is read with ds_read_b64_tr_b16, the LDS
+// transpose load, so no layout needs a transposing copy.  The MFMA is issued with
+// the operands swapped (computes the transposed 32x32 block), which leaves every
+// lane with 4 consecutive columns of one row: 8-byte bf16 / 16-byte fp32 epilogue
+// accesses.  Workgroup ids are remapped so that each XCD (own L2) works on a
+// compact band of tiles.
 #include "common.h"
 
 namespace stg {
@@ -29,101 +33,129 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-#ifndef GEMM_EXPERIMENT
-#define GEMM_EXPERIMENT 0
-#endif
-
 namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int KPAD = BK + 8;      // [row][k] layout: 144-byte rows
-constexpr int MPAD = BM + 32;     // [k][row] layout: 576-byte rows
-constexpr int TILE_ELEMS = BM * KPAD;                      // == BK * MPAD == 18432
-static_assert(BM * KPAD == BK * MPAD, "both layouts use the same LDS footprint");
-constexpr int TILE_CHUNKS = BM * BK / 8;                   // 16-byte chunks of one operand tile = 2048
-constexpr size_t LDS_BYTES = (size_t)4 * TILE_ELEMS * sizeof(bf16);   // A,B x 2 buffers = 147456
+constexpr int THREADS = 512, WAVES = 8;
+constexpr int TILE_BYTES = BM * BK * 2;                      // one operand tile, either layout: 32 KiB
+constexpr int TILE_SLOTS = TILE_BYTES / 16;                  // 16-byte pieces: 2048
+constexpr int CH = TILE_SLOTS / THREADS;                     // pieces per thread per operand tile: 4
+constexpr size_t LDS_BYTES = (size_t)4 * TILE_BYTES;         // A,B x 2 buffers = 128 KiB
+static_assert(BM == BN, "both operand tiles share one geometry");
 
 enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_ACC32 = 2 };
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) char lds_char;
 constexpr unsigned OOB = 0x80000000u;   // any offset >= num_records makes a buffer load return zeros
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
 }
 
-// Per-thread byte offsets of its CHUNKS 16-byte pieces of one operand tile at k = 0.  Rows past the end of
-// the matrix fall outside the buffer's range by themselves (offset >= rows*ld*2); a piece whose contiguous
-// coordinate is out of range is redirected to OOB.  KC: reduction index contiguous in memory.
-template <bool KC, int NTHR>
-__device__ __forceinline__ void tile_offsets(unsigned (&off)[TILE_CHUNKS / NTHR], int64_t ld, int row0, int rows, int tid) {
+// LDS placement of a tile's 16-byte pieces ("slots", slot s at byte 16*s):
+//   [row][k] layout (KC, reduction index contiguous in memory): row r = 8 pieces; piece c (8 k's) of row r sits in
+//     slot 8*r + (c ^ ((r >> 1) & 7)).  A fragment read takes piece c of 32 consecutive rows per half-wave: 16
+//     consecutive rows hit 16 different 16-byte bank groups.
+//   [k][row] layout: reduction row k = 32 pieces of 8 rows; piece p sits in slot 32*k + (p ^ ((k & 3) << 2)).  A
+//     transpose read takes 64 bytes from each of 4 consecutive k rows, which land in 4 different 64-byte bank groups.
+// Per-thread global byte offsets at k = 0 of the pieces it fetches: load j of wavefront w fills slots
+// (j*8 + w)*64 .. +63, lane l the l-th of them.  Rows past the end of the matrix fall outside the buffer's range
+// by themselves or are redirected to OOB, which stores zeros.
+template <bool KC>
+__device__ __forceinline__ void tile_offsets(unsigned (&off)[CH], int64_t ld, int row0, int rows, int wave, int lane) {
 #pragma unroll
-  for (int j = 0; j < TILE_CHUNKS / NTHR; ++j) {
-    const int c = tid + NTHR * j;
+  for (int j = 0; j < CH; ++j) {
+    const int s = (j * WAVES + wave) * 64 + lane;
     if (KC) {
-      const int row = row0 + (c >> 3), k = (c & 7) * 8;
-      off[j] = (unsigned)(((int64_t)row * ld + k) * 2);
-      if (row >= rows) off[j] = OOB;
+      const int r = s >> 3, c = (s & 7) ^ ((r >> 1) & 7);
+      off[j] = row0 + r < rows ? (unsigned)(((int64_t)(row0 + r) * ld + c * 8) * 2) : OOB;
     } else {
-      const int k = c >> 5, row = row0 + (c & 31) * 8;
+      const int k = s >> 5, p = (s & 31) ^ ((k & 3) << 2);
+      const int row = row0 + p * 8;
       off[j] = row < rows ? (unsigned)(((int64_t)k * ld + row) * 2) : OOB;
     }
   }
 }
 
-// one operand tile at reduction offset k0 (a multiple of BK; K % BK == 0 for a KC operand): global -> registers,
-// no branches.  OOB + anything below 2 GiB stays out of range; reduction rows >= K of a non-KC operand are past
-// the end of the buffer.
-template <bool KC, int NCH>
-__device__ __forceinline__ void g2r(uint4 (&r)[NCH], __amdgpu_buffer_rsrc_t rsrc, const unsigned (&off)[NCH],
-                                    int64_t ld, int k0) {
-  const unsigned step = KC ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * ld * 2);
-#pragma unroll
-  for (int j = 0; j < NCH; ++j) {
-    i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(off[j] + step), 0, 0);
-    r[j] = uint4{(unsigned)v[0], (unsigned)v[1], (unsigned)v[2], (unsigned)v[3]};
-  }
+// one operand tile at reduction offset k0 (a multiple of BK; K % BK == 0 for a KC operand): global -> LDS, no
+// registers, no branches.  OOB + anything below 2 GiB stays out of range; reduction rows >= K of a non-KC operand
+// are past the end of the buffer.  `wave` must be wave-uniform (the LDS address of such a load is a scalar).
+//
+// The load is written as inline assembly on purpose: with the builtin, the compiler cannot tell these LDS writes
+// from the fragment reads of the other buffer and drains the vector-memory counter before the next LDS read, which
+// serialises every K tile on the full memory latency.  Completion is awaited by hand (vmcnt(0) before the barrier
+// that publishes the tile).  m0 carries the wavefront's LDS destination; lane l lands at m0 + 16*l.  Nothing else in
+// this kernel uses m0, which the compiler reserves and re-materialises before each use of its own.
+typedef int rsrc_words __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ rsrc_words raw_rsrc(const void* base, unsigned bytes) {
+  const uint64_t a = (uint64_t)base;
+  return rsrc_words{(int)(unsigned)a, (int)(unsigned)((a >> 32) & 0xffffu), (int)bytes, 0x00020000};
 }
-
-template <bool KC, int NTHR>
-__device__ __forceinline__ void r2s(const uint4 (&r)[TILE_CHUNKS / NTHR], bf16* tile, int tid) {
-#pragma unroll
-  for (int j = 0; j < TILE_CHUNKS / NTHR; ++j) {
-    const int c = tid + NTHR * j;
-    int off;
-    if (KC) off = (c >> 3) * KPAD + (c & 7) * 8; else off = (c >> 5) * MPAD + (c & 31) * 8;
-    *reinterpret_cast<uint4*>(tile + off) = r[j];
-  }
+__device__ __forceinline__ void load_to_lds_b128(rsrc_words rsrc, unsigned lds_addr, unsigned voffset) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory");
 }
-
-// 32(row) x 16(k) MFMA operand fragment: lane l holds row l%32, k = (l/32)*8 .. +7
 template <bool KC>
-__device__ __forceinline__ bf16x8 frag(const bf16* tile, int row0, int kk, int lane) {
+__device__ __forceinline__ void g2s_one(lds_char* tile, rsrc_words rsrc, const unsigned (&off)[CH], int64_t ld, int k0,
+                                        int wave, int j) {
+  const unsigned step = KC ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * ld * 2);
+  load_to_lds_b128(rsrc, (unsigned)(size_t)(tile + (j * WAVES + wave) * 1024), off[j] + step);
+}
+template <bool KC>
+__device__ __forceinline__ void g2s(lds_char* tile, rsrc_words rsrc, const unsigned (&off)[CH], int64_t ld, int k0, int wave) {
+#pragma unroll
+  for (int j = 0; j < CH; ++j) g2s_one<KC>(tile, rsrc, off, ld, k0, wave, j);
+}
+
+// Per-lane LDS byte offsets (inside one operand tile) from which the fragments of a 32-row block are read.
+// Fragment = 32(row) x 16(k): lane l holds row l%32, k = (l/32)*8 .. +7.
+//   KC:  ad[ks], ks = k-step 0..3; block b of 32 rows adds 4096 bytes (the swizzle repeats every 16 rows)
+//   else ad[b & 3], b = 32-row block index inside the tile; k-step ks adds 16 reduction rows = 8192 bytes; the
+//        transpose load: in a 16-lane group, lane i addresses row (i/4) of a 4(k) x 16(row) block at column 4*(i%4)
+//        and receives column i of the block, i.e. 4 consecutive k for its own row
+template <bool KC>
+__device__ __forceinline__ void frag_offsets(unsigned (&ad)[4], int row0, int lane) {
   if (KC) {
-    const bf16* p = tile + (row0 + (lane & 31)) * KPAD + kk + (lane >> 5) * 8;
-    return *reinterpret_cast<const bf16x8*>(p);
+    const int r = row0 + (lane & 31), sw = (r >> 1) & 7, h = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ad[ks] = (unsigned)((r * 8 + ((2 * ks + h) ^ sw)) * 16);
   } else {
-    // transpose load: in a 16-lane group, lane i addresses row (i/4) of a 4(k) x 16(row) block at
-    // column 4*(i%4) and receives column i of the block, i.e. 4 consecutive k for its own row
     const int g = lane >> 4, li = lane & 15;
-    const bf16* p = tile + (kk + (g >> 1) * 8 + (li >> 2)) * MPAD + row0 + (g & 1) * 16 + (li & 3) * 4;
+    const int krow = (g >> 1) * 8 + (li >> 2), swv = (li >> 2) & 3;           // krow & 3 == swv
+    const int piece_lo = (g & 1) * 2 + ((li & 3) >> 1);                        // 16-byte piece inside the 32-row block
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int blk = (row0 >> 5) + b;                                        // 32-row block index; row0 % 128 == 0 or b < 2
+      ad[b] = (unsigned)(krow * 512 + ((((blk & ~3) | ((blk ^ swv) & 3)) << 2) + piece_lo) * 16 + (li & 1) * 8);
+    }
+  }
+}
+
+// `pt`: the tile's LDS address plus the offsets above
+template <bool KC>
+__device__ __forceinline__ bf16x8 frag(lds_char* const (&pt)[4], int b, int ks) {
+  if (KC) {
+    return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(pt[ks] + b * 4096);
+  } else {
     typedef s16x4 __attribute__((address_space(3))) * lds_p;
+    lds_char* p = pt[b] + ks * 8192;
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * MPAD));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * 512));
     union { struct { s16x4 a, b; } s; bf16x8 v; } u;
     u.s.a = lo; u.s.b = hi;
     return u.v;
   }
 }
 
-// TN = 32-column accumulator blocks per wavefront: 4 -> 4 wavefronts of 128x128 (one per SIMD, 256 accumulator
-// registers), 2 -> 8 wavefronts of 128x64 (two per SIMD, 128 accumulator registers each)
-template <bool AKC, bool BKC, int EPI, int TN>
-__global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
-  constexpr int THREADS = 1024 / TN, CHUNKS = TILE_CHUNKS / THREADS, WGN = 8 / TN;   // wave grid 2 x WGN
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+template <bool AKC, bool BKC, int EPI>
+__global__ __launch_bounds__(THREADS) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  constexpr int TN = 2, WGN = 4;                             // 4 x TN accumulator blocks per wavefront, wave grid 2 x 4
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  lds_char* smem = (lds_char*)smem_raw;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / WGN) * 128, wn = (wave % WGN) * (TN * 32);
 
   // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give XCD x the
@@ -143,8 +175,22 @@ __global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int ti
   const int tile_n = (bid % in_group) / gsz;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  const bf16* A = (const bf16*)g.A;
-  const bf16* B = (const bf16*)g.B;
+  // buffer descriptors cover exactly the rows that exist: KC operand = [rows, ld], other = [K, ld]
+  const rsrc_words rsA = raw_rsrc(g.A, (unsigned)(((int64_t)((AKC ? g.M : g.K) - 1) * g.lda + (AKC ? g.K : g.M)) * 2));
+  const rsrc_words rsB = raw_rsrc(g.B, (unsigned)(((int64_t)((BKC ? g.N : g.K) - 1) * g.ldb + (BKC ? g.K : g.N)) * 2));
+  unsigned offa[CH], offb[CH];
+  tile_offsets<AKC>(offa, g.lda, m0, g.M, wave, lane);
+  tile_offsets<BKC>(offb, g.ldb, n0, g.N, wave, lane);
+
+  // LDS map: buffer u at byte u * 2 * TILE_BYTES, A tile first, then B tile
+  constexpr int BUF_BYTES = 2 * TILE_BYTES;
+  const int nk = (g.K + BK - 1) / BK;
+  g2s<AKC>(smem, rsA, offa, g.lda, 0, wave);
+  g2s<BKC>(smem + TILE_BYTES, rsB, offb, g.ldb, 0, wave);
+  if (nk > 1) {
+    g2s<AKC>(smem + BUF_BYTES, rsA, offa, g.lda, BK, wave);
+    g2s<BKC>(smem + BUF_BYTES + TILE_BYTES, rsB, offb, g.ldb, BK, wave);
+  }
 
   // Accumulators start at zero, or -- weight gradients, C += A^T.B -- at the current value of C: the read half of
   // the read-modify-write then travels together with the first operand tiles instead of stalling the epilogue.
@@ -173,34 +219,30 @@ __global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int ti
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   }
 
-  // buffer descriptors cover exactly the rows that exist: KC operand = [rows, ld], other = [K, ld]
-  const __amdgpu_buffer_rsrc_t rsA = make_rsrc(A, (unsigned)(((int64_t)((AKC ? g.M : g.K) - 1) * g.lda + (AKC ? g.K : g.M)) * 2));
-  const __amdgpu_buffer_rsrc_t rsB = make_rsrc(B, (unsigned)(((int64_t)((BKC ? g.N : g.K) - 1) * g.ldb + (BKC ? g.K : g.N)) * 2));
-  unsigned offa[CHUNKS], offb[CHUNKS];
-  tile_offsets<AKC, THREADS>(offa, g.lda, m0, g.M, tid);
-  tile_offsets<BKC, THREADS>(offb, g.ldb, n0, g.N, tid);
-
-  uint4 ra[CHUNKS], rb[CHUNKS];
-  const int nk = (g.K + BK - 1) / BK;
-  g2r<AKC, CHUNKS>(ra, rsA, offa, g.lda, 0);
-  g2r<BKC, CHUNKS>(rb, rsB, offb, g.ldb, 0);
-  r2s<AKC, THREADS>(ra, smem, tid);
-  r2s<BKC, THREADS>(rb, smem + TILE_ELEMS, tid);
-  g2r<AKC, CHUNKS>(ra, rsA, offa, g.lda, BK);
-  g2r<BKC, CHUNKS>(rb, rsB, offb, g.ldb, BK);
-  __syncthreads();
+  // fragment addresses in the buffer being read, and where the next loads go; both hop between the two buffers
+  lds_char *pa[4], *pb[4];
+  {
+    unsigned ada[4], adb[4];
+    frag_offsets<AKC>(ada, wm, lane);
+    frag_offsets<BKC>(adb, wn, lane);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) { pa[x] = smem + ada[x]; pb[x] = smem + TILE_BYTES + adb[x]; }
+  }
+  lds_char* fill = smem;      // buffer that the loads issued in this trip fill (wave-uniform)
+  int hop = BUF_BYTES;
 
   // Software pipeline, one K tile (4 k-steps of 16) per trip, fragments double-buffered in registers:
-  //   S0  read frags k1 | MFMA k0            S2  read frags k3 | write tile t+1 to the other LDS buffer | MFMA k2
-  //   S1  read frags k2 | MFMA k1            -- barrier --
-  //                                          S3  read frags k0 of tile t+1 | issue global loads of tile t+2 | MFMA k3
-  // Loads past the last K tile return zeros (buffer range check), so the loop needs no branches.
+  //   S0  read frags k1 | MFMA k0            S2  read frags k3 | MFMA k2
+  //   S1  read frags k2 | MFMA k1            -- wait for tile t+1 to have landed; barrier --
+  //                                          S3  read frags k0 of tile t+1 | issue loads of tile t+2 into the buffer
+  //                                              just vacated | MFMA k3
+  // At the barrier only tile t+1's loads are outstanding, hence vmcnt(0).
   constexpr int NREADS = (AKC ? 4 : 8) + (BKC ? TN : 2 * TN);   // LDS read instructions per k-step
   constexpr int NMFMA = 4 * TN;                                 // MFMAs per k-step
   bf16x8 fa[2][4], fb[2][TN];
-#define LOAD_FRAGS(buf, sa_, sb_, kk_)                                              \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) fa[buf][i] = frag<AKC>(sa_, wm + i * 32, kk_, lane); \
-  _Pragma("unroll") for (int j = 0; j < TN; ++j) fb[buf][j] = frag<BKC>(sb_, wn + j * 32, kk_, lane);
+#define LOAD_FRAGS(buf, ks_)                                                        \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) fa[buf][i] = frag<AKC>(pa, i, ks_); \
+  _Pragma("unroll") for (int j = 0; j < TN; ++j) fb[buf][j] = frag<BKC>(pb, j, ks_);
 #define MFMA_STEP(buf)                                                               \
   _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
   _Pragma("unroll") for (int j = 0; j < TN; ++j)                                     \
@@ -215,84 +257,87 @@ __global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int ti
   __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 4, 0);                                         \
   __builtin_amdgcn_sched_group_barrier(mask, (n) - (3 * (n)) / 4, 0);                                \
   __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 4, 0);
-  // the same with a second instruction class riding along: n reads and m others per stage
-#define SPREAD2(mask2, n, m)                                                                         \
-  __builtin_amdgcn_sched_group_barrier(0x100, (n) / 4, 0);                                           \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 8, 0);                                         \
-  __builtin_amdgcn_sched_group_barrier(mask2, (m) / 4, 0);                                           \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 4 - NMFMA / 8, 0);                             \
-  __builtin_amdgcn_sched_group_barrier(0x100, (2 * (n)) / 4 - (n) / 4, 0);                           \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 8, 0);                                         \
-  __builtin_amdgcn_sched_group_barrier(mask2, (m) / 4, 0);                                           \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 4 - NMFMA / 8, 0);                             \
-  __builtin_amdgcn_sched_group_barrier(0x100, (3 * (n)) / 4 - (2 * (n)) / 4, 0);                     \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 8, 0);                                         \
-  __builtin_amdgcn_sched_group_barrier(mask2, (m) / 4, 0);                                           \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 4 - NMFMA / 8, 0);                             \
-  __builtin_amdgcn_sched_group_barrier(0x100, (n) - (3 * (n)) / 4, 0);                               \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 8, 0);                                         \
-  __builtin_amdgcn_sched_group_barrier(mask2, (m) / 4, 0);                                           \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 4 - NMFMA / 8, 0);
 
-  LOAD_FRAGS(0, smem, smem + TILE_ELEMS, 0)
+  __builtin_amdgcn_s_waitcnt(0);   // tile 0 (and 1, and C for weight gradients) landed
+  __syncthreads();
+  LOAD_FRAGS(0, 0)
   for (int kt = 0; kt < nk; ++kt) {
-    const bf16* sa = smem + (kt & 1) * 2 * TILE_ELEMS;
-    const bf16* sb = sa + TILE_ELEMS;
-    bf16* na = smem + ((kt + 1) & 1) * 2 * TILE_ELEMS;
-    bf16* nb = na + TILE_ELEMS;
-    // S0
-    LOAD_FRAGS(1, sa, sb, 16)
+    LOAD_FRAGS(1, 1)
     MFMA_STEP(0)
     SPREAD(0x100, NREADS)
     __builtin_amdgcn_sched_barrier(0);
-    // S1
-    LOAD_FRAGS(0, sa, sb, 32)
+    LOAD_FRAGS(0, 2)
     MFMA_STEP(1)
     SPREAD(0x100, NREADS)
     __builtin_amdgcn_sched_barrier(0);
-    // S2: LDS reads first (the compiler will not move a read below a write it cannot prove disjoint)
-    LOAD_FRAGS(1, sa, sb, 48)
-    r2s<AKC, THREADS>(ra, na, tid);
-    r2s<BKC, THREADS>(rb, nb, tid);
+    LOAD_FRAGS(1, 3)
     MFMA_STEP(0)
-    __builtin_amdgcn_sched_group_barrier(0x100, NREADS / 2, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 8, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, NREADS - NREADS / 2, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 8, 0);
-    __builtin_amdgcn_sched_group_barrier(0x200, 2 * CHUNKS / 4, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, (NMFMA - 2 * (NMFMA / 8)) / 4, 0);
-    __builtin_amdgcn_sched_group_barrier(0x200, 2 * CHUNKS / 4, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, (NMFMA - 2 * (NMFMA / 8)) / 4, 0);
-    __builtin_amdgcn_sched_group_barrier(0x200, 2 * CHUNKS / 4, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, (NMFMA - 2 * (NMFMA / 8)) / 4, 0);
-    __builtin_amdgcn_sched_group_barrier(0x200, 2 * CHUNKS / 4, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, (NMFMA - 2 * (NMFMA / 8)) / 4, 0);
+    SPREAD(0x100, NREADS)
     __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0);         // vmcnt(0) lgkmcnt(0): tile kt+1 has landed, own LDS reads are done
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
-    // S3
-    LOAD_FRAGS(0, na, nb, 0)
-#if GEMM_EXPERIMENT == 2      // timing experiment only: keep re-reading K tile 0 (cache resident)
-    g2r<AKC, CHUNKS>(ra, rsA, offa, g.lda, 0);
-    g2r<BKC, CHUNKS>(rb, rsB, offb, g.ldb, 0);
-#else
-    g2r<AKC, CHUNKS>(ra, rsA, offa, g.lda, (kt + 2) * BK);
-    g2r<BKC, CHUNKS>(rb, rsB, offb, g.ldb, (kt + 2) * BK);
-#endif
-    MFMA_STEP(1)
-    SPREAD2(0x020, NREADS, 2 * CHUNKS)
-    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) { pa[x] += hop; pb[x] += hop; }
+    LOAD_FRAGS(0, 0)
+    // one load after every MFMA of this stage (the fences pin the order; the LDS reads above go first); nothing is
+    // fetched past the last K tile
+    const bool more = kt + 2 < nk;      // wave-uniform: a scalar branch around each load, none around an MFMA
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][0], fa[1][i], acc[i][0], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) g2s_one<AKC>(fill, rsA, offa, g.lda, (kt + 2) * BK, wave, i);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][1], fa[1][i], acc[i][1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) g2s_one<BKC>(fill + TILE_BYTES, rsB, offb, g.ldb, (kt + 2) * BK, wave, i);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    fill += hop;
+    hop = -hop;
   }
 #undef LOAD_FRAGS
 #undef MFMA_STEP
 #undef SPREAD
-#undef SPREAD2
 
   // epilogue: acc[i][j][e] = C[m][n],  m = m0+wm+i*32 + lane%32,  n = n0+wn+j*32 + (e/4)*8 + (lane/32)*4 + e%4
-#if GEMM_EXPERIMENT == 3      // timing experiment only: no epilogue stores unless a value is NaN
+#if defined(GEMM_X_NOEPI)
   if (!(acc[0][0][0] != acc[0][0][0])) return;
 #endif
   const int row_l = lane & 31, col_l = (lane >> 5) * 4;
+  if (EPI == EPI_STORE) {
+    // bf16 output: the 256 x 256 tile goes through LDS (exactly the 128 KiB the operand buffers held) so that the
+    // global stores are whole 512-byte rows, 16 bytes per lane, instead of 16-byte fragments of 32 rows.  Row r's
+    // 16-byte piece p sits at r*512 + ((p ^ (r & 31)) << 4): the fragment writes of 32 rows spread over all banks
+    // and a row is read back as a permutation of itself.  No loads are in flight here (none is issued past the
+    // last K tile); the barrier waits for the other wavefronts' last fragment reads.
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = wm + i * 32 + row_l;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int p = (wn + j * 32 + q * 8) >> 3;
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[i][j][q * 4 + e];
+          *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4) + (lane >> 5) * 8) = o;
+        }
+    }
+    __syncthreads();
+    const int p = lane & 31, n = n0 + p * 8;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+      const int r = wave * 32 + 2 * t + (lane >> 5), m = m0 + r;
+      const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4));
+      if (m < g.M && n < g.N) *reinterpret_cast<u32x4*>((bf16*)g.C + (int64_t)m * g.ldc + n) = v;   // N % 8 == 0
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int m = m0 + wm + i * 32 + row_l;
@@ -330,27 +375,18 @@ __global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int ti
   }
 }
 
-// Eight wavefronts of 128x64 measured 3-5 % faster than four of 128x128 on the stage's GEMM shapes: the second
-// wavefront per SIMD issues MFMAs while the first waits on LDS or at the barrier.
-constexpr int WAVE_COLS = 2;
-
-template <bool AKC, bool BKC, int EPI, int TN>
-hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
+template <bool AKC, bool BKC, int EPI>
+hipError_t launch(const GemmArgs& g, hipStream_t s) {
   static bool attr_set = false;
-  auto kern = gemm_mfma_kernel<AKC, BKC, EPI, TN>;
+  auto kern = gemm_mfma_kernel<AKC, BKC, EPI>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(1024 / TN), LDS_BYTES, s, g, tiles_m, tiles_n);
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(THREADS), LDS_BYTES, s, g, tiles_m, tiles_n);
   return hipGetLastError();
-}
-
-template <bool AKC, bool BKC, int EPI>
-hipError_t launch(const GemmArgs& g, hipStream_t s) {
-  return launch_tn<AKC, BKC, EPI, WAVE_COLS>(g, s);
 }
 
 }  // namespace
@@ -360,6 +396,7 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
   if (!al16(g.A) || !al16(g.B) || !al16(g.C) || (g.R && !al16(g.R))) return false;
   if (g.lda % 8 || g.ldb % 8 || g.ldc % 4 || (g.R && g.ldr % 4) || g.N % 8) return false;
+  if (!g.acc_f32 && !g.c_f32 && g.ldc % 8) return false;   // bf16 C is stored 16 bytes at a time
   const int64_t lim = (int64_t)1 << 30;   // operand byte offsets are 32-bit buffer offsets below 2 GiB
   const int64_t a_rows = g.mode == GEMM_TN ? g.K : g.M, b_rows = g.mode == GEMM_NT ? g.N : g.K;
   if (a_rows * g.lda >= lim || b_rows * g.ldb >= lim) return false;
