@@ -36,10 +36,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int THREADS = 512, WAVES = 8;
 constexpr int TILE_BYTES = BM * BK * 2;                      // one operand tile, either layout: 32 KiB
 constexpr int TILE_SLOTS = TILE_BYTES / 16;                  // 16-byte pieces: 2048
-constexpr int CH = TILE_SLOTS / THREADS;                     // pieces per thread per operand tile: 4
 constexpr size_t LDS_BYTES = (size_t)4 * TILE_BYTES;         // A,B x 2 buffers = 128 KiB
 static_assert(BM == BN, "both operand tiles share one geometry");
 
@@ -63,8 +61,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, un
 // Per-thread global byte offsets at k = 0 of the pieces it fetches: load j of wavefront w fills slots
 // (j*8 + w)*64 .. +63, lane l the l-th of them.  Rows past the end of the matrix fall outside the buffer's range
 // by themselves or are redirected to OOB, which stores zeros.
-template <bool KC>
+template <bool KC, int WAVES, int CH>
 __device__ __forceinline__ void tile_offsets(unsigned (&off)[CH], int64_t ld, int row0, int rows, int wave, int lane) {
+  static_assert(WAVES * 64 * CH == TILE_SLOTS, "every 16-byte piece of the tile has one owner");
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
     const int s = (j * WAVES + wave) * 64 + lane;
@@ -97,16 +96,16 @@ __device__ __forceinline__ void load_to_lds_b128(rsrc_words rsrc, unsigned lds_a
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory");
 }
-template <bool KC>
+template <bool KC, int WAVES, int CH>
 __device__ __forceinline__ void g2s_one(lds_char* tile, rsrc_words rsrc, const unsigned (&off)[CH], int64_t ld, int k0,
                                         int wave, int j) {
   const unsigned step = KC ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * ld * 2);
   load_to_lds_b128(rsrc, (unsigned)(size_t)(tile + (j * WAVES + wave) * 1024), off[j] + step);
 }
-template <bool KC>
+template <bool KC, int WAVES, int CH>
 __device__ __forceinline__ void g2s(lds_char* tile, rsrc_words rsrc, const unsigned (&off)[CH], int64_t ld, int k0, int wave) {
 #pragma unroll
-  for (int j = 0; j < CH; ++j) g2s_one<KC>(tile, rsrc, off, ld, k0, wave, j);
+  for (int j = 0; j < CH; ++j) g2s_one<KC, WAVES, CH>(tile, rsrc, off, ld, k0, wave, j);
 }
 
 // Per-lane LDS byte offsets (inside one operand tile) from which the fragments of a 32-row block are read.
@@ -149,9 +148,11 @@ __device__ __forceinline__ bf16x8 frag(lds_char* const (&pt)[4], int b, int ks) 
   }
 }
 
-template <bool AKC, bool BKC, int EPI>
-__global__ __launch_bounds__(THREADS) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
-  constexpr int TN = 2, WGN = 4;                             // 4 x TN accumulator blocks per wavefront, wave grid 2 x 4
+// TN = 32-column accumulator blocks per wavefront: 2 -> 8 wavefronts of 128x64 (two per SIMD, 128 accumulator
+// registers each), 4 -> 4 wavefronts of 128x128 (one per SIMD, 256 accumulator registers, a third less LDS read traffic)
+template <bool AKC, bool BKC, int EPI, int TN>
+__global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  constexpr int WGN = 8 / TN, WAVES = 2 * WGN, CH = TILE_SLOTS / (WAVES * 64);   // wave grid 2 x WGN
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char* smem = (lds_char*)smem_raw;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -179,17 +180,17 @@ __global__ __launch_bounds__(THREADS) void gemm_mfma_kernel(GemmArgs g, int tile
   const rsrc_words rsA = raw_rsrc(g.A, (unsigned)(((int64_t)((AKC ? g.M : g.K) - 1) * g.lda + (AKC ? g.K : g.M)) * 2));
   const rsrc_words rsB = raw_rsrc(g.B, (unsigned)(((int64_t)((BKC ? g.N : g.K) - 1) * g.ldb + (BKC ? g.K : g.N)) * 2));
   unsigned offa[CH], offb[CH];
-  tile_offsets<AKC>(offa, g.lda, m0, g.M, wave, lane);
-  tile_offsets<BKC>(offb, g.ldb, n0, g.N, wave, lane);
+  tile_offsets<AKC, WAVES, CH>(offa, g.lda, m0, g.M, wave, lane);
+  tile_offsets<BKC, WAVES, CH>(offb, g.ldb, n0, g.N, wave, lane);
 
   // LDS map: buffer u at byte u * 2 * TILE_BYTES, A tile first, then B tile
   constexpr int BUF_BYTES = 2 * TILE_BYTES;
   const int nk = (g.K + BK - 1) / BK;
-  g2s<AKC>(smem, rsA, offa, g.lda, 0, wave);
-  g2s<BKC>(smem + TILE_BYTES, rsB, offb, g.ldb, 0, wave);
+  g2s<AKC, WAVES, CH>(smem, rsA, offa, g.lda, 0, wave);
+  g2s<BKC, WAVES, CH>(smem + TILE_BYTES, rsB, offb, g.ldb, 0, wave);
   if (nk > 1) {
-    g2s<AKC>(smem + BUF_BYTES, rsA, offa, g.lda, BK, wave);
-    g2s<BKC>(smem + BUF_BYTES + TILE_BYTES, rsB, offb, g.ldb, BK, wave);
+    g2s<AKC, WAVES, CH>(smem + BUF_BYTES, rsA, offa, g.lda, BK, wave);
+    g2s<BKC, WAVES, CH>(smem + BUF_BYTES + TILE_BYTES, rsB, offb, g.ldb, BK, wave);
   }
 
   // Accumulators start at zero, or -- weight gradients, C += A^T.B -- at the current value of C: the read half of
@@ -284,16 +285,18 @@ __global__ __launch_bounds__(THREADS) void gemm_mfma_kernel(GemmArgs g, int tile
     // fetched past the last K tile
     const bool more = kt + 2 < nk;      // wave-uniform: a scalar branch around each load, none around an MFMA
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][0], fa[1][i], acc[i][0], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (more) g2s_one<AKC>(fill, rsA, offa, g.lda, (kt + 2) * BK, wave, i);
-      __builtin_amdgcn_sched_barrier(0);
-      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][1], fa[1][i], acc[i][1], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (more) g2s_one<BKC>(fill + TILE_BYTES, rsB, offb, g.ldb, (kt + 2) * BK, wave, i);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        const int n = i * TN + j;         // 4*TN MFMAs, 2*CH == 4*TN loads
+        if (more) {
+          if (n < CH) g2s_one<AKC, WAVES, CH>(fill, rsA, offa, g.lda, (kt + 2) * BK, wave, n);
+          else g2s_one<BKC, WAVES, CH>(fill + TILE_BYTES, rsB, offb, g.ldb, (kt + 2) * BK, wave, n - CH);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     fill += hop;
     hop = -hop;
   }
@@ -302,9 +305,6 @@ __global__ __launch_bounds__(THREADS) void gemm_mfma_kernel(GemmArgs g, int tile
 #undef SPREAD
 
   // epilogue: acc[i][j][e] = C[m][n],  m = m0+wm+i*32 + lane%32,  n = n0+wn+j*32 + (e/4)*8 + (lane/32)*4 + e%4
-#if defined(GEMM_X_NOEPI)
-  if (!(acc[0][0][0] != acc[0][0][0])) return;
-#endif
   const int row_l = lane & 31, col_l = (lane >> 5) * 4;
   if (EPI == EPI_STORE) {
     // bf16 output: the 256 x 256 tile goes through LDS (exactly the 128 KiB the operand buffers held) so that the
@@ -331,8 +331,8 @@ __global__ __launch_bounds__(THREADS) void gemm_mfma_kernel(GemmArgs g, int tile
     __syncthreads();
     const int p = lane & 31, n = n0 + p * 8;
 #pragma unroll
-    for (int t = 0; t < 16; ++t) {
-      const int r = wave * 32 + 2 * t + (lane >> 5), m = m0 + r;
+    for (int t = 0; t < BM / WAVES / 2; ++t) {
+      const int r = wave * (BM / WAVES) + 2 * t + (lane >> 5), m = m0 + r;
       const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4));
       if (m < g.M && n < g.N) *reinterpret_cast<u32x4*>((bf16*)g.C + (int64_t)m * g.ldc + n) = v;   // N % 8 == 0
     }
@@ -375,10 +375,15 @@ __global__ __launch_bounds__(THREADS) void gemm_mfma_kernel(GemmArgs g, int tile
   }
 }
 
+// Eight wavefronts of 128x64 and four of 128x128 measure within a few percent of each other on the stage's shapes
+// (the narrower ones ahead on forward and input-gradient products, the wider ones on some weight-gradient ones).
+constexpr int WAVE_COLS = 2;
+
 template <bool AKC, bool BKC, int EPI>
 hipError_t launch(const GemmArgs& g, hipStream_t s) {
+  constexpr int THREADS = 1024 / WAVE_COLS;
   static bool attr_set = false;
-  auto kern = gemm_mfma_kernel<AKC, BKC, EPI>;
+  auto kern = gemm_mfma_kernel<AKC, BKC, EPI, WAVE_COLS>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
     if (e != hipSuccess) return e;
