@@ -1,7 +1,8 @@
 // Fused causal / full attention for gfx950 in bf16 with fp32 softmax: forward
 // (online softmax, no s-by-s tensor in HBM) and a deterministic two-kernel
-// backward.  K/V (forward, dQ) or Q/dO (dK/dV) tiles are staged through LDS;
-// every product runs on v_mfma_f32_32x32x16_bf16.
+// backward.  K/V (forward, dQ) or Q/dO (dK/dV) tiles go global -> LDS directly (buffer
+// loads with the LDS bit) into two buffers, one barrier per tile; every product
+// runs on v_mfma_f32_32x32x16_bf16.
 //
 // Orientation trick used throughout: the score block is computed transposed
 // (keys x queries in forward / dQ, queries x keys in dK/dV) so that each lane
@@ -23,6 +24,8 @@
 // rescale skipped when no row maximum moved) and dispatch the heaviest causal tiles first.
 #include "common.h"
 
+#include <utility>
+
 namespace stg {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -33,52 +36,117 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int THREADS = 256;
 constexpr int TK = 64;            // rows of one LDS tile (keys in forward / dQ, queries in dK/dV)
-constexpr int PADE = 40;          // row padding (elements): 16-byte row reads and transpose reads both spread over banks
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-template <int HD, int NTHR = THREADS> struct Cfg {
-  static constexpr int LD = HD + PADE;           // LDS row stride (elements)
+typedef __attribute__((address_space(3))) char lds_char;
+typedef int rsrc_words __attribute__((ext_vector_type(4)));
+
+// LDS tile: TK rows of HD bf16, unpadded, filled by buffer loads that write LDS directly (lane l of a wavefront
+// lands at the wavefront's LDS address + 16*l, out-of-range lanes store zeros).  The 16-byte piece c (8 columns)
+// of row r sits in slot r*PPR + (c ^ swz(r)); the swizzle makes both ways of reading the tile conflict-free:
+//   rows as MFMA operand rows (16 consecutive rows, same piece): 16 different 16-byte bank groups
+//   transpose reads (4 consecutive rows, 64 contiguous bytes each): 4 different 64-byte bank groups
+template <int HD> struct Geo {
+  static constexpr int PPR = HD / 8;             // 16-byte pieces per row
+  static constexpr int ROWB = HD * 2;            // bytes per row
+  static constexpr int TILEB = TK * ROWB;        // bytes per tile
   static constexpr int NKK = HD / 16;            // k-steps of a product reducing over head_dim
   static constexpr int NHB = HD / 32;            // 32-wide head_dim blocks of an output
-  static constexpr int TILE = TK * LD;           // elements per LDS tile
-  static constexpr int CH = TK * HD / 8 / NTHR;    // 16-byte chunks per thread per tile
+  __device__ static __forceinline__ int swz(int r) {
+    return HD == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
+  }
 };
 
-template <int HD, int NTHR> using TileRegs = uint4[Cfg<HD, NTHR>::CH];
+__device__ __forceinline__ rsrc_words raw_rsrc(const void* base, unsigned bytes) {
+  const uint64_t a = (uint64_t)base;
+  return rsrc_words{(int)(unsigned)a, (int)(unsigned)((a >> 32) & 0xffffu), (int)bytes, 0x00020000};
+}
+// Inline assembly on purpose: with the builtin the compiler cannot tell these LDS writes from the fragment reads
+// of the other buffer and drains the vector-memory counter before every LDS read.  Completion is awaited by hand
+// (vmcnt(0) before the barrier that publishes a tile).  m0 = the wavefront's LDS destination.
+__device__ __forceinline__ void load_to_lds_b128(rsrc_words rsrc, unsigned lds_addr, unsigned voffset) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ void load_to_lds_b32(rsrc_words rsrc, unsigned lds_addr, unsigned voffset) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds" :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory");
+}
 
-// ---- tile movement ----------------------------------------------------------
-// rows [row0, row0+TK) of a [*, ld] matrix (HD columns from col0) -> registers; rows >= nrows read as zero
-template <int HD, int NTHR = THREADS>
-__device__ __forceinline__ void tile_g2r(TileRegs<HD, NTHR>& r, const bf16* __restrict__ base, int64_t ld, int row0,
-                                         int nrows, int tid) {
+// Per-thread byte offsets (relative to row 0 of the tile's first row, column 0 of the head) of the pieces it
+// fetches: load j of wavefront w fills slots (j*NW + w)*64 .. +63.
+template <int HD, int NTHR, int ROWS = TK>
+__device__ __forceinline__ void tile_offsets(unsigned (&off)[ROWS * (HD / 8) / NTHR], int64_t ld, int wave, int lane) {
+  using G = Geo<HD>;
 #pragma unroll
-  for (int j = 0; j < Cfg<HD, NTHR>::CH; ++j) {
-    const int c = tid + NTHR * j;
-    const int row = c / (HD / 8), col = (c % (HD / 8)) * 8;
-    uint4 v = {0, 0, 0, 0};
-    if (row0 + row < nrows) v = *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + row) * ld + col);
-    r[j] = v;
+  for (int j = 0; j < ROWS * G::PPR / NTHR; ++j) {
+    const int s = (j * (NTHR / 64) + wave) * 64 + lane;
+    const int r = s / G::PPR, c = (s % G::PPR) ^ G::swz(r);
+    off[j] = (unsigned)(((int64_t)r * ld + c * 8) * 2);
   }
 }
-template <int HD, int NTHR = THREADS>
-__device__ __forceinline__ void tile_r2s(const TileRegs<HD, NTHR>& r, bf16* tile, int tid) {
+// rows [row0, row0+TK) of the matrix behind `rsrc` -> LDS tile; the descriptor ends with the last real row, so rows
+// past it are out of range and store zeros.  `wave` must be wave-uniform.
+template <int HD, int NTHR, int ROWS = TK>
+__device__ __forceinline__ void tile_g2s(lds_char* tile, rsrc_words rsrc, const unsigned (&off)[ROWS * (HD / 8) / NTHR],
+                                         int64_t ld, int row0, int wave) {
+  const unsigned step = (unsigned)((int64_t)row0 * ld * 2);
 #pragma unroll
-  for (int j = 0; j < Cfg<HD, NTHR>::CH; ++j) {
-    const int c = tid + NTHR * j;
-    *reinterpret_cast<uint4*>(tile + (c / (HD / 8)) * Cfg<HD>::LD + (c % (HD / 8)) * 8) = r[j];
-  }
+  for (int j = 0; j < ROWS * (HD / 8) / NTHR; ++j)
+    load_to_lds_b128(rsrc, (unsigned)(size_t)(tile + (j * (NTHR / 64) + wave) * 1024), off[j] + step);
+}
+// descriptor of one head's [nrows, HD] slice of a row-major matrix with row stride ld (elements)
+__device__ __forceinline__ rsrc_words head_rsrc(const bf16* p, int64_t ld, int nrows, int hd) {
+  return raw_rsrc(p, (unsigned)(((int64_t)(nrows - 1) * ld + hd) * 2));
 }
 
 // ---- MFMA operand fragments ---------------------------------------------------
-// operand with rows = tile rows, reduction over head_dim: lane l -> tile row row0 + l%32, columns kk + (l/32)*8 ..+7
-template <int LD>
-__device__ __forceinline__ bf16x8 frag_rows(const bf16* tile, int row0, int kk, int lane) {
-  return *reinterpret_cast<const bf16x8*>(tile + (row0 + (lane & 31)) * LD + kk + (lane >> 5) * 8);
+// Per-lane byte offsets inside a tile.
+//   rows-type operand (rows = tile rows, reduction over head_dim: lane l -> tile row rb + l%32, columns
+//   16*ks + (l/32)*8 ..+7):  ro[ks], plus rb * ROWB for the row block
+//   transposed operand (rows = head_dim columns hb*32 + l%32, reduction over 16 tile rows r0..r0+15; the 8 reduction
+//   slots of lane-half hf = l/32 are tile rows r0 + 4*hf + {0,1,2,3} and r0 + 8 + 4*hf + {0,1,2,3}: the order in
+//   which a lane holds a 32x32 accumulator block's rows, so a register-resident P / dS block pairs with it
+//   directly):  co[hb][0 or 1] for the two 4-row groups, plus r0 * ROWB (r0 a multiple of 16)
+template <int HD>
+struct FragOff {
+  unsigned ro[HD / 16];
+  unsigned co[HD / 32][2];
+  __device__ __forceinline__ void init(int lane) {
+    using G = Geo<HD>;
+    const int r = lane & 31, hf = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < G::NKK; ++ks) ro[ks] = (unsigned)(r * G::ROWB + (((2 * ks + hf) ^ G::swz(r)) << 4));
+    const int g = lane >> 4, li = lane & 15;
+#pragma unroll
+    for (int hb = 0; hb < G::NHB; ++hb)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int row = (g >> 1) * 4 + (li >> 2) + 8 * u;
+        const int piece = hb * 4 + (g & 1) * 2 + ((li & 3) >> 1);
+        co[hb][u] = (unsigned)(row * G::ROWB + ((piece ^ G::swz(row)) << 4) + (li & 1) * 8);
+      }
+  }
+  __device__ __forceinline__ void hop(int bytes) {
+#pragma unroll
+    for (int ks = 0; ks < HD / 16; ++ks) ro[ks] += bytes;
+#pragma unroll
+    for (int hb = 0; hb < HD / 32; ++hb) { co[hb][0] += bytes; co[hb][1] += bytes; }
+  }
+};
+template <int HD>
+__device__ __forceinline__ bf16x8 frag_rows(lds_char* lds, const FragOff<HD>& f, int tile_off, int rb, int ks) {
+  return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(lds + f.ro[ks] + (tile_off + rb * Geo<HD>::ROWB));
 }
-// same operand straight from global memory (kept in registers for the whole kernel); rows >= nrows read as zero
+template <int HD>
+__device__ __forceinline__ bf16x8 frag_cols_tr(lds_char* lds, const FragOff<HD>& f, int tile_off, int r0, int hb) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_p;
+  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+  u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(lds + f.co[hb][0] + (tile_off + r0 * Geo<HD>::ROWB)));
+  u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(lds + f.co[hb][1] + (tile_off + r0 * Geo<HD>::ROWB)));
+  return u.v;
+}
+// rows-type operand straight from global memory (kept in registers for the whole kernel); rows >= nrows read as zero
 __device__ __forceinline__ bf16x8 frag_rows_global(const bf16* base, int64_t ld, int row0, int nrows, int kk, int lane) {
   const int row = row0 + (lane & 31);
   bf16x8 z;
@@ -86,19 +154,6 @@ __device__ __forceinline__ bf16x8 frag_rows_global(const bf16* base, int64_t ld,
   for (int e = 0; e < 8; ++e) z[e] = (bf16)0.f;
   if (row < nrows) z = *reinterpret_cast<const bf16x8*>(base + (int64_t)row * ld + kk + (lane >> 5) * 8);
   return z;
-}
-// transposed operand: rows = head_dim columns c0 + l%32 of the tile, reduction over tile rows.  The 8 reduction
-// slots of lane-half hf = l/32 are tile rows  r0 + 4*hf + {0,1,2,3}  and  r0 + 8 + 4*hf + {0,1,2,3}: the order in
-// which a lane holds a 32x32 accumulator block's rows, so a register-resident P / dS block pairs with it directly.
-template <int LD>
-__device__ __forceinline__ bf16x8 frag_cols_tr(const bf16* tile, int r0, int c0, int lane) {
-  const int g = lane >> 4, li = lane & 15;
-  const bf16* p = tile + (r0 + (g >> 1) * 4 + (li >> 2)) * LD + c0 + (g & 1) * 16 + (li & 3) * 4;
-  typedef s16x4 __attribute__((address_space(3))) * lds_p;
-  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
-  u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
-  u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 8 * LD));
-  return u.v;
 }
 
 __device__ __forceinline__ bf16x8 pack8(const float* v) {
@@ -133,10 +188,12 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 template <int HD>
 __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
-  using C = Cfg<HD, FWD_THREADS>;
-  __shared__ __attribute__((aligned(16))) bf16 sK[C::TILE];
-  __shared__ __attribute__((aligned(16))) bf16 sV[C::TILE];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
+  using G = Geo<HD>;
+  constexpr int KT = 0, VT = G::TILEB, BUFB = 2 * G::TILEB;   // two buffers of (K tile, V tile)
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  lds_char* lds = (lds_char*)smem_raw;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   constexpr int BQ = FWD_BQ;
   const int nqt = (a.s + BQ - 1) / BQ;
   const int qt = nqt - 1 - blockIdx.y;              // slow grid index: heaviest (latest) query tiles are dispatched first
@@ -144,46 +201,53 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
   const int d = a.h * HD, dkv = a.hkv * HD, g = j / (a.h / a.hkv);
   const bf16* base = (const bf16*)a.qkv + (int64_t)ib * a.s * a.ld;
   const bf16* qp = base + j * HD;
-  const bf16* kp = base + d + g * HD;
-  const bf16* vp = base + d + dkv + g * HD;
+  const rsrc_words rsK = head_rsrc(base + d + g * HD, a.ld, a.s, HD);
+  const rsrc_words rsV = head_rsrc(base + d + dkv + g * HD, a.ld, a.s, HD);
   const int q0b = qt * BQ, q0w = q0b + wave * 32;
   const int q = q0w + (lane & 31);
   const float sl2 = rsqrtf((float)HD) * LOG2E;
 
-  bf16x8 qf[C::NKK];
-#pragma unroll
-  for (int kk = 0; kk < C::NKK; ++kk) qf[kk] = frag_rows_global(qp, a.ld, q0w, a.s, kk * 16, lane);
-
-  f32x16 o[C::NHB];
-#pragma unroll
-  for (int hb = 0; hb < C::NHB; ++hb) zero(o[hb]);
-  float m = -1e30f, l = 0.f;                       // running max (in log2 units, scaled) and sum of the lane's query
-
   const int last_q = min(q0b + BQ, a.s) - 1;
   const int ntiles = a.causal ? last_q / TK + 1 : (a.s + TK - 1) / TK;
-  uint4 rk[C::CH], rv[C::CH];
-  tile_g2r<HD, FWD_THREADS>(rk, kp, a.ld, 0, a.s, tid);
-  tile_g2r<HD, FWD_THREADS>(rv, vp, a.ld, 0, a.s, tid);
-  tile_r2s<HD, FWD_THREADS>(rk, sK, tid);
-  tile_r2s<HD, FWD_THREADS>(rv, sV, tid);
+  unsigned off[TK * G::PPR / FWD_THREADS];
+  tile_offsets<HD, FWD_THREADS>(off, a.ld, wave, lane);
+  tile_g2s<HD, FWD_THREADS>(lds + KT, rsK, off, a.ld, 0, wave);
+  tile_g2s<HD, FWD_THREADS>(lds + VT, rsV, off, a.ld, 0, wave);
+  if (ntiles > 1) {
+    tile_g2s<HD, FWD_THREADS>(lds + BUFB + KT, rsK, off, a.ld, TK, wave);
+    tile_g2s<HD, FWD_THREADS>(lds + BUFB + VT, rsV, off, a.ld, TK, wave);
+  }
+
+  bf16x8 qf[G::NKK];
+#pragma unroll
+  for (int kk = 0; kk < G::NKK; ++kk) qf[kk] = frag_rows_global(qp, a.ld, q0w, a.s, kk * 16, lane);
+
+  f32x16 o[G::NHB];
+#pragma unroll
+  for (int hb = 0; hb < G::NHB; ++hb) zero(o[hb]);
+  float m = -1e30f, l = 0.f;                       // running max (in log2 units, scaled) and sum of the lane's query
+
+  FragOff<HD> fo;
+  fo.init(lane);
+  lds_char* fill = lds;                              // buffer the next loads go to (wave-uniform)
+  int hopb = BUFB;
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
+  // Per key tile: compute from one buffer while the next tile lands in the other; then wait for it, one barrier
+  // (every wavefront is done with this buffer), and refill this buffer with the tile after next.
   for (int t = 0; t < ntiles; ++t) {
     const int kv0 = t * TK;
-    if (t + 1 < ntiles) {
-      tile_g2r<HD, FWD_THREADS>(rk, kp, a.ld, kv0 + TK, a.s, tid);
-      tile_g2r<HD, FWD_THREADS>(rv, vp, a.ld, kv0 + TK, a.s, tid);
-    }
     const bool active = !a.causal || kv0 <= min(q0w + 32, a.s) - 1;
     if (active && q0w < a.s) {
       // S^T[key][query] for two 32-key blocks
       f32x16 sacc[2];
-      sacc[0] = mfma0(frag_rows<C::LD>(sK, 0, 0, lane), qf[0]);
-      sacc[1] = mfma0(frag_rows<C::LD>(sK, 32, 0, lane), qf[0]);
+      sacc[0] = mfma0(frag_rows<HD>(lds, fo, KT, 0, 0), qf[0]);
+      sacc[1] = mfma0(frag_rows<HD>(lds, fo, KT, 32, 0), qf[0]);
 #pragma unroll
-      for (int kk = 1; kk < C::NKK; ++kk) {
-        sacc[0] = MFMA(frag_rows<C::LD>(sK, 0, kk * 16, lane), qf[kk], sacc[0]);
-        sacc[1] = MFMA(frag_rows<C::LD>(sK, 32, kk * 16, lane), qf[kk], sacc[1]);
+      for (int kk = 1; kk < G::NKK; ++kk) {
+        sacc[0] = MFMA(frag_rows<HD>(lds, fo, KT, 0, kk), qf[kk], sacc[0]);
+        sacc[1] = MFMA(frag_rows<HD>(lds, fo, KT, 32, kk), qf[kk], sacc[1]);
       }
       const bool need_mask = (a.causal && kv0 + TK - 1 > q0w) || kv0 + TK > a.s;
       float p[2][16];
@@ -212,7 +276,7 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
         const float alpha = fast_exp2(m - mn);
         l *= alpha;
 #pragma unroll
-        for (int hb = 0; hb < C::NHB; ++hb)
+        for (int hb = 0; hb < G::NHB; ++hb)
 #pragma unroll
           for (int e = 0; e < 16; ++e) o[hb][e] *= alpha;
       }
@@ -223,26 +287,29 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
       for (int c = 0; c < 2; ++c) { pf[c][0] = pack8(&p[c][0]); pf[c][1] = pack8(&p[c][8]); }
       // O^T[hd][query] += V^T . P^T
 #pragma unroll
-      for (int hb = 0; hb < C::NHB; ++hb)
+      for (int hb = 0; hb < G::NHB; ++hb)
 #pragma unroll
         for (int c = 0; c < 2; ++c)
 #pragma unroll
           for (int t2 = 0; t2 < 2; ++t2)
-            o[hb] = MFMA(frag_cols_tr<C::LD>(sV, c * 32 + t2 * 16, hb * 32, lane), pf[c][t2], o[hb]);
+            o[hb] = MFMA(frag_cols_tr<HD>(lds, fo, VT, c * 32 + t2 * 16, hb), pf[c][t2], o[hb]);
     }
+    __builtin_amdgcn_s_waitcnt(0);                  // tile t+1 has landed (issued a whole tile ago), own LDS reads done
     __syncthreads();
-    if (t + 1 < ntiles) {
-      tile_r2s<HD, FWD_THREADS>(rk, sK, tid);
-      tile_r2s<HD, FWD_THREADS>(rv, sV, tid);
+    if (t + 2 < ntiles) {
+      tile_g2s<HD, FWD_THREADS>(fill + KT, rsK, off, a.ld, kv0 + 2 * TK, wave);
+      tile_g2s<HD, FWD_THREADS>(fill + VT, rsV, off, a.ld, kv0 + 2 * TK, wave);
     }
-    __syncthreads();
+    fo.hop(hopb);
+    fill += hopb;
+    hopb = -hopb;
   }
 
   if (q < a.s) {
     const float inv = 1.f / l;
     bf16* orow = (bf16*)a.o + ((int64_t)ib * a.s + q) * d + j * HD;
 #pragma unroll
-    for (int hb = 0; hb < C::NHB; ++hb)
+    for (int hb = 0; hb < G::NHB; ++hb)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         bf16x4 v;
@@ -288,10 +355,12 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(AttnArgs a) {
 // ---------------------------------------------------------------------------
 template <int HD>
 __global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
-  using C = Cfg<HD, FWD_THREADS>;
-  __shared__ __attribute__((aligned(16))) bf16 sK[C::TILE];
-  __shared__ __attribute__((aligned(16))) bf16 sV[C::TILE];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
+  using G = Geo<HD>;
+  constexpr int KT = 0, VT = G::TILEB, BUFB = 2 * G::TILEB;   // two buffers of (K tile, V tile)
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  lds_char* lds = (lds_char*)smem_raw;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   constexpr int BQ = FWD_BQ;
   const int nqt = (a.s + BQ - 1) / BQ;
   const int qt = nqt - 1 - blockIdx.y;              // slow grid index: heaviest query tiles first
@@ -299,16 +368,27 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
   const int d = a.h * HD, dkv = a.hkv * HD, g = j / (a.h / a.hkv);
   const bf16* base = (const bf16*)a.qkv + (int64_t)ib * a.s * a.ld;
   const bf16* qp = base + j * HD;
-  const bf16* kp = base + d + g * HD;
-  const bf16* vp = base + d + dkv + g * HD;
+  const rsrc_words rsK = head_rsrc(base + d + g * HD, a.ld, a.s, HD);
+  const rsrc_words rsV = head_rsrc(base + d + dkv + g * HD, a.ld, a.s, HD);
   const bf16* dop = (const bf16*)a.dout + (int64_t)ib * a.s * d + j * HD;
   const int q0b = qt * BQ, q0w = q0b + wave * 32;
   const float scale = rsqrtf((float)HD), sl2 = scale * LOG2E;
   const int q = q0w + (lane & 31);
 
-  bf16x8 qf[C::NKK], dof[C::NKK];
+  const int last_q = min(q0b + BQ, a.s) - 1;
+  const int ntiles = a.causal ? last_q / TK + 1 : (a.s + TK - 1) / TK;
+  unsigned off[TK * G::PPR / FWD_THREADS];
+  tile_offsets<HD, FWD_THREADS>(off, a.ld, wave, lane);
+  tile_g2s<HD, FWD_THREADS>(lds + KT, rsK, off, a.ld, 0, wave);
+  tile_g2s<HD, FWD_THREADS>(lds + VT, rsV, off, a.ld, 0, wave);
+  if (ntiles > 1) {
+    tile_g2s<HD, FWD_THREADS>(lds + BUFB + KT, rsK, off, a.ld, TK, wave);
+    tile_g2s<HD, FWD_THREADS>(lds + BUFB + VT, rsV, off, a.ld, TK, wave);
+  }
+
+  bf16x8 qf[G::NKK], dof[G::NKK];
 #pragma unroll
-  for (int kk = 0; kk < C::NKK; ++kk) {
+  for (int kk = 0; kk < G::NKK; ++kk) {
     qf[kk] = frag_rows_global(qp, a.ld, q0w, a.s, kk * 16, lane);
     dof[kk] = frag_rows_global(dop, d, q0w, a.s, kk * 16, lane);
   }
@@ -317,37 +397,31 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
     lse2 = a.lse[((int64_t)ib * a.h + j) * a.s + q] * LOG2E;
     dl = a.delta[((int64_t)ib * a.h + j) * a.s + q];
   }
-  f32x16 dq[C::NHB];
+  f32x16 dq[G::NHB];
 #pragma unroll
-  for (int hb = 0; hb < C::NHB; ++hb) zero(dq[hb]);
+  for (int hb = 0; hb < G::NHB; ++hb) zero(dq[hb]);
 
-  const int last_q = min(q0b + BQ, a.s) - 1;
-  const int ntiles = a.causal ? last_q / TK + 1 : (a.s + TK - 1) / TK;
-  uint4 rk[C::CH], rv[C::CH];
-  tile_g2r<HD, FWD_THREADS>(rk, kp, a.ld, 0, a.s, tid);
-  tile_g2r<HD, FWD_THREADS>(rv, vp, a.ld, 0, a.s, tid);
-  tile_r2s<HD, FWD_THREADS>(rk, sK, tid);
-  tile_r2s<HD, FWD_THREADS>(rv, sV, tid);
+  FragOff<HD> fo;
+  fo.init(lane);
+  lds_char* fill = lds;
+  int hopb = BUFB;
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
   for (int t = 0; t < ntiles; ++t) {
     const int kv0 = t * TK;
-    if (t + 1 < ntiles) {
-      tile_g2r<HD, FWD_THREADS>(rk, kp, a.ld, kv0 + TK, a.s, tid);
-      tile_g2r<HD, FWD_THREADS>(rv, vp, a.ld, kv0 + TK, a.s, tid);
-    }
     const bool active = !a.causal || kv0 <= min(q0w + 32, a.s) - 1;
     if (active && q0w < a.s) {
       const bool need_mask = (a.causal && kv0 + TK - 1 > q0w) || kv0 + TK > a.s;
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         if (a.causal && kv0 + c * 32 > q0w + 31) continue;          // the whole 32-key block is in the future
-        f32x16 sacc = mfma0(frag_rows<C::LD>(sK, c * 32, 0, lane), qf[0]);             // S^T  = K . Q^T
-        f32x16 pacc = mfma0(frag_rows<C::LD>(sV, c * 32, 0, lane), dof[0]);            // dP^T = V . dO^T
+        f32x16 sacc = mfma0(frag_rows<HD>(lds, fo, KT, c * 32, 0), qf[0]);             // S^T  = K . Q^T
+        f32x16 pacc = mfma0(frag_rows<HD>(lds, fo, VT, c * 32, 0), dof[0]);            // dP^T = V . dO^T
 #pragma unroll
-        for (int kk = 1; kk < C::NKK; ++kk) {
-          sacc = MFMA(frag_rows<C::LD>(sK, c * 32, kk * 16, lane), qf[kk], sacc);
-          pacc = MFMA(frag_rows<C::LD>(sV, c * 32, kk * 16, lane), dof[kk], pacc);
+        for (int kk = 1; kk < G::NKK; ++kk) {
+          sacc = MFMA(frag_rows<HD>(lds, fo, KT, c * 32, kk), qf[kk], sacc);
+          pacc = MFMA(frag_rows<HD>(lds, fo, VT, c * 32, kk), dof[kk], pacc);
         }
         float ds[16];
 #pragma unroll
@@ -362,24 +436,27 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
         const bf16x8 ds0 = pack8(&ds[0]), ds1 = pack8(&ds[8]);
         // dQ^T[hd][query] += K^T . dS^T
 #pragma unroll
-        for (int hb = 0; hb < C::NHB; ++hb) {
-          dq[hb] = MFMA(frag_cols_tr<C::LD>(sK, c * 32, hb * 32, lane), ds0, dq[hb]);
-          dq[hb] = MFMA(frag_cols_tr<C::LD>(sK, c * 32 + 16, hb * 32, lane), ds1, dq[hb]);
+        for (int hb = 0; hb < G::NHB; ++hb) {
+          dq[hb] = MFMA(frag_cols_tr<HD>(lds, fo, KT, c * 32, hb), ds0, dq[hb]);
+          dq[hb] = MFMA(frag_cols_tr<HD>(lds, fo, KT, c * 32 + 16, hb), ds1, dq[hb]);
         }
       }
     }
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (t + 1 < ntiles) {
-      tile_r2s<HD, FWD_THREADS>(rk, sK, tid);
-      tile_r2s<HD, FWD_THREADS>(rv, sV, tid);
+    if (t + 2 < ntiles) {
+      tile_g2s<HD, FWD_THREADS>(fill + KT, rsK, off, a.ld, kv0 + 2 * TK, wave);
+      tile_g2s<HD, FWD_THREADS>(fill + VT, rsV, off, a.ld, kv0 + 2 * TK, wave);
     }
-    __syncthreads();
+    fo.hop(hopb);
+    fill += hopb;
+    hopb = -hopb;
   }
 
   if (q < a.s) {
     bf16* row = (bf16*)a.dqkv + ((int64_t)ib * a.s + q) * a.ld + j * HD;
 #pragma unroll
-    for (int hb = 0; hb < C::NHB; ++hb)
+    for (int hb = 0; hb < G::NHB; ++hb)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         bf16x4 v;
@@ -391,115 +468,226 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// dK/dV: one workgroup = NTHR/64 wavefronts x 32 keys of one (sequence, kv head)
+// dK/dV: one workgroup = 4 wavefronts x 32 keys of one (sequence, kv head), one wavefront per SIMD with the whole
+// register file.  It walks the query heads of its group and their 128-query tiles; per 32-query block the work is
+//   SP   S = Q.K^T, dP = dO.V^T                 16 MFMAs, operands rows of the Q / dO tiles
+//   SOFT P = exp(S - lse), dS = P (dP - delta)  vector arithmetic only
+//   DVK  dV^T += dO^T.P, dK^T += Q^T.dS         16 MFMAs, operands transpose reads of the same tiles
+// and, since vector arithmetic of a wavefront only overlaps with MFMAs issued by that same wavefront earlier, the
+// blocks are software-pipelined: SOFT of block n is written between the MFMAs of SP(n+1) and DVK(n-1).
 // ---------------------------------------------------------------------------
-template <int HD, int NTHR>
-__global__ __launch_bounds__(NTHR) void attn_dkv_kernel(AttnArgs a) {
-  using C = Cfg<HD, NTHR>;
-  __shared__ __attribute__((aligned(16))) bf16 sQ[C::TILE];
-  __shared__ __attribute__((aligned(16))) bf16 sO[C::TILE];
-  __shared__ __attribute__((aligned(16))) float sL[TK];     // lse * log2(e) per query of the tile
-  __shared__ __attribute__((aligned(16))) float sD[TK];     // delta per query of the tile
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
-  constexpr int BKEY = (NTHR / 64) * 32;
+constexpr int DKV_THREADS = 256, DKV_TQ = 128, DKV_BKEY = (DKV_THREADS / 64) * 32;
+
+// compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{})
+template <typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) { (f(std::integral_constant<int, Is>{}), ...); }
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+
+// The slice list of one dK/dV iteration: z < SPS is SP(0); then groups of (SP(n), DVK(n-1)) for n = 1..NB-1; then DVK(NB-1).
+template <int SPS, int DVS, int NB>
+struct DkvList {
+  static constexpr int PER = SPS + DVS, NSL = NB * PER;
+  static constexpr bool is_sp(int z) { return z < SPS || (z < NSL - DVS && (z - SPS) % PER < SPS); }
+  static constexpr int blk(int z) {
+    return z < SPS ? 0 : z >= NSL - DVS ? NB - 1 : (z - SPS) % PER < SPS ? (z - SPS) / PER + 1 : (z - SPS) / PER;
+  }
+  static constexpr int idx(int z) {
+    return z < SPS ? z : z >= NSL - DVS ? z - (NSL - DVS) : (z - SPS) % PER < SPS ? (z - SPS) % PER : (z - SPS) % PER - SPS;
+  }
+};
+
+template <int HD>
+__global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a) {
+  using G = Geo<HD>;
+  constexpr int NTHR = DKV_THREADS, TQ = DKV_TQ, NB = TQ / 32, TILEB = TQ * G::ROWB;
+  // two buffers of (Q tile, dO tile, lse of the tile's queries, delta of the tile's queries)
+  constexpr int QT = 0, OT = TILEB, LT = 2 * TILEB, DT = LT + TQ * 4, BUFB = DT + TQ * 4;
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  lds_char* lds = (lds_char*)smem_raw;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kt = blockIdx.y;                              // slow grid index: early key tiles see the most queries, first
   const int g = blockIdx.x, ib = blockIdx.z;
   const int d = a.h * HD, dkv = a.hkv * HD, grp = a.h / a.hkv;
   const bf16* base = (const bf16*)a.qkv + (int64_t)ib * a.s * a.ld;
+  const bf16* dobase = (const bf16*)a.dout + (int64_t)ib * a.s * d;
   const bf16* kp = base + d + g * HD;
   const bf16* vp = base + d + dkv + g * HD;
-  const int k0b = kt * BKEY, k0w = k0b + wave * 32;
+  const int k0b = kt * DKV_BKEY, k0w = k0b + wave * 32;
   const int key = k0w + (lane & 31);
   const float scale = rsqrtf((float)HD), sl2 = scale * LOG2E;
 
-  bf16x8 kf[C::NKK], vf[C::NKK];
+  static_assert(DKV_BKEY == DKV_TQ, "the diagonal query tile of a key tile has the same index");
+  const int t_first = a.causal ? kt : 0;
+  const int nqt = (a.s + TQ - 1) / TQ;
+  const int per_head = nqt - t_first;
+  const int niter = per_head * grp;
+  // Per-thread offsets of the pieces it fetches: load j covers rows j*SWEEP + (its wavefront's and lane's row inside
+  // a sweep); SWEEP is a multiple of 16, so the swizzle -- and with it the column -- is the same for every j and
+  // one offset per matrix is enough.
+  constexpr int NLD = TQ * G::PPR / NTHR, SWEEP = NTHR / G::PPR;
+  static_assert(SWEEP % 16 == 0, "swizzle period");
+  unsigned offq0, offo0;
+  {
+    const int sl = wave * 64 + lane, r = sl / G::PPR, c = (sl % G::PPR) ^ G::swz(r);
+    offq0 = (unsigned)(((int64_t)r * a.ld + c * 8) * 2);
+    offo0 = (unsigned)(((int64_t)r * d + c * 8) * 2);
+  }
+  auto tile_fetch = [&](lds_char* tile, rsrc_words rsrc, unsigned off0, int64_t ld, int row0) {
 #pragma unroll
-  for (int kk = 0; kk < C::NKK; ++kk) {
+    for (int j = 0; j < NLD; ++j)
+      load_to_lds_b128(rsrc, (unsigned)(size_t)(tile + (j * (NTHR / 64) + wave) * 1024),
+                       off0 + (unsigned)((int64_t)(row0 + j * SWEEP) * ld * 2));
+  };
+
+  // iteration `it` = (query head jj of the group, query tile t): its Q and dO tiles, lse and delta -> buffer at `buf`
+  auto fetch = [&](int it, lds_char* buf) {
+    const int jj = it / per_head, t = t_first + it % per_head;
+    const int j = g * grp + jj;
+    tile_fetch(buf + QT, head_rsrc(base + j * HD, a.ld, a.s, HD), offq0, a.ld, t * TQ);
+    tile_fetch(buf + OT, head_rsrc(dobase + j * HD, d, a.s, HD), offo0, d, t * TQ);
+    if (wave < TQ / 64) {   // 64 floats per load; queries past the end read as zero, and so do their Q and dO rows
+      const int64_t row = ((int64_t)ib * a.h + j) * a.s;
+      const unsigned vo = (unsigned)((t * TQ + wave * 64 + lane) * 4);
+      load_to_lds_b32(raw_rsrc(a.lse + row, (unsigned)a.s * 4u), (unsigned)(size_t)(buf + LT + wave * 256), vo);
+      load_to_lds_b32(raw_rsrc(a.delta + row, (unsigned)a.s * 4u), (unsigned)(size_t)(buf + DT + wave * 256), vo);
+    }
+  };
+  if (niter > 0) fetch(0, lds);
+  if (niter > 1) fetch(1, lds + BUFB);
+
+  bf16x8 kf[G::NKK], vf[G::NKK];
+#pragma unroll
+  for (int kk = 0; kk < G::NKK; ++kk) {
     kf[kk] = frag_rows_global(kp, a.ld, k0w, a.s, kk * 16, lane);
     vf[kk] = frag_rows_global(vp, a.ld, k0w, a.s, kk * 16, lane);
   }
-  f32x16 dk[C::NHB], dv[C::NHB];
+  f32x16 dk[G::NHB], dv[G::NHB];
 #pragma unroll
-  for (int hb = 0; hb < C::NHB; ++hb) { zero(dk[hb]); zero(dv[hb]); }
+  for (int hb = 0; hb < G::NHB; ++hb) { zero(dk[hb]); zero(dv[hb]); }
 
-  const int t_first = a.causal ? k0b / TK : 0;
-  const int nqt = (a.s + TK - 1) / TK;
-  const int per_head = nqt - t_first;
-  const int niter = per_head * grp;
-  uint4 rq[C::CH], ro[C::CH];
-  float rl = 0.f, rd = 0.f;
-
-  auto fetch = [&](int it) {
-    const int jj = it / per_head, t = t_first + it % per_head;
-    const int j = g * grp + jj;
-    tile_g2r<HD, NTHR>(rq, base + j * HD, a.ld, t * TK, a.s, tid);
-    tile_g2r<HD, NTHR>(ro, (const bf16*)a.dout + (int64_t)ib * a.s * d + j * HD, d, t * TK, a.s, tid);
-    if (tid < TK) {
-      const int qi = t * TK + tid;
-      rl = 1e30f; rd = 0.f;
-      if (qi < a.s) {
-        rl = a.lse[((int64_t)ib * a.h + j) * a.s + qi] * LOG2E;
-        rd = a.delta[((int64_t)ib * a.h + j) * a.s + qi];
-      }
-    }
-  };
-  auto stash = [&]() {
-    tile_r2s<HD, NTHR>(rq, sQ, tid);
-    tile_r2s<HD, NTHR>(ro, sO, tid);
-    if (tid < TK) { sL[tid] = rl; sD[tid] = rd; }
-  };
-
-  if (niter > 0) { fetch(0); stash(); }
+  FragOff<HD> fo;
+  fo.init(lane);
+  lds_char* cur = lds;                                // buffer being read, refilled after the barrier (wave-uniform)
+  lds_char* ldp = lds + LT + hf * 16;                 // this lane's lse values of the current buffer; delta follows TQ*4 later
+  int hopb = BUFB;
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
+  // One iteration = NB blocks, run as a fixed list of "slices" of 4 MFMAs whose LDS operands are read one slice
+  // ahead into the other half of fr[][]:
+  //   SP slice  (block, i): k-steps 2i, 2i+1 of S and dP          DVK slice (block, hb): the 4 products into dv[hb], dk[hb]
+  // Order: SP(0) | SP(1) DVK(0) | SP(2) DVK(1) | SP(3) DVK(2) | DVK(3).  The vector arithmetic of block n (4 chunks of 4
+  // elements, packed to bf16 as they complete) is placed among the DVK(n-1) slices, i.e. right after MFMAs that this
+  // wavefront has already issued and that do not depend on it; only block 0's is exposed.
+  constexpr int SPS = G::NKK / 2, DVS = G::NHB;
+  using SL = DkvList<SPS, DVS, NB>;
   for (int it = 0; it < niter; ++it) {
-    const int t = t_first + it % per_head;
-    const int q0 = t * TK;
-    if (it + 1 < niter) fetch(it + 1);
-    if (k0w < a.s) {
-#pragma unroll
-      for (int qc = 0; qc < 2; ++qc) {
-        if (a.causal && q0 + qc * 32 + 31 < k0w) continue;          // every query of the block precedes every key
-        f32x16 sacc = mfma0(frag_rows<C::LD>(sQ, qc * 32, 0, lane), kf[0]);            // S  = Q . K^T
-        f32x16 pacc = mfma0(frag_rows<C::LD>(sO, qc * 32, 0, lane), vf[0]);            // dP = dO . V^T
-#pragma unroll
-        for (int kk = 1; kk < C::NKK; ++kk) {
-          sacc = MFMA(frag_rows<C::LD>(sQ, qc * 32, kk * 16, lane), kf[kk], sacc);
-          pacc = MFMA(frag_rows<C::LD>(sO, qc * 32, kk * 16, lane), vf[kk], pacc);
-        }
-        const bool need_mask = a.causal && q0 + qc * 32 < k0w + 31;
-        float p[16], ds[16];
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sL[qc * 32 + e4 * 8 + hf * 4]);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sD[qc * 32 + e4 * 8 + hf * 4]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float pv = fast_exp2(sacc[e4 * 4 + e] * sl2 - l4[e]);
-            if (need_mask && q0 + qc * 32 + e4 * 8 + hf * 4 + e < key) pv = 0.f;
-            p[e4 * 4 + e] = pv;
-            ds[e4 * 4 + e] = pv * (pacc[e4 * 4 + e] - d4[e]);
-          }
-        }
-        const bf16x8 pf0 = pack8(&p[0]), pf1 = pack8(&p[8]), df0 = pack8(&ds[0]), df1 = pack8(&ds[8]);
-#pragma unroll
-        for (int hb = 0; hb < C::NHB; ++hb) {
-          dv[hb] = MFMA(frag_cols_tr<C::LD>(sO, qc * 32, hb * 32, lane), pf0, dv[hb]);        // dV^T += dO^T . P
-          dv[hb] = MFMA(frag_cols_tr<C::LD>(sO, qc * 32 + 16, hb * 32, lane), pf1, dv[hb]);
-          dk[hb] = MFMA(frag_cols_tr<C::LD>(sQ, qc * 32, hb * 32, lane), df0, dk[hb]);        // dK^T += Q^T . dS
-          dk[hb] = MFMA(frag_cols_tr<C::LD>(sQ, qc * 32 + 16, hb * 32, lane), df1, dk[hb]);
-        }
+    const int q0 = (t_first + it % per_head) * TQ;
+    // Only the diagonal tile needs the causal mask.  Element (e4, e) of a block is query q0 + qc*32 + hf*4 + e4*8 + e;
+    // it is masked when that is < key, i.e. e4*8 + e < lim_qc.
+    const bool diag = a.causal && it % per_head == 0;          // wave-uniform
+    const int lim0 = key - q0 - hf * 4;
+    f32x16 sacc, pacc;
+    bf16x8 pf0[2], df0[2], pf1[2], df1[2];                     // P and dS of even / odd blocks
+    bf16x8 fra[4], frb[4];                                      // operands of even / odd slices
+    float p[8], ds[8];
+
+    auto read_slice = [&](auto zc, bf16x8 (&f)[4]) {
+      constexpr int z = decltype(zc)::value, qc = SL::blk(z), i = SL::idx(z);
+      if constexpr (SL::is_sp(z)) {
+        f[0] = frag_rows<HD>(lds, fo, QT, qc * 32, 2 * i); f[1] = frag_rows<HD>(lds, fo, QT, qc * 32, 2 * i + 1);
+        f[2] = frag_rows<HD>(lds, fo, OT, qc * 32, 2 * i); f[3] = frag_rows<HD>(lds, fo, OT, qc * 32, 2 * i + 1);
+      } else {
+        f[0] = frag_cols_tr<HD>(lds, fo, OT, qc * 32, i); f[1] = frag_cols_tr<HD>(lds, fo, OT, qc * 32 + 16, i);
+        f[2] = frag_cols_tr<HD>(lds, fo, QT, qc * 32, i); f[3] = frag_cols_tr<HD>(lds, fo, QT, qc * 32 + 16, i);
       }
-    }
+    };
+    auto mma_slice = [&](auto zc, const bf16x8 (&f)[4]) {
+      constexpr int z = decltype(zc)::value, qc = SL::blk(z), i = SL::idx(z);
+      if constexpr (SL::is_sp(z)) {                                          // S = Q.K^T, dP = dO.V^T
+        if constexpr (i == 0) { sacc = mfma0(f[0], kf[0]); pacc = mfma0(f[2], vf[0]); }
+        else { sacc = MFMA(f[0], kf[2 * i], sacc); pacc = MFMA(f[2], vf[2 * i], pacc); }
+        sacc = MFMA(f[1], kf[2 * i + 1], sacc); pacc = MFMA(f[3], vf[2 * i + 1], pacc);
+      } else {
+        const bf16x8 (&pfi)[2] = (qc & 1) ? pf1 : pf0;
+        const bf16x8 (&dfi)[2] = (qc & 1) ? df1 : df0;
+        dv[i] = MFMA(f[0], pfi[0], dv[i]);     // dV^T += dO^T . P
+        dk[i] = MFMA(f[2], dfi[0], dk[i]);     // dK^T += Q^T . dS   (alternating: dependent MFMAs are not back to back)
+        dv[i] = MFMA(f[1], pfi[1], dv[i]);
+        dk[i] = MFMA(f[3], dfi[1], dk[i]);
+      }
+    };
+    // elements e4*4 .. +3 of block qc: P and dS, packed to bf16 once a pair of chunks is complete
+    auto chunk = [&](auto qcc, auto e4c) {
+      constexpr int qc = decltype(qcc)::value, e4 = decltype(e4c)::value;
+      typedef __attribute__((address_space(3))) const f32x4* lds_f4;
+      const f32x4 l4 = *reinterpret_cast<lds_f4>(ldp + (qc * 32 + e4 * 8) * 4);
+      const f32x4 d4 = *reinterpret_cast<lds_f4>(ldp + (DT - LT) + (qc * 32 + e4 * 8) * 4);
+      float pv[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pv[e] = fast_exp2(fmaf(sacc[e4 * 4 + e], sl2, -LOG2E * l4[e]));
+      if (diag) {
+        asm volatile("" ::: "memory");                  // keep this a (wave-uniform) branch: it is rarely taken
+        const int lim = lim0 - qc * 32 - e4 * 8;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pv[e] = e < lim ? 0.f : pv[e];
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { p[(e4 & 1) * 4 + e] = pv[e]; ds[(e4 & 1) * 4 + e] = pv[e] * (pacc[e4 * 4 + e] - d4[e]); }
+      if constexpr (e4 & 1) {
+        if constexpr (qc & 1) { pf1[e4 >> 1] = pack8(p); df1[e4 >> 1] = pack8(ds); }
+        else { pf0[e4 >> 1] = pack8(p); df0[e4 >> 1] = pack8(ds); }
+      }
+    };
+#define FENCE __builtin_amdgcn_sched_barrier(0);
+
+    read_slice(std::integral_constant<int, 0>{}, fra);
+    FENCE
+    static_for<SL::NSL>([&](auto zc) {
+      constexpr int z = decltype(zc)::value;
+      if constexpr (z + 1 < SL::NSL) {
+        if constexpr (z & 1) read_slice(std::integral_constant<int, z + 1>{}, fra);
+        else read_slice(std::integral_constant<int, z + 1>{}, frb);
+      }
+      FENCE
+      if constexpr (z & 1) mma_slice(zc, frb); else mma_slice(zc, fra);
+      if constexpr (SL::is_sp(z)) {
+        FENCE
+        if constexpr (SL::blk(z) == 0 && SL::idx(z) == SPS - 1) {            // block 0: nothing to hide behind
+          static_for<4>([&](auto c) { chunk(std::integral_constant<int, 0>{}, c); });
+          FENCE
+        }
+      } else if constexpr (SL::blk(z) + 1 < NB) {                            // DVK(n-1) slice: chunks of block n
+        static_for<4>([&](auto c) {
+          if constexpr (decltype(c)::value * DVS / 4 == SL::idx(z)) chunk(std::integral_constant<int, SL::blk(z) + 1>{}, c);
+        });
+        // the chunk's instructions go between the slice's four MFMAs, about seven per MFMA
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4 / DVS * 8, 0);
+        }
+        FENCE
+      } else {
+        FENCE
+      }
+    });
+#undef FENCE
+    __builtin_amdgcn_s_waitcnt(0);                  // iteration it+1's tiles have landed, own LDS reads are done
     __syncthreads();
-    if (it + 1 < niter) stash();
-    __syncthreads();
+    if (it + 2 < niter) fetch(it + 2, cur);
+    fo.hop(hopb);
+    cur += hopb;
+    ldp += hopb;
+    hopb = -hopb;
   }
 
   if (key < a.s) {
     bf16* row = (bf16*)a.dqkv + ((int64_t)ib * a.s + key) * a.ld + d + g * HD;
 #pragma unroll
-    for (int hb = 0; hb < C::NHB; ++hb)
+    for (int hb = 0; hb < G::NHB; ++hb)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         bf16x4 vk, vv;
@@ -511,23 +699,37 @@ __global__ __launch_bounds__(NTHR) void attn_dkv_kernel(AttnArgs a) {
   }
 }
 
+// dynamic LDS of the kernels above
+template <int HD> constexpr size_t fwd_lds() { return (size_t)4 * Geo<HD>::TILEB; }
+template <int HD> constexpr size_t dkv_lds() { return (size_t)2 * (2 * DKV_TQ * Geo<HD>::ROWB + 2 * DKV_TQ * 4); }
+
+template <typename K>
+hipError_t allow_lds(K kern, size_t bytes) {
+  return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
 template <int HD>
 hipError_t fwd_t(const AttnArgs& a, hipStream_t s) {
+  static bool ready = false;
+  if (!ready) { hipError_t e = allow_lds(attn_fwd_kernel<HD>, fwd_lds<HD>()); if (e != hipSuccess) return e; ready = true; }
   const int nqt = (a.s + FWD_BQ - 1) / FWD_BQ;
-  hipLaunchKernelGGL((attn_fwd_kernel<HD>), dim3(a.h, nqt, a.b), dim3(FWD_THREADS), 0, s, a);
+  hipLaunchKernelGGL((attn_fwd_kernel<HD>), dim3(a.h, nqt, a.b), dim3(FWD_THREADS), fwd_lds<HD>(), s, a);
   return hipGetLastError();
 }
 
 template <int HD>
 hipError_t bwd_t(const AttnArgs& a, hipStream_t s) {
+  static bool ready = false;
+  if (!ready) {
+    hipError_t e = allow_lds(attn_dq_kernel<HD>, fwd_lds<HD>());
+    if (e == hipSuccess) e = allow_lds(attn_dkv_kernel<HD>, dkv_lds<HD>());
+    if (e != hipSuccess) return e;
+    ready = true;
+  }
   const int64_t lanes = (int64_t)a.b * a.s * a.h * (HD / 8);
   hipLaunchKernelGGL((attn_delta_kernel<HD>), dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, s, a);
-  hipLaunchKernelGGL((attn_dq_kernel<HD>), dim3(a.h, (a.s + FWD_BQ - 1) / FWD_BQ, a.b), dim3(FWD_THREADS), 0, s, a);
-    // 256 keys per workgroup (8 wavefronts, two per SIMD) when that still gives two workgroups per CU, else 128
-  if ((int64_t)a.b * a.hkv * ((a.s + 255) / 256) >= 512)
-    hipLaunchKernelGGL((attn_dkv_kernel<HD, 512>), dim3(a.hkv, (a.s + 255) / 256, a.b), dim3(512), 0, s, a);
-  else
-    hipLaunchKernelGGL((attn_dkv_kernel<HD, 256>), dim3(a.hkv, (a.s + 127) / 128, a.b), dim3(256), 0, s, a);
+  hipLaunchKernelGGL((attn_dq_kernel<HD>), dim3(a.h, (a.s + FWD_BQ - 1) / FWD_BQ, a.b), dim3(FWD_THREADS), fwd_lds<HD>(), s, a);
+  hipLaunchKernelGGL((attn_dkv_kernel<HD>), dim3(a.hkv, (a.s + DKV_BKEY - 1) / DKV_BKEY, a.b), dim3(DKV_THREADS), dkv_lds<HD>(), s, a);
   return hipGetLastError();
 }
 
@@ -537,6 +739,7 @@ bool attn_mfma_supported(const AttnArgs& a) {
   if (a.hd != 64 && a.hd != 128) return false;
   if (a.ld % 8 || ((uintptr_t)a.qkv & 15) || ((uintptr_t)a.o & 15)) return false;
   if (a.dout && (((uintptr_t)a.dout & 15) || ((uintptr_t)a.dqkv & 15))) return false;
+  if ((int64_t)a.s * a.ld * 2 >= ((int64_t)1 << 31)) return false;   // tile loads use 32-bit byte offsets inside a sequence
   return a.b > 0 && a.s > 0 && a.h > 0 && a.hkv > 0 && a.h % a.hkv == 0;
 }
 
