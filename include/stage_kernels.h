@@ -30,6 +30,14 @@ extern "C" {
 int stage_kernel_gemm(int dtype, int mode, int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
                       void* C, int64_t ldc, const void* R, int64_t ldr, int acc_f32, int kernel_set, void* hip_stream);
 
+/* n weight-gradient products (mode 2 above) in one call: C_p[M_p,N_p] += A_p^T . B_p for p = 0..n-1, the separately
+ * schedulable W block of the paper's Appendix B for several linear maps at once.  All array arguments are HOST arrays of
+ * length n (the pointers in A, B, C are device pointers); the C_p must not overlap.  Results are bit-identical to n calls
+ * of stage_kernel_gemm in mode 2.  n = 0 is a no-op; STAGE_E_INVAL for a negative n, a null array or a null entry. */
+int stage_kernel_wgrad_group(int dtype, int n, const int* M, const int* N, const int* K, const void* const* A,
+                             const int64_t* lda, const void* const* B, const int64_t* ldb, float* const* C,
+                             const int64_t* ldc, int kernel_set, void* hip_stream);
+
 /* qkv: [b*s, (h + 2*hkv)*hd] rows of q | k | v;  o: [b*s, h*hd];  lse: [b, h, s] fp32. */
 int stage_kernel_attention_fwd(int dtype, int b, int s, int h, int hkv, int hd, int causal, const void* qkv, void* o,
                                float* lse, int kernel_set, void* hip_stream);

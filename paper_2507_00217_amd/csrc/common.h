@@ -84,6 +84,11 @@ hipError_t widen_to_f32(DType dt, float* dst, const void* src, size_t n, hipStre
 // tuned gfx950 kernels (bf16 MFMA)
 bool gemm_mfma_supported(const GemmArgs& g);
 hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s);
+// several weight-gradient (TN, fp32-accumulating) products in one launch of persistent workgroups; each may reduce
+// over nseg operand pairs in turn, pair s at (A + seg_delta[s] bytes, B + seg_delta[s] bytes), seg_delta[0] = 0
+constexpr int GEMM_MAX_SEG = 8;
+bool gemm_mfma_wgrad_group_supported(const GemmArgs* list, int n, int nseg, const int64_t* seg_delta);
+hipError_t gemm_mfma_wgrad_group(const GemmArgs* list, int n, int nseg, const int64_t* seg_delta, hipStream_t s);
 bool attn_mfma_supported(const AttnArgs& a);
 hipError_t attn_fwd_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t attn_bwd_mfma(const AttnArgs& a, hipStream_t s);

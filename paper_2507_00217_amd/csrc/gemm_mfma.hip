@@ -150,47 +150,47 @@ __device__ __forceinline__ bf16x8 frag(lds_char* const (&pt)[4], int b, int ks) 
 
 // TN = 32-column accumulator blocks per wavefront: 2 -> 8 wavefronts of 128x64 (two per SIMD, 128 accumulator
 // registers each), 4 -> 4 wavefronts of 128x128 (one per SIMD, 256 accumulator registers, a third less LDS read traffic)
+// K segments: the reduction may run over `nseg` operand pairs of equal shape, pair s being (A, B) moved by
+// seg_delta[s] bytes (seg_delta[0] == 0): C (+)= sum_s A_s . B_s with the K tiles taken in order s = 0, 1, ...  One
+// pass over K then does the work of nseg launches with a single read-modify-write of C, and -- fp32 accumulators
+// written to and read back from fp32 memory unchanged -- gives the same bits as those launches one after another.
 template <bool AKC, bool BKC, int EPI, int TN>
-__global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds_char* smem, int nseg = 1,
+                                          const int64_t* seg_delta = nullptr) {
   constexpr int WGN = 8 / TN, WAVES = 2 * WGN, CH = TILE_SLOTS / (WAVES * 64);   // wave grid 2 x WGN
-  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
-  lds_char* smem = (lds_char*)smem_raw;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / WGN) * 128, wn = (wave % WGN) * (TN * 32);
 
-  // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give XCD x the
-  // x-th contiguous band of the tile sequence; inside it walk groups of 8 tile rows column by column.
-  int bid = blockIdx.x;
-  const int nb = tiles_m * tiles_n;
-  {
-    const int per = nb >> 3, main = per << 3;
-    if (bid < main) bid = (bid & 7) * per + (bid >> 3);
-  }
-  constexpr int GROUP = 8;
-  const int in_group = GROUP * tiles_n;
-  const int gid = bid / in_group;
-  const int first_m = gid * GROUP;
-  const int gsz = min(tiles_m - first_m, GROUP);
-  const int tile_m = first_m + (bid % in_group) % gsz;
-  const int tile_n = (bid % in_group) / gsz;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-
   // buffer descriptors cover exactly the rows that exist: KC operand = [rows, ld], other = [K, ld]
-  const rsrc_words rsA = raw_rsrc(g.A, (unsigned)(((int64_t)((AKC ? g.M : g.K) - 1) * g.lda + (AKC ? g.K : g.M)) * 2));
-  const rsrc_words rsB = raw_rsrc(g.B, (unsigned)(((int64_t)((BKC ? g.N : g.K) - 1) * g.ldb + (BKC ? g.K : g.N)) * 2));
+  const unsigned bytesA = (unsigned)(((int64_t)((AKC ? g.M : g.K) - 1) * g.lda + (AKC ? g.K : g.M)) * 2);
+  const unsigned bytesB = (unsigned)(((int64_t)((BKC ? g.N : g.K) - 1) * g.ldb + (BKC ? g.K : g.N)) * 2);
+  rsrc_words rsA = raw_rsrc(g.A, bytesA), rsB = raw_rsrc(g.B, bytesB);
+  // where the next K tile to fetch lies: segment and reduction offset inside it (all wave-uniform)
+  int ld_seg = 0, ld_k = 0;
+  auto advance = [&]() {
+    ld_k += BK;
+    if (ld_k >= g.K && ld_seg + 1 < nseg) {
+      ld_k = 0;
+      ++ld_seg;
+      rsA = raw_rsrc((const char*)g.A + seg_delta[ld_seg], bytesA);
+      rsB = raw_rsrc((const char*)g.B + seg_delta[ld_seg], bytesB);
+    }
+  };
   unsigned offa[CH], offb[CH];
   tile_offsets<AKC, WAVES, CH>(offa, g.lda, m0, g.M, wave, lane);
   tile_offsets<BKC, WAVES, CH>(offb, g.ldb, n0, g.N, wave, lane);
 
   // LDS map: buffer u at byte u * 2 * TILE_BYTES, A tile first, then B tile
   constexpr int BUF_BYTES = 2 * TILE_BYTES;
-  const int nk = (g.K + BK - 1) / BK;
+  const int nk = ((g.K + BK - 1) / BK) * nseg;
   g2s<AKC, WAVES, CH>(smem, rsA, offa, g.lda, 0, wave);
   g2s<BKC, WAVES, CH>(smem + TILE_BYTES, rsB, offb, g.ldb, 0, wave);
+  advance();
   if (nk > 1) {
-    g2s<AKC, WAVES, CH>(smem + BUF_BYTES, rsA, offa, g.lda, BK, wave);
-    g2s<BKC, WAVES, CH>(smem + BUF_BYTES + TILE_BYTES, rsB, offb, g.ldb, BK, wave);
+    g2s<AKC, WAVES, CH>(smem + BUF_BYTES, rsA, offa, g.lda, ld_k, wave);
+    g2s<BKC, WAVES, CH>(smem + BUF_BYTES + TILE_BYTES, rsB, offb, g.ldb, ld_k, wave);
+    advance();
   }
 
   // Accumulators start at zero, or -- weight gradients, C += A^T.B -- at the current value of C: the read half of
@@ -292,11 +292,12 @@ __global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int ti
         __builtin_amdgcn_sched_barrier(0);
         const int n = i * TN + j;         // 4*TN MFMAs, 2*CH == 4*TN loads
         if (more) {
-          if (n < CH) g2s_one<AKC, WAVES, CH>(fill, rsA, offa, g.lda, (kt + 2) * BK, wave, n);
-          else g2s_one<BKC, WAVES, CH>(fill + TILE_BYTES, rsB, offb, g.ldb, (kt + 2) * BK, wave, n - CH);
+          if (n < CH) g2s_one<AKC, WAVES, CH>(fill, rsA, offa, g.lda, ld_k, wave, n);
+          else g2s_one<BKC, WAVES, CH>(fill + TILE_BYTES, rsB, offb, g.ldb, ld_k, wave, n - CH);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
+    advance();
     fill += hop;
     hop = -hop;
   }
@@ -375,6 +376,66 @@ __global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int ti
   }
 }
 
+// Walk order of the 256x256 tiles of one product: groups of 8 tile rows, column by column inside a group.
+__device__ __forceinline__ void tile_of(int idx, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+  constexpr int GROUP = 8;
+  const int in_group = GROUP * tiles_n;
+  const int gid = idx / in_group;
+  const int first_m = gid * GROUP;
+  const int gsz = min(tiles_m - first_m, GROUP);
+  tile_m = first_m + (idx % in_group) % gsz;
+  tile_n = (idx % in_group) / gsz;
+}
+
+// one workgroup per tile
+template <bool AKC, bool BKC, int EPI, int TN>
+__global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give XCD x the
+  // x-th contiguous band of the tile sequence.
+  int bid = blockIdx.x;
+  const int nb = tiles_m * tiles_n;
+  {
+    const int per = nb >> 3, main = per << 3;
+    if (bid < main) bid = (bid & 7) * per + (bid >> 3);
+  }
+  int tile_m, tile_n;
+  tile_of(bid, tiles_m, tiles_n, tile_m, tile_n);
+  gemm_tile<AKC, BKC, EPI, TN>(g, tile_m * BM, tile_n * BN, (lds_char*)smem_raw);
+}
+
+// Several weight-gradient products C_p += A_p^T . B_p in one launch of persistent workgroups.  Each workgroup
+// takes the tiles  r * gridDim.x + (its slot)  of the concatenated tile list, r = 0, 1, ...: after it has issued a
+// tile's stores it goes straight on to the next tile's C and operand loads, so the read-modify-write of the fp32
+// gradients -- a quarter of such a product's time when all workgroups do it at once and then wait -- overlaps
+// with MFMA work.  Every C tile is still produced by one workgroup in one pass over K: results are bit-identical
+// to separate launches.
+constexpr int GROUP_MAX = 16;
+struct GemmGroup {
+  int n, total_tiles, nseg;
+  int first_tile[GROUP_MAX + 1];
+  int64_t seg_delta[GEMM_MAX_SEG];
+  GemmArgs p[GROUP_MAX];
+};
+
+template <int TN>
+__global__ __launch_bounds__(1024 / TN) void gemm_wgrad_group_kernel(GemmGroup gg) {
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  const int G = gridDim.x;
+  // slot of this workgroup inside a round: XCD x (workgroup ids x, x+8, ...) gets a contiguous band of the round
+  const int per = G >> 3, main = per << 3;
+  const int slot = (int)blockIdx.x < main ? ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3) : (int)blockIdx.x;
+  for (int t = slot; t < gg.total_tiles; t += G) {
+    int pi = 0;
+    while (pi + 1 < gg.n && t >= gg.first_tile[pi + 1]) ++pi;        // wave-uniform scalar search
+    const GemmArgs& g = gg.p[pi];
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    int tile_m, tile_n;
+    tile_of(t - gg.first_tile[pi], tiles_m, tiles_n, tile_m, tile_n);
+    gemm_tile<false, false, EPI_ACC32, TN>(g, tile_m * BM, tile_n * BN, (lds_char*)smem_raw, gg.nseg, gg.seg_delta);
+  }
+}
+
 // Eight wavefronts of 128x64 and four of 128x128 measure within a few percent of each other on the stage's shapes
 // (the narrower ones ahead on forward and input-gradient products, the wider ones on some weight-gradient ones).
 constexpr int WAVE_COLS = 2;
@@ -421,6 +482,51 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s) {
     case GEMM_TN: return launch<false, false, EPI_ACC32>(g, s);
   }
   return hipErrorInvalidValue;
+}
+
+bool gemm_mfma_wgrad_group_supported(const GemmArgs* list, int n, int nseg, const int64_t* seg_delta) {
+  if (n < 1 || nseg < 1 || nseg > GEMM_MAX_SEG || (nseg > 1 && !seg_delta)) return false;
+  for (int s = 1; s < nseg; ++s)
+    if (seg_delta[s] % 16) return false;
+  for (int i = 0; i < n; ++i)
+    if (list[i].mode != GEMM_TN || !gemm_mfma_supported(list[i])) return false;
+  return true;
+}
+
+hipError_t gemm_mfma_wgrad_group(const GemmArgs* list, int n, int nseg, const int64_t* seg_delta, hipStream_t s) {
+  static bool attr_set = false;
+  auto kern = gemm_wgrad_group_kernel<WAVE_COLS>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  static int n_cu = 0;
+  if (!n_cu) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
+    n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  for (int i0 = 0; i0 < n; i0 += GROUP_MAX) {
+    GemmGroup gg;
+    gg.n = n - i0 < GROUP_MAX ? n - i0 : GROUP_MAX;
+    gg.nseg = nseg;
+    for (int sg = 0; sg < GEMM_MAX_SEG; ++sg) gg.seg_delta[sg] = (sg > 0 && sg < nseg) ? seg_delta[sg] : 0;
+    int total = 0;
+    for (int i = 0; i < gg.n; ++i) {
+      gg.p[i] = list[i0 + i];
+      gg.first_tile[i] = total;
+      total += ((gg.p[i].M + BM - 1) / BM) * ((gg.p[i].N + BN - 1) / BN);
+    }
+    for (int i = gg.n; i <= GROUP_MAX; ++i) gg.first_tile[i] = total;
+    gg.total_tiles = total;
+    const int grid = total < n_cu ? total : n_cu;       // one workgroup per CU (128 KiB of LDS each)
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(1024 / WAVE_COLS), LDS_BYTES, s, gg);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace stg

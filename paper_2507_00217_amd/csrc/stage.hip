@@ -418,18 +418,55 @@ int exec_backward_input(stage* st, int mb, const void* dy, void* dx, int l0, int
   return STAGE_OK;
 }
 
-int exec_backward_weight(stage* st, int mb, int l0, int l1) {
+// A list of weight-gradient products, each reducing over nseg operand pairs in turn (pair s = the list's A and B
+// moved by seg_delta[s] bytes): one launch of persistent workgroups when the tuned kernel takes all of them, else
+// product by product and pair by pair -- the same accumulation order, hence the same bits.
+hipError_t wgrad_list(DType dt, int kernel_set, const GemmArgs* list, int n, int nseg, const int64_t* seg_delta, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  if (kernel_set == 0 && dt == DT_BF16 && gemm_mfma_wgrad_group_supported(list, n, nseg, seg_delta))
+    return gemm_mfma_wgrad_group(list, n, nseg, seg_delta, s);
+  for (int sg = 0; sg < nseg; ++sg)
+    for (int i = 0; i < n; ++i) {
+      GemmArgs g = list[i];
+      if (sg > 0) { g.A = (const char*)g.A + seg_delta[sg]; g.B = (const char*)g.B + seg_delta[sg]; }
+      hipError_t e = (kernel_set == 0 && dt == DT_BF16 && gemm_mfma_supported(g)) ? gemm_mfma(g, s) : gemm_ref(dt, g, s);
+      if (e != hipSuccess) return e;
+    }
+  return hipSuccess;
+}
+
+// W of layers [l0, l1) for the microbatches mbs[0..n_mb), in that order.  The four weight-gradient products of every
+// layer do not depend on each other and go out as one list; the same product of successive microbatches becomes one
+// reduction over their operand pairs (every tensor of a microbatch sits at the same offset inside its stash slot, so
+// one byte offset per microbatch places all its operands), which reads and writes the fp32 gradients once.
+int exec_backward_weight(stage* st, const int* mbs, int n_mb, int l0, int l1) {
   const Dims& D = st->D;
+  std::vector<GemmArgs> list;
+  list.reserve((size_t)4 * (l1 - l0));
+  double flops = 0.0;
+  auto add = [&](int M, int N, const void* A, int64_t lda, const void* B, int64_t ldb, float* C) {
+    list.push_back(GemmArgs{GEMM_TN, M, N, D.T, A, lda, B, ldb, C, (int64_t)N, nullptr, 0, 1, 0, 0});
+    flops += 2.0 * M * N * D.T * n_mb;
+  };
   for (int l = l0; l < l1; ++l) {
-    const LayerBuf o = layer_buf(st, mb, l);
+    const LayerBuf o = layer_buf(st, mbs[0], l);
     const LayerW W = layer_weights(st, l);
-    int rc;
-    if ((rc = do_gemm(st, GEMM_TN, D.d, D.dq, D.T, o.n1, D.d, o.dqkv, D.dq, W.G[STAGE_P_WQKV], D.dq, nullptr, 0, 1))) return rc;
-    if ((rc = do_gemm(st, GEMM_TN, D.d, D.d, D.T, o.o, D.d, o.dx1b, D.d, W.G[STAGE_P_WO], D.d, nullptr, 0, 1))) return rc;
-    if ((rc = do_gemm(st, GEMM_TN, D.d, D.fin, D.T, o.n2, D.d, o.z, D.fin, W.G[STAGE_P_WIN], D.fin, nullptr, 0, 1))) return rc;
-    if ((rc = do_gemm(st, GEMM_TN, D.f, D.d, D.T, o.a, D.f, o.dyb, D.d, W.G[STAGE_P_WOUT], D.d, nullptr, 0, 1))) return rc;
+    add(D.d, D.dq, o.n1, D.d, o.dqkv, D.dq, W.G[STAGE_P_WQKV]);
+    add(D.d, D.d, o.o, D.d, o.dx1b, D.d, W.G[STAGE_P_WO]);
+    add(D.d, D.fin, o.n2, D.d, o.z, D.fin, W.G[STAGE_P_WIN]);
+    add(D.f, D.d, o.a, D.f, o.dyb, D.d, W.G[STAGE_P_WOUT]);
   }
+  int64_t delta[GEMM_MAX_SEG] = {0};
+  for (int i = 1; i < n_mb; ++i) delta[i] = layer_buf(st, mbs[i], l0).n1 - layer_buf(st, mbs[0], l0).n1;
+  ProfScope ps(st, STAGE_K_GEMM_TN, flops);
+  HIPCHK(wgrad_list(st->dt, st->kernel_set, list.data(), (int)list.size(), n_mb, delta, st->stream));
   return STAGE_OK;
+}
+
+void release_slots(stage* st, int mb) {
+  st->free_slots.push_back(st->slot_of[mb]);
+  st->slot_of[mb] = -1;
+  if (st->big_of[mb] >= 0) { st->free_big.push_back(st->big_of[mb]); st->big_of[mb] = -1; }
 }
 
 // Applies one already-validated op (sub < 0: the whole op, every sub-block): allocator bookkeeping + launches.
@@ -451,12 +488,8 @@ int apply_op(stage* st, int kind, int mb, int sub, bool had_slot, bool holds_slo
     }
     rc = exec_backward_input(st, mb, in, out, l0, l1);
   } else {
-    rc = exec_backward_weight(st, mb, l0, l1);
-    if (!holds_slot) {
-      st->free_slots.push_back(st->slot_of[mb]);
-      st->slot_of[mb] = -1;
-      if (st->big_of[mb] >= 0) { st->free_big.push_back(st->big_of[mb]); st->big_of[mb] = -1; }
-    }
+    rc = exec_backward_weight(st, &mb, 1, l0, l1);
+    if (!holds_slot) release_slots(st, mb);
   }
   return rc;
 }
@@ -484,14 +517,37 @@ int run_list(stage* st, int n_ops, GetOp get, const void* x_all, const void* dy_
     if (rc != STAGE_OK) return rc;
   }
   const size_t mb_bytes = (size_t)st->D.T * st->D.d * st->D.es;
+  // Adjacent W ops on the same layers (same sub-block, or whole ops) are enqueued as one: their microbatches, in list
+  // order, become the K segments of one set of weight-gradient products.  The tracker still sees them one by one;
+  // the stash slots are handed back when the merged launch has been enqueued.
+  int run_mb[GEMM_MAX_SEG], run_n = 0, run_sub = 0;
+  bool run_release[GEMM_MAX_SEG];
+  auto flush = [&]() -> int {
+    if (run_n == 0) return STAGE_OK;
+    const int per = st->D.L / st->D.n_sub;
+    const int l0 = run_sub < 0 ? 0 : run_sub * per, l1 = run_sub < 0 ? st->D.L : (run_sub + 1) * per;
+    const int rc = exec_backward_weight(st, run_mb, run_n, l0, l1);
+    for (int i = 0; i < run_n; ++i)
+      if (run_release[i]) release_slots(st, run_mb[i]);
+    run_n = 0;
+    return rc;
+  };
   for (int i = 0; i < n_ops; ++i) {
     int kind, mb, sub; get(i, kind, mb, sub);
-    const void* in = kind == STAGE_F ? (const char*)x_all + mb_bytes * mb : kind == STAGE_B ? (const char*)dy_all + mb_bytes * mb : nullptr;
-    void* out = kind == STAGE_F ? (char*)y_all + mb_bytes * mb : kind == STAGE_B ? (char*)dx_all + mb_bytes * mb : nullptr;
+    if (kind == STAGE_W) {
+      if (run_n > 0 && (sub != run_sub || run_n == GEMM_MAX_SEG)) { const int rc = flush(); if (rc != STAGE_OK) return rc; }
+      const int rc = sub < 0 ? st->tr.step(kind, mb) : st->tr.step_sub(kind, mb, sub);
+      if (rc != STAGE_OK) { flush(); return rc; }
+      run_sub = sub; run_mb[run_n] = mb; run_release[run_n] = !st->tr.slot_held(mb); ++run_n;
+      continue;
+    }
+    { const int rc = flush(); if (rc != STAGE_OK) return rc; }
+    const void* in = kind == STAGE_F ? (const char*)x_all + mb_bytes * mb : (const char*)dy_all + mb_bytes * mb;
+    void* out = kind == STAGE_F ? (char*)y_all + mb_bytes * mb : (char*)dx_all + mb_bytes * mb;
     const int rc = run_one(st, kind, mb, sub, in, out);
     if (rc != STAGE_OK) return rc;
   }
-  return STAGE_OK;
+  return flush();
 }
 
 }  // namespace
@@ -711,6 +767,20 @@ int stage_kernel_gemm(int dtype, int mode, int M, int N, int K, const void* A, i
   GemmArgs g{mode, M, N, K, A, lda, B, ldb, C, ldc, R, ldr, acc_f32};
   if (kernel_set == 0 && dtype == STAGE_DTYPE_BF16 && gemm_mfma_supported(g)) return hip_rc(gemm_mfma(g, (hipStream_t)hip_stream));
   return hip_rc(gemm_ref((DType)dtype, g, (hipStream_t)hip_stream));
+}
+
+int stage_kernel_wgrad_group(int dtype, int n, const int* M, const int* N, const int* K, const void* const* A,
+                             const int64_t* lda, const void* const* B, const int64_t* ldb, float* const* C,
+                             const int64_t* ldc, int kernel_set, void* hip_stream) {
+  if (!dtype_ok(dtype) || n < 0) return STAGE_E_INVAL;
+  if (n == 0) return STAGE_OK;
+  if (!M || !N || !K || !A || !lda || !B || !ldb || !C || !ldc) return STAGE_E_INVAL;
+  std::vector<GemmArgs> list(n);
+  for (int i = 0; i < n; ++i) {
+    if (M[i] < 0 || N[i] < 0 || K[i] < 0 || !A[i] || !B[i] || !C[i]) return STAGE_E_INVAL;
+    list[i] = GemmArgs{GEMM_TN, M[i], N[i], K[i], A[i], lda[i], B[i], ldb[i], C[i], ldc[i], nullptr, 0, 1, 0, 0};
+  }
+  return hip_rc(wgrad_list((DType)dtype, kernel_set, list.data(), n, 1, nullptr, (hipStream_t)hip_stream));
 }
 
 static bool attn_shape(int dtype, int b, int s, int h, int hkv, int hd, int causal) {

@@ -21,6 +21,7 @@ def L():
     if not hasattr(lib, "_ksig"):
         vp, i, i64, fl = C.c_void_p, C.c_int, C.c_int64, C.c_float
         lib.stage_kernel_gemm.argtypes = [i, i, i, i, i, vp, i64, vp, i64, vp, i64, vp, i64, i, i, vp]
+        lib.stage_kernel_wgrad_group.argtypes = [i, i] + [vp] * 9 + [i, vp]
         lib.stage_kernel_attention_fwd.argtypes = [i] * 7 + [vp, vp, vp, i, vp]
         lib.stage_kernel_attention_bwd.argtypes = [i] * 7 + [vp] * 6 + [i, vp]
         lib.stage_kernel_norm_fwd.argtypes = [i, i, i, i, fl, vp, vp, vp, vp, vp, vp]
@@ -66,6 +67,41 @@ def test_gemm(dtype, mode, kernel_set, M, N, K):
     assert rc == 0
     torch.cuda.synchronize()
     assert so.max_rel_err(to_np(Cd), ref) <= (KTOL[dtype] if mode != 2 else 2e-5 if dtype == "fp32" else 1e-5 * math.sqrt(K))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("kernel_set", [0, 1])
+def test_wgrad_group(dtype, kernel_set):
+    """Several weight-gradient products C_p += A_p^T.B_p in one call (the W block of Appendix B for several linear
+    maps): against the definition, and bit for bit against one stage_kernel_gemm call per product.  The shapes give
+    about 300 tiles of 256 x 256 with ragged edges, so the persistent workgroups of the tuned kernel each take more
+    than one tile and cross from one product to the next."""
+    import torch
+    shapes = [(520, 1088, 328), (256, 256, 64), (1536, 2304, 200), (768, 3080, 136), (264, 72, 512), (2560, 5120, 72)]
+    n = len(shapes)
+    As, Bs, Cs, C1, refs = [], [], [], [], []
+    for p, (M, N, K) in enumerate(shapes):
+        A = rnd(synth.normal(5, 3 * p, (K, M)), dtype); Bm = rnd(synth.normal(5, 3 * p + 1, (K, N)), dtype)
+        C0 = synth.normal(5, 3 * p + 2, (M, N))
+        As.append(to_dev(A, dtype)); Bs.append(to_dev(Bm, dtype))
+        Cs.append(to_dev(C0, "fp32")); C1.append(to_dev(C0, "fp32"))
+        refs.append(C0.astype(np.float64) + A.astype(np.float64).T @ Bm.astype(np.float64))
+    ia = lambda v: (C.c_int * n)(*v)
+    la = lambda v: (C.c_int64 * n)(*v)
+    pa = lambda ts: (C.c_void_p * n)(*[t.data_ptr() for t in ts])
+    Ms, Ns, Ks = zip(*shapes)
+    rc = L().stage_kernel_wgrad_group(DT[dtype], n, ia(Ms), ia(Ns), ia(Ks), pa(As), la(Ms), pa(Bs), la(Ns), pa(Cs), la(Ns),
+                                      kernel_set, None)
+    assert rc == 0
+    for p, (M, N, K) in enumerate(shapes):
+        assert L().stage_kernel_gemm(DT[dtype], 2, M, N, K, P(As[p]), M, P(Bs[p]), N, P(C1[p]), N, None, 0, 1, kernel_set, None) == 0
+    torch.cuda.synchronize()
+    for p, (M, N, K) in enumerate(shapes):
+        assert so.max_rel_err(to_np(Cs[p]), refs[p]) <= (2e-5 if dtype == "fp32" else 1e-5 * math.sqrt(K)), p
+        assert torch.equal(Cs[p], C1[p]), p
+    assert L().stage_kernel_wgrad_group(DT[dtype], 0, None, None, None, None, None, None, None, None, None, kernel_set, None) == 0
+    assert L().stage_kernel_wgrad_group(DT[dtype], -1, ia(Ms), ia(Ns), ia(Ks), pa(As), la(Ms), pa(Bs), la(Ns), pa(Cs), la(Ns), 0, None) == -1
+    assert L().stage_kernel_wgrad_group(DT[dtype], n, ia(Ms), ia(Ns), ia(Ks), None, la(Ms), pa(Bs), la(Ns), pa(Cs), la(Ns), 0, None) == -1
 
 
 def test_gemm_rejects_bad_arguments():
