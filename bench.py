@@ -27,10 +27,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per GEMM launch (average over the NN/NT/TN launches of one cfg3 iteration), from two rocprofv3 --pmc
-# runs (FETCH_SIZE, WRITE_SIZE) scaled by the same counters' reading for the plain copy kernel of known size in
-# the same run; summary and commands in profiles/cfg3_schedule_pmc.md.  Only valid for the cfg3 workload.
-MEASURED_GEMM_TRAFFIC_BYTES = {"cfg3": 870.1e6}
+# HBM-side bytes per GEMM launch (average over the forward, input-gradient and grouped weight-gradient launches of one
+# cfg3 iteration: 525 launches for 768 products), from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by the
+# same counters' reading for the plain copy kernel of known size in the same run; summary and commands in
+# profiles/cfg3_schedule_pmc.md.  Only valid for the cfg3 workload with its default schedule.
+MEASURED_GEMM_TRAFFIC_BYTES = {"cfg3": 1304e6}
 
 
 def flops_per_layer_mb(cfg):
@@ -170,10 +171,10 @@ def main():
     gemm_n = sum(prof[k]["launches"] for k in ("gemm_nn", "gemm_nt", "gemm_tn"))
     peak = PEAK_BF16_TFLOPS if cfg["dtype"] == "bf16" else PEAK_FP32_TFLOPS
     achieved = gemm_work / (gemm_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma" if cfg["dtype"] == "bf16" else "alu", "kernel": "gemm_mfma_kernel (NN+NT+TN launches of one iteration)",
+    roofline = {"bound": "mfma" if cfg["dtype"] == "bf16" else "alu", "kernel": "GEMM family: gemm_mfma_kernel (forward, input gradients) + gemm_wgrad_group_kernel (weight gradients), all launches of one iteration",
                 "achieved": round(achieved, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "flops_per_launch": gemm_work / gemm_n, "avg_launch_ms": round(gemm_ms / gemm_n, 5),
-                "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.config) if args.kernel_set == 0 else None}
+                "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.config) if args.kernel_set == 0 and not args.schedule and not args.recompute else None}
     stats = st.stats()
     # what the measured block times mean for a pipeline (the paper's performance model, host code): this stage's
     # T_F/T_D/T_W replicated over 8 stages in 2 datacenters, 2 x n_PP microbatches, memory of 1F1B, with latency and
