@@ -51,7 +51,7 @@ __device__ __forceinline__ void st_row(void* base, int64_t off, const float (&sr
 
 constexpr int NORM_THREADS = 256;
 constexpr int NORM_MAXCH = 4;          // 16-byte chunks per thread: d <= 256*4*(16/sizeof(T))
-constexpr int NORM_PARTIAL_ROWS = 256;   // multiple of 4
+constexpr int NORM_PARTIAL_ROWS = 512;   // multiple of 4; two workgroups per CU keep more rows in flight
 int norm_partial_rows() { return NORM_PARTIAL_ROWS; }
 
 __device__ __forceinline__ float wg_sum(float v, float* red) {
