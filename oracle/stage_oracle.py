@@ -58,10 +58,16 @@ class Shape:
     act: str = "gelu"         # "gelu" | "swiglu"
     causal: bool = True
     eps: float = 1e-5
+    hd: int = 0               # width of one head; 0 = hidden / n_heads.  A tensor-parallel share of a layer (the paper's
+                              # per-GPU shapes at TP > 1) keeps hidden but has fewer heads, so n_heads * hd < hidden.
 
     @property
     def head_dim(self) -> int:
-        return self.hidden // self.n_heads
+        return self.hd if self.hd else self.hidden // self.n_heads
+
+    @property
+    def q_dim(self) -> int:
+        return self.n_heads * self.head_dim
 
     @property
     def kv_dim(self) -> int:
@@ -137,12 +143,13 @@ def layer_forward(sh: Shape, p: Dict[str, np.ndarray], x):
     n1, c["norm1"] = norm_forward(sh.norm, x, p["g1"], p.get("b1", 0.0), sh.eps)
     c["n1"] = n1
     qkv = n1 @ p["wqkv"]
-    q = qkv[..., :d].reshape(b, s, h, hd)
-    k = qkv[..., d:d + dkv].reshape(b, s, hkv, hd)
-    v = qkv[..., d + dkv:].reshape(b, s, hkv, hd)
+    dq_ = sh.q_dim
+    q = qkv[..., :dq_].reshape(b, s, h, hd)
+    k = qkv[..., dq_:dq_ + dkv].reshape(b, s, hkv, hd)
+    v = qkv[..., dq_ + dkv:].reshape(b, s, hkv, hd)
     c["q"], c["k"], c["v"] = q, k, v
     o = attention_forward(sh, q, k, v)
-    o = o.reshape(b, s, d)
+    o = o.reshape(b, s, dq_)
     c["o"] = o
     x1 = x + o @ p["wo"]
     c["x1"] = x1
@@ -236,7 +243,7 @@ def layer_backward_input(sh: Shape, p, c, dy):
     do = dx1 @ p["wo"].T
     dq, dk, dv = attention_backward(sh, c["q"], c["k"], c["v"],
                                     do.reshape(b, s, sh.n_heads, sh.head_dim))
-    dz_qkv = np.concatenate([dq.reshape(b, s, d), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
+    dz_qkv = np.concatenate([dq.reshape(b, s, sh.q_dim), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
     saved["dz_qkv"] = dz_qkv
     dn1 = dz_qkv @ p["wqkv"].T
     dx_n, dg1, db1 = norm_backward(sh.norm, c["norm1"], p["g1"], dn1)
@@ -276,7 +283,7 @@ def layer_backward_full(sh: Shape, p, c, dy):
     do = dx1 @ p["wo"].T
     dq, dk, dv = attention_backward(sh, c["q"], c["k"], c["v"],
                                     do.reshape(b, s, sh.n_heads, sh.head_dim))
-    dqkv = np.concatenate([dq.reshape(b, s, d), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
+    dqkv = np.concatenate([dq.reshape(b, s, sh.q_dim), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
     gr["wqkv"] = _flat(c["n1"]).T @ _flat(dqkv)
     dn1 = dqkv @ p["wqkv"].T
     t, gr["g1"], db1 = norm_backward(sh.norm, c["norm1"], p["g1"], dn1)

@@ -126,10 +126,11 @@ def param_names(cfg: dict) -> Tuple[str, ...]:
 
 def param_shape(cfg: dict, name: str) -> Tuple[int, ...]:
     d, f = cfg["hidden"], cfg["ffn"]
-    dkv = cfg["n_kv_heads"] * (d // cfg["n_heads"])
+    hd = cfg.get("head_dim") or d // cfg["n_heads"]          # a tensor-parallel share keeps hidden but has fewer heads
+    da, dkv = cfg["n_heads"] * hd, cfg["n_kv_heads"] * hd
     fin = 2 * f if cfg["act"] == "swiglu" else f
     return {"g1": (d,), "b1": (d,), "g2": (d,), "b2": (d,),
-            "wqkv": (d, d + 2 * dkv), "wo": (d, d), "win": (d, fin), "wout": (f, d)}[name]
+            "wqkv": (d, da + 2 * dkv), "wo": (da, d), "win": (d, fin), "wout": (f, d)}[name]
 
 
 def make_weights(cfg: dict, seed: int) -> List[Dict[str, np.ndarray]]:

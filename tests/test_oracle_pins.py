@@ -12,14 +12,14 @@ from paper_2507_00217_amd import synth
 F, B, W = so.F, so.B, so.W
 
 
-def tiny_cfg(norm="layernorm", act="gelu", n_kv=2, causal=True, L=2, b=1, n_mb=3):
+def tiny_cfg(norm="layernorm", act="gelu", n_kv=2, causal=True, L=2, b=1, n_mb=3, head_dim=0):
     return dict(n_layers=L, hidden=16, n_heads=2, n_kv_heads=n_kv, ffn=32, seq=8, mb_size=b,
-                n_microbatches=n_mb, norm=norm, act=act, dtype="fp32", causal=causal)
+                n_microbatches=n_mb, norm=norm, act=act, dtype="fp32", causal=causal, head_dim=head_dim)
 
 
 def shape_of(cfg):
     return so.Shape(cfg["n_layers"], cfg["hidden"], cfg["n_heads"], cfg["n_kv_heads"], cfg["ffn"],
-                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], cfg.get("causal", True))
+                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], cfg.get("causal", True), hd=cfg.get("head_dim", 0) or 0)
 
 
 def setup(cfg, seed=11, wstd_boost=10.0):
@@ -128,12 +128,14 @@ def test_sum_over_microbatches_equals_full_batch():
             assert so.max_rel_err(la[k], lb[k]) <= 1e-12, k
 
 
-@pytest.mark.parametrize("norm,act,n_kv,causal", VARIANTS)
-def test_against_torch_autograd(norm, act, n_kv, causal):
+@pytest.mark.parametrize("norm,act,n_kv,causal,head_dim", [v + (0,) for v in VARIANTS] + [("rmsnorm", "swiglu", 1, True, 4),
+                                                                                       ("layernorm", "gelu", 2, True, 12)])
+def test_against_torch_autograd(norm, act, n_kv, causal, head_dim):
     """Second opinion from a library: the same layer stack composed from
-    PyTorch CPU primitives, differentiated by autograd, in fp64."""
+    PyTorch CPU primitives, differentiated by autograd, in fp64.  The last two cases have heads that do not tile the
+    hidden width (n_heads * head_dim = 8 and 24 against hidden 16), as a tensor-parallel share of a layer has."""
     torch = pytest.importorskip("torch")
-    cfg = tiny_cfg(norm, act, n_kv, causal, b=2, n_mb=2)
+    cfg = tiny_cfg(norm, act, n_kv, causal, b=2, n_mb=2, head_dim=head_dim)
     sh, params, X, G = setup(cfg)
     st = so.OracleStage(sh, params)
     Y, dX, _ = st.run_schedule(synth.schedule_1f1b(2, 1), X, G)
@@ -150,11 +152,11 @@ def test_against_torch_autograd(norm, act, n_kv, causal):
     def tlayer(x, p):
         bsz, s, _ = x.shape
         qkv = tnorm(x, p["g1"], p.get("b1")) @ p["wqkv"]
-        q = qkv[..., :d].reshape(bsz, s, h, hd).transpose(1, 2)
-        k = qkv[..., d:d + hkv * hd].reshape(bsz, s, hkv, hd).transpose(1, 2).repeat_interleave(h // hkv, dim=1)
-        v = qkv[..., d + hkv * hd:].reshape(bsz, s, hkv, hd).transpose(1, 2).repeat_interleave(h // hkv, dim=1)
+        q = qkv[..., :h * hd].reshape(bsz, s, h, hd).transpose(1, 2)
+        k = qkv[..., h * hd:(h + hkv) * hd].reshape(bsz, s, hkv, hd).transpose(1, 2).repeat_interleave(h // hkv, dim=1)
+        v = qkv[..., (h + hkv) * hd:].reshape(bsz, s, hkv, hd).transpose(1, 2).repeat_interleave(h // hkv, dim=1)
         o = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=causal)
-        x1 = x + o.transpose(1, 2).reshape(bsz, s, d) @ p["wo"]
+        x1 = x + o.transpose(1, 2).reshape(bsz, s, h * hd) @ p["wo"]
         z = tnorm(x1, p["g2"], p.get("b2")) @ p["win"]
         a = torch.nn.functional.gelu(z) if act == "gelu" else torch.nn.functional.silu(z[..., :f]) * z[..., f:]
         return x1 + a @ p["wout"]
