@@ -36,11 +36,12 @@ MEASURED_GEMM_TRAFFIC_BYTES = {"cfg3": 1304e6}
 
 def flops_per_layer_mb(cfg):
     d, f, h = cfg["hidden"], cfg["ffn"], cfg["n_heads"]
-    dkv = cfg["n_kv_heads"] * (d // h)
+    hd = cfg.get("head_dim") or d // h
+    da, dkv = h * hd, cfg["n_kv_heads"] * hd
     T = cfg["seq"] * cfg["mb_size"]
     fin = 2 * f if cfg["act"] == "swiglu" else f
-    gemm = 2.0 * T * (d * (d + 2 * dkv) + d * d + d * fin + f * d)
-    attn = (2.0 if cfg.get("causal", True) else 4.0) * cfg["mb_size"] * cfg["seq"] ** 2 * d
+    gemm = 2.0 * T * (d * (da + 2 * dkv) + da * d + d * fin + f * d)
+    attn = (2.0 if cfg.get("causal", True) else 4.0) * cfg["mb_size"] * cfg["seq"] ** 2 * da
     return {"F": gemm + attn, "B": gemm + 2.5 * attn, "W": gemm, "gemm": gemm, "attn_fwd": attn}
 
 
@@ -66,7 +67,7 @@ def cpu_baseline(cfg, budget_s=30.0):
     X = synth.make_boundary(one, 2).astype(np.float64)
     G = synth.make_boundary(one, 3).astype(np.float64)
     sh = so.Shape(1, one["hidden"], one["n_heads"], one["n_kv_heads"], one["ffn"], one["seq"], one["mb_size"],
-                  one["norm"], one["act"], True)
+                  one["norm"], one["act"], True, hd=one.get("head_dim", 0) or 0)
     st = so.OracleStage(sh, params)
     t0 = time.perf_counter(); st.forward(0, X[0]); t1 = time.perf_counter()
     st.backward_input(0, G[0]); t2 = time.perf_counter()
@@ -107,7 +108,7 @@ def main():
     ops = synth.make_schedule(cfg)
     n_mb, L = cfg["n_microbatches"], cfg["n_layers"]
     tdt = torch.float32 if cfg["dtype"] == "fp32" else torch.bfloat16
-    seed = 1000 * int(args.config[3])
+    seed = 1000 * int(args.config[3]) if args.config[3:].isdigit() else 9000
     st = S.Stage(cfg)
     st.set_kernel_set(args.kernel_set)
     st.load_weights(synth.make_weights(cfg, seed))

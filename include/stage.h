@@ -74,7 +74,7 @@ typedef struct { int32_t kind; int32_t mb; } stage_op_t;
 typedef struct {
   int32_t n_layers;
   int32_t hidden;          /* d; multiple of 64 */
-  int32_t n_heads;         /* h; head_dim = d / h must be 64 or 128 */
+  int32_t n_heads;         /* h; head_dim (d / h unless given below) must be 64 or 128 */
   int32_t n_kv_heads;      /* divides n_heads (grouped-query attention when smaller) */
   int32_t ffn;             /* f; multiple of 64 */
   int32_t seq;             /* s */
@@ -96,6 +96,11 @@ typedef struct {
                               to recompute = 0. */
   int32_t recompute_cap;   /* recompute = 1: max microbatches holding such a full-size slot (B started, W not
                               finished); 0 = stash_cap; at most stash_cap.  Must be 0 when recompute = 0. */
+  int32_t head_dim;        /* width of one head, 64 or 128; 0 = hidden / n_heads.  With n_heads * head_dim != hidden the
+                              stage computes one tensor-parallel share of a layer (the paper's per-GPU shapes at TP > 1:
+                              fewer heads and a narrower ffn against the full hidden width): WQKV is
+                              [d, (h + 2 h_kv) head_dim] and WO [h head_dim, d].  Summing the shares' outputs is the
+                              caller's collective. */
 } stage_config_t;
 
 typedef struct { size_t weights, grads, stash, workspace; } stage_sizes_t; /* bytes */
@@ -117,7 +122,7 @@ int stage_validate_schedule(const stage_config_t* cfg, const stage_op_t* ops, in
 /* Host only. Where parameter `param_id` of `layer` lives inside the flat
  * weights buffer (compute dtype) and the flat grads buffer (fp32): same element
  * offset in both.  Linear weights are stored [in, out] row-major so that
- * forward is A.W:  WQKV [d, d+2*d_kv] (columns q | k | v),  WO [d, d],
+ * forward is A.W:  WQKV [d, d_q+2*d_kv] (columns q | k | v; d_q = h*head_dim),  WO [d_q, d],
  * WIN [d, f] (GELU) or [d, 2f] (SwiGLU, columns gate | up),  WOUT [f, d];
  * norm vectors have rows = 1, cols = d.  A parameter the config does not have
  * (beta under RMSNorm) reports rows = cols = 0. */

@@ -20,7 +20,7 @@ constexpr size_t ALIGN = 256;
 inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Dims {
-  int L, d, h, hkv, hd, dkv, dq, f, fin, s, b, T, n_mb, cap, n_sub;
+  int L, d, h, hkv, hd, da, dkv, dq, f, fin, s, b, T, n_mb, cap, n_sub;   // da = h*hd: width of the attention output
   int recompute, hcap;   // layer-wise recomputation on; cap on microbatches holding a rebuilt stash (B started, W not finished)
   size_t es;  // bytes per element of the compute dtype
 };
@@ -30,9 +30,11 @@ bool make_dims(const stage_config_t* c, Dims* o) {
   if (c->n_layers < 1 || c->hidden < 64 || c->n_heads < 1 || c->n_kv_heads < 1 || c->ffn < 64 || c->seq < 1 ||
       c->mb_size < 1 || c->n_microbatches < 1)
     return false;
-  if (c->hidden % 64 || c->ffn % 64 || c->hidden % c->n_heads || c->n_heads % c->n_kv_heads) return false;
-  const int hd = c->hidden / c->n_heads;
+  if (c->hidden % 64 || c->ffn % 64 || c->n_heads % c->n_kv_heads) return false;
+  if (c->head_dim < 0 || (c->head_dim == 0 && c->hidden % c->n_heads)) return false;
+  const int hd = c->head_dim ? c->head_dim : c->hidden / c->n_heads;
   if (hd != 64 && hd != 128) return false;
+  if ((int64_t)c->n_heads * hd > (1 << 20)) return false;
   if (c->norm != STAGE_NORM_LAYERNORM && c->norm != STAGE_NORM_RMSNORM) return false;
   if (c->act != STAGE_ACT_GELU && c->act != STAGE_ACT_SWIGLU) return false;
   if (c->dtype != STAGE_DTYPE_FP32 && c->dtype != STAGE_DTYPE_BF16) return false;
@@ -46,7 +48,7 @@ bool make_dims(const stage_config_t* c, Dims* o) {
   if (c->hidden > 256 * 4 * (int)(16 / es)) return false;  // one norm row must fit a workgroup's registers
   if ((int64_t)c->seq * c->mb_size > (1 << 20) || c->seq > 65536) return false;
   o->L = c->n_layers; o->d = c->hidden; o->h = c->n_heads; o->hkv = c->n_kv_heads; o->hd = hd;
-  o->dkv = c->n_kv_heads * hd; o->dq = o->d + 2 * o->dkv; o->f = c->ffn;
+  o->da = c->n_heads * hd; o->dkv = c->n_kv_heads * hd; o->dq = o->da + 2 * o->dkv; o->f = c->ffn;
   o->fin = c->act == STAGE_ACT_SWIGLU ? 2 * c->ffn : c->ffn;
   o->s = c->seq; o->b = c->mb_size; o->T = c->seq * c->mb_size; o->n_mb = c->n_microbatches;
   o->cap = c->stash_cap ? c->stash_cap : c->n_microbatches;
@@ -66,7 +68,7 @@ void param_dims(const Dims& D, int norm, int pid, int64_t* rows, int64_t* cols) 
       if (norm == STAGE_NORM_LAYERNORM) { *rows = 1; *cols = D.d; } else { *rows = 0; *cols = 0; }
       break;
     case STAGE_P_WQKV: *rows = D.d; *cols = D.dq; break;
-    case STAGE_P_WO: *rows = D.d; *cols = D.d; break;
+    case STAGE_P_WO: *rows = D.da; *cols = D.d; break;
     case STAGE_P_WIN: *rows = D.d; *cols = D.fin; break;
     case STAGE_P_WOUT: *rows = D.f; *cols = D.d; break;
     default: *rows = 0; *cols = 0;
@@ -105,7 +107,7 @@ LayerOff layer_off(const Dims& D, size_t base, bool with_x = true) {
   o.n1 = take(T * D.d * D.es);
   o.qkv = take(T * D.dq * D.es);
   o.dqkv = take(T * D.dq * D.es);
-  o.o = take(T * D.d * D.es);
+  o.o = take(T * D.da * D.es);
   o.x1 = take(T * D.d * sizeof(float));
   o.n2 = take(T * D.d * D.es);
   o.z = take(T * D.fin * D.es);
@@ -131,7 +133,7 @@ WsOff ws_off(const Dims& D) {
   WsOff w; size_t p = 0;
   auto take = [&](size_t bytes) { size_t r = p; p += up(bytes); return r; };
   w.da = take((size_t)D.T * D.f * D.es);
-  w.dn = take((size_t)D.T * D.d * D.es);
+  w.dn = take((size_t)D.T * (D.d > D.da ? D.d : D.da) * D.es);
   w.delta = take((size_t)D.b * D.h * D.s * sizeof(float));
   w.partial = take((size_t)norm_partial_rows() * 2 * D.d * sizeof(float));
   w.rec = take(D.recompute ? rec_bytes(D) : 0);       // the layer record F works in under recomputation
@@ -266,7 +268,7 @@ double act_bytes_fwd(const stage* st) { return (double)st->D.T * (st->D.fin + st
 double norm_bytes(const stage* st, int n_f32, int n_lp) { return (double)st->D.T * st->D.d * (4.0 * n_f32 + (double)st->D.es * n_lp); }
 double attn_flops(const stage* st, bool bwd) {
   const Dims& D = st->D;
-  const double dense = 4.0 * D.b * (double)D.s * D.s * D.d;
+  const double dense = 4.0 * D.b * (double)D.s * D.s * D.da;
   return (st->cfg.causal ? 0.5 : 1.0) * dense * (bwd ? 2.5 : 1.0);
 }
 
@@ -332,7 +334,7 @@ int forward_layer(stage* st, int l, const LayerBuf& o, void* y_l, bool y_lp) {
     if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_fwd_mfma(a, st->stream));
     else HIPCHK(attn_fwd_ref(st->dt, a, st->stream));
   }
-  rc = do_gemm(st, GEMM_NN, D.T, D.d, D.d, o.o, D.d, W.wo, D.d, o.x1, D.d, o.x, D.d, 0, 1, 1);
+  rc = do_gemm(st, GEMM_NN, D.T, D.d, D.da, o.o, D.da, W.wo, D.d, o.x1, D.d, o.x, D.d, 0, 1, 1);
   if (rc) return rc;
   n.x = o.x1; n.gamma = W.g2; n.beta = W.b2; n.out = o.n2; n.stats = o.st2;
   { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 1, 1)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
@@ -397,7 +399,7 @@ int exec_backward_input(stage* st, int mb, const void* dy, void* dx, int l0, int
     n.dgamma = W.G[STAGE_P_NORM2_GAMMA]; n.dbeta = W.G[STAGE_P_NORM2_BETA]; n.partial = (float*)(st->ws + w.partial);
     { ProfScope ps(st, STAGE_K_NORM_BWD, norm_bytes(st, last ? 2 : 3, last ? 3 : 2)); HIPCHK(norm_bwd(st->dt, n, st->stream)); }
     // attention: do = dx1.Wo^T ; (dq,dk,dv) ; dn1 = dqkv.Wqkv^T
-    rc = do_gemm(st, GEMM_NT, D.T, D.d, D.d, o.dx1b, D.d, W.wo, D.d, dn, D.d, nullptr, 0, 0);
+    rc = do_gemm(st, GEMM_NT, D.T, D.da, D.d, o.dx1b, D.d, W.wo, D.d, dn, D.da, nullptr, 0, 0);
     if (rc) return rc;
     AttnArgs a = attn_args(st, o, dn, w);
     {
@@ -452,7 +454,7 @@ int exec_backward_weight(stage* st, const int* mbs, int n_mb, int l0, int l1) {
     const LayerBuf o = layer_buf(st, mbs[0], l);
     const LayerW W = layer_weights(st, l);
     add(D.d, D.dq, o.n1, D.d, o.dqkv, D.dq, W.G[STAGE_P_WQKV]);
-    add(D.d, D.d, o.o, D.d, o.dx1b, D.d, W.G[STAGE_P_WO]);
+    add(D.da, D.d, o.o, D.da, o.dx1b, D.d, W.G[STAGE_P_WO]);
     add(D.d, D.fin, o.n2, D.d, o.z, D.fin, W.G[STAGE_P_WIN]);
     add(D.f, D.d, o.a, D.f, o.dyb, D.d, W.G[STAGE_P_WOUT]);
   }

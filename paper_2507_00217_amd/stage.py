@@ -28,7 +28,7 @@ OK, E_INVAL, E_ORDER, E_STASH_FULL, E_HIP = 0, -1, -2, -3, -4
 class StageConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_heads", "n_kv_heads", "ffn", "seq", "mb_size", "n_microbatches",
-        "norm", "act", "causal", "dtype", "stash_cap", "enforce_mb_order")] + [("norm_eps", C.c_float), ("n_sub", C.c_int32), ("recompute", C.c_int32), ("recompute_cap", C.c_int32)]
+        "norm", "act", "causal", "dtype", "stash_cap", "enforce_mb_order")] + [("norm_eps", C.c_float), ("n_sub", C.c_int32), ("recompute", C.c_int32), ("recompute_cap", C.c_int32), ("head_dim", C.c_int32)]
 
 
 class StageSubOp(C.Structure):
@@ -105,7 +105,8 @@ def make_config(cfg: dict) -> StageConfig:
         norm=NORM[cfg["norm"]], act=ACT[cfg["act"]], causal=int(cfg.get("causal", True)), dtype=DTYPE[cfg["dtype"]],
         stash_cap=cfg.get("stash_cap", 0), enforce_mb_order=int(cfg.get("enforce_mb_order", 0)),
         norm_eps=cfg.get("norm_eps", 1e-5), n_sub=cfg.get("n_sub", 0),
-        recompute=int(cfg.get("recompute", 0)), recompute_cap=cfg.get("recompute_cap", 0))
+        recompute=int(cfg.get("recompute", 0)), recompute_cap=cfg.get("recompute_cap", 0),
+        head_dim=cfg.get("head_dim", 0) or 0)
 
 
 def make_ops(ops: Sequence[Tuple[int, int]]):

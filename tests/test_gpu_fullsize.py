@@ -20,12 +20,12 @@ from tests.gpu_util import TOL, shape_of, to_dev, to_np
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5"])
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5", "m8", "m70_tp4", "m8_tp4"])
 def test_one_layer_one_microbatch_full_shapes(name):
     import torch
     from paper_2507_00217_amd import stage as S
     cfg = dict(synth.CONFIGS[name], n_layers=1, n_microbatches=1, stash_cap=1, enforce_mb_order=1)
-    seed = 3000 + int(name[3])
+    seed = 3000 + (int(name[3]) if name.startswith("cfg") else 10 + len(name))
     params = synth.make_weights(cfg, seed)
     X, G = synth.make_boundary(cfg, seed + 1), synth.make_boundary(cfg, seed + 2)
     st = S.Stage(cfg)

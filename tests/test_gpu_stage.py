@@ -70,6 +70,19 @@ def test_small_variants_bf16(name, kernel_set):
     compare(cfg, run_gpu(cfg, params, X, G, ops, kernel_set), run_oracle(cfg, params, X, G, ops), TOL["bf16"])
 
 
+@pytest.mark.parametrize("kernel_set", [0, 1])
+@pytest.mark.parametrize("heads,kv,hidden", [(2, 1, 512), (6, 2, 512), (3, 3, 256)])
+def test_head_width_independent_of_hidden(heads, kv, hidden, kernel_set):
+    """Tensor-parallel shares of a layer (the paper's per-GPU shapes at TP > 1): n_heads * head_dim is smaller or
+    larger than hidden, so the attention block is rectangular (WQKV [d, (h + 2 h_kv) 128], WO [128 h, d])."""
+    cfg = dict(SMALL["cfg3s"], hidden=hidden, n_heads=heads, n_kv_heads=kv, head_dim=128, ffn=704, seq=328,
+               n_microbatches=4, stash_cap=3, warmup=2)
+    params, X, G = inputs(cfg, 2700 + heads)
+    assert params[0]["wo"].shape == (heads * 128, hidden)
+    ops = synth.schedule_1f1b(4, 2)
+    compare(cfg, run_gpu(cfg, params, X, G, ops, kernel_set), run_oracle(cfg, params, X, G, ops), TOL["bf16"])
+
+
 @pytest.mark.parametrize("name", ["cfg3s", "cfg4s"])
 def test_small_variants_fp32_storage(name):
     """Same shapes in fp32: isolates arithmetic from bf16 storage rounding."""
