@@ -45,6 +45,14 @@ int stage_kernel_attention_fwd(int dtype, int b, int s, int h, int hkv, int hd, 
 int stage_kernel_attention_bwd(int dtype, int b, int s, int h, int hkv, int hd, int causal, const void* qkv,
                                const void* o, const float* lse, const void* dout, void* dqkv, float* delta,
                                int kernel_set, void* hip_stream);
+/* The same with caller-provided scratch of at least stage_kernel_attention_bwd_scratch_bytes() bytes (16-byte aligned):
+ * with grouped-query attention and few KV heads the dK/dV pass then splits each KV head's query heads over several
+ * workgroups (fp32 partial sums in the scratch, added up in a fixed order), which fills the chip.  scratch == NULL, or a
+ * shape that needs none (the size query returns 0), behaves like stage_kernel_attention_bwd. */
+size_t stage_kernel_attention_bwd_scratch_bytes(int b, int s, int h, int hkv, int hd);
+int stage_kernel_attention_bwd_ws(int dtype, int b, int s, int h, int hkv, int hd, int causal, const void* qkv,
+                                  const void* o, const float* lse, const void* dout, void* dqkv, float* delta,
+                                  void* scratch, size_t scratch_bytes, int kernel_set, void* hip_stream);
 
 /* stats: [rows, 2] fp32 (mean, rstd). beta ignored for RMSNorm. */
 int stage_kernel_norm_fwd(int dtype, int norm, int rows, int d, float eps, const void* x, const void* gamma,

@@ -498,7 +498,7 @@ struct DkvList {
 };
 
 template <int HD>
-__global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a) {
+__global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int nsplit) {
   using G = Geo<HD>;
   constexpr int NTHR = DKV_THREADS, TQ = DKV_TQ, NB = TQ / 32, TILEB = TQ * G::ROWB;
   // two buffers of (Q tile, dO tile, lse of the tile's queries, delta of the tile's queries)
@@ -508,8 +508,9 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kt = blockIdx.y;                              // slow grid index: early key tiles see the most queries, first
-  const int g = blockIdx.x, ib = blockIdx.z;
-  const int d = a.h * HD, dkv = a.hkv * HD, grp = a.h / a.hkv;
+  // grid.x = KV heads x splits: this workgroup takes `grp` of the query heads of KV head g, starting at head j0
+  const int g = blockIdx.x / nsplit, sp = blockIdx.x % nsplit, ib = blockIdx.z;
+  const int d = a.h * HD, dkv = a.hkv * HD, grp = a.h / a.hkv / nsplit, j0 = g * (a.h / a.hkv) + sp * grp;
   const bf16* base = (const bf16*)a.qkv + (int64_t)ib * a.s * a.ld;
   const bf16* dobase = (const bf16*)a.dout + (int64_t)ib * a.s * d;
   const bf16* kp = base + d + g * HD;
@@ -544,7 +545,7 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a) {
   // iteration `it` = (query head jj of the group, query tile t): its Q and dO tiles, lse and delta -> buffer at `buf`
   auto fetch = [&](int it, lds_char* buf) {
     const int jj = it / per_head, t = t_first + it % per_head;
-    const int j = g * grp + jj;
+    const int j = j0 + jj;
     tile_fetch(buf + QT, head_rsrc(base + j * HD, a.ld, a.s, HD), offq0, a.ld, t * TQ);
     tile_fetch(buf + OT, head_rsrc(dobase + j * HD, d, a.s, HD), offo0, d, t * TQ);
     if (wave < TQ / 64) {   // 64 floats per load; queries past the end read as zero, and so do their Q and dO rows
@@ -685,18 +686,48 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a) {
   }
 
   if (key < a.s) {
-    bf16* row = (bf16*)a.dqkv + ((int64_t)ib * a.s + key) * a.ld + d + g * HD;
+    if (nsplit == 1) {
+      bf16* row = (bf16*)a.dqkv + ((int64_t)ib * a.s + key) * a.ld + d + g * HD;
 #pragma unroll
-    for (int hb = 0; hb < G::NHB; ++hb)
+      for (int hb = 0; hb < G::NHB; ++hb)
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        bf16x4 vk, vv;
+        for (int q4 = 0; q4 < 4; ++q4) {
+          bf16x4 vk, vv;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { vk[e] = (bf16)(dk[hb][q4 * 4 + e] * scale); vv[e] = (bf16)dv[hb][q4 * 4 + e]; }
-        *reinterpret_cast<bf16x4*>(row + hb * 32 + q4 * 8 + hf * 4) = vk;
-        *reinterpret_cast<bf16x4*>(row + dkv + hb * 32 + q4 * 8 + hf * 4) = vv;
-      }
+          for (int e = 0; e < 4; ++e) { vk[e] = (bf16)(dk[hb][q4 * 4 + e] * scale); vv[e] = (bf16)dv[hb][q4 * 4 + e]; }
+          *reinterpret_cast<bf16x4*>(row + hb * 32 + q4 * 8 + hf * 4) = vk;
+          *reinterpret_cast<bf16x4*>(row + dkv + hb * 32 + q4 * 8 + hf * 4) = vv;
+        }
+    } else {      // this split's share, fp32; attn_dkv_reduce_kernel adds the splits up in a fixed order
+      float* row = a.dkv_part + (((int64_t)sp * a.b + ib) * a.s + key) * (2 * dkv) + g * HD;
+#pragma unroll
+      for (int hb = 0; hb < G::NHB; ++hb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          f32x4 vk, vv;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { vk[e] = dk[hb][q4 * 4 + e] * scale; vv[e] = dv[hb][q4 * 4 + e]; }
+          *reinterpret_cast<f32x4*>(row + hb * 32 + q4 * 8 + hf * 4) = vk;
+          *reinterpret_cast<f32x4*>(row + dkv + hb * 32 + q4 * 8 + hf * 4) = vv;
+        }
+    }
   }
+}
+
+// dK | dV of dqkv = sum over splits, in split order (bit-reproducible), rounded once to bf16
+__global__ __launch_bounds__(256) void attn_dkv_reduce_kernel(AttnArgs a, int nsplit, int d, int dkv) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;       // one 4-column piece of one row
+  const int per_row = 2 * dkv / 4;
+  const int64_t rows = (int64_t)a.b * a.s;
+  if (i >= rows * per_row) return;
+  const int64_t row = i / per_row;
+  const int c = (int)(i % per_row) * 4;
+  f32x4 acc = *reinterpret_cast<const f32x4*>(a.dkv_part + row * (2 * dkv) + c);
+  for (int sp = 1; sp < nsplit; ++sp) acc += *reinterpret_cast<const f32x4*>(a.dkv_part + ((int64_t)sp * rows + row) * (2 * dkv) + c);
+  bf16x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[e];
+  *reinterpret_cast<bf16x4*>((bf16*)a.dqkv + row * a.ld + d + c) = o;
 }
 
 // dynamic LDS of the kernels above
@@ -729,11 +760,35 @@ hipError_t bwd_t(const AttnArgs& a, hipStream_t s) {
   const int64_t lanes = (int64_t)a.b * a.s * a.h * (HD / 8);
   hipLaunchKernelGGL((attn_delta_kernel<HD>), dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, s, a);
   hipLaunchKernelGGL((attn_dq_kernel<HD>), dim3(a.h, (a.s + FWD_BQ - 1) / FWD_BQ, a.b), dim3(FWD_THREADS), fwd_lds<HD>(), s, a);
-  hipLaunchKernelGGL((attn_dkv_kernel<HD>), dim3(a.hkv, (a.s + DKV_BKEY - 1) / DKV_BKEY, a.b), dim3(DKV_THREADS), dkv_lds<HD>(), s, a);
+  const int nsplit = a.dkv_part ? attn_bwd_splits(a.b, a.s, a.h, a.hkv) : 1;
+  hipLaunchKernelGGL((attn_dkv_kernel<HD>), dim3(a.hkv * nsplit, (a.s + DKV_BKEY - 1) / DKV_BKEY, a.b), dim3(DKV_THREADS),
+                     dkv_lds<HD>(), s, a, nsplit);
+  if (nsplit > 1) {
+    const int64_t pieces = (int64_t)a.b * a.s * (2 * a.hkv * HD / 4);
+    hipLaunchKernelGGL(attn_dkv_reduce_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, a, nsplit, a.h * HD, a.hkv * HD);
+  }
   return hipGetLastError();
 }
 
 }  // namespace
+
+// Split a KV head's query heads over workgroups until the dK/dV grid has two workgroups per CU of a 256-CU chip
+// (or every query head has its own workgroup); the count must divide the group size.
+int attn_bwd_splits(int b, int s, int h, int hkv) {
+  const int grp = h / hkv;
+  const int64_t wgs = (int64_t)b * hkv * ((s + DKV_BKEY - 1) / DKV_BKEY);
+  int ns = 1;
+  while (ns < grp && wgs * ns < 512) {
+    int nx = ns + 1;
+    while (grp % nx) ++nx;
+    ns = nx;
+  }
+  return ns;
+}
+size_t attn_bwd_part_bytes(int b, int s, int h, int hkv, int hd) {
+  const int ns = attn_bwd_splits(b, s, h, hkv);
+  return ns > 1 ? (size_t)ns * b * s * 2 * hkv * hd * sizeof(float) : 0;
+}
 
 bool attn_mfma_supported(const AttnArgs& a) {
   if (a.hd != 64 && a.hd != 128) return false;

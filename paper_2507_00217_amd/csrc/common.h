@@ -35,7 +35,13 @@ struct AttnArgs {
   const void* dout;              // [b*s, d]
   void* dqkv;                    // [b*s, d + 2*dkv]
   float* delta;                  // [b, h, s] scratch: rowsum(dout * o)
+  float* dkv_part;               // scratch for grouped-query attention, attn_bwd_part_bytes() bytes, or null: fp32 partial
+                                 // dK | dV of each split of a KV head's query heads, [nsplit][b*s][2*dkv]
 };
+// Into how many workgroups the query heads of one KV head are split in the dK/dV kernel (1 = not at all), and the
+// scratch that needs.  Depends on the shape only.
+int attn_bwd_splits(int b, int s, int h, int hkv);
+size_t attn_bwd_part_bytes(int b, int s, int h, int hkv, int hd);
 
 struct NormArgs {
   int kind;                      // 0 LayerNorm, 1 RMSNorm

@@ -128,7 +128,7 @@ size_t slot_bytes(const Dims& D) { return (D.recompute ? x_bytes(D) : rec_bytes(
 size_t big_slot_bytes(const Dims& D) { return D.recompute ? rec_bytes(D) * D.L : 0; }
 size_t stash_bytes(const Dims& D) { return slot_bytes(D) * D.cap + big_slot_bytes(D) * D.hcap; }
 
-struct WsOff { size_t da, dn, delta, partial, rec, end; };
+struct WsOff { size_t da, dn, delta, partial, rec, dkvp, end; };
 WsOff ws_off(const Dims& D) {
   WsOff w; size_t p = 0;
   auto take = [&](size_t bytes) { size_t r = p; p += up(bytes); return r; };
@@ -137,6 +137,7 @@ WsOff ws_off(const Dims& D) {
   w.delta = take((size_t)D.b * D.h * D.s * sizeof(float));
   w.partial = take((size_t)norm_partial_rows() * 2 * D.d * sizeof(float));
   w.rec = take(D.recompute ? rec_bytes(D) : 0);       // the layer record F works in under recomputation
+  w.dkvp = take(D.es == 2 ? attn_bwd_part_bytes(D.b, D.s, D.h, D.hkv, D.hd) : 0);   // grouped-query dK/dV partials
   w.end = p;
   return w;
 }
@@ -314,6 +315,7 @@ AttnArgs attn_args(const stage* st, const LayerBuf& o, const void* dout, const W
   a.b = D.b; a.s = D.s; a.h = D.h; a.hkv = D.hkv; a.hd = D.hd; a.causal = st->cfg.causal;
   a.qkv = o.qkv; a.ld = D.dq; a.o = o.o; a.lse = o.lse;
   a.dout = dout; a.dqkv = o.dqkv; a.delta = (float*)(st->ws + w.delta);
+  a.dkv_part = w.dkvp != w.end ? (float*)(st->ws + w.dkvp) : nullptr;
   return a;
 }
 
@@ -799,13 +801,27 @@ int stage_kernel_attention_fwd(int dtype, int b, int s, int h, int hkv, int hd, 
   return hip_rc(attn_fwd_ref((DType)dtype, a, (hipStream_t)hip_stream));
 }
 
+size_t stage_kernel_attention_bwd_scratch_bytes(int b, int s, int h, int hkv, int hd) {
+  if (b < 1 || s < 1 || h < 1 || hkv < 1 || h % hkv || (hd != 64 && hd != 128)) return 0;
+  return attn_bwd_part_bytes(b, s, h, hkv, hd);
+}
+
 int stage_kernel_attention_bwd(int dtype, int b, int s, int h, int hkv, int hd, int causal, const void* qkv,
                                const void* o, const float* lse, const void* dout, void* dqkv, float* delta,
                                int kernel_set, void* hip_stream) {
+  return stage_kernel_attention_bwd_ws(dtype, b, s, h, hkv, hd, causal, qkv, o, lse, dout, dqkv, delta, nullptr, 0,
+                                       kernel_set, hip_stream);
+}
+
+int stage_kernel_attention_bwd_ws(int dtype, int b, int s, int h, int hkv, int hd, int causal, const void* qkv,
+                                  const void* o, const float* lse, const void* dout, void* dqkv, float* delta,
+                                  void* scratch, size_t scratch_bytes, int kernel_set, void* hip_stream) {
   if (!attn_shape(dtype, b, s, h, hkv, hd, causal) || !qkv || !o || !lse || !dout || !dqkv || !delta) return STAGE_E_INVAL;
+  if (scratch && (scratch_bytes < attn_bwd_part_bytes(b, s, h, hkv, hd) || ((uintptr_t)scratch & 15))) return STAGE_E_INVAL;
   AttnArgs a{}; a.b = b; a.s = s; a.h = h; a.hkv = hkv; a.hd = hd; a.causal = causal;
   a.qkv = qkv; a.ld = (int64_t)(h + 2 * hkv) * hd; a.o = (void*)o; a.lse = (float*)lse;
   a.dout = dout; a.dqkv = dqkv; a.delta = delta;
+  a.dkv_part = attn_bwd_part_bytes(b, s, h, hkv, hd) ? (float*)scratch : nullptr;
   if (kernel_set == 0 && dtype == STAGE_DTYPE_BF16 && attn_mfma_supported(a)) return hip_rc(attn_bwd_mfma(a, (hipStream_t)hip_stream));
   return hip_rc(attn_bwd_ref((DType)dtype, a, (hipStream_t)hip_stream));
 }

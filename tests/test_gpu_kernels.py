@@ -24,6 +24,9 @@ def L():
         lib.stage_kernel_wgrad_group.argtypes = [i, i] + [vp] * 9 + [i, vp]
         lib.stage_kernel_attention_fwd.argtypes = [i] * 7 + [vp, vp, vp, i, vp]
         lib.stage_kernel_attention_bwd.argtypes = [i] * 7 + [vp] * 6 + [i, vp]
+        lib.stage_kernel_attention_bwd_ws.argtypes = [i] * 7 + [vp] * 7 + [C.c_size_t, i, vp]
+        lib.stage_kernel_attention_bwd_scratch_bytes.argtypes = [i] * 5
+        lib.stage_kernel_attention_bwd_scratch_bytes.restype = C.c_size_t
         lib.stage_kernel_norm_fwd.argtypes = [i, i, i, i, fl, vp, vp, vp, vp, vp, vp]
         lib.stage_kernel_norm_bwd.argtypes = [i, i, i, i] + [vp] * 10
         lib.stage_kernel_norm_partial_bytes.restype = C.c_size_t
@@ -155,6 +158,46 @@ def test_attention(dtype, kernel_set, causal, b, s, h, hkv, hd):
     assert so.max_rel_err(got[..., :d], dq.reshape(b, s, d)) <= tol
     assert so.max_rel_err(got[..., d:d + dkv], dk.reshape(b, s, dkv)) <= tol
     assert so.max_rel_err(got[..., d + dkv:], dv.reshape(b, s, dkv)) <= tol
+
+
+@pytest.mark.parametrize("causal", [1, 0])
+@pytest.mark.parametrize("b,s,h,hkv,hd", [(1, 392, 8, 1, 128), (2, 300, 12, 2, 64), (1, 448, 4, 2, 128)])
+def test_attention_bwd_with_split_query_heads(causal, b, s, h, hkv, hd):
+    """Grouped-query dK/dV with each KV head's query heads split over several workgroups (fp32 partials in caller
+    scratch, summed in a fixed order): against the oracle, and equal to the unsplit pass up to the one extra bf16
+    rounding order."""
+    import torch
+    d, dkv = h * hd, hkv * hd
+    qkv = rnd(synth.normal(6, 1, (b, s, d + 2 * dkv)), "bf16")
+    do = rnd(synth.normal(6, 2, (b, s, d)), "bf16")
+    sh = so.Shape(1, d, h, hkv, 64, s, b, causal=bool(causal))
+    q = qkv[..., :d].astype(np.float64).reshape(b, s, h, hd)
+    k = qkv[..., d:d + dkv].astype(np.float64).reshape(b, s, hkv, hd)
+    v = qkv[..., d + dkv:].astype(np.float64).reshape(b, s, hkv, hd)
+    qd, dod = to_dev(qkv, "bf16"), to_dev(do, "bf16")
+    od = torch.zeros((b, s, d), dtype=qd.dtype, device="cuda:0")
+    lse = torch.zeros((b, h, s), dtype=torch.float32, device="cuda:0")
+    assert L().stage_kernel_attention_fwd(1, b, s, h, hkv, hd, causal, P(qd), P(od), P(lse), 0, None) == 0
+    nbytes = L().stage_kernel_attention_bwd_scratch_bytes(b, s, h, hkv, hd)
+    assert nbytes > 0 and nbytes % (b * s * 2 * dkv * 4) == 0
+    scratch = torch.zeros(nbytes, dtype=torch.uint8, device="cuda:0")
+    delta = torch.zeros((b, h, s), dtype=torch.float32, device="cuda:0")
+    outs = []
+    for use in (True, False):
+        dqkv = torch.zeros_like(qd)
+        rc = L().stage_kernel_attention_bwd_ws(1, b, s, h, hkv, hd, causal, P(qd), P(od), P(lse), P(dod), P(dqkv), P(delta),
+                                               P(scratch) if use else None, nbytes if use else 0, 0, None)
+        assert rc == 0
+        torch.cuda.synchronize()
+        outs.append(to_np(dqkv))
+    dq, dk, dv = so.attention_backward(sh, q, k, v, do.astype(np.float64).reshape(b, s, h, hd))
+    ref = np.concatenate([dq.reshape(b, s, d), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
+    for got in outs:
+        for lo, hi in ((0, d), (d, d + dkv), (d + dkv, d + 2 * dkv)):
+            assert so.max_rel_err(got[..., lo:hi], ref[..., lo:hi]) <= KTOL["bf16"]
+    assert np.array_equal(outs[0][..., :d], outs[1][..., :d])              # dQ does not depend on the split
+    assert L().stage_kernel_attention_bwd_ws(1, b, s, h, hkv, hd, causal, P(qd), P(od), P(lse), P(dod), P(dqkv), P(delta),
+                                             P(scratch), nbytes - 16, 0, None) == -1
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
