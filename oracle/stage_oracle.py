@@ -58,6 +58,7 @@ class Shape:
     act: str = "gelu"         # "gelu" | "swiglu"
     causal: bool = True
     eps: float = 1e-5
+    rope_theta: float = 0.0   # > 0: rotary position embedding on q and k with this base (Llama-style layers); 0 = none
     hd: int = 0               # width of one head; 0 = hidden / n_heads.  A tensor-parallel share of a layer (the paper's
                               # per-GPU shapes at TP > 1) keeps hidden but has fewer heads, so n_heads * hd < hidden.
 
@@ -135,6 +136,24 @@ def sigmoid(g):
     return 1.0 / (1.0 + np.exp(-g))
 
 
+def rope(sh: Shape, t, inverse: bool = False):
+    """Rotary position embedding of t [b, s, heads, head_dim] (RoFormer, section 3.4.2 there; the paper's layers are
+    Llama-style): consecutive pairs (2p, 2p+1) of a head are rotated by the angle pos * theta^(-2p / head_dim), pos =
+    position in the sequence.  The inverse rotation is its transpose, which is what the backward pass applies."""
+    if not sh.rope_theta:
+        return t
+    b, s, nh, hd = t.shape
+    ang = np.arange(s, dtype=np.float64)[:, None] * sh.rope_theta ** (-2.0 * np.arange(hd // 2, dtype=np.float64) / hd)[None, :]
+    cos, sin = np.cos(ang)[None, :, None, :], np.sin(ang)[None, :, None, :]
+    if inverse:
+        sin = -sin
+    te, to = t[..., 0::2], t[..., 1::2]
+    out = np.empty_like(t)
+    out[..., 0::2] = te * cos - to * sin
+    out[..., 1::2] = te * sin + to * cos
+    return out
+
+
 def layer_forward(sh: Shape, p: Dict[str, np.ndarray], x):
     """x [b,s,d] -> (y [b,s,d], cache)."""
     b, s, d = x.shape
@@ -144,8 +163,8 @@ def layer_forward(sh: Shape, p: Dict[str, np.ndarray], x):
     c["n1"] = n1
     qkv = n1 @ p["wqkv"]
     dq_ = sh.q_dim
-    q = qkv[..., :dq_].reshape(b, s, h, hd)
-    k = qkv[..., dq_:dq_ + dkv].reshape(b, s, hkv, hd)
+    q = rope(sh, qkv[..., :dq_].reshape(b, s, h, hd))
+    k = rope(sh, qkv[..., dq_:dq_ + dkv].reshape(b, s, hkv, hd))
     v = qkv[..., dq_ + dkv:].reshape(b, s, hkv, hd)
     c["q"], c["k"], c["v"] = q, k, v
     o = attention_forward(sh, q, k, v)
@@ -243,6 +262,7 @@ def layer_backward_input(sh: Shape, p, c, dy):
     do = dx1 @ p["wo"].T
     dq, dk, dv = attention_backward(sh, c["q"], c["k"], c["v"],
                                     do.reshape(b, s, sh.n_heads, sh.head_dim))
+    dq, dk = rope(sh, dq, inverse=True), rope(sh, dk, inverse=True)
     dz_qkv = np.concatenate([dq.reshape(b, s, sh.q_dim), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
     saved["dz_qkv"] = dz_qkv
     dn1 = dz_qkv @ p["wqkv"].T
@@ -283,6 +303,7 @@ def layer_backward_full(sh: Shape, p, c, dy):
     do = dx1 @ p["wo"].T
     dq, dk, dv = attention_backward(sh, c["q"], c["k"], c["v"],
                                     do.reshape(b, s, sh.n_heads, sh.head_dim))
+    dq, dk = rope(sh, dq, inverse=True), rope(sh, dk, inverse=True)
     dqkv = np.concatenate([dq.reshape(b, s, sh.q_dim), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
     gr["wqkv"] = _flat(c["n1"]).T @ _flat(dqkv)
     dn1 = dqkv @ p["wqkv"].T

@@ -9,7 +9,7 @@ TOL = {"fp32": 1e-4, "bf16": 2e-2}      # max_i |gpu - ref| / max_j |ref|, per t
 
 def shape_of(cfg):
     return so.Shape(cfg["n_layers"], cfg["hidden"], cfg["n_heads"], cfg["n_kv_heads"], cfg["ffn"],
-                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], bool(cfg.get("causal", True)), hd=cfg.get("head_dim", 0) or 0)
+                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], bool(cfg.get("causal", True)), hd=cfg.get("head_dim", 0) or 0, rope_theta=float(cfg.get("rope_theta", 0.0) or 0.0))
 
 
 def to_dev(a, dtype, device="cuda:0"):

@@ -12,14 +12,15 @@ from paper_2507_00217_amd import synth
 F, B, W = so.F, so.B, so.W
 
 
-def tiny_cfg(norm="layernorm", act="gelu", n_kv=2, causal=True, L=2, b=1, n_mb=3, head_dim=0):
+def tiny_cfg(norm="layernorm", act="gelu", n_kv=2, causal=True, L=2, b=1, n_mb=3, head_dim=0, rope_theta=0.0):
     return dict(n_layers=L, hidden=16, n_heads=2, n_kv_heads=n_kv, ffn=32, seq=8, mb_size=b,
-                n_microbatches=n_mb, norm=norm, act=act, dtype="fp32", causal=causal, head_dim=head_dim)
+                n_microbatches=n_mb, norm=norm, act=act, dtype="fp32", causal=causal, head_dim=head_dim,
+                rope_theta=rope_theta)
 
 
 def shape_of(cfg):
     return so.Shape(cfg["n_layers"], cfg["hidden"], cfg["n_heads"], cfg["n_kv_heads"], cfg["ffn"],
-                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], cfg.get("causal", True), hd=cfg.get("head_dim", 0) or 0)
+                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], cfg.get("causal", True), hd=cfg.get("head_dim", 0) or 0, rope_theta=float(cfg.get("rope_theta", 0.0) or 0.0))
 
 
 def setup(cfg, seed=11, wstd_boost=10.0):
@@ -42,9 +43,10 @@ def loss(sh, params, X, G):
     return sum(float((st.forward(m, X[m]) * G[m]).sum()) for m in range(X.shape[0]))
 
 
-@pytest.mark.parametrize("norm,act,n_kv,causal", VARIANTS)
-def test_finite_differences(norm, act, n_kv, causal):
-    cfg = tiny_cfg(norm, act, n_kv, causal, n_mb=2)
+@pytest.mark.parametrize("norm,act,n_kv,causal,rope_theta", [v + (0.0,) for v in VARIANTS] + [("rmsnorm", "swiglu", 1, True, 10000.0),
+                                                                                        ("layernorm", "gelu", 2, False, 30.0)])
+def test_finite_differences(norm, act, n_kv, causal, rope_theta):
+    cfg = tiny_cfg(norm, act, n_kv, causal, n_mb=2, rope_theta=rope_theta)
     sh, params, X, G = setup(cfg)
     st = so.OracleStage(sh, params)
     ops = synth.schedule_1f1b(2, 1)
@@ -128,14 +130,15 @@ def test_sum_over_microbatches_equals_full_batch():
             assert so.max_rel_err(la[k], lb[k]) <= 1e-12, k
 
 
-@pytest.mark.parametrize("norm,act,n_kv,causal,head_dim", [v + (0,) for v in VARIANTS] + [("rmsnorm", "swiglu", 1, True, 4),
-                                                                                       ("layernorm", "gelu", 2, True, 12)])
-def test_against_torch_autograd(norm, act, n_kv, causal, head_dim):
+@pytest.mark.parametrize("norm,act,n_kv,causal,head_dim,rope_theta",
+                         [v + (0, 0.0) for v in VARIANTS] + [("rmsnorm", "swiglu", 1, True, 4, 0.0), ("layernorm", "gelu", 2, True, 12, 0.0),
+                                                             ("rmsnorm", "swiglu", 1, True, 0, 10000.0), ("layernorm", "gelu", 2, False, 4, 50.0)])
+def test_against_torch_autograd(norm, act, n_kv, causal, head_dim, rope_theta):
     """Second opinion from a library: the same layer stack composed from
     PyTorch CPU primitives, differentiated by autograd, in fp64.  The last two cases have heads that do not tile the
     hidden width (n_heads * head_dim = 8 and 24 against hidden 16), as a tensor-parallel share of a layer has."""
     torch = pytest.importorskip("torch")
-    cfg = tiny_cfg(norm, act, n_kv, causal, b=2, n_mb=2, head_dim=head_dim)
+    cfg = tiny_cfg(norm, act, n_kv, causal, b=2, n_mb=2, head_dim=head_dim, rope_theta=rope_theta)
     sh, params, X, G = setup(cfg)
     st = so.OracleStage(sh, params)
     Y, dX, _ = st.run_schedule(synth.schedule_1f1b(2, 1), X, G)
@@ -155,6 +158,11 @@ def test_against_torch_autograd(norm, act, n_kv, causal, head_dim):
         q = qkv[..., :h * hd].reshape(bsz, s, h, hd).transpose(1, 2)
         k = qkv[..., h * hd:(h + hkv) * hd].reshape(bsz, s, hkv, hd).transpose(1, 2).repeat_interleave(h // hkv, dim=1)
         v = qkv[..., (h + hkv) * hd:].reshape(bsz, s, hkv, hd).transpose(1, 2).repeat_interleave(h // hkv, dim=1)
+        if rope_theta:      # the same rotation written as a complex multiplication: (x_2p + i x_2p+1) * exp(i pos theta_p)
+            ang = torch.arange(s, dtype=torch.float64)[:, None] * rope_theta ** (-torch.arange(0, hd, 2, dtype=torch.float64) / hd)
+            rot = torch.polar(torch.ones_like(ang), ang)
+            turn = lambda t: torch.view_as_real(torch.view_as_complex(t.reshape(*t.shape[:-1], hd // 2, 2).contiguous()) * rot).flatten(-2)
+            q, k = turn(q), turn(k)
         o = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=causal)
         x1 = x + o.transpose(1, 2).reshape(bsz, s, h * hd) @ p["wo"]
         z = tnorm(x1, p["g2"], p.get("b2")) @ p["win"]
@@ -310,3 +318,26 @@ def test_recomputation_changes_memory_not_results(norm, act, n_kv, causal):
         for k in la:
             assert np.array_equal(la[k], lb[k]) and np.array_equal(la[k], lc[k]), k
             np.testing.assert_allclose(ld[k], la[k], rtol=1e-12, atol=1e-12)
+
+
+def test_rope_properties():
+    """Rotary embedding: a rotation (norms kept, inverse = transpose), identity at position 0, and the attention scores of
+    rotated q, k depend on the two positions only through their difference."""
+    sh = so.Shape(1, 16, 2, 2, 32, 12, 1, rope_theta=100.0)
+    t = synth.normal(9, 1, (1, 12, 2, 8)).astype(np.float64)
+    r = so.rope(sh, t)
+    assert np.allclose(np.linalg.norm(r, axis=-1), np.linalg.norm(t, axis=-1), rtol=1e-13)
+    assert np.array_equal(r[:, 0], t[:, 0]) and not np.allclose(r[:, 1:], t[:, 1:])
+    assert np.allclose(so.rope(sh, r, inverse=True), t, atol=1e-14)
+    u = synth.normal(9, 2, (1, 12, 2, 8)).astype(np.float64)
+    assert abs((so.rope(sh, t) * u).sum() - (t * so.rope(sh, u, inverse=True)).sum()) < 1e-12      # <R t, u> = <t, R^T u>
+    q = np.broadcast_to(t[:, :1], t.shape)          # the same vector at every position
+    k = np.broadcast_to(u[:, :1], u.shape)
+    S = np.einsum("bmhd,bnhd->bhmn", so.rope(sh, q), so.rope(sh, k))
+    for off in range(-5, 6):
+        dgl = np.diagonal(S, offset=off, axis1=-2, axis2=-1)
+        assert np.allclose(dgl, dgl[..., :1], atol=1e-12), off
+    # hand value: pair 0 at position 3 turns by 3 rad (theta^0 = 1)
+    one = np.zeros((1, 4, 1, 8)); one[..., 0] = 1.0
+    got = so.rope(sh, one)[0, 3, 0]
+    assert np.allclose(got[:2], [math.cos(3.0), math.sin(3.0)]) and np.allclose(got[2:], 0.0)
