@@ -101,6 +101,9 @@ typedef struct {
                               fewer heads and a narrower ffn against the full hidden width): WQKV is
                               [d, (h + 2 h_kv) head_dim] and WO [h head_dim, d].  Summing the shares' outputs is the
                               caller's collective. */
+  float   rope_theta;      /* > 0: rotary position embedding on q and k (Llama-style layers, which is what the paper
+                              trains): pairs (2p, 2p+1) of a head turn by position * rope_theta^(-2p / head_dim),
+                              position = index in the sequence; 0 = none */
 } stage_config_t;
 
 typedef struct { size_t weights, grads, stash, workspace; } stage_sizes_t; /* bytes */
@@ -188,11 +191,11 @@ int stage_set_kernel_set(stage_t* st, int which);
  * synchronises the stream and returns, for one class, the summed duration in
  * ms, the number of launches, and the summed algorithmic work: FLOPs (2MNK per
  * GEMM; 2*b*s^2*d causal / 4*b*s^2*d full per attention forward, 2.5x that for
- * backward) for classes 0-4, bytes moved by definition for classes 5-9. */
+ * backward) for classes 0-4, bytes moved by definition for classes 5-10. */
 enum {
   STAGE_K_GEMM_NN = 0, STAGE_K_GEMM_NT = 1, STAGE_K_GEMM_TN = 2, STAGE_K_ATTN_FWD = 3, STAGE_K_ATTN_BWD = 4,
   STAGE_K_NORM_FWD = 5, STAGE_K_NORM_BWD = 6, STAGE_K_ACT_FWD = 7, STAGE_K_ACT_BWD = 8, STAGE_K_COPY = 9,
-  STAGE_K_COUNT = 10
+  STAGE_K_ROPE = 10, STAGE_K_COUNT = 11
 };
 int stage_profile(stage_t* st, int enable);
 int stage_profile_read(stage_t* st, int kernel_class, double* total_ms, int64_t* launches, double* work);

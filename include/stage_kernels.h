@@ -38,6 +38,13 @@ int stage_kernel_wgrad_group(int dtype, int n, const int* M, const int* N, const
                              const int64_t* lda, const void* const* B, const int64_t* ldb, float* const* C,
                              const int64_t* ldc, int kernel_set, void* hip_stream);
 
+/* Rotary position embedding.  table: [s, hd/2] pairs (cos, sin) of position * theta^(-2p/hd), built by the first call;
+ * the second rotates, in place, pairs (2p, 2p+1) of the first n_heads heads of every row of x [b*s, ld] (q and k of a
+ * qkv buffer: n_heads = h + hkv), or applies the transpose (inverse != 0), which is the backward pass. */
+int stage_kernel_rope_table(int s, int hd, float theta, float* table, void* hip_stream);
+int stage_kernel_rope(int dtype, int b, int s, int n_heads, int hd, int inverse, void* x, int64_t ld, const float* table,
+                      void* hip_stream);
+
 /* qkv: [b*s, (h + 2*hkv)*hd] rows of q | k | v;  o: [b*s, h*hd];  lse: [b, h, s] fp32. */
 int stage_kernel_attention_fwd(int dtype, int b, int s, int h, int hkv, int hd, int causal, const void* qkv, void* o,
                                float* lse, int kernel_set, void* hip_stream);

@@ -393,4 +393,61 @@ hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Rotary position embedding (the paper's layers are Llama-style): consecutive pairs (2p, 2p+1) of every q and k head
+// are rotated by pos * theta^(-2p/hd), pos = position in the sequence; the backward pass applies the transpose.
+// The angles' cosines and sines come from a table [s][hd/2] of (cos, sin), built once in double precision.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rope_table_kernel(float2* table, int s, int half, double theta) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)s * half) return;
+  const int pos = (int)(i / half), p = (int)(i % half);
+  const double ang = (double)pos * pow(theta, -(double)p / (double)half);
+  table[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+// in place on the first nh heads of every row of x [rows, ld]; one 16-byte vector per thread and step
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kernel(T* x, int64_t ld, int64_t rows, int s, int nh, int hd, const float2* table,
+                                                   int inverse) {
+  constexpr int V = Vec<T>::N;
+  const int per_row = nh * hd / V, vec_per_head = hd / V;
+  const int64_t total = rows * per_row;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t row = i / per_row;
+    const int c = (int)(i % per_row);
+    const int pos = (int)(row % s), p0 = (c % vec_per_head) * (V / 2);          // first pair index inside the head
+    T* ptr = x + row * ld + (int64_t)c * V;
+    Vec<T> v = ldv(ptr);
+    const float2* t = table + (int64_t)pos * (hd / 2) + p0;
+#pragma unroll
+    for (int q = 0; q < V / 2; ++q) {
+      const float2 cs = t[q];
+      const float sn = inverse ? -cs.y : cs.y;
+      const float a = to_f32(v.v[2 * q]), b = to_f32(v.v[2 * q + 1]);
+      v.v[2 * q] = from_f32<T>(a * cs.x - b * sn);
+      v.v[2 * q + 1] = from_f32<T>(a * sn + b * cs.x);
+    }
+    stv(ptr, v);
+  }
+}
+
+hipError_t rope_table(float* table, int s, int hd, double theta, hipStream_t st) {
+  if (s < 1 || hd < 2 || hd % 2 || !(theta > 0.0) || !table) return hipErrorInvalidValue;
+  const int64_t n = (int64_t)s * (hd / 2);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (float2*)table, s, hd / 2, theta);
+  return hipGetLastError();
+}
+
+hipError_t rope_apply(DType dt, void* x, int64_t ld, int64_t rows, int s, int nh, int hd, const float* table, int inverse,
+                      hipStream_t st) {
+  const int V = dt == DT_F32 ? 4 : 8;
+  if (rows < 1 || s < 1 || nh < 1 || hd % V || ld % V || !x || !table || ((uintptr_t)x & 15)) return hipErrorInvalidValue;
+  const int64_t total = rows * (nh * hd / V), want = (total + 255) / 256;
+  const int grid = (int)(want > 16384 ? 16384 : want);
+  if (dt == DT_F32) hipLaunchKernelGGL((rope_kernel<float>), dim3(grid), dim3(256), 0, st, (float*)x, ld, rows, s, nh, hd, (const float2*)table, inverse);
+  else hipLaunchKernelGGL((rope_kernel<bf16>), dim3(grid), dim3(256), 0, st, (bf16*)x, ld, rows, s, nh, hd, (const float2*)table, inverse);
+  return hipGetLastError();
+}
+
 }  // namespace stg

@@ -86,6 +86,10 @@ hipError_t act_bwd(DType dt, const ActArgs& a, hipStream_t s);
 hipError_t fill_zero_f32(float* p, size_t n, hipStream_t s);
 hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t widen_to_f32(DType dt, float* dst, const void* src, size_t n, hipStream_t s);   // dst[i] = (float)src[i]
+// rotary position embedding: table [s][hd/2] of (cos, sin) pairs; rotation in place of the first nh heads of each row
+hipError_t rope_table(float* table, int s, int hd, double theta, hipStream_t st);
+hipError_t rope_apply(DType dt, void* x, int64_t ld, int64_t rows, int s, int nh, int hd, const float* table, int inverse,
+                      hipStream_t st);
 
 // tuned gfx950 kernels (bf16 MFMA)
 bool gemm_mfma_supported(const GemmArgs& g);

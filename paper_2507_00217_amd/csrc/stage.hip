@@ -21,6 +21,7 @@ inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Dims {
   int L, d, h, hkv, hd, da, dkv, dq, f, fin, s, b, T, n_mb, cap, n_sub;   // da = h*hd: width of the attention output
+  int rope;              // rotary position embedding on
   int recompute, hcap;   // layer-wise recomputation on; cap on microbatches holding a rebuilt stash (B started, W not finished)
   size_t es;  // bytes per element of the compute dtype
 };
@@ -40,7 +41,7 @@ bool make_dims(const stage_config_t* c, Dims* o) {
   if (c->dtype != STAGE_DTYPE_FP32 && c->dtype != STAGE_DTYPE_BF16) return false;
   if (c->causal != 0 && c->causal != 1) return false;
   if (c->stash_cap < 0 || c->stash_cap > c->n_microbatches) return false;
-  if (!(c->norm_eps >= 0.f)) return false;
+  if (!(c->norm_eps >= 0.f) || !(c->rope_theta >= 0.f)) return false;
   if (c->n_sub < 0 || c->n_sub > 32 || (c->n_sub > 0 && c->n_layers % c->n_sub)) return false;
   if ((c->recompute != 0 && c->recompute != 1) || c->recompute_cap < 0 || c->recompute_cap > c->n_microbatches) return false;
   if (!c->recompute && c->recompute_cap) return false;
@@ -53,6 +54,7 @@ bool make_dims(const stage_config_t* c, Dims* o) {
   o->s = c->seq; o->b = c->mb_size; o->T = c->seq * c->mb_size; o->n_mb = c->n_microbatches;
   o->cap = c->stash_cap ? c->stash_cap : c->n_microbatches;
   o->n_sub = c->n_sub > 0 ? c->n_sub : 1;
+  o->rope = c->rope_theta > 0.f;
   o->recompute = c->recompute;
   o->hcap = !c->recompute ? 0 : (c->recompute_cap ? c->recompute_cap : o->cap);
   if (o->hcap > o->cap) return false;   // a microbatch with a rebuilt stash is also live
@@ -128,7 +130,7 @@ size_t slot_bytes(const Dims& D) { return (D.recompute ? x_bytes(D) : rec_bytes(
 size_t big_slot_bytes(const Dims& D) { return D.recompute ? rec_bytes(D) * D.L : 0; }
 size_t stash_bytes(const Dims& D) { return slot_bytes(D) * D.cap + big_slot_bytes(D) * D.hcap; }
 
-struct WsOff { size_t da, dn, delta, partial, rec, dkvp, end; };
+struct WsOff { size_t da, dn, delta, partial, rec, dkvp, rope, end; };
 WsOff ws_off(const Dims& D) {
   WsOff w; size_t p = 0;
   auto take = [&](size_t bytes) { size_t r = p; p += up(bytes); return r; };
@@ -138,6 +140,7 @@ WsOff ws_off(const Dims& D) {
   w.partial = take((size_t)norm_partial_rows() * 2 * D.d * sizeof(float));
   w.rec = take(D.recompute ? rec_bytes(D) : 0);       // the layer record F works in under recomputation
   w.dkvp = take(D.es == 2 ? attn_bwd_part_bytes(D.b, D.s, D.h, D.hkv, D.hd) : 0);   // grouped-query dK/dV partials
+  w.rope = take(D.rope ? (size_t)D.s * (D.hd / 2) * 2 * sizeof(float) : 0);          // (cos, sin) per position and pair
   w.end = p;
   return w;
 }
@@ -315,7 +318,7 @@ AttnArgs attn_args(const stage* st, const LayerBuf& o, const void* dout, const W
   a.b = D.b; a.s = D.s; a.h = D.h; a.hkv = D.hkv; a.hd = D.hd; a.causal = st->cfg.causal;
   a.qkv = o.qkv; a.ld = D.dq; a.o = o.o; a.lse = o.lse;
   a.dout = dout; a.dqkv = o.dqkv; a.delta = (float*)(st->ws + w.delta);
-  a.dkv_part = w.dkvp != w.end ? (float*)(st->ws + w.dkvp) : nullptr;
+  a.dkv_part = w.dkvp != w.rope ? (float*)(st->ws + w.dkvp) : nullptr;
   return a;
 }
 
@@ -330,6 +333,10 @@ int forward_layer(stage* st, int l, const LayerBuf& o, void* y_l, bool y_lp) {
   { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 1, 1)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
   int rc = do_gemm(st, GEMM_NN, D.T, D.dq, D.d, o.n1, D.d, W.wqkv, D.dq, o.qkv, D.dq, nullptr, 0, 0);
   if (rc) return rc;
+  if (D.rope) {      // q and k of the stash are the rotated ones: attention forward and backward both want those
+    ProfScope ps(st, STAGE_K_ROPE, 2.0 * D.T * (D.da + D.dkv) * D.es);
+    HIPCHK(rope_apply(st->dt, o.qkv, D.dq, D.T, D.s, D.h + D.hkv, D.hd, (const float*)(st->ws + w.rope), 0, st->stream));
+  }
   AttnArgs a = attn_args(st, o, nullptr, w);
   {
     ProfScope ps(st, STAGE_K_ATTN_FWD, attn_flops(st, false));
@@ -408,6 +415,10 @@ int exec_backward_input(stage* st, int mb, const void* dy, void* dx, int l0, int
       ProfScope ps(st, STAGE_K_ATTN_BWD, attn_flops(st, true));
       if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_bwd_mfma(a, st->stream));
       else HIPCHK(attn_bwd_ref(st->dt, a, st->stream));
+    }
+    if (D.rope) {    // gradients with respect to the unrotated q and k: the transposed rotation
+      ProfScope ps(st, STAGE_K_ROPE, 2.0 * D.T * (D.da + D.dkv) * D.es);
+      HIPCHK(rope_apply(st->dt, o.dqkv, D.dq, D.T, D.s, D.h + D.hkv, D.hd, (const float*)(st->ws + w.rope), 1, st->stream));
     }
     rc = do_gemm(st, GEMM_NT, D.T, D.d, D.dq, o.dqkv, D.dq, W.wqkv, D.dq, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
@@ -619,6 +630,10 @@ int stage_init(const stage_config_t* cfg, void* weights_dev, void* grads_dev, vo
   for (int i = D.cap - 1; i >= 0; --i) st->free_slots.push_back(i);
   for (int i = D.hcap - 1; i >= 0; --i) st->free_big.push_back(i);
   if (fill_zero_f32(st->grads, st->n_param_elems, st->stream) != hipSuccess) { delete st; return STAGE_E_HIP; }
+  if (D.rope && rope_table((float*)(st->ws + ws_off(D).rope), D.s, D.hd, (double)cfg->rope_theta, st->stream) != hipSuccess) {
+    delete st;
+    return STAGE_E_HIP;
+  }
   *out = st;
   return STAGE_OK;
 }
@@ -799,6 +814,18 @@ int stage_kernel_attention_fwd(int dtype, int b, int s, int h, int hkv, int hd, 
   a.qkv = qkv; a.ld = (int64_t)(h + 2 * hkv) * hd; a.o = o; a.lse = lse;
   if (kernel_set == 0 && dtype == STAGE_DTYPE_BF16 && attn_mfma_supported(a)) return hip_rc(attn_fwd_mfma(a, (hipStream_t)hip_stream));
   return hip_rc(attn_fwd_ref((DType)dtype, a, (hipStream_t)hip_stream));
+}
+
+int stage_kernel_rope_table(int s, int hd, float theta, float* table, void* hip_stream) {
+  if (s < 1 || (hd != 64 && hd != 128) || !(theta > 0.f) || !table) return STAGE_E_INVAL;
+  return hip_rc(rope_table(table, s, hd, (double)theta, (hipStream_t)hip_stream));
+}
+
+int stage_kernel_rope(int dtype, int b, int s, int n_heads, int hd, int inverse, void* x, int64_t ld, const float* table,
+                      void* hip_stream) {
+  if (!dtype_ok(dtype) || b < 1 || s < 1 || n_heads < 1 || (hd != 64 && hd != 128) || !x || !table || ld < (int64_t)n_heads * hd)
+    return STAGE_E_INVAL;
+  return hip_rc(rope_apply((DType)dtype, x, ld, (int64_t)b * s, s, n_heads, hd, table, inverse != 0, (hipStream_t)hip_stream));
 }
 
 size_t stage_kernel_attention_bwd_scratch_bytes(int b, int s, int h, int hkv, int hd) {

@@ -38,13 +38,14 @@ CONFIGS: Dict[str, dict] = {
     "cfg5": dict(n_layers=2, hidden=8192, n_heads=64, n_kv_heads=8, ffn=28672, seq=4096, mb_size=1,
                  n_microbatches=32, norm="rmsnorm", act="swiglu", dtype="bf16", stash_cap=8, schedule="greedy", warmup=4),
     # further shapes of the paper's models (section 7): the M8 layer, and the share of an M70 / M8 layer that one GPU
-    # holds under 4-way tensor parallelism (a quarter of the heads and of the ffn against the full hidden width)
-    "m8": dict(n_layers=4, hidden=4096, n_heads=32, n_kv_heads=8, ffn=14336, seq=4096, mb_size=1,
+    # holds under 4-way tensor parallelism (a quarter of the heads and of the ffn against the full hidden width); these
+    # are Llama-style layers, so they carry the rotary position embedding
+    "m8": dict(n_layers=4, hidden=4096, n_heads=32, n_kv_heads=8, ffn=14336, seq=4096, mb_size=1, rope_theta=10000.0,
                n_microbatches=16, norm="rmsnorm", act="swiglu", dtype="bf16", stash_cap=8, schedule="w_deferred", warmup=7),
     "m70_tp4": dict(n_layers=4, hidden=8192, n_heads=16, n_kv_heads=2, head_dim=128, ffn=7168, seq=4096, mb_size=1,
-                    n_microbatches=16, norm="rmsnorm", act="swiglu", dtype="bf16", stash_cap=8, schedule="w_deferred", warmup=7),
+                    rope_theta=10000.0, n_microbatches=16, norm="rmsnorm", act="swiglu", dtype="bf16", stash_cap=8, schedule="w_deferred", warmup=7),
     "m8_tp4": dict(n_layers=4, hidden=4096, n_heads=8, n_kv_heads=2, head_dim=128, ffn=3584, seq=4096, mb_size=1,
-                   n_microbatches=16, norm="rmsnorm", act="swiglu", dtype="bf16", stash_cap=8, schedule="w_deferred", warmup=7),
+                   rope_theta=10000.0, n_microbatches=16, norm="rmsnorm", act="swiglu", dtype="bf16", stash_cap=8, schedule="w_deferred", warmup=7),
 }
 
 _MASK = np.uint64(0xFFFFFFFFFFFFFFFF)

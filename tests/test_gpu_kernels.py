@@ -22,6 +22,8 @@ def L():
         vp, i, i64, fl = C.c_void_p, C.c_int, C.c_int64, C.c_float
         lib.stage_kernel_gemm.argtypes = [i, i, i, i, i, vp, i64, vp, i64, vp, i64, vp, i64, i, i, vp]
         lib.stage_kernel_wgrad_group.argtypes = [i, i] + [vp] * 9 + [i, vp]
+        lib.stage_kernel_rope_table.argtypes = [i, i, fl, vp, vp]
+        lib.stage_kernel_rope.argtypes = [i, i, i, i, i, i, vp, i64, vp, vp]
         lib.stage_kernel_attention_fwd.argtypes = [i] * 7 + [vp, vp, vp, i, vp]
         lib.stage_kernel_attention_bwd.argtypes = [i] * 7 + [vp] * 6 + [i, vp]
         lib.stage_kernel_attention_bwd_ws.argtypes = [i] * 7 + [vp] * 7 + [C.c_size_t, i, vp]
@@ -158,6 +160,33 @@ def test_attention(dtype, kernel_set, causal, b, s, h, hkv, hd):
     assert so.max_rel_err(got[..., :d], dq.reshape(b, s, d)) <= tol
     assert so.max_rel_err(got[..., d:d + dkv], dk.reshape(b, s, dkv)) <= tol
     assert so.max_rel_err(got[..., d + dkv:], dv.reshape(b, s, dkv)) <= tol
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("b,s,h,hkv,hd,theta", [(2, 200, 5, 1, 128, 10000.0), (1, 333, 4, 4, 64, 500000.0), (1, 4096, 2, 1, 128, 10000.0)])
+def test_rope(dtype, b, s, h, hkv, hd, theta):
+    """Rotary embedding of the q and k heads of a qkv buffer in place (v untouched), and its transpose, against the
+    oracle's definition; forward then transpose gives back the input up to rounding."""
+    import torch
+    nh, ld = h + hkv, (h + 2 * hkv) * hd
+    x = rnd(synth.normal(7, 1, (b, s, ld)), dtype)
+    sh = so.Shape(1, h * hd, h, hkv, 64, s, b, rope_theta=theta)
+    table = torch.zeros((s, hd // 2, 2), dtype=torch.float32, device="cuda:0")
+    assert L().stage_kernel_rope_table(s, hd, theta, P(table), None) == 0
+    torch.cuda.synchronize()
+    ang = np.arange(s)[:, None] * theta ** (-2.0 * np.arange(hd // 2) / hd)[None, :]
+    assert np.abs(table.cpu().numpy()[..., 0] - np.cos(ang)).max() <= 1e-7 and np.abs(table.cpu().numpy()[..., 1] - np.sin(ang)).max() <= 1e-7
+    for inverse in (0, 1):
+        xd = to_dev(x, dtype)
+        assert L().stage_kernel_rope(DT[dtype], b, s, nh, hd, inverse, P(xd), ld, P(table), None) == 0
+        torch.cuda.synchronize()
+        got = to_np(xd)
+        ref = x.astype(np.float64).copy()
+        ref[..., :nh * hd] = so.rope(sh, ref[..., :nh * hd].reshape(b, s, nh, hd), inverse=bool(inverse)).reshape(b, s, nh * hd)
+        assert np.array_equal(got[..., nh * hd:], x[..., nh * hd:].astype(got.dtype))
+        assert so.max_rel_err(got, ref) <= (1e-6 if dtype == "fp32" else 4e-3)
+    assert L().stage_kernel_rope(DT[dtype], b, s, nh, hd, 0, P(xd), nh * hd - 8, P(table), None) == -1
+    assert L().stage_kernel_rope_table(s, 96, theta, P(table), None) == -1
 
 
 @pytest.mark.parametrize("causal", [1, 0])

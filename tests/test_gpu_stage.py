@@ -83,6 +83,30 @@ def test_head_width_independent_of_hidden(heads, kv, hidden, kernel_set):
     compare(cfg, run_gpu(cfg, params, X, G, ops, kernel_set), run_oracle(cfg, params, X, G, ops), TOL["bf16"])
 
 
+@pytest.mark.parametrize("variant", ["cfg1_fp32", "cfg3s", "cfg5s_recompute", "tp_share"])
+def test_rotary_position_embedding(variant):
+    """Llama-style layers: q and k rotated by position after the QKV product, the transposed rotation on dq and dk
+    in B; also under recomputation (the rebuilt stash must hold the rotated q, k again) and with a rectangular
+    attention block."""
+    if variant == "cfg1_fp32":
+        cfg = dict(synth.CONFIGS["cfg1"], rope_theta=10000.0)
+    elif variant == "cfg3s":
+        cfg = dict(SMALL["cfg3s"], rope_theta=500000.0)
+    elif variant == "cfg5s_recompute":
+        cfg = dict(SMALL["cfg5s"], rope_theta=10000.0, recompute=1)
+    else:
+        cfg = dict(SMALL["cfg3s"], hidden=512, n_heads=2, n_kv_heads=1, head_dim=128, ffn=704, rope_theta=10000.0)
+    params, X, G = inputs(cfg, 2800 + len(variant))
+    ops = synth.make_schedule(cfg)
+    cfg["stash_cap"] = synth.peak_live(ops)
+    got = run_gpu(cfg, params, X, G, ops)
+    ref = so.OracleStage(shape_of(cfg), params, recompute=bool(cfg.get("recompute")))
+    Yr, dXr, peak = ref.run_schedule(ops, X.astype(np.float64), G.astype(np.float64))
+    compare(cfg, got, (Yr, dXr, ref.grads, peak), TOL[cfg["dtype"]])
+    plain = run_oracle(dict(cfg, rope_theta=0.0), params, X, G, ops)
+    assert so.max_rel_err(plain[0], Yr) > 1e-3          # the embedding is not a no-op on these inputs
+
+
 @pytest.mark.parametrize("name", ["cfg3s", "cfg4s"])
 def test_small_variants_fp32_storage(name):
     """Same shapes in fp32: isolates arithmetic from bf16 storage rounding."""
