@@ -171,12 +171,34 @@ int stage_backward_weight_sub(stage_t* st, int mb, int sub);
 int stage_run_subschedule(stage_t* st, const stage_subop_t* ops, int n_ops,
                           const void* x_all_dev, const void* dy_all_dev, void* y_all_dev, void* dx_all_dev);
 
+/* Several model chunks on one device (paper section 3.1: an op is identified by (stage, chunk, type, microbatch); looped
+ * and V-shaped placements such as interleaved 1F1B or ZB-V put two chunks on a device).  A chunk is a stage_t of its
+ * own -- own weights, gradients and microbatch states -- that shares the stash of the stage it is attached to: slots come
+ * from one pool and stash_cap (and recompute_cap) bound the live microbatches of all chunks together.  The chunk's config
+ * must give the same slot size and caps as share_with's (in practice: the same shape); it uses share_with's stash and
+ * stream; workspace_dev may be share_with's workspace (one stream orders all uses).  Destroy in any order. */
+int stage_init_chunk(const stage_config_t* cfg, void* weights_dev, void* grads_dev, void* workspace_dev, stage_t* share_with,
+                     stage_t** out);
+/* One op of a per-device schedule over chunks: sub = -1 for a whole op, else the sub-block. */
+typedef struct { int32_t kind; int32_t mb; int32_t sub; int32_t chunk; } stage_chunkop_t;
+/* Host only: like stage_validate_subschedule, for n_chunks chunks of the given config sharing its caps;
+ * *peak_live counts live microbatches over all chunks. */
+int stage_validate_chunk_schedule(const stage_config_t* cfg, int n_chunks, const stage_chunkop_t* ops, int n_ops,
+                                  int* first_bad_index, int* peak_live);
+/* Runs an op list over chunks[0..n_chunks) (all attached to one stash; op.chunk indexes this array).  The whole list is
+ * validated first, shared caps included.  x_all_dev[c] ... dx_all_dev[c] are chunk c's boundary tensors, laid out as for
+ * stage_run_schedule (HOST arrays of device pointers; an entry may be NULL if no op of the list needs it). */
+int stage_run_chunk_schedule(stage_t* const* chunks, int n_chunks, const stage_chunkop_t* ops, int n_ops,
+                             const void* const* x_all_dev, const void* const* dy_all_dev, void* const* y_all_dev,
+                             void* const* dx_all_dev);
+
 /* Borrowed pointer to the fp32 gradient buffer (== grads_dev) and its length.
  * After a full iteration it holds the SUM over microbatches of d<Y_m,dY_m>/dtheta. */
 int stage_grads(stage_t* st, float** grads_dev, size_t* n_elems);
 int stage_zero_grads(stage_t* st);
 
-/* Counters: live microbatches now, their peak since init, peak stash bytes in use (slots of both kinds). */
+/* Counters: live microbatches now (of this chunk), their peak since init and the peak stash bytes in use (slots of both
+ * kinds) -- over all chunks when the stash is shared. */
 int stage_stats(stage_t* st, int* live, int* peak_live, size_t* peak_stash_bytes);
 
 /* Kernel selection for debugging and A/B measurements: 0 = tuned gfx950 kernels

@@ -9,6 +9,7 @@
 #include "../../include/stage.h"
 #include "common.h"
 
+#include <memory>
 #include <new>
 #include <vector>
 
@@ -156,6 +157,7 @@ struct Tracker {
   int hlive = 0, hpeak = 0;       // microbatches between their first B sub-block and their last W
   std::vector<int> last;          // [kind][sub] -> last microbatch that ran it in this iteration
   int cap = 0, hcap = 0, enforce = 0;   // hcap 0: no limit on hlive (no recomputation)
+  int ext_live = 0, ext_hlive = 0;      // live microbatches of the other model chunks that share this stash
   size_t slot_b = 0, big_b = 0, peak_b = 0;   // bytes per slot of either kind, peak bytes in use
 
   void init(const Dims& D, int enforce_) {
@@ -164,7 +166,7 @@ struct Tracker {
     slot_b = slot_bytes(D); big_b = big_slot_bytes(D); peak_b = 0;
     last.assign(3 * n_sub, -1);
   }
-  void note_bytes() { const size_t b = live * slot_b + hlive * big_b; if (b > peak_b) peak_b = b; }
+  void note_bytes() { const size_t b = (live + ext_live) * slot_b + (hlive + ext_hlive) * big_b; if (b > peak_b) peak_b = b; }
   bool waits(int m, int kind, int sub) const {       // microbatch m could run (kind, sub) right now
     if (kind == STAGE_B) return nf[m] == n_sub && sub == n_sub - 1 - nb[m];
     if (kind == STAGE_W) return sub >= n_sub - nb[m] && !(wmask[m] >> sub & 1);
@@ -184,8 +186,8 @@ struct Tracker {
         for (int m = 0; m < mb; ++m)
           if (waits(m, kind, sub)) return STAGE_E_ORDER;
     }
-    if (kind == STAGE_F && sub == 0 && live >= cap) return STAGE_E_STASH_FULL;
-    if (kind == STAGE_B && nb[mb] == 0 && hcap > 0 && hlive >= hcap) return STAGE_E_STASH_FULL;
+    if (kind == STAGE_F && sub == 0 && live + ext_live >= cap) return STAGE_E_STASH_FULL;
+    if (kind == STAGE_B && nb[mb] == 0 && hcap > 0 && hlive + ext_hlive >= hcap) return STAGE_E_STASH_FULL;
     last[kind * n_sub + sub] = mb;
     if (kind == STAGE_F) { if (sub == 0) { ++live; if (live > peak) peak = live; note_bytes(); } ++nf[mb]; }
     else if (kind == STAGE_B) { if (nb[mb] == 0) { ++hlive; if (hlive > hpeak) hpeak = hlive; note_bytes(); } ++nb[mb]; }
@@ -216,6 +218,13 @@ struct Tracker {
 
 }  // namespace
 
+// Slot allocator and occupancy of one stash, shared by the model chunks that live on it.
+struct StashPool {
+  std::vector<int> free_slots, free_big;
+  int live = 0, hlive = 0, peak = 0;
+  size_t peak_b = 0;
+};
+
 struct stage {
   stage_config_t cfg;
   Dims D;
@@ -225,7 +234,7 @@ struct stage {
   size_t slot_sz, big_sz, n_param_elems;
   Tracker tr;
   std::vector<int> slot_of, big_of;      // microbatch -> slot index of either kind, -1 if none
-  std::vector<int> free_slots, free_big;
+  std::shared_ptr<StashPool> pool;
   int sticky = STAGE_OK;
   int kernel_set = 0;
   // optional per-launch timing (HIP events on the stage's stream), by kernel class
@@ -479,9 +488,9 @@ int exec_backward_weight(stage* st, const int* mbs, int n_mb, int l0, int l1) {
 }
 
 void release_slots(stage* st, int mb) {
-  st->free_slots.push_back(st->slot_of[mb]);
+  st->pool->free_slots.push_back(st->slot_of[mb]);
   st->slot_of[mb] = -1;
-  if (st->big_of[mb] >= 0) { st->free_big.push_back(st->big_of[mb]); st->big_of[mb] = -1; }
+  if (st->big_of[mb] >= 0) { st->pool->free_big.push_back(st->big_of[mb]); st->big_of[mb] = -1; }
 }
 
 // Applies one already-validated op (sub < 0: the whole op, every sub-block): allocator bookkeeping + launches.
@@ -492,14 +501,14 @@ int apply_op(stage* st, int kind, int mb, int sub, bool had_slot, bool holds_slo
   int rc = STAGE_OK;
   if (kind == STAGE_F) {
     if (!had_slot) {
-      st->slot_of[mb] = st->free_slots.back();
-      st->free_slots.pop_back();
+      st->slot_of[mb] = st->pool->free_slots.back();
+      st->pool->free_slots.pop_back();
     }
     rc = exec_forward(st, mb, in, out, l0, l1);
   } else if (kind == STAGE_B) {
     if (st->D.recompute && st->big_of[mb] < 0) {
-      st->big_of[mb] = st->free_big.back();
-      st->free_big.pop_back();
+      st->big_of[mb] = st->pool->free_big.back();
+      st->pool->free_big.pop_back();
     }
     rc = exec_backward_input(st, mb, in, out, l0, l1);
   } else {
@@ -509,60 +518,145 @@ int apply_op(stage* st, int kind, int mb, int sub, bool had_slot, bool holds_slo
   return rc;
 }
 
+// The tracker counts its own chunk; what the other chunks on the same stash hold comes from the pool.
+void pull_pool(stage* st, Tracker& t) {
+  t.ext_live = st->pool->live - st->tr.live;
+  t.ext_hlive = st->pool->hlive - st->tr.hlive;
+  if (st->pool->peak_b > t.peak_b) t.peak_b = st->pool->peak_b;
+}
+void push_pool(stage* st) {
+  StashPool& p = *st->pool;
+  p.live = st->tr.live + st->tr.ext_live;
+  p.hlive = st->tr.hlive + st->tr.ext_hlive;
+  if (p.live > p.peak) p.peak = p.live;
+  if (st->tr.peak_b > p.peak_b) p.peak_b = st->tr.peak_b;
+}
+int step_tracked(stage* st, int kind, int mb, int sub) {
+  pull_pool(st, st->tr);
+  const int rc = sub < 0 ? st->tr.step(kind, mb) : st->tr.step_sub(kind, mb, sub);
+  if (rc == STAGE_OK) push_pool(st);
+  return rc;
+}
+
 // validate + apply one op against the stage's tracker
 int run_one(stage* st, int kind, int mb, int sub, const void* in, void* out) {
   if (mb < 0 || mb >= st->D.n_mb) return STAGE_E_INVAL;
   const bool had = st->tr.slot_held(mb);
-  const int rc = sub < 0 ? st->tr.step(kind, mb) : st->tr.step_sub(kind, mb, sub);
+  const int rc = step_tracked(st, kind, mb, sub);
   if (rc != STAGE_OK) return rc;
   return apply_op(st, kind, mb, sub, had, st->tr.slot_held(mb), in, out);
 }
 
 // shared body of the two schedule runners: op i is (kind(i), mb(i), sub(i)), sub < 0 meaning a whole op
+// Probes a list spread over the model chunks of one stash: every chunk's tracker is stepped on a copy, with the
+// other chunks' live counts kept up to date, so caps that the chunks share are checked across them.
+// get(i, chunk, kind, mb, sub); returns the first error and its position.
 template <typename GetOp>
-int run_list(stage* st, int n_ops, GetOp get, const void* x_all, const void* dy_all, void* y_all, void* dx_all) {
-  // validate the whole list on a copy of the tracker before enqueuing anything
-  Tracker probe = st->tr;
-  const int ns = st->D.n_sub;
+int probe_list(stage* const* chunks, int n_chunks, int n_ops, GetOp get, int* bad) {
+  std::vector<Tracker> probe(n_chunks);
+  int live = chunks[0]->pool->live, hlive = chunks[0]->pool->hlive;
+  for (int c = 0; c < n_chunks; ++c) probe[c] = chunks[c]->tr;
   for (int i = 0; i < n_ops; ++i) {
-    int kind, mb, sub; get(i, kind, mb, sub);
-    if (kind == STAGE_F && ((sub <= 0 && !x_all) || ((sub < 0 || sub == ns - 1) && !y_all))) return STAGE_E_INVAL;
-    if (kind == STAGE_B && (((sub < 0 || sub == ns - 1) && !dy_all) || (sub <= 0 && !dx_all))) return STAGE_E_INVAL;
-    const int rc = sub < 0 ? probe.step(kind, mb) : probe.step_sub(kind, mb, sub);
+    int c, kind, mb, sub; get(i, c, kind, mb, sub);
+    if (bad) *bad = i;
+    if (c < 0 || c >= n_chunks) return STAGE_E_INVAL;
+    Tracker& t = probe[c];
+    t.ext_live = live - t.live; t.ext_hlive = hlive - t.hlive;
+    const int rc = sub < 0 ? t.step(kind, mb) : t.step_sub(kind, mb, sub);
     if (rc != STAGE_OK) return rc;
+    live = t.live + t.ext_live; hlive = t.hlive + t.ext_hlive;
   }
-  const size_t mb_bytes = (size_t)st->D.T * st->D.d * st->D.es;
-  // Adjacent W ops on the same layers (same sub-block, or whole ops) are enqueued as one: their microbatches, in list
-  // order, become the K segments of one set of weight-gradient products.  The tracker still sees them one by one;
-  // the stash slots are handed back when the merged launch has been enqueued.
+  if (bad) *bad = -1;
+  return STAGE_OK;
+}
+
+// Shared body of the schedule runners: op i is (chunk(i), kind(i), mb(i), sub(i)), sub < 0 meaning a whole op; chunk c
+// reads and writes the boundary tensors x_all[c] ... dx_all[c].
+template <typename GetOp>
+int run_list(stage* const* chunks, int n_chunks, int n_ops, GetOp get, const void* const* x_all, const void* const* dy_all,
+             void* const* y_all, void* const* dx_all) {
+  // validate the whole list before enqueuing anything
+  for (int i = 0; i < n_ops; ++i) {
+    int c, kind, mb, sub; get(i, c, kind, mb, sub);
+    if (c < 0 || c >= n_chunks) return STAGE_E_INVAL;
+    const int ns = chunks[c]->D.n_sub;
+    if (kind == STAGE_F && ((sub <= 0 && !x_all[c]) || ((sub < 0 || sub == ns - 1) && !y_all[c]))) return STAGE_E_INVAL;
+    if (kind == STAGE_B && (((sub < 0 || sub == ns - 1) && !dy_all[c]) || (sub <= 0 && !dx_all[c]))) return STAGE_E_INVAL;
+  }
+  { const int rc = probe_list(chunks, n_chunks, n_ops, get, nullptr); if (rc != STAGE_OK) return rc; }
+  // Adjacent W ops on the same layers of the same chunk (same sub-block, or whole ops) are enqueued as one: their
+  // microbatches, in list order, become the K segments of one set of weight-gradient products.  The tracker still sees
+  // them one by one; the stash slots are handed back when the merged launch has been enqueued.
+  stage* run_st = nullptr;
   int run_mb[GEMM_MAX_SEG], run_n = 0, run_sub = 0;
   bool run_release[GEMM_MAX_SEG];
   auto flush = [&]() -> int {
     if (run_n == 0) return STAGE_OK;
-    const int per = st->D.L / st->D.n_sub;
-    const int l0 = run_sub < 0 ? 0 : run_sub * per, l1 = run_sub < 0 ? st->D.L : (run_sub + 1) * per;
-    const int rc = exec_backward_weight(st, run_mb, run_n, l0, l1);
+    const int per = run_st->D.L / run_st->D.n_sub;
+    const int l0 = run_sub < 0 ? 0 : run_sub * per, l1 = run_sub < 0 ? run_st->D.L : (run_sub + 1) * per;
+    const int rc = exec_backward_weight(run_st, run_mb, run_n, l0, l1);
     for (int i = 0; i < run_n; ++i)
-      if (run_release[i]) release_slots(st, run_mb[i]);
+      if (run_release[i]) release_slots(run_st, run_mb[i]);
     run_n = 0;
     return rc;
   };
   for (int i = 0; i < n_ops; ++i) {
-    int kind, mb, sub; get(i, kind, mb, sub);
+    int c, kind, mb, sub; get(i, c, kind, mb, sub);
+    stage* st = chunks[c];
     if (kind == STAGE_W) {
-      if (run_n > 0 && (sub != run_sub || run_n == GEMM_MAX_SEG)) { const int rc = flush(); if (rc != STAGE_OK) return rc; }
-      const int rc = sub < 0 ? st->tr.step(kind, mb) : st->tr.step_sub(kind, mb, sub);
+      if (run_n > 0 && (st != run_st || sub != run_sub || run_n == GEMM_MAX_SEG)) { const int rc = flush(); if (rc != STAGE_OK) return rc; }
+      const int rc = step_tracked(st, kind, mb, sub);
       if (rc != STAGE_OK) { flush(); return rc; }
-      run_sub = sub; run_mb[run_n] = mb; run_release[run_n] = !st->tr.slot_held(mb); ++run_n;
+      run_st = st; run_sub = sub; run_mb[run_n] = mb; run_release[run_n] = !st->tr.slot_held(mb); ++run_n;
       continue;
     }
     { const int rc = flush(); if (rc != STAGE_OK) return rc; }
-    const void* in = kind == STAGE_F ? (const char*)x_all + mb_bytes * mb : (const char*)dy_all + mb_bytes * mb;
-    void* out = kind == STAGE_F ? (char*)y_all + mb_bytes * mb : (char*)dx_all + mb_bytes * mb;
+    const size_t mb_bytes = (size_t)st->D.T * st->D.d * st->D.es;
+    const void* in = kind == STAGE_F ? (const char*)x_all[c] + mb_bytes * mb : (const char*)dy_all[c] + mb_bytes * mb;
+    void* out = kind == STAGE_F ? (char*)y_all[c] + mb_bytes * mb : (char*)dx_all[c] + mb_bytes * mb;
     const int rc = run_one(st, kind, mb, sub, in, out);
     if (rc != STAGE_OK) return rc;
   }
   return flush();
+}
+
+int init_stage(const stage_config_t* cfg, void* weights_dev, void* grads_dev, void* stash_dev, void* workspace_dev,
+               void* hip_stream, stage* share_with, stage_t** out) {
+  Dims D;
+  if (!out) return STAGE_E_INVAL;
+  *out = nullptr;
+  if (!make_dims(cfg, &D) || !weights_dev || !grads_dev || !stash_dev || !workspace_dev) return STAGE_E_INVAL;
+  if (((uintptr_t)weights_dev | (uintptr_t)grads_dev | (uintptr_t)stash_dev | (uintptr_t)workspace_dev) % ALIGN)
+    return STAGE_E_INVAL;
+  if (share_with) {   // chunks of one stash: same slot geometry and caps
+    const Dims& S = share_with->D;
+    if (slot_bytes(D) != slot_bytes(S) || big_slot_bytes(D) != big_slot_bytes(S) || D.cap != S.cap || D.hcap != S.hcap ||
+        D.recompute != S.recompute)
+      return STAGE_E_INVAL;
+  }
+  stage* st = new (std::nothrow) stage();
+  if (!st) return STAGE_E_INVAL;
+  st->cfg = *cfg; st->D = D; st->dt = cfg->dtype == STAGE_DTYPE_FP32 ? DT_F32 : DT_BF16;
+  st->weights = (char*)weights_dev; st->grads = (float*)grads_dev; st->stash = (char*)stash_dev; st->ws = (char*)workspace_dev;
+  st->stream = (hipStream_t)hip_stream;
+  st->slot_sz = slot_bytes(D); st->big_sz = big_slot_bytes(D);
+  st->n_param_elems = layer_param_elems(D, cfg->norm) * D.L;
+  st->tr.init(D, cfg->enforce_mb_order);
+  st->slot_of.assign(D.n_mb, -1); st->big_of.assign(D.n_mb, -1);
+  if (share_with) {
+    st->pool = share_with->pool;
+  } else {
+    st->pool = std::make_shared<StashPool>();
+    for (int i = D.cap - 1; i >= 0; --i) st->pool->free_slots.push_back(i);
+    for (int i = D.hcap - 1; i >= 0; --i) st->pool->free_big.push_back(i);
+  }
+  if (fill_zero_f32(st->grads, st->n_param_elems, st->stream) != hipSuccess) { delete st; return STAGE_E_HIP; }
+  if (D.rope && rope_table((float*)(st->ws + ws_off(D).rope), D.s, D.hd, (double)cfg->rope_theta, st->stream) != hipSuccess) {
+    delete st;
+    return STAGE_E_HIP;
+  }
+  *out = st;
+  return STAGE_OK;
 }
 
 }  // namespace
@@ -612,30 +706,13 @@ int stage_param_layout(const stage_config_t* cfg, int layer, int param_id, size_
 
 int stage_init(const stage_config_t* cfg, void* weights_dev, void* grads_dev, void* stash_dev, void* workspace_dev,
                void* hip_stream, stage_t** out) {
-  Dims D;
-  if (!out) return STAGE_E_INVAL;
-  *out = nullptr;
-  if (!make_dims(cfg, &D) || !weights_dev || !grads_dev || !stash_dev || !workspace_dev) return STAGE_E_INVAL;
-  if (((uintptr_t)weights_dev | (uintptr_t)grads_dev | (uintptr_t)stash_dev | (uintptr_t)workspace_dev) % ALIGN)
-    return STAGE_E_INVAL;
-  stage* st = new (std::nothrow) stage();
-  if (!st) return STAGE_E_INVAL;
-  st->cfg = *cfg; st->D = D; st->dt = cfg->dtype == STAGE_DTYPE_FP32 ? DT_F32 : DT_BF16;
-  st->weights = (char*)weights_dev; st->grads = (float*)grads_dev; st->stash = (char*)stash_dev; st->ws = (char*)workspace_dev;
-  st->stream = (hipStream_t)hip_stream;
-  st->slot_sz = slot_bytes(D); st->big_sz = big_slot_bytes(D);
-  st->n_param_elems = layer_param_elems(D, cfg->norm) * D.L;
-  st->tr.init(D, cfg->enforce_mb_order);
-  st->slot_of.assign(D.n_mb, -1); st->big_of.assign(D.n_mb, -1);
-  for (int i = D.cap - 1; i >= 0; --i) st->free_slots.push_back(i);
-  for (int i = D.hcap - 1; i >= 0; --i) st->free_big.push_back(i);
-  if (fill_zero_f32(st->grads, st->n_param_elems, st->stream) != hipSuccess) { delete st; return STAGE_E_HIP; }
-  if (D.rope && rope_table((float*)(st->ws + ws_off(D).rope), D.s, D.hd, (double)cfg->rope_theta, st->stream) != hipSuccess) {
-    delete st;
-    return STAGE_E_HIP;
-  }
-  *out = st;
-  return STAGE_OK;
+  return init_stage(cfg, weights_dev, grads_dev, stash_dev, workspace_dev, hip_stream, nullptr, out);
+}
+
+int stage_init_chunk(const stage_config_t* cfg, void* weights_dev, void* grads_dev, void* workspace_dev, stage_t* share_with,
+                     stage_t** out) {
+  if (!share_with) { if (out) *out = nullptr; return STAGE_E_INVAL; }
+  return init_stage(cfg, weights_dev, grads_dev, share_with->stash, workspace_dev, (void*)share_with->stream, share_with, out);
 }
 
 static int single_op(stage_t* st, int kind, int mb, int sub, const void* in, void* out) {
@@ -667,8 +744,8 @@ int stage_run_schedule(stage_t* st, const stage_op_t* ops, int n_ops, const void
                        void* y_all_dev, void* dx_all_dev) {
   if (!st || n_ops < 0 || (n_ops > 0 && !ops)) return STAGE_E_INVAL;
   if (st->sticky) return st->sticky;
-  return run_list(st, n_ops, [&](int i, int& k, int& m, int& s) { k = ops[i].kind; m = ops[i].mb; s = -1; },
-                  x_all_dev, dy_all_dev, y_all_dev, dx_all_dev);
+  return run_list(&st, 1, n_ops, [&](int i, int& c, int& k, int& m, int& s) { c = 0; k = ops[i].kind; m = ops[i].mb; s = -1; },
+                  &x_all_dev, &dy_all_dev, &y_all_dev, &dx_all_dev);
 }
 
 int stage_run_subschedule(stage_t* st, const stage_subop_t* ops, int n_ops, const void* x_all_dev, const void* dy_all_dev,
@@ -677,8 +754,56 @@ int stage_run_subschedule(stage_t* st, const stage_subop_t* ops, int n_ops, cons
   if (st->sticky) return st->sticky;
   for (int i = 0; i < n_ops; ++i)
     if (ops[i].sub < 0 || ops[i].sub >= st->D.n_sub) return STAGE_E_INVAL;
-  return run_list(st, n_ops, [&](int i, int& k, int& m, int& s) { k = ops[i].kind; m = ops[i].mb; s = ops[i].sub; },
+  return run_list(&st, 1, n_ops, [&](int i, int& c, int& k, int& m, int& s) { c = 0; k = ops[i].kind; m = ops[i].mb; s = ops[i].sub; },
+                  &x_all_dev, &dy_all_dev, &y_all_dev, &dx_all_dev);
+}
+
+int stage_run_chunk_schedule(stage_t* const* chunks, int n_chunks, const stage_chunkop_t* ops, int n_ops,
+                             const void* const* x_all_dev, const void* const* dy_all_dev, void* const* y_all_dev,
+                             void* const* dx_all_dev) {
+  if (!chunks || n_chunks < 1 || n_chunks > 16 || n_ops < 0 || (n_ops > 0 && !ops) || !x_all_dev || !dy_all_dev || !y_all_dev ||
+      !dx_all_dev)
+    return STAGE_E_INVAL;
+  for (int c = 0; c < n_chunks; ++c) {
+    if (!chunks[c] || chunks[c]->pool != chunks[0]->pool) return STAGE_E_INVAL;      // chunks of one stash only
+    for (int e = 0; e < c; ++e) if (chunks[e] == chunks[c]) return STAGE_E_INVAL;
+    if (chunks[c]->sticky) return chunks[c]->sticky;
+  }
+  for (int i = 0; i < n_ops; ++i) {
+    const int c = ops[i].chunk;
+    if (c < 0 || c >= n_chunks || ops[i].sub < -1 || ops[i].sub >= chunks[c]->D.n_sub) return STAGE_E_INVAL;
+  }
+  return run_list(chunks, n_chunks, n_ops,
+                  [&](int i, int& c, int& k, int& m, int& s) { c = ops[i].chunk; k = ops[i].kind; m = ops[i].mb; s = ops[i].sub; },
                   x_all_dev, dy_all_dev, y_all_dev, dx_all_dev);
+}
+
+int stage_validate_chunk_schedule(const stage_config_t* cfg, int n_chunks, const stage_chunkop_t* ops, int n_ops,
+                                  int* first_bad_index, int* peak_live) {
+  Dims D;
+  if (first_bad_index) *first_bad_index = -1;
+  if (peak_live) *peak_live = 0;
+  if (!make_dims(cfg, &D) || n_chunks < 1 || n_chunks > 16 || n_ops < 0 || (n_ops > 0 && !ops)) return STAGE_E_INVAL;
+  std::vector<Tracker> t(n_chunks);
+  for (auto& x : t) x.init(D, cfg->enforce_mb_order);
+  int live = 0, hlive = 0, peak = 0;
+  for (int i = 0; i < n_ops; ++i) {
+    const int c = ops[i].chunk, sub = ops[i].sub;
+    int rc = STAGE_E_INVAL;
+    if (c >= 0 && c < n_chunks && sub >= -1 && sub < D.n_sub) {
+      t[c].ext_live = live - t[c].live; t[c].ext_hlive = hlive - t[c].hlive;
+      rc = sub < 0 ? t[c].step(ops[i].kind, ops[i].mb) : t[c].step_sub(ops[i].kind, ops[i].mb, sub);
+    }
+    if (rc != STAGE_OK) {
+      if (first_bad_index) *first_bad_index = i;
+      if (peak_live) *peak_live = peak;
+      return rc;
+    }
+    live = t[c].live + t[c].ext_live; hlive = t[c].hlive + t[c].ext_hlive;
+    if (live > peak) peak = live;
+  }
+  if (peak_live) *peak_live = peak;
+  return STAGE_OK;
 }
 
 int stage_validate_subschedule(const stage_config_t* cfg, const stage_subop_t* ops, int n_ops, int* first_bad_index,
@@ -716,8 +841,8 @@ int stage_zero_grads(stage_t* st) {
 int stage_stats(stage_t* st, int* live, int* peak_live, size_t* peak_stash_bytes) {
   if (!st) return STAGE_E_INVAL;
   if (live) *live = st->tr.live;
-  if (peak_live) *peak_live = st->tr.peak;
-  if (peak_stash_bytes) *peak_stash_bytes = st->tr.peak_b;
+  if (peak_live) *peak_live = st->pool.use_count() > 1 ? st->pool->peak : st->tr.peak;
+  if (peak_stash_bytes) *peak_stash_bytes = st->pool->peak_b > st->tr.peak_b ? st->pool->peak_b : st->tr.peak_b;
   return STAGE_OK;
 }
 

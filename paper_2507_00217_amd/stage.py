@@ -35,6 +35,10 @@ class StageSubOp(C.Structure):
     _fields_ = [("kind", C.c_int32), ("mb", C.c_int32), ("sub", C.c_int32)]
 
 
+class StageChunkOp(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("mb", C.c_int32), ("sub", C.c_int32), ("chunk", C.c_int32)]
+
+
 class StageOp(C.Structure):
     _fields_ = [("kind", C.c_int32), ("mb", C.c_int32)]
 
@@ -78,6 +82,10 @@ def lib() -> C.CDLL:
             "stage_backward_input_sub": (C.c_int, [vp, C.c_int, C.c_int, vp, vp]),
             "stage_backward_weight_sub": (C.c_int, [vp, C.c_int, C.c_int]),
             "stage_run_subschedule": (C.c_int, [vp, sopp, C.c_int, vp, vp, vp, vp]),
+            "stage_init_chunk": (C.c_int, [cfgp, vp, vp, vp, vp, C.POINTER(vp)]),
+            "stage_validate_chunk_schedule": (C.c_int, [cfgp, C.c_int, C.POINTER(StageChunkOp), C.c_int, ip, ip]),
+            "stage_run_chunk_schedule": (C.c_int, [C.POINTER(vp), C.c_int, C.POINTER(StageChunkOp), C.c_int,
+                                                   C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]),
             "stage_grads": (C.c_int, [vp, C.POINTER(vp), C.POINTER(C.c_size_t)]),
             "stage_zero_grads": (C.c_int, [vp]),
             "stage_stats": (C.c_int, [vp, ip, ip, C.POINTER(C.c_size_t)]),
@@ -130,6 +138,31 @@ def stage_validate_subschedule(cfg: dict, ops) -> Tuple[int, int, int]:
     return rc, bad.value, peak.value
 
 
+def make_chunkops(ops: Sequence[Tuple[int, int, int, int]]):
+    """ops: (kind, mb, sub, chunk), sub = -1 for a whole op."""
+    arr = (StageChunkOp * max(1, len(ops)))()
+    for i, (k, m, sb, c) in enumerate(ops):
+        arr[i].kind, arr[i].mb, arr[i].sub, arr[i].chunk = k, m, sb, c
+    return arr
+
+
+def stage_validate_chunk_schedule(cfg: dict, n_chunks: int, ops) -> Tuple[int, int, int]:
+    """Host only. Returns (rc, first_bad_index, peak_live over all chunks)."""
+    bad, peak = C.c_int(-1), C.c_int(0)
+    rc = lib().stage_validate_chunk_schedule(C.byref(make_config(cfg)), n_chunks, make_chunkops(ops), len(ops), C.byref(bad), C.byref(peak))
+    return rc, bad.value, peak.value
+
+
+def run_chunk_schedule(chunks: "List[Stage]", ops, Xs, dYs, Ys, dXs):
+    """Runs (kind, mb, sub, chunk) ops over stages that share one stash; Xs[c] ... dXs[c] are chunk c's boundary tensors."""
+    n = len(chunks)
+    ptrs = lambda ts: (C.c_void_p * n)(*[(t.data_ptr() if t is not None else None) for t in ts])
+    hs = (C.c_void_p * n)(*[st.h for st in chunks])
+    rc = lib().stage_run_chunk_schedule(hs, n, make_chunkops(ops), len(ops), ptrs(Xs), ptrs(dYs), ptrs(Ys), ptrs(dXs))
+    if rc:
+        raise StageError(rc, "stage_run_chunk_schedule")
+
+
 def stage_query_sizes(cfg: dict) -> Dict[str, int]:
     out = StageSizes()
     rc = lib().stage_query_sizes(C.byref(make_config(cfg)), C.byref(out))
@@ -157,7 +190,9 @@ def stage_param_layout(cfg: dict, layer: int, name: str) -> Tuple[int, int, int]
 class Stage:
     """Owns the device buffers (torch tensors) and the stage_t handle."""
 
-    def __init__(self, cfg: dict, device: str = "cuda:0", stream=None):
+    def __init__(self, cfg: dict, device: str = "cuda:0", stream=None, share_with: "Stage" = None):
+        """share_with: make this stage a further model chunk on share_with's stash (and stream): slots and caps are
+        then common to both."""
         import torch
         self.torch = torch
         self.cfg = dict(cfg)
@@ -170,13 +205,19 @@ class Stage:
             self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
             self._weights = torch.zeros(sz["weights"], dtype=torch.uint8, device=self.device)
             self._grads = torch.zeros(sz["grads"], dtype=torch.uint8, device=self.device)
-            self._stash = torch.empty(sz["stash"], dtype=torch.uint8, device=self.device)
-            self._ws = torch.empty(sz["workspace"], dtype=torch.uint8, device=self.device)
             h = C.c_void_p()
-            rc = lib().stage_init(C.byref(self.ccfg), self._weights.data_ptr(), self._grads.data_ptr(),
-                                  self._stash.data_ptr(), self._ws.data_ptr(), self.stream.cuda_stream, C.byref(h))
+            if share_with is None:
+                self._stash = torch.empty(sz["stash"], dtype=torch.uint8, device=self.device)
+                self._ws = torch.empty(sz["workspace"], dtype=torch.uint8, device=self.device)
+                rc = lib().stage_init(C.byref(self.ccfg), self._weights.data_ptr(), self._grads.data_ptr(),
+                                      self._stash.data_ptr(), self._ws.data_ptr(), self.stream.cuda_stream, C.byref(h))
+            else:
+                self.stream = share_with.stream
+                self._stash, self._ws = share_with._stash, share_with._ws      # keeps them alive; one stream orders all uses
+                rc = lib().stage_init_chunk(C.byref(self.ccfg), self._weights.data_ptr(), self._grads.data_ptr(),
+                                            self._ws.data_ptr(), share_with.h, C.byref(h))
         if rc:
-            raise StageError(rc, "stage_init")
+            raise StageError(rc, "stage_init" if share_with is None else "stage_init_chunk")
         self.h = h
 
     # -- weights / grads marshalling ------------------------------------------

@@ -181,6 +181,58 @@ def schedule_1f1b(n_mb: int, warmup: int) -> List[Tuple[int, int]]:
     return ops
 
 
+def schedule_two_chunks(n_mb: int, cap: int, defer_w: bool = False) -> List[Tuple[int, int, int, int]]:
+    """Per-device op list (kind, mb, sub=-1, chunk) for a device that holds two model chunks of a looped placement (the
+    situation of interleaved 1F1B / ZB-V in the paper's table of schedules): microbatch m runs F on chunk 0, later F on
+    chunk 1, B on chunk 1, then B on chunk 0.  A list scheduler: backward work first when there is any (deepest chunk
+    first), else the forward that is furthest along, while at most `cap` (chunk, microbatch) stashes are live;
+    W follows its B at once, or (defer_w) as late as the cap allows."""
+    assert cap >= 2
+    ops: List[Tuple[int, int, int, int]] = []
+    f_done = [0, 0]                  # forwards issued per chunk (microbatches go in order)
+    b_done = [0, 0]
+    w_pending: List[Tuple[int, int]] = []
+    live = 0
+    while b_done[0] < n_mb or w_pending:
+        # backward available?  chunk 1 needs its own F; chunk 0 needs chunk 1's B of the same microbatch
+        if b_done[1] < f_done[1] and (b_done[1] <= b_done[0] or True):
+            c = 1
+        elif b_done[0] < b_done[1]:
+            c = 0
+        else:
+            c = -1
+        can_f1 = f_done[1] < f_done[0] and f_done[1] < n_mb
+        can_f0 = f_done[0] < n_mb and live <= cap - 2      # keep a slot for that microbatch's chunk-1 forward
+        if live >= cap and w_pending:
+            cc, m = w_pending.pop(0); ops.append((W, m, -1, cc)); live -= 1
+            continue
+        if c >= 0 and (live >= cap or not (can_f0 or can_f1) or f_done[0] - b_done[0] >= cap // 2 + 1):
+            m = b_done[c]; ops.append((B, m, -1, c)); b_done[c] += 1
+            if defer_w:
+                w_pending.append((c, m))
+            else:
+                ops.append((W, m, -1, c)); live -= 1
+            continue
+        if live < cap and can_f1 and (f_done[0] - f_done[1] >= 2 or not can_f0):
+            ops.append((F, f_done[1], -1, 1)); f_done[1] += 1; live += 1
+            continue
+        if live < cap and can_f0:
+            ops.append((F, f_done[0], -1, 0)); f_done[0] += 1; live += 1
+            continue
+        if live < cap and can_f1:
+            ops.append((F, f_done[1], -1, 1)); f_done[1] += 1; live += 1
+            continue
+        if c >= 0:
+            m = b_done[c]; ops.append((B, m, -1, c)); b_done[c] += 1
+            if defer_w:
+                w_pending.append((c, m))
+            else:
+                ops.append((W, m, -1, c)); live -= 1
+            continue
+        cc, m = w_pending.pop(0); ops.append((W, m, -1, cc)); live -= 1
+    return ops
+
+
 def schedule_w_deferred(n_mb: int, warmup: int, tail: int) -> List[Tuple[int, int]]:
     """1F1B body, but the last `tail` microbatches run all their B first and
     their W afterwards (W fills what would be the tear-down bubbles)."""

@@ -348,3 +348,57 @@ def test_recomputation_with_sub_blocks_and_cap():
     assert st.stats()["live"] == 0
     assert torch.equal(Y, res[0][0]) and torch.equal(dX, res[0][1]) and torch.equal(st.grads_tensor(), res[0][2])
     st.close()
+
+
+@pytest.mark.parametrize("defer_w", [False, True])
+def test_two_chunks_share_one_stash(defer_w):
+    """Two model chunks on one device (paper section 3.1; looped / V-shaped placements): separate weights and
+    gradients, one stash and one cap.  A two-chunk order runs through stage_run_chunk_schedule; every chunk matches its
+    own oracle and, bit for bit, the same chunk run alone; the shared cap refuses an F on either chunk when the pool
+    is empty and leaves everything untouched."""
+    import torch
+    from paper_2507_00217_amd import stage as S
+    n_mb, cap = 5, 3
+    cfg = dict(SMALL["cfg3s"], n_microbatches=n_mb, stash_cap=cap, enforce_mb_order=1)
+    ops = synth.schedule_two_chunks(n_mb, cap, defer_w)
+    assert S.stage_validate_chunk_schedule(cfg, 2, ops)[:2] == (0, -1)
+    data = [inputs(cfg, 2900 + 10 * c) for c in range(2)]
+    c0 = S.Stage(cfg)
+    c1 = S.Stage(cfg, share_with=c0)
+    chunks = [c0, c1]
+    Xd, Gd, Y, dX = [], [], [], []
+    for c, (params, X, G) in enumerate(data):
+        chunks[c].load_weights(params)
+        Xd.append(to_dev(X, "bf16")); Gd.append(to_dev(G, "bf16"))
+        Y.append(torch.zeros_like(Xd[c])); dX.append(torch.zeros_like(Xd[c]))
+    S.run_chunk_schedule(chunks, ops, Xd, Gd, Y, dX)
+    torch.cuda.synchronize()
+    assert c0.stats()["live"] == 0 and c1.stats()["live"] == 0 and c0.stats()["peak_live"] == cap == c1.stats()["peak_live"]
+    for c, (params, X, G) in enumerate(data):
+        own = [(k, m) for k, m, _, cc in ops if cc == c]
+        ref = so.OracleStage(shape_of(cfg), params)
+        Yr, dXr, _ = ref.run_schedule(own, X.astype(np.float64), G.astype(np.float64))
+        got = (to_np(Y[c]), to_np(dX[c]), chunks[c].grads(), {"peak_live": 0, "live": 0})
+        compare(cfg, got, (Yr, dXr, ref.grads, 0), TOL["bf16"])
+        alone = S.Stage(dict(cfg, stash_cap=n_mb))
+        alone.load_weights(params)
+        Ya, dXa = torch.zeros_like(Xd[c]), torch.zeros_like(Xd[c])
+        alone.run_schedule(own, Xd[c], Gd[c], Ya, dXa)
+        torch.cuda.synchronize()
+        assert torch.equal(Ya, Y[c]) and torch.equal(dXa, dX[c]) and torch.equal(alone.grads_tensor(), chunks[c].grads_tensor())
+        alone.close()
+    # shared cap: three live microbatches spread over both chunks fill the pool
+    c0.forward(0, Xd[0][0], Y[0][0]); c1.forward(0, Xd[1][0], Y[1][0]); c0.forward(1, Xd[0][1], Y[0][1])
+    for st, m in ((c1, 1), (c0, 2)):
+        with pytest.raises(S.StageError) as e:
+            st.forward(m, Xd[0][m], Y[0][m])
+        assert e.value.code == S.E_STASH_FULL
+    assert (c0.stats()["live"], c1.stats()["live"]) == (2, 1)
+    with pytest.raises(S.StageError) as e:          # a list that would overflow the shared cap is refused as a whole
+        S.run_chunk_schedule(chunks, [(B, 0, -1, 1), (F, 1, -1, 1)], Xd, Gd, Y, dX)
+    assert e.value.code == S.E_STASH_FULL and (c0.stats()["live"], c1.stats()["live"]) == (2, 1)
+    S.run_chunk_schedule(chunks, [(B, 0, -1, 1), (W, 0, -1, 1), (F, 1, -1, 1), (B, 1, -1, 1), (W, 1, -1, 1),
+                                  (B, 0, -1, 0), (W, 0, -1, 0), (B, 1, -1, 0), (W, 1, -1, 0)], Xd, Gd, Y, dX)
+    torch.cuda.synchronize()
+    assert (c0.stats()["live"], c1.stats()["live"]) == (0, 0)
+    c1.close(); c0.close()

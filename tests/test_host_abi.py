@@ -6,6 +6,7 @@ import itertools
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2507_00217_amd import stage as S
@@ -233,3 +234,49 @@ def test_recomputation_sizes_and_validator():
     rc, bad, _ = S.stage_validate_subschedule(sub, [(F, 0, 0), (F, 0, 1), (F, 1, 0), (F, 1, 1), (B, 0, 1), (B, 0, 0), (W, 0, 1),
                                                     (W, 0, 0), (B, 1, 1)])
     assert (rc, bad) == (0, -1)
+
+
+def ref_validate_chunks(ops, n_chunks, n_mb, cap, enforce):
+    """Reference for the chunk validator: per-chunk microbatch state machines, one cap over all chunks."""
+    state = [[0] * n_mb for _ in range(n_chunks)]
+    last = [[-1, -1, -1] for _ in range(n_chunks)]
+    own = [0] * n_chunks
+    live = peak = 0
+    for i, (k, m, sub, c) in enumerate(ops):
+        if not (0 <= c < n_chunks and 0 <= k <= 2 and 0 <= m < n_mb and sub == -1):
+            return S.E_INVAL, i, peak
+        if state[c][m] != k or (enforce and (m <= last[c][k] or (k != F and k in state[c][:m]))):
+            return S.E_ORDER, i, peak
+        if k == F and live >= cap:
+            return S.E_STASH_FULL, i, peak
+        state[c][m] = (k + 1) % 3; last[c][k] = m
+        d = (k == F) - (k == W)
+        live += d; own[c] += d; peak = max(peak, live)
+        if own[c] == 0 and k == W:
+            last[c] = [-1, -1, -1]
+    return 0, -1, peak
+
+
+@pytest.mark.parametrize("enforce", [0, 1])
+@pytest.mark.parametrize("cap", [2, 3])
+def test_chunk_validator(cap, enforce):
+    """Two model chunks on one stash (paper section 3.1: ops carry a chunk index): generated two-chunk orders are
+    legal at their cap and not below it; random op sequences agree with the reference, error code, position and peak."""
+    cfg = dict(synth.CONFIGS["cfg1"], n_microbatches=3, stash_cap=cap, enforce_mb_order=enforce)
+    ops = synth.schedule_two_chunks(3, cap, defer_w=bool(enforce))
+    rc, bad, peak = S.stage_validate_chunk_schedule(cfg, 2, ops)
+    assert (rc, bad) == (0, -1) and peak == cap
+    if cap > 2:
+        rc, bad, _ = S.stage_validate_chunk_schedule(dict(cfg, stash_cap=cap - 1), 2, ops)
+        assert rc == S.E_STASH_FULL and ops[bad][0] == F
+    assert S.stage_validate_chunk_schedule(cfg, 1, ops)[0] == S.E_INVAL            # chunk index out of range
+    rng = np.random.default_rng(100 * cap + enforce)
+    seen = set()
+    for _ in range(3000):
+        n = int(rng.integers(1, 12))
+        seq = [(int(rng.integers(0, 3)), int(rng.integers(0, 3)), -1, int(rng.integers(0, 2))) for _ in range(n)]
+        got = S.stage_validate_chunk_schedule(cfg, 2, seq)
+        want = ref_validate_chunks(seq, 2, 3, cap, enforce)
+        assert got == want, (seq, got, want)
+        seen.add(want[0])
+    assert seen >= {S.E_ORDER, S.E_STASH_FULL} or cap > 2
