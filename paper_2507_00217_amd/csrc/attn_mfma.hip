@@ -18,10 +18,14 @@
 //                 heads of the group and their query tiles in a fixed order
 // both recompute P = exp(S - lse) from the forward's log-sum-exp.
 //
-// On this chip plain VALU instructions do not overlap with MFMAs of the same wavefront (v_exp_f32 does), and at
-// head_dim 128 the softmax arithmetic is ~5 VALU instructions per MFMA, so the kernels keep that arithmetic
-// minimal (scale folded into the exponent's fma, first MFMA of a chain takes C = 0 as an inline constant, output
-// rescale skipped when no row maximum moved) and dispatch the heaviest causal tiles first.
+// Measured on this chip: plain vector instructions do not overlap with MFMAs of the same wavefront (an interleaved
+// stream runs slower than the two parts back to back; v_exp_f32 is the exception), but those of another wavefront on
+// the same SIMD do, each MFMA costing that other wavefront about nine issue cycles.  So forward and dQ run two
+// wavefronts per SIMD, keep the softmax arithmetic minimal (scale folded into the exponent's fma, first MFMA of a
+// chain takes C = 0 as an inline constant, output rescale skipped when no row maximum moved, row sums two at a time
+// with the bf16 dot instruction, masks as one compare per element against a per-tile bound, absolute LDS addresses
+// so that a fragment read is one register plus an immediate) and read LDS fragments a few MFMAs ahead of their use.
+// The heaviest causal tiles are dispatched first.
 #include "common.h"
 
 #include <utility>
@@ -112,11 +116,14 @@ template <int HD>
 struct FragOff {
   unsigned ro[HD / 16];
   unsigned co[HD / 32][2];
-  __device__ __forceinline__ void init(int lane) {
+  // `lds`: the workgroup's LDS base; the offsets are absolute LDS addresses, so a read's address is one register
+  // plus an immediate
+  __device__ __forceinline__ void init(int lane, lds_char* lds) {
     using G = Geo<HD>;
+    const unsigned base = (unsigned)(size_t)lds;
     const int r = lane & 31, hf = lane >> 5;
 #pragma unroll
-    for (int ks = 0; ks < G::NKK; ++ks) ro[ks] = (unsigned)(r * G::ROWB + (((2 * ks + hf) ^ G::swz(r)) << 4));
+    for (int ks = 0; ks < G::NKK; ++ks) ro[ks] = base + (unsigned)(r * G::ROWB + (((2 * ks + hf) ^ G::swz(r)) << 4));
     const int g = lane >> 4, li = lane & 15;
 #pragma unroll
     for (int hb = 0; hb < G::NHB; ++hb)
@@ -124,7 +131,7 @@ struct FragOff {
       for (int u = 0; u < 2; ++u) {
         const int row = (g >> 1) * 4 + (li >> 2) + 8 * u;
         const int piece = hb * 4 + (g & 1) * 2 + ((li & 3) >> 1);
-        co[hb][u] = (unsigned)(row * G::ROWB + ((piece ^ G::swz(row)) << 4) + (li & 1) * 8);
+        co[hb][u] = base + (unsigned)(row * G::ROWB + ((piece ^ G::swz(row)) << 4) + (li & 1) * 8);
       }
   }
   __device__ __forceinline__ void hop(int bytes) {
@@ -136,14 +143,14 @@ struct FragOff {
 };
 template <int HD>
 __device__ __forceinline__ bf16x8 frag_rows(lds_char* lds, const FragOff<HD>& f, int tile_off, int rb, int ks) {
-  return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(lds + f.ro[ks] + (tile_off + rb * Geo<HD>::ROWB));
+  return *(__attribute__((address_space(3))) const bf16x8*)(size_t)(f.ro[ks] + (unsigned)(tile_off + rb * Geo<HD>::ROWB));
 }
 template <int HD>
 __device__ __forceinline__ bf16x8 frag_cols_tr(lds_char* lds, const FragOff<HD>& f, int tile_off, int r0, int hb) {
   typedef s16x4 __attribute__((address_space(3))) * lds_p;
   union { struct { s16x4 a, b; } s; bf16x8 v; } u;
-  u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(lds + f.co[hb][0] + (tile_off + r0 * Geo<HD>::ROWB)));
-  u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(lds + f.co[hb][1] + (tile_off + r0 * Geo<HD>::ROWB)));
+  u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(size_t)(f.co[hb][0] + (unsigned)(tile_off + r0 * Geo<HD>::ROWB)));
+  u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(size_t)(f.co[hb][1] + (unsigned)(tile_off + r0 * Geo<HD>::ROWB)));
   return u.v;
 }
 // rows-type operand straight from global memory (kept in registers for the whole kernel); rows >= nrows read as zero
@@ -163,6 +170,19 @@ __device__ __forceinline__ bf16x8 pack8(const float* v) {
   return r;
 }
 __device__ __forceinline__ float xhalf(float v) { return __shfl_xor(v, 32, 64); }
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// acc + sum of the 8 elements of v (v_dot2c_f32_bf16 against (1, 1): exact products, fp32 accumulation)
+__device__ __forceinline__ float dot_ones(bf16x8 v, float acc) {
+  bf16x2 one;
+  one[0] = (bf16)1.f; one[1] = (bf16)1.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    bf16x2 pr;
+    pr[0] = v[2 * i]; pr[1] = v[2 * i + 1];
+    acc = __builtin_amdgcn_fdot2_f32_bf16(pr, one, acc, false);
+  }
+  return acc;
+}
 __device__ __forceinline__ void zero(f32x16& a) {
 #pragma unroll
   for (int e = 0; e < 16; ++e) a[e] = 0.f;
@@ -185,6 +205,95 @@ constexpr int FWD_THREADS = 512;
 constexpr int FWD_BQ = (FWD_THREADS / 64) * 32;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; -inf -> 0
+
+#define SCHED_FENCE __builtin_amdgcn_sched_barrier(0)
+// One key tile of the forward for one wavefront (32 queries x 64 keys).  LDS fragment reads run ahead of the MFMAs
+// that consume them (K fragments three k-steps ahead; the first V^T fragments are fetched before the softmax
+// arithmetic and land while it runs), so a wavefront does not sit out one LDS round trip per MFMA.
+template <int HD, int BUF>
+__device__ __forceinline__ void fwd_tile(lds_char* lds, const FragOff<HD>& fo, const bf16x8 (&qf)[HD / 16], f32x16 (&o)[HD / 32],
+                                         float& m, float& l, int kv0, int q, int hf, int s, int causal, float sl2, bool need_mask) {
+  using G = Geo<HD>;
+  constexpr int KT = BUF, VT = BUF + G::TILEB, AHEAD = 3, NPV = G::NHB * 4, VA = 4;
+  // S^T[key][query] for two 32-key blocks
+  bf16x8 kf[AHEAD + 1][2];
+#pragma unroll
+  for (int kk = 0; kk < AHEAD; ++kk) { kf[kk][0] = frag_rows<HD>(lds, fo, KT, 0, kk); kf[kk][1] = frag_rows<HD>(lds, fo, KT, 32, kk); }
+  f32x16 sacc[2];
+#pragma unroll
+  for (int kk = 0; kk < G::NKK; ++kk) {
+    if (kk + AHEAD < G::NKK) {
+      kf[(kk + AHEAD) % (AHEAD + 1)][0] = frag_rows<HD>(lds, fo, KT, 0, kk + AHEAD);
+      kf[(kk + AHEAD) % (AHEAD + 1)][1] = frag_rows<HD>(lds, fo, KT, 32, kk + AHEAD);
+    }
+    if (kk == 0) { sacc[0] = mfma0(kf[0][0], qf[0]); sacc[1] = mfma0(kf[0][1], qf[0]); }
+    else {
+      sacc[0] = MFMA(kf[kk % (AHEAD + 1)][0], qf[kk], sacc[0]);
+      sacc[1] = MFMA(kf[kk % (AHEAD + 1)][1], qf[kk], sacc[1]);
+    }
+    SCHED_FENCE;
+  }
+  // step i of the P.V product: head_dim block i % NHB (consecutive MFMAs hit different accumulators), 16-key part i / NHB
+  bf16x8 vf[VA];
+#pragma unroll
+  for (int i = 0; i < VA; ++i) vf[i] = frag_cols_tr<HD>(lds, fo, VT, (i / G::NHB) * 16, i % G::NHB);
+  SCHED_FENCE;
+  // key kv0 + c*32 + acc_row(e, hf) is masked when it is past the end or (causal) after the lane's query: one bound
+  // per tile, compared with compile-time constants; the branch only wraps in-place selects
+  if (need_mask) {
+    const int bound = min(causal ? q - kv0 : 0x7fffffff, s - 1 - kv0) - hf * 4;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (c * 32 + acc_row(e, 0) > bound) sacc[c][e] = -INFINITY;
+  }
+  float mx = -INFINITY;                           // raw scores; sl2 > 0, so the max can be taken before scaling
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[c][e]);
+  float p[2][16];
+  mx = fmaxf(mx, xhalf(mx));
+  const float mn = fmaxf(m, mx * sl2);
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) p[c][e] = fast_exp2(fmaf(sacc[c][e], sl2, -mn));
+  if (__any(mn != m)) {                          // the running max moved for some query of the wavefront
+    const float alpha = fast_exp2(m - mn);
+    l *= alpha;
+#pragma unroll
+    for (int hb = 0; hb < G::NHB; ++hb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[hb][e] *= alpha;
+  }
+  bf16x8 pf[2][2];
+#pragma unroll
+  for (int c = 0; c < 2; ++c) { pf[c][0] = pack8(&p[c][0]); pf[c][1] = pack8(&p[c][8]); }
+  // row sum of the probabilities as rounded for the P.V product (so the weights applied to V sum to one exactly),
+  // two per instruction
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) sum = dot_ones(pf[c][t2], sum);
+  sum += xhalf(sum);
+  l += sum;
+  m = mn;
+  SCHED_FENCE;
+  // O^T[hd][query] += V^T . P^T
+#pragma unroll
+  for (int i = 0; i < NPV; ++i) {
+    const bf16x8 v = vf[i % VA];
+    if (i + VA < NPV) {
+      const int n = i + VA;
+      vf[i % VA] = frag_cols_tr<HD>(lds, fo, VT, (n / G::NHB) * 16, n % G::NHB);
+    }
+    o[i % G::NHB] = MFMA(v, pf[(i / G::NHB) >> 1][(i / G::NHB) & 1], o[i % G::NHB]);
+    SCHED_FENCE;
+  }
+}
 
 template <int HD>
 __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
@@ -228,81 +337,31 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
   float m = -1e30f, l = 0.f;                       // running max (in log2 units, scaled) and sum of the lane's query
 
   FragOff<HD> fo;
-  fo.init(lane);
-  lds_char* fill = lds;                              // buffer the next loads go to (wave-uniform)
-  int hopb = BUFB;
+  fo.init(lane, lds);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
   // Per key tile: compute from one buffer while the next tile lands in the other; then wait for it, one barrier
-  // (every wavefront is done with this buffer), and refill this buffer with the tile after next.
-  for (int t = 0; t < ntiles; ++t) {
+  // (every wavefront is done with this buffer), and refill this buffer with the tile after next.  The loop body
+  // covers two tiles so that the buffer is a compile-time part of every LDS address.
+  auto step = [&](int t, auto buf) {
+    constexpr int BUF = decltype(buf)::value;
     const int kv0 = t * TK;
     const bool active = !a.causal || kv0 <= min(q0w + 32, a.s) - 1;
     if (active && q0w < a.s) {
-      // S^T[key][query] for two 32-key blocks
-      f32x16 sacc[2];
-      sacc[0] = mfma0(frag_rows<HD>(lds, fo, KT, 0, 0), qf[0]);
-      sacc[1] = mfma0(frag_rows<HD>(lds, fo, KT, 32, 0), qf[0]);
-#pragma unroll
-      for (int kk = 1; kk < G::NKK; ++kk) {
-        sacc[0] = MFMA(frag_rows<HD>(lds, fo, KT, 0, kk), qf[kk], sacc[0]);
-        sacc[1] = MFMA(frag_rows<HD>(lds, fo, KT, 32, kk), qf[kk], sacc[1]);
-      }
       const bool need_mask = (a.causal && kv0 + TK - 1 > q0w) || kv0 + TK > a.s;
-      float p[2][16];
-      float mx = -INFINITY;
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float x = sacc[c][e];                       // raw score; sl2 > 0, so the max can be taken before scaling
-          if (need_mask) {
-            const int key = kv0 + c * 32 + acc_row(e, hf);
-            if (key >= a.s || (a.causal && key > q)) x = -INFINITY;
-          }
-          p[c][e] = x;
-          mx = fmaxf(mx, x);
-        }
-      mx = fmaxf(mx, xhalf(mx));
-      const float mn = fmaxf(m, mx * sl2);
-      float sum = 0.f;
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { p[c][e] = fast_exp2(fmaf(p[c][e], sl2, -mn)); sum += p[c][e]; }
-      sum += xhalf(sum);
-      if (__any(mn != m)) {                          // the running max moved for some query of the wavefront
-        const float alpha = fast_exp2(m - mn);
-        l *= alpha;
-#pragma unroll
-        for (int hb = 0; hb < G::NHB; ++hb)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) o[hb][e] *= alpha;
-      }
-      l += sum;
-      m = mn;
-      bf16x8 pf[2][2];
-#pragma unroll
-      for (int c = 0; c < 2; ++c) { pf[c][0] = pack8(&p[c][0]); pf[c][1] = pack8(&p[c][8]); }
-      // O^T[hd][query] += V^T . P^T
-#pragma unroll
-      for (int hb = 0; hb < G::NHB; ++hb)
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int t2 = 0; t2 < 2; ++t2)
-            o[hb] = MFMA(frag_cols_tr<HD>(lds, fo, VT, c * 32 + t2 * 16, hb), pf[c][t2], o[hb]);
+      fwd_tile<HD, BUF>(lds, fo, qf, o, m, l, kv0, q, hf, a.s, a.causal, sl2, need_mask);
     }
     __builtin_amdgcn_s_waitcnt(0);                  // tile t+1 has landed (issued a whole tile ago), own LDS reads done
     __syncthreads();
     if (t + 2 < ntiles) {
-      tile_g2s<HD, FWD_THREADS>(fill + KT, rsK, off, a.ld, kv0 + 2 * TK, wave);
-      tile_g2s<HD, FWD_THREADS>(fill + VT, rsV, off, a.ld, kv0 + 2 * TK, wave);
+      tile_g2s<HD, FWD_THREADS>(lds + BUF + KT, rsK, off, a.ld, kv0 + 2 * TK, wave);
+      tile_g2s<HD, FWD_THREADS>(lds + BUF + VT, rsV, off, a.ld, kv0 + 2 * TK, wave);
     }
-    fo.hop(hopb);
-    fill += hopb;
-    hopb = -hopb;
+  };
+  for (int t = 0; t < ntiles; t += 2) {
+    step(t, std::integral_constant<int, 0>{});
+    if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, BUFB>{});
   }
 
   if (q < a.s) {
@@ -346,6 +405,61 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(AttnArgs a) {
     const int64_t row = item / a.h; const int j = (int)(item % a.h);
     const int64_t ib = row / a.s, i = row % a.s;
     a.delta[(ib * a.h + j) * a.s + i] = acc;
+  }
+}
+
+// One 32-key block of the dQ pass for one wavefront (32 queries), fragment reads running ahead of the MFMAs like
+// in the forward.
+template <int HD, int BUF>
+__device__ __forceinline__ void dq_block(lds_char* lds, const FragOff<HD>& fo, const bf16x8 (&qf)[HD / 16], const bf16x8 (&dof)[HD / 16],
+                                         f32x16 (&dq)[HD / 32], int c, int kv0, int q, int hf, int s, int causal, float sl2,
+                                         float lse2, float dl, bool need_mask) {
+  using G = Geo<HD>;
+  constexpr int KT = BUF, VT = BUF + G::TILEB, AHEAD = 3, NDQ = G::NHB * 2, VA = 4;
+  bf16x8 kf[AHEAD + 1][2];                                          // [ring slot][K rows, V rows]
+#pragma unroll
+  for (int kk = 0; kk < AHEAD; ++kk) { kf[kk][0] = frag_rows<HD>(lds, fo, KT, c * 32, kk); kf[kk][1] = frag_rows<HD>(lds, fo, VT, c * 32, kk); }
+  f32x16 sacc, pacc;
+#pragma unroll
+  for (int kk = 0; kk < G::NKK; ++kk) {
+    if (kk + AHEAD < G::NKK) {
+      kf[(kk + AHEAD) % (AHEAD + 1)][0] = frag_rows<HD>(lds, fo, KT, c * 32, kk + AHEAD);
+      kf[(kk + AHEAD) % (AHEAD + 1)][1] = frag_rows<HD>(lds, fo, VT, c * 32, kk + AHEAD);
+    }
+    if (kk == 0) { sacc = mfma0(kf[0][0], qf[0]); pacc = mfma0(kf[0][1], dof[0]); }          // S^T = K . Q^T, dP^T = V . dO^T
+    else {
+      sacc = MFMA(kf[kk % (AHEAD + 1)][0], qf[kk], sacc);
+      pacc = MFMA(kf[kk % (AHEAD + 1)][1], dof[kk], pacc);
+    }
+    SCHED_FENCE;
+  }
+  // step i of dQ^T[hd][query] += K^T . dS^T: head_dim block i % NHB, 16-key half i / NHB
+  bf16x8 tf[VA];
+#pragma unroll
+  for (int i = 0; i < VA; ++i) tf[i] = frag_cols_tr<HD>(lds, fo, KT, c * 32 + (i / G::NHB) * 16, i % G::NHB);
+  SCHED_FENCE;
+  float ds[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) ds[e] = fast_exp2(fmaf(sacc[e], sl2, -lse2));
+  if (need_mask) {                                                  // one bound per block against compile-time constants
+    const int bound = min(causal ? q - kv0 : 0x7fffffff, s - 1 - kv0) - hf * 4 - c * 32;
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+      if (acc_row(e, 0) > bound) ds[e] = 0.f;
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) ds[e] *= pacc[e] - dl;
+  const bf16x8 dsf[2] = {pack8(&ds[0]), pack8(&ds[8])};
+  SCHED_FENCE;
+#pragma unroll
+  for (int i = 0; i < NDQ; ++i) {
+    const bf16x8 v = tf[i % VA];
+    if (i + VA < NDQ) {
+      const int n = i + VA;
+      tf[i % VA] = frag_cols_tr<HD>(lds, fo, KT, c * 32 + (n / G::NHB) * 16, n % G::NHB);
+    }
+    dq[i % G::NHB] = MFMA(v, dsf[i / G::NHB], dq[i % G::NHB]);
+    SCHED_FENCE;
   }
 }
 
@@ -402,13 +516,13 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
   for (int hb = 0; hb < G::NHB; ++hb) zero(dq[hb]);
 
   FragOff<HD> fo;
-  fo.init(lane);
-  lds_char* fill = lds;
-  int hopb = BUFB;
+  fo.init(lane, lds);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
-  for (int t = 0; t < ntiles; ++t) {
+  // two tiles per loop body, so that the buffer is a compile-time part of every LDS address
+  auto step = [&](int t, auto buf) {
+    constexpr int BUF = decltype(buf)::value;
     const int kv0 = t * TK;
     const bool active = !a.causal || kv0 <= min(q0w + 32, a.s) - 1;
     if (active && q0w < a.s) {
@@ -416,41 +530,19 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         if (a.causal && kv0 + c * 32 > q0w + 31) continue;          // the whole 32-key block is in the future
-        f32x16 sacc = mfma0(frag_rows<HD>(lds, fo, KT, c * 32, 0), qf[0]);             // S^T  = K . Q^T
-        f32x16 pacc = mfma0(frag_rows<HD>(lds, fo, VT, c * 32, 0), dof[0]);            // dP^T = V . dO^T
-#pragma unroll
-        for (int kk = 1; kk < G::NKK; ++kk) {
-          sacc = MFMA(frag_rows<HD>(lds, fo, KT, c * 32, kk), qf[kk], sacc);
-          pacc = MFMA(frag_rows<HD>(lds, fo, VT, c * 32, kk), dof[kk], pacc);
-        }
-        float ds[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float p = fast_exp2(sacc[e] * sl2 - lse2);
-          if (need_mask) {
-            const int key = kv0 + c * 32 + acc_row(e, hf);
-            if (key >= a.s || (a.causal && key > q)) p = 0.f;
-          }
-          ds[e] = p * (pacc[e] - dl);
-        }
-        const bf16x8 ds0 = pack8(&ds[0]), ds1 = pack8(&ds[8]);
-        // dQ^T[hd][query] += K^T . dS^T
-#pragma unroll
-        for (int hb = 0; hb < G::NHB; ++hb) {
-          dq[hb] = MFMA(frag_cols_tr<HD>(lds, fo, KT, c * 32, hb), ds0, dq[hb]);
-          dq[hb] = MFMA(frag_cols_tr<HD>(lds, fo, KT, c * 32 + 16, hb), ds1, dq[hb]);
-        }
+        dq_block<HD, BUF>(lds, fo, qf, dof, dq, c, kv0, q, hf, a.s, a.causal, sl2, lse2, dl, need_mask);
       }
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (t + 2 < ntiles) {
-      tile_g2s<HD, FWD_THREADS>(fill + KT, rsK, off, a.ld, kv0 + 2 * TK, wave);
-      tile_g2s<HD, FWD_THREADS>(fill + VT, rsV, off, a.ld, kv0 + 2 * TK, wave);
+      tile_g2s<HD, FWD_THREADS>(lds + BUF + KT, rsK, off, a.ld, kv0 + 2 * TK, wave);
+      tile_g2s<HD, FWD_THREADS>(lds + BUF + VT, rsV, off, a.ld, kv0 + 2 * TK, wave);
     }
-    fo.hop(hopb);
-    fill += hopb;
-    hopb = -hopb;
+  };
+  for (int t = 0; t < ntiles; t += 2) {
+    step(t, std::integral_constant<int, 0>{});
+    if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, BUFB>{});
   }
 
   if (q < a.s) {
@@ -569,7 +661,7 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
   for (int hb = 0; hb < G::NHB; ++hb) { zero(dk[hb]); zero(dv[hb]); }
 
   FragOff<HD> fo;
-  fo.init(lane);
+  fo.init(lane, lds);
   lds_char* cur = lds;                                // buffer being read, refilled after the barrier (wave-uniform)
   lds_char* ldp = lds + LT + hf * 16;                 // this lane's lse values of the current buffer; delta follows TQ*4 later
   int hopb = BUFB;
