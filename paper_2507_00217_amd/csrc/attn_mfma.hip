@@ -560,34 +560,78 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// dK/dV: one workgroup = 4 wavefronts x 32 keys of one (sequence, kv head), one wavefront per SIMD with the whole
-// register file.  It walks the query heads of its group and their 128-query tiles; per 32-query block the work is
-//   SP   S = Q.K^T, dP = dO.V^T                 16 MFMAs, operands rows of the Q / dO tiles
-//   SOFT P = exp(S - lse), dS = P (dP - delta)  vector arithmetic only
-//   DVK  dV^T += dO^T.P, dK^T += Q^T.dS         16 MFMAs, operands transpose reads of the same tiles
-// and, since vector arithmetic of a wavefront only overlaps with MFMAs issued by that same wavefront earlier, the
-// blocks are software-pipelined: SOFT of block n is written between the MFMAs of SP(n+1) and DVK(n-1).
+// dK/dV: one workgroup = 128 keys of one (sequence, kv head) = 4 key blocks of 32, each worked on by TWO wavefronts
+// that share a SIMD (wavefronts w and w+4):
+//   the dV wavefront:  S = Q.K^T, P = exp(S - lse),                       dV^T += dO^T.P      16 MFMAs per 32 queries
+//   the dK wavefront:  S = Q.K^T, dP = dO.V^T, P, dS = P (dP - delta),    dK^T += Q^T.dS      24 MFMAs per 32 queries
+// S is computed twice, a quarter more MFMAs than one wavefront doing both.  What it buys: each role fits the
+// 256-register budget of two wavefronts per SIMD with every accumulator in ordinary registers, and the vector
+// arithmetic of one role runs under the MFMAs of the other -- a single wavefront cannot overlap the two.
+// The workgroup walks the query heads of its group and their 128-query tiles (Q, dO, lse, delta of a tile go global ->
+// LDS directly, two buffers, one barrier per tile).
 // ---------------------------------------------------------------------------
-constexpr int DKV_THREADS = 256, DKV_TQ = 128, DKV_BKEY = (DKV_THREADS / 64) * 32;
+constexpr int DKV_THREADS = 512, DKV_TQ = 128, DKV_BKEY = 4 * 32;
 
-// compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{})
-template <typename F, int... Is>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) { (f(std::integral_constant<int, Is>{}), ...); }
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
-
-// The slice list of one dK/dV iteration: z < SPS is SP(0); then groups of (SP(n), DVK(n-1)) for n = 1..NB-1; then DVK(NB-1).
-template <int SPS, int DVS, int NB>
-struct DkvList {
-  static constexpr int PER = SPS + DVS, NSL = NB * PER;
-  static constexpr bool is_sp(int z) { return z < SPS || (z < NSL - DVS && (z - SPS) % PER < SPS); }
-  static constexpr int blk(int z) {
-    return z < SPS ? 0 : z >= NSL - DVS ? NB - 1 : (z - SPS) % PER < SPS ? (z - SPS) / PER + 1 : (z - SPS) / PER;
+// acc = sum over head_dim of rows(tile `TILE`, rows rb..rb+31) x bfr (the wavefront's K or V fragments); fragment
+// reads run three k-steps ahead
+template <int HD, int TILE>
+__device__ __forceinline__ void dkv_rows_product(lds_char* lds, const FragOff<HD>& fo, int rb, const bf16x8 (&bfr)[HD / 16], f32x16& acc) {
+  using G = Geo<HD>;
+  constexpr int AHEAD = 3;
+  bf16x8 f[AHEAD + 1];
+#pragma unroll
+  for (int kk = 0; kk < AHEAD; ++kk) f[kk] = frag_rows<HD>(lds, fo, TILE, rb, kk);
+#pragma unroll
+  for (int kk = 0; kk < G::NKK; ++kk) {
+    if (kk + AHEAD < G::NKK) f[(kk + AHEAD) % (AHEAD + 1)] = frag_rows<HD>(lds, fo, TILE, rb, kk + AHEAD);
+    if (kk == 0) acc = mfma0(f[0], bfr[0]);
+    else acc = MFMA(f[kk % (AHEAD + 1)], bfr[kk], acc);
+    SCHED_FENCE;
   }
-  static constexpr int idx(int z) {
-    return z < SPS ? z : z >= NSL - DVS ? z - (NSL - DVS) : (z - SPS) % PER < SPS ? (z - SPS) % PER : (z - SPS) % PER - SPS;
+}
+// the same for two products at once (S from the Q tile, dP from the dO tile), their MFMAs alternating
+template <int HD, int TILE_A, int TILE_B>
+__device__ __forceinline__ void dkv_rows_product2(lds_char* lds, const FragOff<HD>& fo, int rb, const bf16x8 (&bfa)[HD / 16],
+                                                  const bf16x8 (&bfb)[HD / 16], f32x16& acca, f32x16& accb) {
+  using G = Geo<HD>;
+  constexpr int AHEAD = 3;
+  bf16x8 f[AHEAD + 1][2];
+#pragma unroll
+  for (int kk = 0; kk < AHEAD; ++kk) { f[kk][0] = frag_rows<HD>(lds, fo, TILE_A, rb, kk); f[kk][1] = frag_rows<HD>(lds, fo, TILE_B, rb, kk); }
+#pragma unroll
+  for (int kk = 0; kk < G::NKK; ++kk) {
+    if (kk + AHEAD < G::NKK) {
+      f[(kk + AHEAD) % (AHEAD + 1)][0] = frag_rows<HD>(lds, fo, TILE_A, rb, kk + AHEAD);
+      f[(kk + AHEAD) % (AHEAD + 1)][1] = frag_rows<HD>(lds, fo, TILE_B, rb, kk + AHEAD);
+    }
+    if (kk == 0) { acca = mfma0(f[0][0], bfa[0]); accb = mfma0(f[0][1], bfb[0]); }
+    else { acca = MFMA(f[kk % (AHEAD + 1)][0], bfa[kk], acca); accb = MFMA(f[kk % (AHEAD + 1)][1], bfb[kk], accb); }
+    SCHED_FENCE;
   }
-};
+}
+// out[hb]^T += (tile `TILE`, rows rb..rb+31)^T . w, w = the 32 x 32 block of P or dS held as two bf16 fragments;
+// the first transposed fragments must already be in tf[] (read before the vector arithmetic that made w)
+template <int HD, int TILE>
+__device__ __forceinline__ void dkv_tr_read(lds_char* lds, const FragOff<HD>& fo, int rb, bf16x8 (&tf)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) tf[i] = frag_cols_tr<HD>(lds, fo, TILE, rb + (i / Geo<HD>::NHB) * 16, i % Geo<HD>::NHB);
+}
+template <int HD, int TILE>
+__device__ __forceinline__ void dkv_tr_product(lds_char* lds, const FragOff<HD>& fo, int rb, bf16x8 (&tf)[4], const bf16x8 (&w)[2],
+                                               f32x16 (&out)[HD / 32]) {
+  using G = Geo<HD>;
+  constexpr int N = G::NHB * 2, VA = 4;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const bf16x8 v = tf[i % VA];
+    if (i + VA < N) {
+      const int n = i + VA;
+      tf[i % VA] = frag_cols_tr<HD>(lds, fo, TILE, rb + (n / G::NHB) * 16, n % G::NHB);
+    }
+    out[i % G::NHB] = MFMA(v, w[i / G::NHB], out[i % G::NHB]);
+    SCHED_FENCE;
+  }
+}
 
 template <int HD>
 __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int nsplit) {
@@ -599,6 +643,7 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
   lds_char* lds = (lds_char*)smem_raw;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int role = 1 - (wave >> 2), kw = wave & 3;       // role 0: dV, role 1: dK (the longer one, on the older wavefront); kw and kw+4 share a SIMD
   const int kt = blockIdx.y;                              // slow grid index: early key tiles see the most queries, first
   // grid.x = KV heads x splits: this workgroup takes `grp` of the query heads of KV head g, starting at head j0
   const int g = blockIdx.x / nsplit, sp = blockIdx.x % nsplit, ib = blockIdx.z;
@@ -607,7 +652,7 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
   const bf16* dobase = (const bf16*)a.dout + (int64_t)ib * a.s * d;
   const bf16* kp = base + d + g * HD;
   const bf16* vp = base + d + dkv + g * HD;
-  const int k0b = kt * DKV_BKEY, k0w = k0b + wave * 32;
+  const int k0b = kt * DKV_BKEY, k0w = k0b + kw * 32;
   const int key = k0w + (lane & 31);
   const float scale = rsqrtf((float)HD), sl2 = scale * LOG2E;
 
@@ -633,7 +678,6 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
       load_to_lds_b128(rsrc, (unsigned)(size_t)(tile + (j * (NTHR / 64) + wave) * 1024),
                        off0 + (unsigned)((int64_t)(row0 + j * SWEEP) * ld * 2));
   };
-
   // iteration `it` = (query head jj of the group, query tile t): its Q and dO tiles, lse and delta -> buffer at `buf`
   auto fetch = [&](int it, lds_char* buf) {
     const int jj = it / per_head, t = t_first + it % per_head;
@@ -650,157 +694,130 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
   if (niter > 0) fetch(0, lds);
   if (niter > 1) fetch(1, lds + BUFB);
 
-  bf16x8 kf[G::NKK], vf[G::NKK];
-#pragma unroll
-  for (int kk = 0; kk < G::NKK; ++kk) {
-    kf[kk] = frag_rows_global(kp, a.ld, k0w, a.s, kk * 16, lane);
-    vf[kk] = frag_rows_global(vp, a.ld, k0w, a.s, kk * 16, lane);
-  }
-  f32x16 dk[G::NHB], dv[G::NHB];
-#pragma unroll
-  for (int hb = 0; hb < G::NHB; ++hb) { zero(dk[hb]); zero(dv[hb]); }
-
   FragOff<HD> fo;
   fo.init(lane, lds);
   lds_char* cur = lds;                                // buffer being read, refilled after the barrier (wave-uniform)
   lds_char* ldp = lds + LT + hf * 16;                 // this lane's lse values of the current buffer; delta follows TQ*4 later
   int hopb = BUFB;
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
+  typedef __attribute__((address_space(3))) const f32x4* lds_f4;
 
-  // One iteration = NB blocks, run as a fixed list of "slices" of 4 MFMAs whose LDS operands are read one slice
-  // ahead into the other half of fr[][]:
-  //   SP slice  (block, i): k-steps 2i, 2i+1 of S and dP          DVK slice (block, hb): the 4 products into dv[hb], dk[hb]
-  // Order: SP(0) | SP(1) DVK(0) | SP(2) DVK(1) | SP(3) DVK(2) | DVK(3).  The vector arithmetic of block n (4 chunks of 4
-  // elements, packed to bf16 as they complete) is placed among the DVK(n-1) slices, i.e. right after MFMAs that this
-  // wavefront has already issued and that do not depend on it; only block 0's is exposed.
-  constexpr int SPS = G::NKK / 2, DVS = G::NHB;
-  using SL = DkvList<SPS, DVS, NB>;
-  for (int it = 0; it < niter; ++it) {
-    const int q0 = (t_first + it % per_head) * TQ;
-    // Only the diagonal tile needs the causal mask.  Element (e4, e) of a block is query q0 + qc*32 + hf*4 + e4*8 + e;
-    // it is masked when that is < key, i.e. e4*8 + e < lim_qc.
-    const bool diag = a.causal && it % per_head == 0;          // wave-uniform
-    const int lim0 = key - q0 - hf * 4;
-    f32x16 sacc, pacc;
-    bf16x8 pf0[2], df0[2], pf1[2], df1[2];                     // P and dS of even / odd blocks
-    bf16x8 fra[4], frb[4];                                      // operands of even / odd slices
-    float p[8], ds[8];
-
-    auto read_slice = [&](auto zc, bf16x8 (&f)[4]) {
-      constexpr int z = decltype(zc)::value, qc = SL::blk(z), i = SL::idx(z);
-      if constexpr (SL::is_sp(z)) {
-        f[0] = frag_rows<HD>(lds, fo, QT, qc * 32, 2 * i); f[1] = frag_rows<HD>(lds, fo, QT, qc * 32, 2 * i + 1);
-        f[2] = frag_rows<HD>(lds, fo, OT, qc * 32, 2 * i); f[3] = frag_rows<HD>(lds, fo, OT, qc * 32, 2 * i + 1);
-      } else {
-        f[0] = frag_cols_tr<HD>(lds, fo, OT, qc * 32, i); f[1] = frag_cols_tr<HD>(lds, fo, OT, qc * 32 + 16, i);
-        f[2] = frag_cols_tr<HD>(lds, fo, QT, qc * 32, i); f[3] = frag_cols_tr<HD>(lds, fo, QT, qc * 32 + 16, i);
-      }
-    };
-    auto mma_slice = [&](auto zc, const bf16x8 (&f)[4]) {
-      constexpr int z = decltype(zc)::value, qc = SL::blk(z), i = SL::idx(z);
-      if constexpr (SL::is_sp(z)) {                                          // S = Q.K^T, dP = dO.V^T
-        if constexpr (i == 0) { sacc = mfma0(f[0], kf[0]); pacc = mfma0(f[2], vf[0]); }
-        else { sacc = MFMA(f[0], kf[2 * i], sacc); pacc = MFMA(f[2], vf[2 * i], pacc); }
-        sacc = MFMA(f[1], kf[2 * i + 1], sacc); pacc = MFMA(f[3], vf[2 * i + 1], pacc);
-      } else {
-        const bf16x8 (&pfi)[2] = (qc & 1) ? pf1 : pf0;
-        const bf16x8 (&dfi)[2] = (qc & 1) ? df1 : df0;
-        dv[i] = MFMA(f[0], pfi[0], dv[i]);     // dV^T += dO^T . P
-        dk[i] = MFMA(f[2], dfi[0], dk[i]);     // dK^T += Q^T . dS   (alternating: dependent MFMAs are not back to back)
-        dv[i] = MFMA(f[1], pfi[1], dv[i]);
-        dk[i] = MFMA(f[3], dfi[1], dk[i]);
-      }
-    };
-    // elements e4*4 .. +3 of block qc: P and dS, packed to bf16 once a pair of chunks is complete
-    auto chunk = [&](auto qcc, auto e4c) {
-      constexpr int qc = decltype(qcc)::value, e4 = decltype(e4c)::value;
-      typedef __attribute__((address_space(3))) const f32x4* lds_f4;
-      const f32x4 l4 = *reinterpret_cast<lds_f4>(ldp + (qc * 32 + e4 * 8) * 4);
-      const f32x4 d4 = *reinterpret_cast<lds_f4>(ldp + (DT - LT) + (qc * 32 + e4 * 8) * 4);
-      float pv[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) pv[e] = fast_exp2(fmaf(sacc[e4 * 4 + e], sl2, -LOG2E * l4[e]));
-      if (diag) {
-        asm volatile("" ::: "memory");                  // keep this a (wave-uniform) branch: it is rarely taken
-        const int lim = lim0 - qc * 32 - e4 * 8;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pv[e] = e < lim ? 0.f : pv[e];
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { p[(e4 & 1) * 4 + e] = pv[e]; ds[(e4 & 1) * 4 + e] = pv[e] * (pacc[e4 * 4 + e] - d4[e]); }
-      if constexpr (e4 & 1) {
-        if constexpr (qc & 1) { pf1[e4 >> 1] = pack8(p); df1[e4 >> 1] = pack8(ds); }
-        else { pf0[e4 >> 1] = pack8(p); df0[e4 >> 1] = pack8(ds); }
-      }
-    };
-#define FENCE __builtin_amdgcn_sched_barrier(0);
-
-    read_slice(std::integral_constant<int, 0>{}, fra);
-    FENCE
-    static_for<SL::NSL>([&](auto zc) {
-      constexpr int z = decltype(zc)::value;
-      if constexpr (z + 1 < SL::NSL) {
-        if constexpr (z & 1) read_slice(std::integral_constant<int, z + 1>{}, fra);
-        else read_slice(std::integral_constant<int, z + 1>{}, frb);
-      }
-      FENCE
-      if constexpr (z & 1) mma_slice(zc, frb); else mma_slice(zc, fra);
-      if constexpr (SL::is_sp(z)) {
-        FENCE
-        if constexpr (SL::blk(z) == 0 && SL::idx(z) == SPS - 1) {            // block 0: nothing to hide behind
-          static_for<4>([&](auto c) { chunk(std::integral_constant<int, 0>{}, c); });
-          FENCE
-        }
-      } else if constexpr (SL::blk(z) + 1 < NB) {                            // DVK(n-1) slice: chunks of block n
-        static_for<4>([&](auto c) {
-          if constexpr (decltype(c)::value * DVS / 4 == SL::idx(z)) chunk(std::integral_constant<int, SL::blk(z) + 1>{}, c);
-        });
-        // the chunk's instructions go between the slice's four MFMAs, about seven per MFMA
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x002, 4 / DVS * 8, 0);
-        }
-        FENCE
-      } else {
-        FENCE
-      }
-    });
-#undef FENCE
-    __builtin_amdgcn_s_waitcnt(0);                  // iteration it+1's tiles have landed, own LDS reads are done
+  // end of an iteration: the next tiles have landed and every wavefront is done with this buffer; refill it
+  auto turn = [&](int it) {
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (it + 2 < niter) fetch(it + 2, cur);
     fo.hop(hopb);
     cur += hopb;
     ldp += hopb;
     hopb = -hopb;
+  };
+  // P of elements e4*4 .. +3 of query block qc (element e is query q0 + qc*32 + e4*8 + hf*4 + e).  Only the diagonal
+  // tile needs the causal mask: an element is masked when its query is before the lane's key, i.e. e < lim.
+  auto probs4 = [&](const f32x16& sacc, int qc, int e4, bool diag, int lim0, float (&pv)[4]) {
+    const f32x4 l4 = *reinterpret_cast<lds_f4>(ldp + (qc * 32 + e4 * 8) * 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pv[e] = fast_exp2(fmaf(sacc[e4 * 4 + e], sl2, -LOG2E * l4[e]));
+    if (diag) {
+      asm volatile("" ::: "memory");                  // keep this a (wave-uniform) branch: it is rarely taken
+      const int lim = lim0 - qc * 32 - e4 * 8;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pv[e] = e < lim ? 0.f : pv[e];
+    }
+  };
+
+  bf16x8 kf[G::NKK];
+#pragma unroll
+  for (int kk = 0; kk < G::NKK; ++kk) kf[kk] = frag_rows_global(kp, a.ld, k0w, a.s, kk * 16, lane);
+  f32x16 acc[G::NHB];                                  // dV^T or dK^T of the wavefront's 32 keys
+#pragma unroll
+  for (int hb = 0; hb < G::NHB; ++hb) zero(acc[hb]);
+
+  if (role == 0) {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int it = 0; it < niter; ++it) {
+      const int q0 = (t_first + it % per_head) * TQ;
+      const bool diag = a.causal && it % per_head == 0;          // wave-uniform
+      const int lim0 = key - q0 - hf * 4;
+#pragma unroll
+      for (int qc = 0; qc < NB; ++qc) {
+        f32x16 sacc;
+        dkv_rows_product<HD, QT>(lds, fo, qc * 32, kf, sacc);
+        bf16x8 tf[4];
+        dkv_tr_read<HD, OT>(lds, fo, qc * 32, tf);
+        SCHED_FENCE;
+        float p[16];
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          float pv[4];
+          probs4(sacc, qc, e4, diag, lim0, pv);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) p[e4 * 4 + e] = pv[e];
+        }
+        const bf16x8 pf[2] = {pack8(&p[0]), pack8(&p[8])};
+        SCHED_FENCE;
+        dkv_tr_product<HD, OT>(lds, fo, qc * 32, tf, pf, acc);          // dV^T += dO^T . P
+      }
+      turn(it);
+    }
+  } else {
+    bf16x8 vf[G::NKK];
+#pragma unroll
+    for (int kk = 0; kk < G::NKK; ++kk) vf[kk] = frag_rows_global(vp, a.ld, k0w, a.s, kk * 16, lane);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int it = 0; it < niter; ++it) {
+      const int q0 = (t_first + it % per_head) * TQ;
+      const bool diag = a.causal && it % per_head == 0;
+      const int lim0 = key - q0 - hf * 4;
+#pragma unroll
+      for (int qc = 0; qc < NB; ++qc) {
+        f32x16 sacc, pacc;
+        dkv_rows_product2<HD, QT, OT>(lds, fo, qc * 32, kf, vf, sacc, pacc);      // S = Q.K^T, dP = dO.V^T
+        bf16x8 tf[4];
+        dkv_tr_read<HD, QT>(lds, fo, qc * 32, tf);
+        SCHED_FENCE;
+        float ds[16];
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          float pv[4];
+          probs4(sacc, qc, e4, diag, lim0, pv);
+          const f32x4 d4 = *reinterpret_cast<lds_f4>(ldp + (DT - LT) + (qc * 32 + e4 * 8) * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ds[e4 * 4 + e] = pv[e] * (pacc[e4 * 4 + e] - d4[e]);
+        }
+        const bf16x8 df[2] = {pack8(&ds[0]), pack8(&ds[8])};
+        SCHED_FENCE;
+        dkv_tr_product<HD, QT>(lds, fo, qc * 32, tf, df, acc);          // dK^T += Q^T . dS
+      }
+      turn(it);
+    }
   }
 
+  // role 0 holds dV, role 1 holds dK (still to be scaled)
   if (key < a.s) {
+    const float osc = role ? scale : 1.f;
     if (nsplit == 1) {
-      bf16* row = (bf16*)a.dqkv + ((int64_t)ib * a.s + key) * a.ld + d + g * HD;
+      bf16* row = (bf16*)a.dqkv + ((int64_t)ib * a.s + key) * a.ld + d + g * HD + (role ? 0 : dkv);
 #pragma unroll
       for (int hb = 0; hb < G::NHB; ++hb)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          bf16x4 vk, vv;
+          bf16x4 v;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) { vk[e] = (bf16)(dk[hb][q4 * 4 + e] * scale); vv[e] = (bf16)dv[hb][q4 * 4 + e]; }
-          *reinterpret_cast<bf16x4*>(row + hb * 32 + q4 * 8 + hf * 4) = vk;
-          *reinterpret_cast<bf16x4*>(row + dkv + hb * 32 + q4 * 8 + hf * 4) = vv;
+          for (int e = 0; e < 4; ++e) v[e] = (bf16)(acc[hb][q4 * 4 + e] * osc);
+          *reinterpret_cast<bf16x4*>(row + hb * 32 + q4 * 8 + hf * 4) = v;
         }
     } else {      // this split's share, fp32; attn_dkv_reduce_kernel adds the splits up in a fixed order
-      float* row = a.dkv_part + (((int64_t)sp * a.b + ib) * a.s + key) * (2 * dkv) + g * HD;
+      float* row = a.dkv_part + (((int64_t)sp * a.b + ib) * a.s + key) * (2 * dkv) + g * HD + (role ? 0 : dkv);
 #pragma unroll
       for (int hb = 0; hb < G::NHB; ++hb)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 vk, vv;
+          f32x4 v;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) { vk[e] = dk[hb][q4 * 4 + e] * scale; vv[e] = dv[hb][q4 * 4 + e]; }
-          *reinterpret_cast<f32x4*>(row + hb * 32 + q4 * 8 + hf * 4) = vk;
-          *reinterpret_cast<f32x4*>(row + dkv + hb * 32 + q4 * 8 + hf * 4) = vv;
+          for (int e = 0; e < 4; ++e) v[e] = acc[hb][q4 * 4 + e] * osc;
+          *reinterpret_cast<f32x4*>(row + hb * 32 + q4 * 8 + hf * 4) = v;
         }
     }
   }
