@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libstage.so")
-SOURCES = ["stage.hip", "ref_kernels.hip", "bw_kernels.hip", "gemm_mfma.hip", "attn_mfma.hip", "sched.cpp"]
+SOURCES = ["stage.hip", "ref_kernels.hip", "bw_kernels.hip", "gemm_mfma.hip", "attn_mfma.hip", "mfma_ceiling.hip", "sched.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -281,3 +281,20 @@ def test_activation(dtype, act, rows, f):
     torch.cuda.synchronize()
     assert so.max_rel_err(to_np(ad), a_ref) <= KTOL[dtype]
     assert so.max_rel_err(to_np(zd), dz_ref) <= KTOL[dtype]
+
+
+def test_mfma_ceiling_probe():
+    """The measurement aid returns sane figures: the rate and the clock it reports agree (16 MFMAs of 32 cycles per
+    round on each SIMD), random operands do not beat constant ones, and bad arguments are refused."""
+    import torch
+    from paper_2507_00217_amd import stage as S
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    tf_c, mhz_c = S.probe_mfma_ceiling(False, 20000)
+    tf_r, mhz_r = S.probe_mfma_ceiling(True, 20000)
+    assert 0.0 < tf_r <= tf_c * 1.05 and 0.0 < mhz_r <= mhz_c * 1.05, (tf_r, tf_c, mhz_r, mhz_c)
+    for tf, mhz in ((tf_c, mhz_c), (tf_r, mhz_r)):
+        implied_mhz = tf * 1e12 / (cus * 4 * 32768 / 32.0) / 1e6
+        assert abs(implied_mhz - mhz) / mhz < 0.1, (tf, mhz, implied_mhz)
+    out = C.c_double()
+    assert S.lib().stage_probe_mfma_ceiling(1, 0, C.byref(out), C.byref(out), None) == -1
+    assert S.lib().stage_probe_mfma_ceiling(1, 100, None, C.byref(out), None) == -1
