@@ -402,3 +402,42 @@ def test_two_chunks_share_one_stash(defer_w):
     torch.cuda.synchronize()
     assert (c0.stats()["live"], c1.stats()["live"]) == (0, 0)
     c1.close(); c0.close()
+
+
+@pytest.mark.parametrize("name", ["cfg3s", "cfg5s"])
+def test_schedule_replays_from_a_hip_graph(name):
+    """A whole schedule iteration (gradient clearing included) captured into a HIP graph on a side stream replays to
+    the eager result, bit for bit, on every replay -- with eager work and synchronisations between the replays.  The
+    path launches kernels only (no memset or memcpy nodes), and the slot assignment made at capture time is the
+    one every replay uses, because the tracker is back to empty at the end of an iteration."""
+    import torch
+    from paper_2507_00217_amd import stage as S
+    cfg = SMALL[name]
+    params, X, G = inputs(cfg, 9100)
+    ops = synth.make_schedule(cfg)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        st = S.Stage(cfg, stream=side)
+        st.load_weights(params)
+        Xd, Gd = to_dev(X, cfg["dtype"]), to_dev(G, cfg["dtype"])
+        Y, dX = torch.zeros_like(Xd), torch.zeros_like(Xd)
+        st.zero_grads()
+        st.run_schedule(ops, Xd, Gd, Y, dX)            # eager: the reference, and the first launch of every kernel
+        side.synchronize()
+        Yr, dXr, gr = Y.clone(), dX.clone(), st.grads_tensor().clone()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            st.zero_grads()
+            st.run_schedule(ops, Xd, Gd, Y, dX)
+        for rep in range(3):
+            Y.fill_(7.0)
+            dX.fill_(7.0)
+            st.grads_tensor().fill_(3.0)
+            noise = torch.randn(1 << 18, device="cuda").sum().item()      # eager work and a synchronisation in between
+            assert noise == noise
+            graph.replay()
+            side.synchronize()
+            assert torch.equal(Y, Yr) and torch.equal(dX, dXr), rep
+            assert torch.equal(st.grads_tensor(), gr), rep
+        assert st.stats()["live"] == 0
+        st.close()
