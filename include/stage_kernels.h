@@ -10,7 +10,10 @@
  * allocated, work is enqueued on `hip_stream` (hipStream_t, NULL = default
  * stream) without synchronising.  dtype / norm / act codes are the STAGE_*
  * enums of stage.h.  kernel_set: 0 = tuned gfx950 kernels where one exists for
- * the shape, 1 = plain reference HIP kernels.  Return: 0, or STAGE_E_INVAL for
+ * the shape, 1 = plain reference HIP kernels (the attention entries also take 2
+ * and 3: the tuned kernels with the forward / dQ workgroup width fixed at 8 or 4
+ * wavefronts instead of chosen from the shape, so that tests reach both on any
+ * shape).  Return: 0, or STAGE_E_INVAL for
  * a shape the kernel does not take, STAGE_E_HIP for a failed launch.
  */
 #ifndef PAPER_2507_00217_STAGE_KERNELS_H

@@ -201,8 +201,11 @@ __device__ __forceinline__ int acc_row(int e, int hf) { return (e >> 2) * 8 + hf
 // forward: one workgroup = 8 wavefronts x 32 queries of one (sequence, head).  Two wavefronts share a SIMD, so
 // one can run its softmax (VALU, exp) while the other runs MFMAs.
 // ---------------------------------------------------------------------------
-constexpr int FWD_THREADS = 512;
-constexpr int FWD_BQ = (FWD_THREADS / 64) * 32;
+// Forward and dQ come with 8 wavefronts (256 queries) or 4 (128 queries) per workgroup.  Two workgroups of 4 share
+// a CU, so either way two wavefronts sit on each SIMD; 8 read every K/V tile once for twice the queries and are faster
+// when there is plenty of work, 4 give twice as many workgroups and win when 8 would leave CUs idle.
+constexpr int FWD_WIDE = 512, FWD_NARROW = 256;
+constexpr int fwd_bq(int nthr) { return (nthr / 64) * 32; }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; -inf -> 0
 
@@ -295,15 +298,15 @@ __device__ __forceinline__ void fwd_tile(lds_char* lds, const FragOff<HD>& fo, c
   }
 }
 
-template <int HD>
-__global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(AttnArgs a) {
+template <int HD, int FWD_THREADS>
+__global__ __launch_bounds__(FWD_THREADS, 2) void attn_fwd_kernel(AttnArgs a) {
   using G = Geo<HD>;
   constexpr int KT = 0, VT = G::TILEB, BUFB = 2 * G::TILEB;   // two buffers of (K tile, V tile)
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char* lds = (lds_char*)smem_raw;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  constexpr int BQ = FWD_BQ;
+  constexpr int BQ = fwd_bq(FWD_THREADS);
   const int nqt = (a.s + BQ - 1) / BQ;
   const int qt = nqt - 1 - blockIdx.y;              // slow grid index: heaviest (latest) query tiles are dispatched first
   const int j = blockIdx.x, ib = blockIdx.z;
@@ -467,15 +470,15 @@ __device__ __forceinline__ void dq_block(lds_char* lds, const FragOff<HD>& fo, c
 // dQ: one workgroup = 8 wavefronts x 32 queries of one (sequence, head); two wavefronts per SIMD so that one
 // wavefront's exp / dS arithmetic overlaps the other's MFMAs
 // ---------------------------------------------------------------------------
-template <int HD>
-__global__ __launch_bounds__(FWD_THREADS) void attn_dq_kernel(AttnArgs a) {
+template <int HD, int FWD_THREADS>
+__global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a) {
   using G = Geo<HD>;
   constexpr int KT = 0, VT = G::TILEB, BUFB = 2 * G::TILEB;   // two buffers of (K tile, V tile)
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char* lds = (lds_char*)smem_raw;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  constexpr int BQ = FWD_BQ;
+  constexpr int BQ = fwd_bq(FWD_THREADS);
   const int nqt = (a.s + BQ - 1) / BQ;
   const int qt = nqt - 1 - blockIdx.y;              // slow grid index: heaviest query tiles first
   const int j = blockIdx.x, ib = blockIdx.z;
@@ -848,12 +851,37 @@ hipError_t allow_lds(K kern, size_t bytes) {
   return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
+// 4-wavefront workgroups when 8-wavefront ones would number fewer than two per CU
+static bool fwd_narrow(const AttnArgs& a) {
+  if (a.width) return a.width == 2;
+  static int n_cu = 0;
+  if (!n_cu) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+      n_cu = 256;
+  }
+  const int64_t wide = (int64_t)a.b * a.h * ((a.s + fwd_bq(FWD_WIDE) - 1) / fwd_bq(FWD_WIDE));
+  return wide < 2 * (int64_t)n_cu;
+}
+
+template <int HD, int NT>
+hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
+  static bool ready = false;
+  if (!ready) { hipError_t e = allow_lds(attn_fwd_kernel<HD, NT>, fwd_lds<HD>()); if (e != hipSuccess) return e; ready = true; }
+  const int nqt = (a.s + fwd_bq(NT) - 1) / fwd_bq(NT);
+  hipLaunchKernelGGL((attn_fwd_kernel<HD, NT>), dim3(a.h, nqt, a.b), dim3(NT), fwd_lds<HD>(), s, a);
+  return hipGetLastError();
+}
 template <int HD>
 hipError_t fwd_t(const AttnArgs& a, hipStream_t s) {
+  return fwd_narrow(a) ? fwd_launch<HD, FWD_NARROW>(a, s) : fwd_launch<HD, FWD_WIDE>(a, s);
+}
+
+template <int HD, int NT>
+hipError_t dq_launch(const AttnArgs& a, hipStream_t s) {
   static bool ready = false;
-  if (!ready) { hipError_t e = allow_lds(attn_fwd_kernel<HD>, fwd_lds<HD>()); if (e != hipSuccess) return e; ready = true; }
-  const int nqt = (a.s + FWD_BQ - 1) / FWD_BQ;
-  hipLaunchKernelGGL((attn_fwd_kernel<HD>), dim3(a.h, nqt, a.b), dim3(FWD_THREADS), fwd_lds<HD>(), s, a);
+  if (!ready) { hipError_t e = allow_lds(attn_dq_kernel<HD, NT>, fwd_lds<HD>()); if (e != hipSuccess) return e; ready = true; }
+  hipLaunchKernelGGL((attn_dq_kernel<HD, NT>), dim3(a.h, (a.s + fwd_bq(NT) - 1) / fwd_bq(NT), a.b), dim3(NT), fwd_lds<HD>(), s, a);
   return hipGetLastError();
 }
 
@@ -861,14 +889,16 @@ template <int HD>
 hipError_t bwd_t(const AttnArgs& a, hipStream_t s) {
   static bool ready = false;
   if (!ready) {
-    hipError_t e = allow_lds(attn_dq_kernel<HD>, fwd_lds<HD>());
-    if (e == hipSuccess) e = allow_lds(attn_dkv_kernel<HD>, dkv_lds<HD>());
+    hipError_t e = allow_lds(attn_dkv_kernel<HD>, dkv_lds<HD>());
     if (e != hipSuccess) return e;
     ready = true;
   }
   const int64_t lanes = (int64_t)a.b * a.s * a.h * (HD / 8);
   hipLaunchKernelGGL((attn_delta_kernel<HD>), dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, s, a);
-  hipLaunchKernelGGL((attn_dq_kernel<HD>), dim3(a.h, (a.s + FWD_BQ - 1) / FWD_BQ, a.b), dim3(FWD_THREADS), fwd_lds<HD>(), s, a);
+  {
+    const hipError_t e = fwd_narrow(a) ? dq_launch<HD, FWD_NARROW>(a, s) : dq_launch<HD, FWD_WIDE>(a, s);
+    if (e != hipSuccess) return e;
+  }
   const int nsplit = a.dkv_part ? attn_bwd_splits(a.b, a.s, a.h, a.hkv) : 1;
   hipLaunchKernelGGL((attn_dkv_kernel<HD>), dim3(a.hkv * nsplit, (a.s + DKV_BKEY - 1) / DKV_BKEY, a.b), dim3(DKV_THREADS),
                      dkv_lds<HD>(), s, a, nsplit);

@@ -35,6 +35,7 @@ struct AttnArgs {
   const void* dout;              // [b*s, d]
   void* dqkv;                    // [b*s, d + 2*dkv]
   float* delta;                  // [b, h, s] scratch: rowsum(dout * o)
+  int width;                     // forward / dQ workgroups: 0 = chosen from the shape, 1 = 8 wavefronts, 2 = 4 wavefronts
   float* dkv_part;               // scratch for grouped-query attention, attn_bwd_part_bytes() bytes, or null: fp32 partial
                                  // dK | dV of each split of a KV head's query heads, [nsplit][b*s][2*dkv]
 };

@@ -120,11 +120,11 @@ def test_gemm_rejects_bad_arguments():
 ATT_SHAPES = [(1, 128, 4, 4, 64), (2, 200, 5, 5, 128), (1, 392, 8, 1, 128), (1, 448, 4, 2, 128), (1, 1, 2, 1, 64), (1, 640, 2, 2, 64)]
 
 
-@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
-@pytest.mark.parametrize("kernel_set", [0, 1])
+@pytest.mark.parametrize("dtype,kernel_set", [("fp32", 0), ("fp32", 1), ("bf16", 0), ("bf16", 1), ("bf16", 2), ("bf16", 3)])
 @pytest.mark.parametrize("causal", [1, 0])
 @pytest.mark.parametrize("b,s,h,hkv,hd", ATT_SHAPES)
 def test_attention(dtype, kernel_set, causal, b, s, h, hkv, hd):
+    """kernel_set 2 / 3: the tuned kernels with 8- / 4-wavefront forward and dQ workgroups forced (0 picks by shape)."""
     import torch
     d, dkv = h * hd, hkv * hd
     qkv = rnd(synth.normal(2, 1, (b, s, d + 2 * dkv)), dtype)
