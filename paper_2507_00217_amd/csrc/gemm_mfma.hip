@@ -235,8 +235,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   // Software pipeline, one K tile (4 k-steps of 16) per trip, fragments double-buffered in registers:
   //   S0  read frags k1 | MFMA k0            S2  read frags k3 | MFMA k2
   //   S1  read frags k2 | MFMA k1            -- wait for tile t+1 to have landed; barrier --
-  //                                          S3  read frags k0 of tile t+1 | issue loads of tile t+2 into the buffer
-  //                                              just vacated | MFMA k3
+  //                                          S3  MFMA k3, and after each MFMA one fragment of k0 of tile t+1 and one
+  //                                              load of tile t+2 into the buffer just vacated
   // At the barrier only tile t+1's loads are outstanding, hence vmcnt(0).
   constexpr int NREADS = (AKC ? 4 : 8) + (BKC ? TN : 2 * TN);   // LDS read instructions per k-step
   constexpr int NMFMA = 4 * TN;                                 // MFMAs per k-step
@@ -280,9 +280,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int x = 0; x < 4; ++x) { pa[x] += hop; pb[x] += hop; }
-    LOAD_FRAGS(0, 0)
-    // one load after every MFMA of this stage (the fences pin the order; the LDS reads above go first); nothing is
-    // fetched past the last K tile
+    // after every MFMA of this stage: one fragment of the next tile's first k-step (while there are any) and one
+    // tile load; the fences pin the order.  Right after the barrier every wavefront wants the LDS at once: with all
+    // of a wavefront's fragment reads ahead of its MFMAs the matrix core waits for the LDS queue.  Nothing is
+    // fetched past the last K tile.
     const bool more = kt + 2 < nk;      // wave-uniform: a scalar branch around each load, none around an MFMA
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -290,7 +291,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
       for (int j = 0; j < TN; ++j) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        const int n = i * TN + j;         // 4*TN MFMAs, 2*CH == 4*TN loads
+        const int n = i * TN + j;         // 4*TN MFMAs, 2*CH == 4*TN loads, 4 + TN fragments
+        if (n < 4) fa[0][n] = frag<AKC>(pa, n, 0);
+        else if (n < 4 + TN) fb[0][n - 4] = frag<BKC>(pb, n - 4, 0);
+        __builtin_amdgcn_sched_barrier(0);
         if (more) {
           if (n < CH) g2s_one<AKC, WAVES, CH>(fill, rsA, offa, g.lda, ld_k, wave, n);
           else g2s_one<BKC, WAVES, CH>(fill + TILE_BYTES, rsB, offb, g.ldb, ld_k, wave, n - CH);
