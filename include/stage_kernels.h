@@ -10,10 +10,12 @@
  * allocated, work is enqueued on `hip_stream` (hipStream_t, NULL = default
  * stream) without synchronising.  dtype / norm / act codes are the STAGE_*
  * enums of stage.h.  kernel_set: 0 = tuned gfx950 kernels where one exists for
- * the shape, 1 = plain reference HIP kernels (the attention entries also take 2
- * and 3: the tuned kernels with the forward / dQ workgroup width fixed at 8 or 4
- * wavefronts instead of chosen from the shape, so that tests reach both on any
- * shape).  Return: 0, or STAGE_E_INVAL for
+ * the shape, 1 = plain reference HIP kernels.  stage_kernel_gemm and the
+ * attention entries also take 2 and 3: the tuned kernels with a choice they
+ * normally make from the shape fixed, so that tests reach both variants on any
+ * shape -- GEMM: 2 = full 256 x 256 tiles only, 3 = half-height tiles only;
+ * attention: 2 / 3 = forward and dQ workgroups of 8 / 4 wavefronts.
+ * Return: 0, or STAGE_E_INVAL for
  * a shape the kernel does not take, STAGE_E_HIP for a failed launch.
  */
 #ifndef PAPER_2507_00217_STAGE_KERNELS_H

@@ -94,7 +94,9 @@ hipError_t rope_apply(DType dt, void* x, int64_t ld, int64_t rows, int s, int nh
 
 // tuned gfx950 kernels (bf16 MFMA)
 bool gemm_mfma_supported(const GemmArgs& g);
-hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s);
+// tile_shape: 0 = full 256 x 256 tiles, half-height ones for a thin last round or a small product; 1 = full tiles only;
+// 2 = half-height tiles only (1 and 2 exist so that tests reach both on any shape)
+hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s, int tile_shape = 0);
 // several weight-gradient (TN, fp32-accumulating) products in one launch of persistent workgroups; each may reduce
 // over nseg operand pairs in turn, pair s at (A + seg_delta[s] bytes, B + seg_delta[s] bytes), seg_delta[0] = 0
 constexpr int GEMM_MAX_SEG = 8;

@@ -61,9 +61,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, un
 // Per-thread global byte offsets at k = 0 of the pieces it fetches: load j of wavefront w fills slots
 // (j*8 + w)*64 .. +63, lane l the l-th of them.  Rows past the end of the matrix fall outside the buffer's range
 // by themselves or are redirected to OOB, which stores zeros.
+// (a [row][k] tile may have any multiple of 8 rows: WAVES * 64 * CH pieces; a [k][row] tile always has 256 rows)
 template <bool KC, int WAVES, int CH>
 __device__ __forceinline__ void tile_offsets(unsigned (&off)[CH], int64_t ld, int row0, int rows, int wave, int lane) {
-  static_assert(WAVES * 64 * CH == TILE_SLOTS, "every 16-byte piece of the tile has one owner");
+  static_assert(KC || WAVES * 64 * CH == TILE_SLOTS, "every 16-byte piece of the tile has one owner");
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
     const int s = (j * WAVES + wave) * 64 + lane;
@@ -154,10 +155,16 @@ __device__ __forceinline__ bf16x8 frag(lds_char* const (&pt)[4], int b, int ks) 
 // seg_delta[s] bytes (seg_delta[0] == 0): C (+)= sum_s A_s . B_s with the K tiles taken in order s = 0, 1, ...  One
 // pass over K then does the work of nseg launches with a single read-modify-write of C, and -- fp32 accumulators
 // written to and read back from fp32 memory unchanged -- gives the same bits as those launches one after another.
-template <bool AKC, bool BKC, int EPI, int TN>
+// WR = rows of 128 in the tile: 2 -> 256 x 256 (wave grid 2 x WGN), 1 -> 128 x 256 (wave grid 1 x WGN, half the
+// wavefronts; A must be a [row][k] operand).  The half-height tile exists for the work a grid of full tiles would
+// leave to a fraction of the CUs: the last, partly filled round of a product, and products with few tiles.
+template <bool AKC, bool BKC, int EPI, int TN, int WR = 2>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds_char* smem, int nseg = 1,
                                           const int64_t* seg_delta = nullptr) {
-  constexpr int WGN = 8 / TN, WAVES = 2 * WGN, CH = TILE_SLOTS / (WAVES * 64);   // wave grid 2 x WGN
+  static_assert(WR == 2 || (WR == 1 && AKC), "the half-height tile takes a [row][k] A operand");
+  constexpr int WGN = 8 / TN, WAVES = WR * WGN;
+  constexpr int BMV = WR * 128, A_BYTES = BMV * BK * 2;                            // A tile: BMV rows
+  constexpr int CHA = (A_BYTES / 16) / (WAVES * 64), CHB = TILE_SLOTS / (WAVES * 64); // loads per thread and K tile
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / WGN) * 128, wn = (wave % WGN) * (TN * 32);
@@ -177,19 +184,19 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
       rsB = raw_rsrc((const char*)g.B + seg_delta[ld_seg], bytesB);
     }
   };
-  unsigned offa[CH], offb[CH];
-  tile_offsets<AKC, WAVES, CH>(offa, g.lda, m0, g.M, wave, lane);
-  tile_offsets<BKC, WAVES, CH>(offb, g.ldb, n0, g.N, wave, lane);
+  unsigned offa[CHA], offb[CHB];
+  tile_offsets<AKC, WAVES, CHA>(offa, g.lda, m0, g.M, wave, lane);
+  tile_offsets<BKC, WAVES, CHB>(offb, g.ldb, n0, g.N, wave, lane);
 
-  // LDS map: buffer u at byte u * 2 * TILE_BYTES, A tile first, then B tile
-  constexpr int BUF_BYTES = 2 * TILE_BYTES;
+  // LDS map: buffer u at byte u * BUF_BYTES, A tile first, then B tile
+  constexpr int BUF_BYTES = A_BYTES + TILE_BYTES;
   const int nk = ((g.K + BK - 1) / BK) * nseg;
-  g2s<AKC, WAVES, CH>(smem, rsA, offa, g.lda, 0, wave);
-  g2s<BKC, WAVES, CH>(smem + TILE_BYTES, rsB, offb, g.ldb, 0, wave);
+  g2s<AKC, WAVES, CHA>(smem, rsA, offa, g.lda, 0, wave);
+  g2s<BKC, WAVES, CHB>(smem + A_BYTES, rsB, offb, g.ldb, 0, wave);
   advance();
   if (nk > 1) {
-    g2s<AKC, WAVES, CH>(smem + BUF_BYTES, rsA, offa, g.lda, ld_k, wave);
-    g2s<BKC, WAVES, CH>(smem + BUF_BYTES + TILE_BYTES, rsB, offb, g.ldb, ld_k, wave);
+    g2s<AKC, WAVES, CHA>(smem + BUF_BYTES, rsA, offa, g.lda, ld_k, wave);
+    g2s<BKC, WAVES, CHB>(smem + BUF_BYTES + A_BYTES, rsB, offb, g.ldb, ld_k, wave);
     advance();
   }
 
@@ -227,7 +234,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     frag_offsets<AKC>(ada, wm, lane);
     frag_offsets<BKC>(adb, wn, lane);
 #pragma unroll
-    for (int x = 0; x < 4; ++x) { pa[x] = smem + ada[x]; pb[x] = smem + TILE_BYTES + adb[x]; }
+    for (int x = 0; x < 4; ++x) { pa[x] = smem + ada[x]; pb[x] = smem + A_BYTES + adb[x]; }
   }
   lds_char* fill = smem;      // buffer that the loads issued in this trip fill (wave-uniform)
   int hop = BUF_BYTES;
@@ -291,13 +298,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
       for (int j = 0; j < TN; ++j) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        const int n = i * TN + j;         // 4*TN MFMAs, 2*CH == 4*TN loads, 4 + TN fragments
+        const int n = i * TN + j;         // 4*TN MFMAs, 4 + TN fragments, CHA + CHB <= 8*TN loads
         if (n < 4) fa[0][n] = frag<AKC>(pa, n, 0);
         else if (n < 4 + TN) fb[0][n - 4] = frag<BKC>(pb, n - 4, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (more) {
-          if (n < CH) g2s_one<AKC, WAVES, CH>(fill, rsA, offa, g.lda, ld_k, wave, n);
-          else g2s_one<BKC, WAVES, CH>(fill + TILE_BYTES, rsB, offb, g.ldb, ld_k, wave, n - CH);
+#pragma unroll
+          for (int l = n; l < CHA + CHB; l += 4 * TN) {
+            if (l < CHA) g2s_one<AKC, WAVES, CHA>(fill, rsA, offa, g.lda, ld_k, wave, l);
+            else g2s_one<BKC, WAVES, CHB>(fill + A_BYTES, rsB, offb, g.ldb, ld_k, wave, l - CHA);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -336,8 +346,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     __syncthreads();
     const int p = lane & 31, n = n0 + p * 8;
 #pragma unroll
-    for (int t = 0; t < BM / WAVES / 2; ++t) {
-      const int r = wave * (BM / WAVES) + 2 * t + (lane >> 5), m = m0 + r;
+    for (int t = 0; t < BMV / WAVES / 2; ++t) {
+      const int r = wave * (BMV / WAVES) + 2 * t + (lane >> 5), m = m0 + r;
       const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4));
       if (m < g.M && n < g.N) *reinterpret_cast<u32x4*>((bf16*)g.C + (int64_t)m * g.ldc + n) = v;   // N % 8 == 0
     }
@@ -391,21 +401,22 @@ __device__ __forceinline__ void tile_of(int idx, int tiles_m, int tiles_n, int& 
   tile_n = (idx % in_group) / gsz;
 }
 
-// one workgroup per tile
-template <bool AKC, bool BKC, int EPI, int TN>
-__global__ __launch_bounds__(1024 / TN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+// one workgroup per tile: workgroup `bid` takes the full tile number first + bid of the walk order (WR == 2), or the
+// upper (even bid) / lower (odd bid) 128 rows of full tile number first + bid / 2 (WR == 1)
+template <bool AKC, bool BKC, int EPI, int TN, int WR>
+__global__ __launch_bounds__(WR * 512 / TN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n, int first) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give XCD x the
   // x-th contiguous band of the tile sequence.
   int bid = blockIdx.x;
-  const int nb = tiles_m * tiles_n;
+  const int nb = gridDim.x;
   {
     const int per = nb >> 3, main = per << 3;
     if (bid < main) bid = (bid & 7) * per + (bid >> 3);
   }
   int tile_m, tile_n;
-  tile_of(bid, tiles_m, tiles_n, tile_m, tile_n);
-  gemm_tile<AKC, BKC, EPI, TN>(g, tile_m * BM, tile_n * BN, (lds_char*)smem_raw);
+  tile_of(first + (WR == 2 ? bid : bid >> 1), tiles_m, tiles_n, tile_m, tile_n);
+  gemm_tile<AKC, BKC, EPI, TN, WR>(g, tile_m * BM + (WR == 2 ? 0 : (bid & 1) * 128), tile_n * BN, (lds_char*)smem_raw);
 }
 
 // Several weight-gradient products C_p += A_p^T . B_p in one launch of persistent workgroups.  Each workgroup
@@ -444,19 +455,50 @@ __global__ __launch_bounds__(1024 / TN) void gemm_wgrad_group_kernel(GemmGroup g
 // (the narrower ones ahead on forward and input-gradient products, the wider ones on some weight-gradient ones).
 constexpr int WAVE_COLS = 2;
 
-template <bool AKC, bool BKC, int EPI>
-hipError_t launch(const GemmArgs& g, hipStream_t s) {
-  constexpr int THREADS = 1024 / WAVE_COLS;
+int cu_count() {
+  static int n_cu = 0;
+  if (!n_cu) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    n_cu = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+               ? prop.multiProcessorCount : 256;
+  }
+  return n_cu;
+}
+
+template <bool AKC, bool BKC, int EPI, int WR>
+hipError_t launch_tiles(const GemmArgs& g, hipStream_t s, int tiles_m, int tiles_n, int first, int n_wg) {
+  constexpr size_t LDS = (size_t)2 * (WR * 128 * BK * 2 + TILE_BYTES);
   static bool attr_set = false;
-  auto kern = gemm_mfma_kernel<AKC, BKC, EPI, WAVE_COLS>;
+  auto kern = gemm_mfma_kernel<AKC, BKC, EPI, WAVE_COLS, WR>;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(THREADS), LDS_BYTES, s, g, tiles_m, tiles_n);
+  hipLaunchKernelGGL(kern, dim3(n_wg), dim3(WR * 512 / WAVE_COLS), LDS, s, g, tiles_m, tiles_n, first);
   return hipGetLastError();
+}
+
+// Full tiles for every complete round of one tile per CU; what is left over -- a last round that would keep at most
+// half of the CUs busy, or a whole product with that few tiles -- goes out as twice as many half-height tiles, which
+// take about half as long each.  `shape`: 0 = this rule, 1 = full tiles only, 2 = half-height tiles only.
+template <bool AKC, bool BKC, int EPI>
+hipError_t launch(const GemmArgs& g, hipStream_t s, int shape) {
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN, total = tiles_m * tiles_n;
+  int n_half = 0;                         // full tiles at the end of the walk order that are split in two
+  if constexpr (AKC) {
+    const int n_cu = cu_count(), tail = total % n_cu;
+    n_half = shape == 2 ? total : shape == 1 ? 0 : (2 * tail <= n_cu ? tail : 0);
+  }
+  if (total > n_half) {
+    hipError_t e = launch_tiles<AKC, BKC, EPI, 2>(g, s, tiles_m, tiles_n, 0, total - n_half);
+    if (e != hipSuccess) return e;
+  }
+  if constexpr (AKC) {
+    if (n_half) return launch_tiles<AKC, BKC, EPI, 1>(g, s, tiles_m, tiles_n, total - n_half, 2 * n_half);
+  }
+  return hipSuccess;
 }
 
 }  // namespace
@@ -479,11 +521,11 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   return false;
 }
 
-hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s) {
+hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s, int tile_shape) {
   switch (g.mode) {
-    case GEMM_NN: return (g.R || g.c_f32) ? launch<true, false, EPI_RESID>(g, s) : launch<true, false, EPI_STORE>(g, s);
-    case GEMM_NT: return launch<true, true, EPI_STORE>(g, s);
-    case GEMM_TN: return launch<false, false, EPI_ACC32>(g, s);
+    case GEMM_NN: return (g.R || g.c_f32) ? launch<true, false, EPI_RESID>(g, s, tile_shape) : launch<true, false, EPI_STORE>(g, s, tile_shape);
+    case GEMM_NT: return launch<true, true, EPI_STORE>(g, s, tile_shape);
+    case GEMM_TN: return launch<false, false, EPI_ACC32>(g, s, tile_shape);
   }
   return hipErrorInvalidValue;
 }
@@ -505,13 +547,7 @@ hipError_t gemm_mfma_wgrad_group(const GemmArgs* list, int n, int nseg, const in
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  static int n_cu = 0;
-  if (!n_cu) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-    n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  }
+  const int n_cu = cu_count();
   for (int i0 = 0; i0 < n; i0 += GROUP_MAX) {
     GemmGroup gg;
     gg.n = n - i0 < GROUP_MAX ? n - i0 : GROUP_MAX;

@@ -909,7 +909,8 @@ int stage_kernel_gemm(int dtype, int mode, int M, int N, int K, const void* A, i
   if (!dtype_ok(dtype) || mode < 0 || mode > 2 || M < 0 || N < 0 || K < 0 || !A || !B || !C) return STAGE_E_INVAL;
   if ((mode == GEMM_TN) != (acc_f32 != 0) || (acc_f32 && R)) return STAGE_E_INVAL;
   GemmArgs g{mode, M, N, K, A, lda, B, ldb, C, ldc, R, ldr, acc_f32};
-  if (kernel_set == 0 && dtype == STAGE_DTYPE_BF16 && gemm_mfma_supported(g)) return hip_rc(gemm_mfma(g, (hipStream_t)hip_stream));
+  if (kernel_set != 1 && dtype == STAGE_DTYPE_BF16 && gemm_mfma_supported(g))
+    return hip_rc(gemm_mfma(g, (hipStream_t)hip_stream, kernel_set == 2 ? 1 : kernel_set == 3 ? 2 : 0));
   return hip_rc(gemm_ref((DType)dtype, g, (hipStream_t)hip_stream));
 }
 
