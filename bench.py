@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 # cfg3 iteration: 525 launches for 768 products), from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by the
 # same counters' reading for the plain copy kernel of known size in the same run; summary and commands in
 # profiles/cfg3_schedule_pmc.md.  Only valid for the cfg3 workload with its default schedule.
-MEASURED_GEMM_TRAFFIC_BYTES = {"cfg3": 1370e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {"cfg3": 1298e6}
 
 
 def flops_per_layer_mb(cfg):
