@@ -22,7 +22,9 @@
 // the operands swapped (computes the transposed 32x32 block), which leaves every
 // lane with 4 consecutive columns of one row: 8-byte bf16 / 16-byte fp32 epilogue
 // accesses.  Workgroup ids are remapped so that each XCD (own L2) works on a
-// compact band of tiles.
+// compact band of tiles.  A 128x256 half-height tile (4 wavefronts) takes over
+// where full tiles would keep at most half of the CUs busy: the last round of a
+// product, or a product with few tiles.
 #include "common.h"
 
 namespace stg {
