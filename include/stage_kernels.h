@@ -83,9 +83,12 @@ int stage_kernel_act_bwd(int dtype, int act, int rows, int f, void* z, const voi
 /* Measurement aid (not an operation of the paper): runs nothing but back-to-back bf16 MFMAs on every compute unit for
  * `iters` (1 .. 2^22) rounds of 16 per wavefront and reports the rate reached and the shader clock held meanwhile.
  * random_operands = 0 uses the constant 1.0, != 0 uniform values in [-1, 1): the clock, and with it the rate a kernel
- * can approach on real data, depends on the operands.  Allocates and frees a few KiB of device memory; synchronizes
- * hip_stream.  Returns STAGE_OK, STAGE_E_INVAL (iters out of range, null output) or STAGE_E_HIP. */
-int stage_probe_mfma_ceiling(int random_operands, int iters, double* tflops, double* shader_mhz, void* hip_stream);
+ * can approach on real data, depends on the operands.  scratch_dev: device memory of at least 16 + 2048 * (number of
+ * compute units) bytes, 16-byte aligned (1 MiB covers any gfx950 part); its contents afterwards are meaningless.
+ * Allocates nothing; synchronizes hip_stream.  Returns STAGE_OK, STAGE_E_INVAL (iters out of range, null output,
+ * scratch null, misaligned or too small) or STAGE_E_HIP. */
+int stage_probe_mfma_ceiling(int random_operands, int iters, void* scratch_dev, size_t scratch_bytes, double* tflops,
+                             double* shader_mhz, void* hip_stream);
 
 #ifdef __cplusplus
 }

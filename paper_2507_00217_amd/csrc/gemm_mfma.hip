@@ -457,27 +457,23 @@ __global__ __launch_bounds__(1024 / TN) void gemm_wgrad_group_kernel(GemmGroup g
 // (the narrower ones ahead on forward and input-gradient products, the wider ones on some weight-gradient ones).
 constexpr int WAVE_COLS = 2;
 
+// One-time set-up (CU count, a kernel's LDS limit) sits in function-local statics, whose initialisation the language
+// makes thread-safe: concurrent first calls from several threads run it once.
 int cu_count() {
-  static int n_cu = 0;
-  if (!n_cu) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    n_cu = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
-               ? prop.multiProcessorCount : 256;
-  }
+  static const int n_cu = [] {
+    int dev = 0, n = 0;
+    return (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+  }();
   return n_cu;
 }
 
 template <bool AKC, bool BKC, int EPI, int WR>
 hipError_t launch_tiles(const GemmArgs& g, hipStream_t s, int tiles_m, int tiles_n, int first, int n_wg) {
   constexpr size_t LDS = (size_t)2 * (WR * 128 * BK * 2 + TILE_BYTES);
-  static bool attr_set = false;
   auto kern = gemm_mfma_kernel<AKC, BKC, EPI, WAVE_COLS, WR>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+  if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kern, dim3(n_wg), dim3(WR * 512 / WAVE_COLS), LDS, s, g, tiles_m, tiles_n, first);
   return hipGetLastError();
 }
@@ -542,13 +538,9 @@ bool gemm_mfma_wgrad_group_supported(const GemmArgs* list, int n, int nseg, cons
 }
 
 hipError_t gemm_mfma_wgrad_group(const GemmArgs* list, int n, int nseg, const int64_t* seg_delta, hipStream_t s) {
-  static bool attr_set = false;
   auto kern = gemm_wgrad_group_kernel<WAVE_COLS>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+  if (attr != hipSuccess) return attr;
   const int n_cu = cu_count();
   for (int i0 = 0; i0 < n; i0 += GROUP_MAX) {
     GemmGroup gg;

@@ -50,21 +50,22 @@ __global__ __launch_bounds__(CEIL_THREADS) void mfma_ceiling_kernel(float* out, 
 }  // namespace
 }  // namespace stg
 
-extern "C" int stage_probe_mfma_ceiling(int random_operands, int iters, double* tflops, double* shader_mhz, void* hip_stream) {
+extern "C" int stage_probe_mfma_ceiling(int random_operands, int iters, void* scratch_dev, size_t scratch_bytes, double* tflops,
+                                        double* shader_mhz, void* hip_stream) {
   using namespace stg;
-  if (iters < 1 || iters > (1 << 22) || !tflops || !shader_mhz) return STAGE_E_INVAL;
+  if (iters < 1 || iters > (1 << 22) || !tflops || !shader_mhz || !scratch_dev || ((uintptr_t)scratch_dev & 15)) return STAGE_E_INVAL;
   hipStream_t s = (hipStream_t)hip_stream;
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
     return STAGE_E_HIP;
-  float* out = nullptr;
-  unsigned long long* clocks = nullptr;
+  // scratch: two clock counts, then one float per thread (so that the compiler cannot drop the MFMAs)
+  if (scratch_bytes < 16 + (size_t)cus * CEIL_THREADS * sizeof(float)) return STAGE_E_INVAL;
+  unsigned long long* clocks = (unsigned long long*)scratch_dev;
+  float* out = (float*)((char*)scratch_dev + 16);
   hipEvent_t e0 = nullptr, e1 = nullptr;
   int rc = STAGE_E_HIP;
   float ms = 0.f;
   unsigned long long h[2] = {0, 0};
-  if (hipMalloc(&out, (size_t)cus * CEIL_THREADS * sizeof(float)) != hipSuccess) goto done;
-  if (hipMalloc(&clocks, 2 * sizeof(unsigned long long)) != hipSuccess) goto done;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) goto done;
   hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(cus), dim3(CEIL_THREADS), 0, s, out, clocks, iters / 8 + 1, random_operands);   // warm-up
   if (hipEventRecord(e0, s) != hipSuccess) goto done;
@@ -78,7 +79,5 @@ extern "C" int stage_probe_mfma_ceiling(int random_operands, int iters, double* 
 done:
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
-  if (out) (void)hipFree(out);
-  if (clocks) (void)hipFree(clocks);
   return rc;
 }

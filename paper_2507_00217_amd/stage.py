@@ -94,7 +94,7 @@ def lib() -> C.CDLL:
             "stage_profile_read": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
             "stage_destroy": (None, [vp]),
             "stage_strerror": (C.c_char_p, [C.c_int]),
-            "stage_probe_mfma_ceiling": (C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]),
+            "stage_probe_mfma_ceiling": (C.c_int, [C.c_int, C.c_int, vp, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -106,9 +106,11 @@ def lib() -> C.CDLL:
 def probe_mfma_ceiling(random_operands: bool, iters: int = 100000, stream=None) -> Tuple[float, float]:
     """(TFLOP/s, shader MHz) of back-to-back bf16 MFMAs on every compute unit: the rate this GPU sustains on the
     matrix cores alone, which with random operands is well below the published peak."""
+    import torch
     tf, mhz = C.c_double(), C.c_double()
-    rc = lib().stage_probe_mfma_ceiling(int(bool(random_operands)), iters, C.byref(tf), C.byref(mhz),
-                                        stream.cuda_stream if stream is not None else None)
+    scratch = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    rc = lib().stage_probe_mfma_ceiling(int(bool(random_operands)), iters, scratch.data_ptr(), scratch.numel(), C.byref(tf),
+                                        C.byref(mhz), stream.cuda_stream if stream is not None else None)
     if rc:
         raise StageError(rc, "stage_probe_mfma_ceiling")
     return tf.value, mhz.value

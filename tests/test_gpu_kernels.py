@@ -317,5 +317,8 @@ def test_mfma_ceiling_probe():
         implied_mhz = tf * 1e12 / (cus * 4 * 32768 / 32.0) / 1e6
         assert abs(implied_mhz - mhz) / mhz < 0.1, (tf, mhz, implied_mhz)
     out = C.c_double()
-    assert S.lib().stage_probe_mfma_ceiling(1, 0, C.byref(out), C.byref(out), None) == -1
-    assert S.lib().stage_probe_mfma_ceiling(1, 100, None, C.byref(out), None) == -1
+    scr = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    assert S.lib().stage_probe_mfma_ceiling(1, 0, scr.data_ptr(), scr.numel(), C.byref(out), C.byref(out), None) == -1
+    assert S.lib().stage_probe_mfma_ceiling(1, 100, scr.data_ptr(), scr.numel(), None, C.byref(out), None) == -1
+    assert S.lib().stage_probe_mfma_ceiling(1, 100, None, scr.numel(), C.byref(out), C.byref(out), None) == -1       # no scratch
+    assert S.lib().stage_probe_mfma_ceiling(1, 100, scr.data_ptr(), 4096, C.byref(out), C.byref(out), None) == -1    # too small

@@ -341,3 +341,13 @@ def test_rope_properties():
     one = np.zeros((1, 4, 1, 8)); one[..., 0] = 1.0
     got = so.rope(sh, one)[0, 3, 0]
     assert np.allclose(got[:2], [math.cos(3.0), math.sin(3.0)]) and np.allclose(got[2:], 0.0)
+
+
+def test_max_rel_err_hand_values():
+    """The metric every parity verdict passes through, on values worked by hand: largest absolute difference over the
+    largest absolute reference value of the whole tensor; a zero reference falls back to the largest absolute value."""
+    assert so.max_rel_err([1.0, 2.0, 3.5], [1.0, 2.0, 4.0]) == 0.125            # 0.5 / 4
+    assert so.max_rel_err([[-8.0, 2.0]], [[-8.0, 1.0]]) == 0.125                # the denominator is max |ref| = 8, not 1
+    assert so.max_rel_err([0.25, -0.5], [0.0, 0.0]) == 0.5                      # zero reference: max |got|
+    assert so.max_rel_err([3.0, -4.0], [3.0, -4.0]) == 0.0
+    assert so.max_rel_err(np.float32([1.0, 100.0]), np.float64([2.0, 100.0])) == 0.01   # mixed dtypes compare in fp64

@@ -1,5 +1,6 @@
 """Schedule generator (greedy CrossUDSub) and performance model: pins for the
 CPU oracle, and bit-exact parity of the library's host code with it."""
+import collections
 import itertools
 
 import pytest
@@ -190,6 +191,84 @@ def test_library_matches_oracle_exactly(n_pp, n_mb, n_sub, lat, bw, ml_mul):
         cfg = dict(synth.CONFIGS["cfg1"], n_layers=n_sub * 2, n_microbatches=n_mb, n_sub=n_sub,
                    stash_cap=min(n_mb, ml_mul * n_pp), enforce_mb_order=1)
         assert S.stage_validate_subschedule(cfg, ops)[0] == 0, (s, ops)
+
+
+# ---------------------------------------------------------------------------
+# The same pins applied to the LIBRARY's own output (through the C ABI), so that the host C++ is held by the
+# properties the paper and the definitions fix, not only by agreeing with the Python oracle.
+# ---------------------------------------------------------------------------
+LibSlot = collections.namedtuple("LibSlot", "stage kind mb sub t_start t_end")
+
+
+def lib_greedy(pl):
+    got, mk = L.crosspipe_greedy(pl)
+    return [LibSlot(*g) for g in got], mk
+
+
+@pytest.mark.parametrize("n_pp,n_mb,n_sub", GRID)
+def test_library_zero_delay_uniform_equals_zbh1_closed_form(n_pp, n_mb, n_sub):
+    """Paper section 4.2.4 on crosspipe_greedy's output: ZB-H1's iteration time with negligible communication."""
+    po, (pl, keep) = params(n_pp, n_mb, n_sub)
+    slots, mk = lib_greedy(pl)
+    assert len(slots) == 3 * n_mb * n_sub * n_pp                   # section 4.2.5: one sub-block per loop iteration
+    check_timeline(po, slots)
+    assert abs(mk - (3 * n_mb + (n_pp - 1))) < 1e-9
+    assert abs(mk - max(x.t_end for x in slots)) < 1e-12
+    po2, (pl2, keep2) = params(n_pp, n_mb, n_sub, 1.0, 1.25, 0.75)
+    slots2, mk2 = lib_greedy(pl2)
+    check_timeline(po2, slots2)
+    assert n_mb * 3.0 + (n_pp - 1) * 1.5 - 1e-9 <= mk2 <= (n_mb + n_pp - 1) * 3.0 + 1e-9
+
+
+def test_library_hand_worked_two_stage_example():
+    """golden/sched_two_stage.txt (worked by hand from the selection rules) against crosspipe_greedy."""
+    import os
+    _, (pl, keep) = params(2, 2, 1, ml=2)
+    slots, mk = lib_greedy(pl)
+    got = sorted((x.stage, x.t_start, "FDW"[x.kind], x.mb) for x in slots)
+    want = []
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "sched_two_stage.txt")):
+        if line.strip() and not line.startswith("#"):
+            st, rest = line.split(":")
+            for tok in rest.split():
+                op, t = tok.split("@")
+                want.append((int(st), float(t), op[0], int(op[1:])))
+    assert got == sorted(want) and mk == 7.0
+
+
+@pytest.mark.parametrize("n_pp,n_mb,n_sub", GRID)
+@pytest.mark.parametrize("lat,bw,ml_mul", [(0.0, 0.0, 1), (0.5, 0.0, 1), (2.0, 0.0, 2), (0.0, 1.5, 1), (2.0, 2.0, 1), (0.25, 2.0, 3)])
+def test_library_timeline_is_consistent_and_adapts(n_pp, n_mb, n_sub, lat, bw, ml_mul):
+    """Dependencies, non-overlap, memory limit and sub-block order of crosspipe_greedy's timeline, checked from the
+    definitions; crosspipe_simulate replays that timeline exactly; the 1F1B closed form holds for crosspipe_simulate."""
+    n_dc = 2 if n_pp % 2 == 0 else 1
+    po, (pl, keep) = params(n_pp, n_mb, n_sub, 1.0, 1.1, 0.9, ml=ml_mul * n_pp, n_dc=n_dc, lat=lat, bw=bw)
+    slots, mk = lib_greedy(pl)
+    check_timeline(po, slots)
+    lists = [L.crosspipe_stage_ops([tuple(x) for x in slots], s) for s in range(n_pp)]
+    rc, timed, mk_sim = L.crosspipe_simulate(pl, lists)
+    assert rc == 0 and abs(mk_sim - mk) < 1e-9
+    assert sorted((t[0], t[1], t[2], t[3], round(t[4], 9)) for t in timed) == \
+        sorted((x.stage, x.kind, x.mb, x.sub, round(x.t_start, 9)) for x in slots)
+    check_timeline(po, [LibSlot(*t) for t in timed])
+    # static orders replayed under the same delays are never much better, and clearly worse at large delays
+    _, (pl0, keep0) = params(n_pp, n_mb, n_sub, 1.0, 1.1, 0.9, ml=ml_mul * n_pp)
+    slots0, _ = lib_greedy(pl0)
+    static = L.crosspipe_simulate(pl, [L.crosspipe_stage_ops([tuple(x) for x in slots0], s) for s in range(n_pp)])[2]
+    f1b = L.crosspipe_simulate(pl, synth.pipeline_1f1b(n_pp, n_mb, n_sub))[2]
+    assert mk <= 1.05 * static and mk <= 1.05 * f1b
+    if ml_mul == 1 and n_dc == 2 and n_pp >= 4 and (lat >= 2.0 or bw >= 1.5):
+        assert mk < static - 1.0 and mk < f1b - 1.0
+
+
+@pytest.mark.parametrize("n_pp,n_mb,n_sub", GRID)
+def test_library_simulator_is_the_textbook_pipeline_model(n_pp, n_mb, n_sub):
+    """1F1B with no communication cost runs (n_mb + n_PP - 1)(T_F + T_D) when T_W = 0 -- on crosspipe_simulate."""
+    if n_mb < n_pp:
+        pytest.skip("closed form needs n_mb >= n_pp")
+    po, (pl, keep) = params(n_pp, n_mb, n_sub, 1.0, 2.0, 0.0)
+    rc, timed, mk = L.crosspipe_simulate(pl, synth.pipeline_1f1b(n_pp, n_mb, n_sub))
+    assert rc == 0 and abs(mk - (n_mb + n_pp - 1) * 3.0) < 1e-9
 
 
 def test_library_rejects_bad_arguments():
