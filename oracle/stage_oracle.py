@@ -17,10 +17,33 @@ out in NumPy, in fp64 unless a dtype is passed, with the full s-by-s attention
 matrix materialised and no blocking or fusion.
 
 The paper does not itemise the layer ("Llama-style Transformer layers",
-section 7).  The reading used here: pre-norm decoder layer, no biases, no
-rotary embedding, no dropout, exact-erf GELU, eps = 1e-5, biased variance,
-gradients summed (not averaged) over microbatches, norm-parameter gradients
-produced by B.
+section 7).  The reading used here: pre-norm decoder layer, no dropout,
+exact-erf GELU, eps = 1e-5, biased variance, gradients summed (not averaged)
+over microbatches, norm-parameter gradients produced by B.  Linear biases and
+the rotary embedding are optional (Llama-style layers have no biases; GPT-style
+ones do): a layer has the biases whose keys (bqkv, bo, bin, bout) its parameter
+dict holds, and their gradients -- column sums of the dZ tensors, which B
+produces -- are accumulated by B, like the norm parameters'.
+
+Precision.  The paper trains in bf16 (section 7; Appendix E counts two bytes
+per element).  Two readings of that are implemented, selected by
+Shape.operand_bits:
+  0   exact: every tensor stays in the working dtype (fp64).  This is the plain
+      definition and the reference for fp32 workloads, for every pin below and
+      for bf16 workloads wherever the stated tolerance can be met against it.
+  8   bf16 compute: BOTH OPERANDS OF EVERY MATRIX PRODUCT (the linear maps and
+      their two gradient products, Q K^T, P V and the four products of the
+      attention backward) are rounded to 8 significant bits (bf16, nearest
+      even) and the product is accumulated exactly; everything else -- norms,
+      softmax, activations, residual adds, reductions -- stays exact.  That is
+      the least any engine whose matrix units take bf16 operands must round,
+      and it says nothing about where an implementation stores what.  The
+      softmax exponent multiplies a score's rounding error by the score's
+      magnitude, so for wide layers (logit standard deviation 2-3 with the
+      synthetic N(0, 0.02^2) weights at hidden 4096-8192) this reading and
+      the exact one differ by more than the 2e-2 tolerance at depth; parity of
+      a bf16 engine at such sizes is therefore stated against this reading,
+      and the exact one is reported beside it.
 
     n1 = Norm1(x);  [q|k|v] = n1 Wqkv;  o = Attention(q, k, v)
     x1 = x + o Wo;  n2 = Norm2(x1)
@@ -61,6 +84,8 @@ class Shape:
     rope_theta: float = 0.0   # > 0: rotary position embedding on q and k with this base (Llama-style layers); 0 = none
     hd: int = 0               # width of one head; 0 = hidden / n_heads.  A tensor-parallel share of a layer (the paper's
                               # per-GPU shapes at TP > 1) keeps hidden but has fewer heads, so n_heads * hd < hidden.
+    operand_bits: int = 0     # 0: exact.  n > 0: both operands of every matrix product are rounded to n significant bits
+                              # (8 = bf16) before the product, which is then accumulated exactly (see "Precision" above)
 
     @property
     def head_dim(self) -> int:
@@ -75,9 +100,44 @@ class Shape:
         return self.n_kv_heads * self.head_dim
 
 
+def round_sig(t, bits: int):
+    """t (fp64) rounded to `bits` significant binary digits, ties to even; the exponent range stays fp64's (values of
+    a stage are far from bf16's under- and overflow).  Done on the bit patterns: an fp64 significand has 53 digits,
+    so the low 53 - bits are dropped after adding half of the last kept place (one less when that place is even);
+    a carry out of the significand moves into the exponent field, which is what rounding up to a power of two is."""
+    drop = 53 - bits
+    u = np.array(t, dtype=np.float64).view(np.uint64)             # a copy: the input is left alone
+    u += ((u >> np.uint64(drop)) & np.uint64(1)) + np.uint64((1 << (drop - 1)) - 1)
+    u &= np.uint64(~((1 << drop) - 1) & 0xFFFFFFFFFFFFFFFF)
+    return u.view(np.float64)
+
+
+def _op(sh: "Shape", t):
+    """A matrix-product operand in the precision the reading fixes."""
+    return round_sig(t, sh.operand_bits) if sh.operand_bits else t
+
+
+def _mm(sh: "Shape", a, b):
+    """a @ b with both operands in operand precision, accumulated in the working dtype."""
+    return _op(sh, a) @ _op(sh, b)
+
+
 Params = List[Dict[str, np.ndarray]]
 # per layer: g1, (b1), wqkv [d, d+2*dkv], wo [d, d], g2, (b2),
-#            win [d, f] or [d, 2f] (gate | up), wout [f, d]
+#            win [d, f] or [d, 2f] (gate | up), wout [f, d],
+#            optional linear biases bqkv [d+2*dkv], bo [d], bin [f] or [2f], bout [d]
+BIAS_OF = {"wqkv": "bqkv", "wo": "bo", "win": "bin", "wout": "bout"}
+
+
+def _linear(sh: "Shape", p, w: str, a):
+    """a W (+ b when the layer has that bias)."""
+    y = _mm(sh, a, p[w])
+    return y + p[BIAS_OF[w]] if BIAS_OF[w] in p else y
+
+
+def _bias_grads(p, dz: Dict[str, np.ndarray]) -> Dict[str, np.ndarray]:
+    """db = column sums of the dZ of each linear map that has a bias (dz: weight name -> dZ)."""
+    return {BIAS_OF[w]: _flat(t).sum(axis=0) for w, t in dz.items() if BIAS_OF[w] in p}
 
 
 # --------------------------------------------------------------------------
@@ -103,7 +163,7 @@ def norm_forward(kind: str, x, gamma, beta, eps):
 def head_probs(sh: Shape, qh, kh):
     """softmax_rows(qh kh^T / sqrt(hd) + causal mask) for one head: [s,s]."""
     s, hd = qh.shape
-    S = (qh @ kh.T) * (1.0 / math.sqrt(hd))
+    S = _mm(sh, qh, kh.T) * (1.0 / math.sqrt(hd))
     if sh.causal:
         S = np.where(np.tril(np.ones((s, s), dtype=bool)), S, -np.inf)
     S = S - S.max(axis=-1, keepdims=True)
@@ -120,7 +180,7 @@ def attention_forward(sh: Shape, q, k, v):
     for ib in range(b):
         for j in range(h):
             g = j // group
-            o[ib, :, j, :] = head_probs(sh, q[ib, :, j, :], k[ib, :, g, :]) @ v[ib, :, g, :]
+            o[ib, :, j, :] = _mm(sh, head_probs(sh, q[ib, :, j, :], k[ib, :, g, :]), v[ib, :, g, :])
     return o
 
 
@@ -161,7 +221,7 @@ def layer_forward(sh: Shape, p: Dict[str, np.ndarray], x):
     c = {"x": x}
     n1, c["norm1"] = norm_forward(sh.norm, x, p["g1"], p.get("b1", 0.0), sh.eps)
     c["n1"] = n1
-    qkv = n1 @ p["wqkv"]
+    qkv = _linear(sh, p, "wqkv", n1)
     dq_ = sh.q_dim
     q = rope(sh, qkv[..., :dq_].reshape(b, s, h, hd))
     k = rope(sh, qkv[..., dq_:dq_ + dkv].reshape(b, s, hkv, hd))
@@ -170,11 +230,11 @@ def layer_forward(sh: Shape, p: Dict[str, np.ndarray], x):
     o = attention_forward(sh, q, k, v)
     o = o.reshape(b, s, dq_)
     c["o"] = o
-    x1 = x + o @ p["wo"]
+    x1 = x + _linear(sh, p, "wo", o)
     c["x1"] = x1
     n2, c["norm2"] = norm_forward(sh.norm, x1, p["g2"], p.get("b2", 0.0), sh.eps)
     c["n2"] = n2
-    z = n2 @ p["win"]
+    z = _linear(sh, p, "win", n2)
     c["z"] = z
     if sh.act == "gelu":
         a = gelu(z)
@@ -184,7 +244,7 @@ def layer_forward(sh: Shape, p: Dict[str, np.ndarray], x):
     else:
         raise ValueError(sh.act)
     c["a"] = a
-    y = x1 + a @ p["wout"]
+    y = x1 + _linear(sh, p, "wout", a)
     return y, c
 
 
@@ -223,12 +283,13 @@ def attention_backward(sh: Shape, q, k, v, do):
         for j in range(h):
             g = j // group
             p = head_probs(sh, q[ib, :, j, :], k[ib, :, g, :])
-            doj = do[ib, :, j, :]
-            dv[ib, :, g, :] += p.T @ doj
-            dp = doj @ v[ib, :, g, :].T
+            doj = _op(sh, do[ib, :, j, :])
+            dv[ib, :, g, :] += _op(sh, p).T @ doj
+            dp = doj @ _op(sh, v[ib, :, g, :]).T
             ds = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
-            dq[ib, :, j, :] = (ds @ k[ib, :, g, :]) * scale
-            dk[ib, :, g, :] += (ds.T @ q[ib, :, j, :]) * scale
+            ds_op = _op(sh, ds)                      # operand of both remaining products
+            dq[ib, :, j, :] = (ds_op @ _op(sh, k[ib, :, g, :])) * scale
+            dk[ib, :, g, :] += (ds_op.T @ _op(sh, q[ib, :, j, :])) * scale
     return dq, dk, dv
 
 
@@ -252,35 +313,36 @@ def layer_backward_input(sh: Shape, p, c, dy):
     b, s, d = dy.shape
     dkv = sh.kv_dim
     saved = {"dz_out": dy}
-    da = dy @ p["wout"].T
+    da = _mm(sh, dy, p["wout"].T)
     dz_in = act_backward(sh, c["z"], da)
     saved["dz_in"] = dz_in
-    dn2 = dz_in @ p["win"].T
+    dn2 = _mm(sh, dz_in, p["win"].T)
     dx1_n, dg2, db2 = norm_backward(sh.norm, c["norm2"], p["g2"], dn2)
     dx1 = dy + dx1_n
     saved["dz_o"] = dx1
-    do = dx1 @ p["wo"].T
+    do = _mm(sh, dx1, p["wo"].T)
     dq, dk, dv = attention_backward(sh, c["q"], c["k"], c["v"],
                                     do.reshape(b, s, sh.n_heads, sh.head_dim))
     dq, dk = rope(sh, dq, inverse=True), rope(sh, dk, inverse=True)
     dz_qkv = np.concatenate([dq.reshape(b, s, sh.q_dim), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
     saved["dz_qkv"] = dz_qkv
-    dn1 = dz_qkv @ p["wqkv"].T
+    dn1 = _mm(sh, dz_qkv, p["wqkv"].T)
     dx_n, dg1, db1 = norm_backward(sh.norm, c["norm1"], p["g1"], dn1)
     dx = dx1 + dx_n
     ng = {"g1": dg1, "g2": dg2}
     if sh.norm == "layernorm":
         ng["b1"], ng["b2"] = db1, db2
+    ng.update(_bias_grads(p, {"wout": dy, "win": dz_in, "wo": dx1, "wqkv": dz_qkv}))
     return dx, saved, ng
 
 
 def layer_backward_weight(sh: Shape, c, saved):
     """The W op of one layer: dW = A^T dZ for the four linear maps."""
     return {
-        "wout": _flat(c["a"]).T @ _flat(saved["dz_out"]),
-        "win": _flat(c["n2"]).T @ _flat(saved["dz_in"]),
-        "wo": _flat(c["o"]).T @ _flat(saved["dz_o"]),
-        "wqkv": _flat(c["n1"]).T @ _flat(saved["dz_qkv"]),
+        "wout": _mm(sh, _flat(c["a"]).T, _flat(saved["dz_out"])),
+        "win": _mm(sh, _flat(c["n2"]).T, _flat(saved["dz_in"])),
+        "wo": _mm(sh, _flat(c["o"]).T, _flat(saved["dz_o"])),
+        "wqkv": _mm(sh, _flat(c["n1"]).T, _flat(saved["dz_qkv"])),
     }
 
 
@@ -292,21 +354,29 @@ def layer_backward_full(sh: Shape, p, c, dy):
     dkv = sh.kv_dim
     gr = {}
     A = _flat(c["a"]); G = _flat(dy)
-    gr["wout"] = A.T @ G
-    da = (G @ p["wout"].T).reshape(c["a"].shape)
+    gr["wout"] = _mm(sh, A.T, G)
+    if "bout" in p:
+        gr["bout"] = G.sum(axis=0)
+    da = _mm(sh, G, p["wout"].T).reshape(c["a"].shape)
     dz = act_backward(sh, c["z"], da)
-    gr["win"] = _flat(c["n2"]).T @ _flat(dz)
-    dn2 = dz @ p["win"].T
+    gr["win"] = _mm(sh, _flat(c["n2"]).T, _flat(dz))
+    if "bin" in p:
+        gr["bin"] = _flat(dz).sum(axis=0)
+    dn2 = _mm(sh, dz, p["win"].T)
     t, gr["g2"], db2 = norm_backward(sh.norm, c["norm2"], p["g2"], dn2)
     dx1 = dy + t
-    gr["wo"] = _flat(c["o"]).T @ _flat(dx1)
-    do = dx1 @ p["wo"].T
+    gr["wo"] = _mm(sh, _flat(c["o"]).T, _flat(dx1))
+    if "bo" in p:
+        gr["bo"] = _flat(dx1).sum(axis=0)
+    do = _mm(sh, dx1, p["wo"].T)
     dq, dk, dv = attention_backward(sh, c["q"], c["k"], c["v"],
                                     do.reshape(b, s, sh.n_heads, sh.head_dim))
     dq, dk = rope(sh, dq, inverse=True), rope(sh, dk, inverse=True)
     dqkv = np.concatenate([dq.reshape(b, s, sh.q_dim), dk.reshape(b, s, dkv), dv.reshape(b, s, dkv)], axis=-1)
-    gr["wqkv"] = _flat(c["n1"]).T @ _flat(dqkv)
-    dn1 = dqkv @ p["wqkv"].T
+    gr["wqkv"] = _mm(sh, _flat(c["n1"]).T, _flat(dqkv))
+    if "bqkv" in p:
+        gr["bqkv"] = _flat(dqkv).sum(axis=0)
+    dn1 = _mm(sh, dqkv, p["wqkv"].T)
     t, gr["g1"], db1 = norm_backward(sh.norm, c["norm1"], p["g1"], dn1)
     if sh.norm == "layernorm":
         gr["b1"], gr["b2"] = db1, db2

@@ -127,10 +127,12 @@ def from_bf16_bits(b: np.ndarray) -> np.ndarray:
 
 PARAM_NAMES_LN = ("g1", "b1", "wqkv", "wo", "g2", "b2", "win", "wout")
 PARAM_NAMES_RMS = ("g1", "wqkv", "wo", "g2", "win", "wout")
+BIAS_NAMES = ("bqkv", "bo", "bin", "bout")      # linear biases, present when cfg["bias"] is set (GPT-style layers)
 
 
 def param_names(cfg: dict) -> Tuple[str, ...]:
-    return PARAM_NAMES_LN if cfg["norm"] == "layernorm" else PARAM_NAMES_RMS
+    base = PARAM_NAMES_LN if cfg["norm"] == "layernorm" else PARAM_NAMES_RMS
+    return base + BIAS_NAMES if cfg.get("bias") else base
 
 
 def param_shape(cfg: dict, name: str) -> Tuple[int, ...]:
@@ -139,16 +141,17 @@ def param_shape(cfg: dict, name: str) -> Tuple[int, ...]:
     da, dkv = cfg["n_heads"] * hd, cfg["n_kv_heads"] * hd
     fin = 2 * f if cfg["act"] == "swiglu" else f
     return {"g1": (d,), "b1": (d,), "g2": (d,), "b2": (d,),
-            "wqkv": (d, da + 2 * dkv), "wo": (da, d), "win": (d, fin), "wout": (f, d)}[name]
+            "wqkv": (d, da + 2 * dkv), "wo": (da, d), "win": (d, fin), "wout": (f, d),
+            "bqkv": (da + 2 * dkv,), "bo": (d,), "bin": (fin,), "bout": (d,)}[name]
 
 
 def make_weights(cfg: dict, seed: int) -> List[Dict[str, np.ndarray]]:
-    """Linear weights N(0, 0.02^2); norm scales 1 + N(0, 0.02^2); norm shifts
+    """Linear weights N(0, 0.02^2); norm scales 1 + N(0, 0.02^2); norm shifts and linear biases
     N(0, 0.02^2).  Rounded once to bf16 when cfg['dtype'] == 'bf16'."""
     out = []
     for li in range(cfg["n_layers"]):
         lp = {}
-        for pi, name in enumerate(PARAM_NAMES_LN):
+        for pi, name in enumerate(PARAM_NAMES_LN + BIAS_NAMES):
             if name not in param_names(cfg):
                 continue
             w = normal(seed, 100 * li + pi, param_shape(cfg, name), mean=1.0 if name in ("g1", "g2") else 0.0, std=0.02)

@@ -7,9 +7,11 @@ from paper_2507_00217_amd import synth
 TOL = {"fp32": 1e-4, "bf16": 2e-2}      # max_i |gpu - ref| / max_j |ref|, per tensor
 
 
-def shape_of(cfg):
+def shape_of(cfg, operand_bits=0):
+    """operand_bits = 8: the oracle's bf16-compute reading (both operands of every matrix product rounded to bf16)."""
     return so.Shape(cfg["n_layers"], cfg["hidden"], cfg["n_heads"], cfg["n_kv_heads"], cfg["ffn"],
-                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], bool(cfg.get("causal", True)), hd=cfg.get("head_dim", 0) or 0, rope_theta=float(cfg.get("rope_theta", 0.0) or 0.0))
+                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], bool(cfg.get("causal", True)), hd=cfg.get("head_dim", 0) or 0, rope_theta=float(cfg.get("rope_theta", 0.0) or 0.0),
+                    operand_bits=operand_bits)
 
 
 def to_dev(a, dtype, device="cuda:0"):

@@ -12,26 +12,28 @@ from paper_2507_00217_amd import synth
 F, B, W = so.F, so.B, so.W
 
 
-def tiny_cfg(norm="layernorm", act="gelu", n_kv=2, causal=True, L=2, b=1, n_mb=3, head_dim=0, rope_theta=0.0):
+def tiny_cfg(norm="layernorm", act="gelu", n_kv=2, causal=True, L=2, b=1, n_mb=3, head_dim=0, rope_theta=0.0, bias=0):
     return dict(n_layers=L, hidden=16, n_heads=2, n_kv_heads=n_kv, ffn=32, seq=8, mb_size=b,
                 n_microbatches=n_mb, norm=norm, act=act, dtype="fp32", causal=causal, head_dim=head_dim,
-                rope_theta=rope_theta)
+                rope_theta=rope_theta, bias=bias)
 
 
-def shape_of(cfg):
+def shape_of(cfg, operand_bits=0):
     return so.Shape(cfg["n_layers"], cfg["hidden"], cfg["n_heads"], cfg["n_kv_heads"], cfg["ffn"],
-                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], cfg.get("causal", True), hd=cfg.get("head_dim", 0) or 0, rope_theta=float(cfg.get("rope_theta", 0.0) or 0.0))
+                    cfg["seq"], cfg["mb_size"], cfg["norm"], cfg["act"], cfg.get("causal", True), hd=cfg.get("head_dim", 0) or 0, rope_theta=float(cfg.get("rope_theta", 0.0) or 0.0),
+                    operand_bits=operand_bits)
 
 
-def setup(cfg, seed=11, wstd_boost=10.0):
+def setup(cfg, seed=11, wstd_boost=10.0, operand_bits=0):
     params = synth.make_weights(cfg, seed)
-    # larger linear weights than N(0,0.02) so every path carries signal in fp64 checks
+    # larger linear weights (and biases) than N(0,0.02) so every path carries signal in fp64 checks
     for lp in params:
-        for k in ("wqkv", "wo", "win", "wout"):
-            lp[k] = lp[k].astype(np.float64) * wstd_boost
+        for k in ("wqkv", "wo", "win", "wout") + synth.BIAS_NAMES:
+            if k in lp:
+                lp[k] = lp[k].astype(np.float64) * wstd_boost
     X = synth.make_boundary(cfg, seed + 1).astype(np.float64)
     G = synth.make_boundary(cfg, seed + 2).astype(np.float64)
-    return shape_of(cfg), params, X, G
+    return shape_of(cfg, operand_bits), params, X, G
 
 
 VARIANTS = [("layernorm", "gelu", 2, True), ("rmsnorm", "swiglu", 1, True),
@@ -43,10 +45,11 @@ def loss(sh, params, X, G):
     return sum(float((st.forward(m, X[m]) * G[m]).sum()) for m in range(X.shape[0]))
 
 
-@pytest.mark.parametrize("norm,act,n_kv,causal,rope_theta", [v + (0.0,) for v in VARIANTS] + [("rmsnorm", "swiglu", 1, True, 10000.0),
-                                                                                        ("layernorm", "gelu", 2, False, 30.0)])
-def test_finite_differences(norm, act, n_kv, causal, rope_theta):
-    cfg = tiny_cfg(norm, act, n_kv, causal, n_mb=2, rope_theta=rope_theta)
+@pytest.mark.parametrize("norm,act,n_kv,causal,rope_theta,bias",
+                         [v + (0.0, 0) for v in VARIANTS] + [("rmsnorm", "swiglu", 1, True, 10000.0, 0), ("layernorm", "gelu", 2, False, 30.0, 0),
+                                                             ("layernorm", "gelu", 2, True, 0.0, 1), ("rmsnorm", "swiglu", 1, True, 10000.0, 1)])
+def test_finite_differences(norm, act, n_kv, causal, rope_theta, bias):
+    cfg = tiny_cfg(norm, act, n_kv, causal, n_mb=2, rope_theta=rope_theta, bias=bias)
     sh, params, X, G = setup(cfg)
     st = so.OracleStage(sh, params)
     ops = synth.schedule_1f1b(2, 1)
@@ -75,10 +78,11 @@ def test_finite_differences(norm, act, n_kv, causal, rope_theta):
         assert abs(fd - dX[idx]) <= 1e-6 * max(1.0, abs(fd)), (idx, fd, dX[idx])
 
 
+@pytest.mark.parametrize("operand_bits,bias", [(0, 0), (8, 0), (0, 1), (8, 1)])
 @pytest.mark.parametrize("norm,act,n_kv,causal", VARIANTS)
-def test_b_then_w_equals_fused_backward(norm, act, n_kv, causal):
-    cfg = tiny_cfg(norm, act, n_kv, causal)
-    sh, params, X, G = setup(cfg)
+def test_b_then_w_equals_fused_backward(norm, act, n_kv, causal, operand_bits, bias):
+    cfg = tiny_cfg(norm, act, n_kv, causal, bias=bias)
+    sh, params, X, G = setup(cfg, operand_bits=operand_bits)
     a = so.OracleStage(sh, params)
     b = so.OracleStage(sh, params)
     for m in range(X.shape[0]):
@@ -92,9 +96,10 @@ def test_b_then_w_equals_fused_backward(norm, act, n_kv, causal):
             assert so.max_rel_err(la[k], lb[k]) <= 1e-12, k
 
 
-def test_schedule_order_invariance():
+@pytest.mark.parametrize("operand_bits", [0, 8])
+def test_schedule_order_invariance(operand_bits):
     cfg = tiny_cfg("rmsnorm", "swiglu", 1, n_mb=6)
-    sh, params, X, G = setup(cfg)
+    sh, params, X, G = setup(cfg, operand_bits=operand_bits)
     res = []
     for ops in (synth.schedule_1f1b(6, 2), synth.schedule_w_deferred(6, 2, 3), synth.schedule_w_lag1(6, 2),
                 synth.schedule_greedy(6, 2), synth.schedule_random(6, 3, 42)):
@@ -115,13 +120,14 @@ def test_schedule_order_invariance():
                     assert so.max_rel_err(la[k], lb[k]) <= 1e-12, k
 
 
-def test_sum_over_microbatches_equals_full_batch():
-    cfg = tiny_cfg("layernorm", "gelu", 2, n_mb=4)
-    sh, params, X, G = setup(cfg)
+@pytest.mark.parametrize("operand_bits,bias", [(0, 0), (8, 0), (0, 1)])
+def test_sum_over_microbatches_equals_full_batch(operand_bits, bias):
+    cfg = tiny_cfg("layernorm", "gelu", 2, n_mb=4, bias=bias)
+    sh, params, X, G = setup(cfg, operand_bits=operand_bits)
     st = so.OracleStage(sh, params)
     st.run_schedule(synth.schedule_1f1b(4, 2), X, G)
     big = so.Shape(sh.n_layers, sh.hidden, sh.n_heads, sh.n_kv_heads, sh.ffn, sh.seq, 4 * sh.mb_size,
-                   sh.norm, sh.act, sh.causal)
+                   sh.norm, sh.act, sh.causal, operand_bits=operand_bits)
     sb = so.OracleStage(big, params)
     Yb = sb.forward(0, X.reshape(4, sh.seq, sh.hidden))
     sb.backward_input(0, G.reshape(4, sh.seq, sh.hidden)); sb.backward_weight(0)
@@ -130,18 +136,20 @@ def test_sum_over_microbatches_equals_full_batch():
             assert so.max_rel_err(la[k], lb[k]) <= 1e-12, k
 
 
+@pytest.mark.parametrize("bias", [0, 1])
 @pytest.mark.parametrize("norm,act,n_kv,causal,head_dim,rope_theta",
                          [v + (0, 0.0) for v in VARIANTS] + [("rmsnorm", "swiglu", 1, True, 4, 0.0), ("layernorm", "gelu", 2, True, 12, 0.0),
                                                              ("rmsnorm", "swiglu", 1, True, 0, 10000.0), ("layernorm", "gelu", 2, False, 4, 50.0)])
-def test_against_torch_autograd(norm, act, n_kv, causal, head_dim, rope_theta):
+def test_against_torch_autograd(norm, act, n_kv, causal, head_dim, rope_theta, bias):
     """Second opinion from a library: the same layer stack composed from
     PyTorch CPU primitives, differentiated by autograd, in fp64.  The last two cases have heads that do not tile the
     hidden width (n_heads * head_dim = 8 and 24 against hidden 16), as a tensor-parallel share of a layer has."""
     torch = pytest.importorskip("torch")
-    cfg = tiny_cfg(norm, act, n_kv, causal, b=2, n_mb=2, head_dim=head_dim, rope_theta=rope_theta)
+    cfg = tiny_cfg(norm, act, n_kv, causal, b=2, n_mb=2, head_dim=head_dim, rope_theta=rope_theta, bias=bias)
     sh, params, X, G = setup(cfg)
     st = so.OracleStage(sh, params)
     Y, dX, _ = st.run_schedule(synth.schedule_1f1b(2, 1), X, G)
+    lin = lambda t, p, w, b_: torch.nn.functional.linear(t, p[w].T, p.get(b_))      # t W (+ b): the library's linear layer
 
     tp = [{k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in lp.items()} for lp in params]
     tX = torch.tensor(X, requires_grad=True)
@@ -154,7 +162,7 @@ def test_against_torch_autograd(norm, act, n_kv, causal, head_dim, rope_theta):
 
     def tlayer(x, p):
         bsz, s, _ = x.shape
-        qkv = tnorm(x, p["g1"], p.get("b1")) @ p["wqkv"]
+        qkv = lin(tnorm(x, p["g1"], p.get("b1")), p, "wqkv", "bqkv")
         q = qkv[..., :h * hd].reshape(bsz, s, h, hd).transpose(1, 2)
         k = qkv[..., h * hd:(h + hkv) * hd].reshape(bsz, s, hkv, hd).transpose(1, 2).repeat_interleave(h // hkv, dim=1)
         v = qkv[..., (h + hkv) * hd:].reshape(bsz, s, hkv, hd).transpose(1, 2).repeat_interleave(h // hkv, dim=1)
@@ -164,10 +172,10 @@ def test_against_torch_autograd(norm, act, n_kv, causal, head_dim, rope_theta):
             turn = lambda t: torch.view_as_real(torch.view_as_complex(t.reshape(*t.shape[:-1], hd // 2, 2).contiguous()) * rot).flatten(-2)
             q, k = turn(q), turn(k)
         o = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=causal)
-        x1 = x + o.transpose(1, 2).reshape(bsz, s, h * hd) @ p["wo"]
-        z = tnorm(x1, p["g2"], p.get("b2")) @ p["win"]
+        x1 = x + lin(o.transpose(1, 2).reshape(bsz, s, h * hd), p, "wo", "bo")
+        z = lin(tnorm(x1, p["g2"], p.get("b2")), p, "win", "bin")
         a = torch.nn.functional.gelu(z) if act == "gelu" else torch.nn.functional.silu(z[..., :f]) * z[..., f:]
-        return x1 + a @ p["wout"]
+        return x1 + lin(a, p, "wout", "bout")
 
     total = 0
     for m in range(2):
@@ -351,3 +359,99 @@ def test_max_rel_err_hand_values():
     assert so.max_rel_err([0.25, -0.5], [0.0, 0.0]) == 0.5                      # zero reference: max |got|
     assert so.max_rel_err([3.0, -4.0], [3.0, -4.0]) == 0.0
     assert so.max_rel_err(np.float32([1.0, 100.0]), np.float64([2.0, 100.0])) == 0.01   # mixed dtypes compare in fp64
+
+
+# ---------------------------------------------------------------------------
+# the bf16-compute reading (Shape.operand_bits): both operands of every matrix product rounded, exact accumulation
+# ---------------------------------------------------------------------------
+
+def round_sig_by_definition(t, bits):
+    """x = m 2^e with 0.5 <= |m| < 1  ->  rint(m 2^bits) 2^(e - bits), halves to even: the definition, via frexp."""
+    m, e = np.frexp(np.asarray(t, dtype=np.float64))
+    return np.ldexp(np.rint(np.ldexp(m, bits)), e - bits)
+
+
+def test_round_sig_hand_values_definition_and_library():
+    r = lambda x: float(so.round_sig(np.array([x]), 8)[0])
+    assert r(1.0) == 1.0 and r(0.0) == 0.0 and r(-3.0) == -3.0
+    assert r(1 + 2.0 ** -8) == 1.0                       # half-way, kept digit even: down
+    assert r(1 + 3 * 2.0 ** -8) == 1 + 2.0 ** -6         # half-way, kept digit odd: up
+    assert r(1 + 2.0 ** -8 + 2.0 ** -30) == 1 + 2.0 ** -7    # just above half-way: up
+    assert r(255.5) == 256.0 and r(-255.5) == -256.0     # the carry moves into the exponent
+    assert r(0.1) == 0.10009765625                       # bf16(0.1) = 0x3DCD
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(20000) * np.exp2(rng.integers(-40, 40, 20000))
+    for bits in (8, 11, 24):
+        assert np.array_equal(so.round_sig(x, bits), round_sig_by_definition(x, bits))
+    assert np.array_equal(so.round_sig(so.round_sig(x, 8), 8), so.round_sig(x, 8))      # idempotent
+    x0 = x.copy(); so.round_sig(x, 8); assert np.array_equal(x, x0)                      # input untouched
+    torch = pytest.importorskip("torch")                 # a library's float32 -> bfloat16 conversion on float32 values
+    x32 = x.astype(np.float32)
+    want = torch.from_numpy(x32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(so.round_sig(x32.astype(np.float64), 8), want)
+
+
+def test_operand_rounding_attention_brute_force():
+    """Attention forward and backward under the bf16-compute reading against scalar loops that round every product's
+    operands one by one (one sequence, GQA, causal)."""
+    s, h, hkv, hd = 5, 2, 1, 4
+    sh = so.Shape(1, h * hd, h, hkv, 8, s, 1, operand_bits=8)
+    rng = np.random.default_rng(9)
+    q, k, v, do = (rng.standard_normal((1, s, n, hd)) * 1.7 for n in (h, hkv, hkv, h))
+    r = lambda x: float(round_sig_by_definition(np.array([x]), 8)[0])
+    o = np.zeros((s, h, hd)); dq = np.zeros((s, h, hd)); dk = np.zeros((s, hkv, hd)); dv = np.zeros((s, hkv, hd))
+    for j in range(h):
+        P = np.zeros((s, s))
+        for i in range(s):
+            sc = [sum(r(q[0, i, j, t]) * r(k[0, u, 0, t]) for t in range(hd)) / math.sqrt(hd) for u in range(i + 1)]
+            e = [math.exp(x - max(sc)) for x in sc]
+            for u in range(i + 1):
+                P[i, u] = e[u] / sum(e)
+        for i in range(s):
+            for t in range(hd):
+                o[i, j, t] = sum(r(P[i, u]) * r(v[0, u, 0, t]) for u in range(s))
+        dP = np.array([[sum(r(do[0, i, j, t]) * r(v[0, u, 0, t]) for t in range(hd)) for u in range(s)] for i in range(s)])
+        dS = P * (dP - (dP * P).sum(axis=1, keepdims=True))
+        for u in range(s):
+            for t in range(hd):
+                dv[u, 0, t] += sum(r(P[i, u]) * r(do[0, i, j, t]) for i in range(s))
+                dk[u, 0, t] += sum(r(dS[i, u]) * r(q[0, i, j, t]) for i in range(s)) / math.sqrt(hd)
+        for i in range(s):
+            for t in range(hd):
+                dq[i, j, t] = sum(r(dS[i, u]) * r(k[0, u, 0, t]) for u in range(s)) / math.sqrt(hd)
+    assert so.max_rel_err(so.attention_forward(sh, q, k, v)[0], o) <= 1e-13
+    gq, gk, gv = so.attention_backward(sh, q, k, v, do)
+    assert so.max_rel_err(gq[0], dq) <= 1e-13 and so.max_rel_err(gk[0], dk) <= 1e-13 and so.max_rel_err(gv[0], dv) <= 1e-13
+    # and the rounding matters at this size: the exact reading gives something else
+    assert so.max_rel_err(so.attention_forward(so.Shape(1, h * hd, h, hkv, 8, s, 1), q, k, v)[0], o) > 1e-4
+
+
+def test_operand_rounding_linear_maps_brute_force():
+    """_linear and the two gradient products of a linear map under the bf16-compute reading: every operand element
+    rounded, sums exact -- against scalar loops."""
+    rng = np.random.default_rng(4)
+    sh = so.Shape(1, 8, 1, 1, 8, 3, 1, operand_bits=8)
+    a, w, b, dz = rng.standard_normal((3, 5)), rng.standard_normal((5, 4)), rng.standard_normal(4), rng.standard_normal((3, 4))
+    r = lambda x: float(round_sig_by_definition(np.array([x]), 8)[0])
+    y = np.array([[sum(r(a[i, t]) * r(w[t, n]) for t in range(5)) + b[n] for n in range(4)] for i in range(3)])
+    assert so.max_rel_err(so._linear(sh, {"wo": w, "bo": b}, "wo", a), y) <= 1e-15
+    da = np.array([[sum(r(dz[i, n]) * r(w[t, n]) for n in range(4)) for t in range(5)] for i in range(3)])
+    dw = np.array([[sum(r(a[i, t]) * r(dz[i, n]) for i in range(3)) for n in range(4)] for t in range(5)])
+    assert so.max_rel_err(so._mm(sh, dz, w.T), da) <= 1e-15 and so.max_rel_err(so._mm(sh, a.T, dz), dw) <= 1e-15
+
+
+@pytest.mark.parametrize("norm,act,n_kv", [("layernorm", "gelu", 2), ("rmsnorm", "swiglu", 1)])
+def test_operand_rounding_error_scales_with_the_digits_kept(norm, act, n_kv):
+    """The stage under the operand-rounding reading differs from the exact one by an amount that shrinks like
+    2^-bits (8 -> 12 digits: a factor 16, here within [5, 50]); with 52 digits kept the two agree to rounding error."""
+    cfg = tiny_cfg(norm, act, n_kv, n_mb=2, bias=1)
+    ops = synth.schedule_1f1b(2, 1)
+    sh, params, X, G = setup(cfg, wstd_boost=4.0)
+    ref = so.OracleStage(sh, params); Y0, dX0, _ = ref.run_schedule(ops, X, G)
+    dev = {}
+    for bits in (8, 12, 52):
+        st = so.OracleStage(shape_of(cfg, bits), params)
+        Y, dX, _ = st.run_schedule(ops, X, G)
+        dev[bits] = max([so.max_rel_err(Y, Y0), so.max_rel_err(dX, dX0)] +
+                        [so.max_rel_err(st.grads[l][k], ref.grads[l][k]) for l in range(sh.n_layers) for k in ref.grads[l]])
+    assert 1e-4 < dev[8] < 5e-2 and 5.0 < dev[8] / dev[12] < 50.0 and dev[52] < 1e-12, dev
