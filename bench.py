@@ -27,11 +27,25 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per GEMM launch (average over the forward, input-gradient and grouped weight-gradient launches of one
-# cfg3 iteration: 525 launches for 768 products), from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by the
-# same counters' reading for the plain copy kernel of known size in the same run; summary and commands in
-# profiles/cfg3_schedule_pmc.md.  Only valid for the cfg3 workload with its default schedule.
-MEASURED_GEMM_TRAFFIC_BYTES = {"cfg3": 1298e6}
+
+
+def measured_gemm_traffic(config):
+    """HBM-side bytes per GEMM launch (average over the forward, input-gradient and grouped weight-gradient launches of
+    one iteration of the workload's default schedule), taken from the rocprofv3 --pmc summary
+    profiles/<config>_schedule_pmc.md (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a plain
+    copy kernel of known size).  That file records which GEMM source it was measured with; when the source in the tree
+    is another one the figure is stale and None is returned."""
+    import hashlib
+    import re
+    path = os.path.join(ROOT, "profiles", f"{config}_schedule_pmc.md")
+    src = os.path.join(ROOT, "paper_2507_00217_amd", "csrc", "gemm_mfma.hip")
+    try:
+        text = open(path).read()
+        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    m = re.search(r"gemm_traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)\s*;\s*gemm_mfma\.hip sha256/16\s*=\s*([0-9a-f]{16})", text)
+    return float(m.group(1)) if m and m.group(2) == sha else None
 
 
 def flops_per_layer_mb(cfg):
@@ -79,6 +93,74 @@ def cpu_baseline(cfg, budget_s=30.0):
             "seconds": t3 - t0}
 
 
+def gemm_table(cfg, name, rounds=20):
+    """Every matrix product of one layer of the workload (forward, input gradient, weight gradient) through
+    stage_kernel_gemm, and the same product through torch.matmul (hipBLASLt / rocBLAS) on the same operands, timed
+    alternately after a common warm-up so that both run at the clock the chip settles to under load.  Prints a
+    markdown table; the weight-gradient rows include the library's fp32 read-modify-write of C (torch.matmul writes a
+    bf16 C and accumulates nothing)."""
+    import ctypes as C
+    import torch
+    from paper_2507_00217_amd import stage as S
+    lib = S.lib()
+    vp, i, i64 = C.c_void_p, C.c_int, C.c_int64
+    lib.stage_kernel_gemm.argtypes = [i, i, i, i, i, vp, i64, vp, i64, vp, i64, vp, i64, i, i, vp]
+    d, f, h = cfg["hidden"], cfg["ffn"], cfg["n_heads"]
+    hd = cfg.get("head_dim") or d // h
+    da, dq = h * hd, (h + 2 * cfg["n_kv_heads"]) * hd
+    T = cfg["seq"] * cfg["mb_size"]
+    fin = 2 * f if cfg["act"] == "swiglu" else f
+    lin = (("qkv", d, dq), ("wo", da, d), ("win", d, fin), ("wout", f, d))           # name, in, out
+    shapes = [(0, T, o, k, "F " + n) for n, k, o in lin] + [(1, T, k, o, "B " + n) for n, k, o in lin] + \
+             [(2, k, o, T, "W " + n) for n, k, o in lin]
+    stream = torch.cuda.current_stream().cuda_stream
+    cases = []
+    for mode, M, N, K, label in shapes:
+        a_shape = (K, M) if mode == 2 else (M, K)
+        b_shape = (N, K) if mode == 1 else (K, N)
+        A = torch.randn(a_shape, device="cuda", dtype=torch.bfloat16)
+        B = (torch.randn(b_shape, device="cuda", dtype=torch.bfloat16) * 0.02)
+        Cm = torch.zeros((M, N), device="cuda", dtype=torch.float32 if mode == 2 else torch.bfloat16)
+        At, Bt = (A.t() if mode == 2 else A), (B.t() if mode == 1 else B)
+        out_t = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+
+        def ours(A=A, B=B, Cm=Cm, mode=mode, M=M, N=N, K=K, a_shape=a_shape, b_shape=b_shape):
+            rc = lib.stage_kernel_gemm(1, mode, M, N, K, A.data_ptr(), a_shape[1], B.data_ptr(), b_shape[1], Cm.data_ptr(), N,
+                                       None, 0, int(mode == 2), 0, stream)
+            assert rc == 0
+
+        def theirs(At=At, Bt=Bt, out_t=out_t):
+            torch.matmul(At, Bt, out=out_t)
+        cases.append((label, mode, M, N, K, ours, theirs))
+    t_end = time.perf_counter() + 2.0                      # common warm-up: the clock settles under sustained load
+    while time.perf_counter() < t_end:
+        for c in cases:
+            c[5](); c[6]()
+        torch.cuda.synchronize()
+    rows = []
+    for label, mode, M, N, K, ours, theirs in cases:
+        ms = []
+        for fn in (ours, theirs):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for _ in range(3):
+                fn()
+            e0.record()
+            for _ in range(rounds):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1) / rounds)
+        fl = 2.0 * M * N * K
+        rows.append((label, M, N, K, ms[0], fl / ms[0] / 1e9, ms[1], fl / ms[1] / 1e9))
+    print(f"| product ({name}) | M | N | K | this library ms | TFLOP/s | torch.matmul ms | TFLOP/s | ratio |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for label, M, N, K, m0, t0, m1, t1 in rows:
+        print(f"| {label} | {M} | {N} | {K} | {m0:.3f} | {t0:.0f} | {m1:.3f} | {t1:.0f} | {t0 / t1:.2f} |")
+    s0, s1 = sum(r[4] for r in rows), sum(r[6] for r in rows)
+    fl = sum(2.0 * r[1] * r[2] * r[3] for r in rows)
+    print(f"| all twelve | | | | {s0:.3f} | {fl / s0 / 1e9:.0f} | {s1:.3f} | {fl / s1 / 1e9:.0f} | {s1 / s0:.2f} |")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +169,8 @@ def main():
     ap.add_argument("--config", default="cfg3")
     ap.add_argument("--kernel-set", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-table", action="store_true",
+                    help="instead of the benchmark: time every matrix product of one layer against torch.matmul, print markdown")
     ap.add_argument("--schedule", default=None, help="override the config's schedule (1f1b, w_deferred, w_lag1, greedy)")
     ap.add_argument("--recompute", type=int, default=0, metavar="CAP",
                     help="layer-wise activation recomputation with at most CAP rebuilt stashes (0 = off); the reported "
@@ -101,6 +185,9 @@ def main():
     from paper_2507_00217_amd import synth
 
     cfg = dict(synth.CONFIGS[args.config], enforce_mb_order=1)
+    if args.gemm_table:
+        gemm_table(cfg, args.config)
+        return
     if args.schedule:
         cfg["schedule"] = args.schedule
     if args.recompute:
@@ -175,7 +262,7 @@ def main():
     roofline = {"bound": "mfma" if cfg["dtype"] == "bf16" else "alu", "kernel": "GEMM family: gemm_mfma_kernel (forward, input gradients) + gemm_wgrad_group_kernel (weight gradients), all launches of one iteration",
                 "achieved": round(achieved, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "flops_per_launch": gemm_work / gemm_n, "avg_launch_ms": round(gemm_ms / gemm_n, 5),
-                "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.config) if args.kernel_set == 0 and not args.schedule and not args.recompute else None}
+                "traffic": measured_gemm_traffic(args.config) if args.kernel_set == 0 and not args.schedule and not args.recompute else None}
     stats = st.stats()
     # what the measured block times mean for a pipeline (the paper's performance model, host code): this stage's
     # T_F/T_D/T_W replicated over 8 stages in 2 datacenters, 2 x n_PP microbatches, memory of 1F1B, with latency and

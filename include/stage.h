@@ -69,7 +69,8 @@ enum {
 enum {
   STAGE_P_NORM1_GAMMA = 0, STAGE_P_NORM1_BETA = 1, STAGE_P_WQKV = 2, STAGE_P_WO = 3,
   STAGE_P_NORM2_GAMMA = 4, STAGE_P_NORM2_BETA = 5, STAGE_P_WIN = 6, STAGE_P_WOUT = 7,
-  STAGE_P_COUNT = 8
+  STAGE_P_BQKV = 8, STAGE_P_BO = 9, STAGE_P_BIN = 10, STAGE_P_BOUT = 11,   /* linear biases, present when cfg.bias */
+  STAGE_P_COUNT = 12
 };
 
 /* One op of a per-stage schedule: (type, microbatch) -- the paper's compute-op
@@ -109,6 +110,9 @@ typedef struct {
   float   rope_theta;      /* > 0: rotary position embedding on q and k (Llama-style layers, which is what the paper
                               trains): pairs (2p, 2p+1) of a head turn by position * rope_theta^(-2p / head_dim),
                               position = index in the sequence; 0 = none */
+  int32_t bias;            /* 1: every linear map carries a bias vector (GPT-style layers; Llama-style ones, which the
+                              paper trains, have none): y = x W + b.  The bias gradients -- column sums of the dZ
+                              tensors -- are accumulated by B, like the norm parameters'. */
 } stage_config_t;
 
 typedef struct { size_t weights, grads, stash, workspace; } stage_sizes_t; /* bytes */
@@ -132,8 +136,8 @@ int stage_validate_schedule(const stage_config_t* cfg, const stage_op_t* ops, in
  * offset in both.  Linear weights are stored [in, out] row-major so that
  * forward is A.W:  WQKV [d, d_q+2*d_kv] (columns q | k | v; d_q = h*head_dim),  WO [d_q, d],
  * WIN [d, f] (GELU) or [d, 2f] (SwiGLU, columns gate | up),  WOUT [f, d];
- * norm vectors have rows = 1, cols = d.  A parameter the config does not have
- * (beta under RMSNorm) reports rows = cols = 0. */
+ * norm vectors have rows = 1, cols = d; bias vectors rows = 1, cols = the map's output width.  A parameter the
+ * config does not have (beta under RMSNorm, biases without cfg.bias) reports rows = cols = 0. */
 int stage_param_layout(const stage_config_t* cfg, int layer, int param_id,
                        size_t* offset_elems, int64_t* rows, int64_t* cols);
 
@@ -146,7 +150,7 @@ int stage_init(const stage_config_t* cfg, void* weights_dev, void* grads_dev, vo
 
 /* F(mb): y = layers(x); stashes what B and W need. x_dev, y_dev: [mb_size, seq, hidden]. */
 int stage_forward(stage_t* st, int mb, const void* x_dev, void* y_dev);
-/* B(mb): dx = d<y,dy>/dx; accumulates norm-parameter gradients; keeps the dZ
+/* B(mb): dx = d<y,dy>/dx; accumulates norm-parameter (and bias) gradients; keeps the dZ
  * tensors W needs inside the stash slot. */
 int stage_backward_input(stage_t* st, int mb, const void* dy_dev, void* dx_dev);
 /* W(mb): grads += A^T dZ for the four linear maps of every layer; releases the slot. */
@@ -181,7 +185,9 @@ int stage_run_subschedule(stage_t* st, const stage_subop_t* ops, int n_ops,
  * own -- own weights, gradients and microbatch states -- that shares the stash of the stage it is attached to: slots come
  * from one pool and stash_cap (and recompute_cap) bound the live microbatches of all chunks together.  The chunk's config
  * must give the same slot size and caps as share_with's (in practice: the same shape); it uses share_with's stash and
- * stream; workspace_dev may be share_with's workspace (one stream orders all uses).  Destroy in any order. */
+ * stream.  workspace_dev is a workspace of the chunk's own (stage_query_sizes of ITS config), or share_with's when the
+ * chunk needs no more than that one holds and uses the same rotary table (same seq, head_dim, rope_theta; one stream
+ * orders all uses) -- anything else returns STAGE_E_INVAL.  Destroy in any order. */
 int stage_init_chunk(const stage_config_t* cfg, void* weights_dev, void* grads_dev, void* workspace_dev, stage_t* share_with,
                      stage_t** out);
 /* One op of a per-device schedule over chunks: sub = -1 for a whole op, else the sub-block. */
@@ -198,7 +204,9 @@ int stage_run_chunk_schedule(stage_t* const* chunks, int n_chunks, const stage_c
                              void* const* dx_all_dev);
 
 /* Borrowed pointer to the fp32 gradient buffer (== grads_dev) and its length.
- * After a full iteration it holds the SUM over microbatches of d<Y_m,dY_m>/dtheta. */
+ * After a full iteration it holds the SUM over microbatches of d<Y_m,dY_m>/dtheta.  A microbatch's contribution arrives
+ * in two parts: B adds the norm-parameter (and bias) gradients, W the linear weights', so the buffer is complete for a
+ * microbatch only after its W, and stage_zero_grads belongs between iterations (no microbatch between its B and its W). */
 int stage_grads(stage_t* st, float** grads_dev, size_t* n_elems);
 int stage_zero_grads(stage_t* st);
 

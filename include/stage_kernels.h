@@ -35,6 +35,14 @@ extern "C" {
 int stage_kernel_gemm(int dtype, int mode, int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
                       void* C, int64_t ldc, const void* R, int64_t ldr, int acc_f32, int kernel_set, void* hip_stream);
 
+/* The forward FFN-in product with its activation (paper section 3.1: part of a chunk's F block): Z = A.B with B [K, f]
+ * (GELU) or [K, 2f] (SwiGLU, columns gate | up), and Aout [M, f] = gelu(Z) or silu(Z[:, :f]) * Z[:, f:].  The tuned kernel
+ * forms the activation from the fp32 accumulators in the product's epilogue (one rounding less than reading Z back, and Z
+ * is not re-read); the plain kernels (kernel_set 1, or fp32) run the product and then the activation kernel on the stored
+ * Z, which needs ldz = f or 2f and lda_out = f.  kernel_set 2 / 3 as for stage_kernel_gemm. */
+int stage_kernel_gemm_act(int dtype, int act, int M, int f, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
+                          void* Z, int64_t ldz, void* Aout, int64_t lda_out, int kernel_set, void* hip_stream);
+
 /* n weight-gradient products (mode 2 above) in one call: C_p[M_p,N_p] += A_p^T . B_p for p = 0..n-1, the separately
  * schedulable W block of the paper's Appendix B for several linear maps at once.  All array arguments are HOST arrays of
  * length n (the pointers in A, B, C are device pointers); the C_p must not overlap.  Results are bit-identical to n calls
@@ -75,6 +83,10 @@ int stage_kernel_norm_bwd(int dtype, int norm, int rows, int d, const void* x, c
                           const void* dout, const void* resid, void* dx, float* dgamma, float* dbeta, float* partial,
                           void* hip_stream);
 size_t stage_kernel_norm_partial_bytes(int d);
+/* Gradient of a linear map's bias (layers with biases): dbias[j] += sum over rows of dz[row * ld + j], j < n, fp32, in a
+ * fixed summation order.  n and ld multiples of 16 bytes' worth of elements; scratch: stage_kernel_bias_grad_scratch_bytes(n). */
+size_t stage_kernel_bias_grad_scratch_bytes(int n);
+int stage_kernel_bias_grad(int dtype, int rows, int n, const void* dz, int64_t ld, float* dbias, float* scratch, void* hip_stream);
 
 /* GELU: z [rows, f]; SwiGLU: z [rows, 2f] (gate | up).  a, da: [rows, f].  Backward overwrites z with dz. */
 int stage_kernel_act_fwd(int dtype, int act, int rows, int f, const void* z, void* a, void* hip_stream);

@@ -13,7 +13,8 @@
 // the LDS transpose load ds_read_b64_tr_b16.
 //
 // Backward is split so that no atomics are needed (bit-reproducible gradients):
-//   dQ kernel:    one workgroup per (sequence, head, query tile), loops over key tiles
+//   dQ kernel:    one workgroup per (sequence, head, query tile), loops over key tiles; also forms
+//                 delta = rowsum(dO * O) of its queries and leaves it in the scratch for the second kernel
 //   dK/dV kernel: one workgroup per (sequence, kv head, key tile), loops over the query
 //                 heads of the group and their query tiles in a fixed order
 // both recompute P = exp(S - lse) from the forward's log-sum-exp.
@@ -383,34 +384,6 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_fwd_kernel(AttnArgs a) {
   }
 }
 
-// ---------------------------------------------------------------------------
-// delta[b,h,i] = sum_t dout[i,h,t] * o[i,h,t]; HD/8 lanes per (row, head)
-// ---------------------------------------------------------------------------
-template <int HD>
-__global__ __launch_bounds__(256) void attn_delta_kernel(AttnArgs a) {
-  constexpr int LPR = HD / 8;
-  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t item = gid / LPR;                      // (row, head)
-  const int part = (int)(gid % LPR);
-  const int64_t nitems = (int64_t)a.b * a.s * a.h;
-  float acc = 0.f;
-  if (item < nitems) {
-    const int64_t row = item / a.h; const int j = (int)(item % a.h);
-    const int64_t off = row * a.h * HD + (int64_t)j * HD + part * 8;
-    bf16x8 x = *reinterpret_cast<const bf16x8*>((const bf16*)a.dout + off);
-    bf16x8 y = *reinterpret_cast<const bf16x8*>((const bf16*)a.o + off);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc += (float)x[e] * (float)y[e];
-  }
-#pragma unroll
-  for (int o = LPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-  if (item < nitems && part == 0) {
-    const int64_t row = item / a.h; const int j = (int)(item % a.h);
-    const int64_t ib = row / a.s, i = row % a.s;
-    a.delta[(ib * a.h + j) * a.s + i] = acc;
-  }
-}
-
 // One 32-key block of the dQ pass for one wavefront (32 queries), fragment reads running ahead of the MFMAs like
 // in the forward.
 template <int HD, int BUF>
@@ -509,10 +482,23 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a) {
     qf[kk] = frag_rows_global(qp, a.ld, q0w, a.s, kk * 16, lane);
     dof[kk] = frag_rows_global(dop, d, q0w, a.s, kk * 16, lane);
   }
+  // delta = rowsum(dO * O) of the lane's query, formed here from the dO fragments already in registers: a lane holds 8
+  // of every 16 columns of its row, the lane 32 further on the other 8.  Written out for the dK/dV kernel.
   float lse2 = 1e30f, dl = 0.f;                       // rows past the end: P = 0
+  {
+    const bf16* op = (const bf16*)a.o + (int64_t)ib * a.s * d + j * HD;
+    float part = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < G::NKK; ++kk) {
+      const bf16x8 of = frag_rows_global(op, d, q0w, a.s, kk * 16, lane);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part = fmaf((float)dof[kk][e], (float)of[e], part);
+    }
+    dl = part + xhalf(part);
+  }
   if (q < a.s) {
     lse2 = a.lse[((int64_t)ib * a.h + j) * a.s + q] * LOG2E;
-    dl = a.delta[((int64_t)ib * a.h + j) * a.s + q];
+    if (hf == 0) a.delta[((int64_t)ib * a.h + j) * a.s + q] = dl;
   }
   f32x16 dq[G::NHB];
 #pragma unroll
@@ -893,9 +879,7 @@ hipError_t bwd_t(const AttnArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     ready = true;
   }
-  const int64_t lanes = (int64_t)a.b * a.s * a.h * (HD / 8);
-  hipLaunchKernelGGL((attn_delta_kernel<HD>), dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, s, a);
-  {
+  {      // dQ first: it also leaves delta = rowsum(dO * O) in a.delta for the dK/dV pass
     const hipError_t e = fwd_narrow(a) ? dq_launch<HD, FWD_NARROW>(a, s) : dq_launch<HD, FWD_WIDE>(a, s);
     if (e != hipSuccess) return e;
   }

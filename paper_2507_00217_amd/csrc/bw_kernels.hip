@@ -253,6 +253,64 @@ hipError_t norm_bwd(DType dt, const NormArgs& n, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------
+// Gradient of a linear map's bias: the column sums of its dZ, added to the fp32 accumulator.  Two steps with a fixed
+// summation order (no atomics): BIAS_PARTS row ranges are summed by one workgroup each per 32 x (16 / sizeof(T))
+// columns -- 8 row lanes per column group, combined through LDS in lane order -- then one thread per column adds the
+// parts in order.
+// ---------------------------------------------------------------------------
+constexpr int BIAS_PARTS = 64;
+size_t bias_grad_partial_bytes(int n) { return n > 0 ? (size_t)BIAS_PARTS * n * sizeof(float) : 0; }
+
+template <typename T>
+__global__ __launch_bounds__(256) void bias_grad_partial_kernel(const T* dz, int64_t ld, int rows, int n, float* partial) {
+  constexpr int V = Vec<T>::N;
+  __shared__ float red[8][32 * V];
+  const int cg = threadIdx.x & 31, rl = threadIdx.x >> 5;
+  const int col = (blockIdx.x * 32 + cg) * V;
+  const int per = (rows + BIAS_PARTS - 1) / BIAS_PARTS;
+  const int r0 = blockIdx.y * per, r1 = min(rows, r0 + per);
+  float acc[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) acc[e] = 0.f;
+  if (col < n)
+    for (int r = r0 + rl; r < r1; r += 8) {
+      Vec<T> v = ldv(dz + (int64_t)r * ld + col);
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[e] += to_f32(v.v[e]);
+    }
+#pragma unroll
+  for (int e = 0; e < V; ++e) red[rl][cg * V + e] = acc[e];
+  __syncthreads();
+  if (rl == 0 && col < n) {
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      float s = red[0][cg * V + e];
+#pragma unroll
+      for (int k = 1; k < 8; ++k) s += red[k][cg * V + e];
+      partial[(int64_t)blockIdx.y * n + col + e] = s;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void bias_grad_finalize_kernel(const float* partial, int n, float* dbias) {
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= n) return;
+  float s = partial[col];
+  for (int p = 1; p < BIAS_PARTS; ++p) s += partial[(int64_t)p * n + col];
+  dbias[col] += s;
+}
+
+hipError_t bias_grad(DType dt, const void* dz, int64_t ld, int rows, int n, float* partial, float* dbias, hipStream_t s) {
+  const int V = dt == DT_F32 ? 4 : 8;
+  if (rows < 1 || n < 1 || n % V || ld % V || !dz || !partial || !dbias || ((uintptr_t)dz & 15)) return hipErrorInvalidValue;
+  const dim3 grid((n / V + 31) / 32, BIAS_PARTS);
+  if (dt == DT_F32) hipLaunchKernelGGL((bias_grad_partial_kernel<float>), grid, dim3(256), 0, s, (const float*)dz, ld, rows, n, partial);
+  else hipLaunchKernelGGL((bias_grad_partial_kernel<bf16>), grid, dim3(256), 0, s, (const bf16*)dz, ld, rows, n, partial);
+  hipLaunchKernelGGL(bias_grad_finalize_kernel, dim3((n + 255) / 256), dim3(256), 0, s, partial, n, dbias);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // activations
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); }

@@ -24,6 +24,13 @@ struct GemmArgs {
   int acc_f32;                   // 1: C is fp32 and the product is added to it (C += A^T.B)
   int r_f32;                     // 1: R is fp32 (the fp32 residual stream) instead of the compute dtype
   int c_f32;                     // 1: C is stored as fp32 (no accumulate) instead of the compute dtype
+  // Fused activation (forward FFN-in product only, mode GEMM_NN, no residual): besides C = z the kernel writes
+  // C2 = act(z), computed from the fp32 accumulators, so the activation costs one rounding less and z is not re-read.
+  int act;                       // 0 none; 1 GELU: N = f, C2[m,n] = gelu(z[m,n]); 2 SwiGLU: N = 2f (gate | up),
+                                 // C2[m,j] = silu(z[m,j]) * z[m,f+j], j < f
+  void* C2; int64_t ldc2;        // [M, f] in the compute dtype
+  const void* bias;              // optional bias vector [N] in the compute dtype, added to every row of the product
+                                 // (before the residual / activation); forward products only
 };
 
 struct AttnArgs {
@@ -84,6 +91,9 @@ hipError_t norm_fwd(DType dt, const NormArgs& n, hipStream_t s);
 hipError_t norm_bwd(DType dt, const NormArgs& n, hipStream_t s);
 hipError_t act_fwd(DType dt, const ActArgs& a, hipStream_t s);
 hipError_t act_bwd(DType dt, const ActArgs& a, hipStream_t s);
+// dbias[n] += sum over rows of dz[row, n] (fp32, fixed summation order); partial: bias_grad_partial_bytes(n) bytes
+size_t bias_grad_partial_bytes(int n);
+hipError_t bias_grad(DType dt, const void* dz, int64_t ld, int rows, int n, float* partial, float* dbias, hipStream_t s);
 hipError_t fill_zero_f32(float* p, size_t n, hipStream_t s);
 hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t widen_to_f32(DType dt, float* dst, const void* src, size_t n, hipStream_t s);   // dst[i] = (float)src[i]

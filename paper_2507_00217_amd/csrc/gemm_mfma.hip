@@ -43,7 +43,11 @@ constexpr int TILE_SLOTS = TILE_BYTES / 16;                  // 16-byte pieces: 
 constexpr size_t LDS_BYTES = (size_t)4 * TILE_BYTES;         // A,B x 2 buffers = 128 KiB
 static_assert(BM == BN, "both operand tiles share one geometry");
 
-enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_ACC32 = 2 };
+enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_ACC32 = 2, EPI_GELU = 3, EPI_SWIGLU = 4 };
+// EPI_SWIGLU: a tile covers GLU_BN features j and holds, side by side in 32-column blocks, the gate columns j and
+// the up columns f + j of the product (even blocks gate, odd blocks up), so that a lane's two accumulator blocks are
+// the gate and the up value of the same 32 features and silu(gate) * up is formed in registers.
+constexpr int GLU_BN = 128;
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -64,8 +68,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, un
 // (j*8 + w)*64 .. +63, lane l the l-th of them.  Rows past the end of the matrix fall outside the buffer's range
 // by themselves or are redirected to OOB, which stores zeros.
 // (a [row][k] tile may have any multiple of 8 rows: WAVES * 64 * CH pieces; a [k][row] tile always has 256 rows)
+// glu_f > 0 (a [k][row] B tile of EPI_SWIGLU): row0 is the tile's first feature and piece p = 8 columns of block p / 4
+// fetches columns (odd block ? glu_f : 0) + row0 + (p / 8) * 32 + (p % 4) * 8 ..
 template <bool KC, int WAVES, int CH>
-__device__ __forceinline__ void tile_offsets(unsigned (&off)[CH], int64_t ld, int row0, int rows, int wave, int lane) {
+__device__ __forceinline__ void tile_offsets(unsigned (&off)[CH], int64_t ld, int row0, int rows, int wave, int lane,
+                                             int glu_f = 0) {
   static_assert(KC || WAVES * 64 * CH == TILE_SLOTS, "every 16-byte piece of the tile has one owner");
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
@@ -75,8 +82,14 @@ __device__ __forceinline__ void tile_offsets(unsigned (&off)[CH], int64_t ld, in
       off[j] = row0 + r < rows ? (unsigned)(((int64_t)(row0 + r) * ld + c * 8) * 2) : OOB;
     } else {
       const int k = s >> 5, p = (s & 31) ^ ((k & 3) << 2);
-      const int row = row0 + p * 8;
-      off[j] = row < rows ? (unsigned)(((int64_t)k * ld + row) * 2) : OOB;
+      int row = row0 + p * 8;
+      bool ok = row < rows;
+      if (glu_f) {
+        const int feat = row0 + (p >> 3) * 32 + (p & 3) * 8;
+        ok = feat < glu_f;
+        row = ((p >> 2) & 1) ? glu_f + feat : feat;
+      }
+      off[j] = ok ? (unsigned)(((int64_t)k * ld + row) * 2) : OOB;
     }
   }
 }
@@ -164,6 +177,8 @@ template <bool AKC, bool BKC, int EPI, int TN, int WR = 2>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds_char* smem, int nseg = 1,
                                           const int64_t* seg_delta = nullptr) {
   static_assert(WR == 2 || (WR == 1 && AKC), "the half-height tile takes a [row][k] A operand");
+  constexpr bool GLU = EPI == EPI_SWIGLU;
+  static_assert(!GLU || (TN == 2 && !BKC), "gate and up blocks are a wavefront's two accumulator columns");
   constexpr int WGN = 8 / TN, WAVES = WR * WGN;
   constexpr int BMV = WR * 128, A_BYTES = BMV * BK * 2;                            // A tile: BMV rows
   constexpr int CHA = (A_BYTES / 16) / (WAVES * 64), CHB = TILE_SLOTS / (WAVES * 64); // loads per thread and K tile
@@ -188,7 +203,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   };
   unsigned offa[CHA], offb[CHB];
   tile_offsets<AKC, WAVES, CHA>(offa, g.lda, m0, g.M, wave, lane);
-  tile_offsets<BKC, WAVES, CHB>(offb, g.ldb, n0, g.N, wave, lane);
+  tile_offsets<BKC, WAVES, CHB>(offb, g.ldb, n0, g.N, wave, lane, GLU ? g.N / 2 : 0);
 
   // LDS map: buffer u at byte u * BUF_BYTES, A tile first, then B tile
   constexpr int BUF_BYTES = A_BYTES + TILE_BYTES;
@@ -323,35 +338,99 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
 
   // epilogue: acc[i][j][e] = C[m][n],  m = m0+wm+i*32 + lane%32,  n = n0+wn+j*32 + (e/4)*8 + (lane/32)*4 + e%4
   const int row_l = lane & 31, col_l = (lane >> 5) * 4;
-  if (EPI == EPI_STORE) {
+  if (EPI != EPI_ACC32 && g.bias) {       // wave-uniform; the bias of a column goes to every row of it
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        int n = n0 + wn + j * 32 + q * 8 + col_l;
+        bool ok = n < g.N;
+        if (GLU) { const int feat = n0 + (wn >> 6) * 32 + q * 8 + col_l; ok = feat < g.N / 2; n = j ? g.N / 2 + feat : feat; }
+        if (ok) {
+          const bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16*)g.bias + n);
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[i][j][q * 4 + e] += (float)b[e];
+        }
+      }
+  }
+  if (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_SWIGLU) {
     // bf16 output: the 256 x 256 tile goes through LDS (exactly the 128 KiB the operand buffers held) so that the
     // global stores are whole 512-byte rows, 16 bytes per lane, instead of 16-byte fragments of 32 rows.  Row r's
     // 16-byte piece p sits at r*512 + ((p ^ (r & 31)) << 4): the fragment writes of 32 rows spread over all banks
     // and a row is read back as a permutation of itself.  No loads are in flight here (none is issued past the
     // last K tile); the barrier waits for the other wavefronts' last fragment reads.
+    // EPI_SWIGLU: pieces 0..15 of a staged row are the tile's 128 gate columns, pieces 16..31 its 128 up columns (two
+    // 256-byte runs of the output row).
+    const int glu_f = g.N / 2;
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    auto stage_tile = [&](auto fn) {         // fn(acc) -> LDS as bf16, in the layout above
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = wm + i * 32 + row_l;
+      for (int i = 0; i < 4; ++i) {
+        const int r = wm + i * 32 + row_l;
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int p = GLU ? j * 16 + (wn >> 6) * 4 + q : (wn + j * 32 + q * 8) >> 3;
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)fn(acc[i][j][q * 4 + e]);
+            *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4) + (lane >> 5) * 8) = o;
+            if (EPI == EPI_GELU) __builtin_amdgcn_sched_barrier(0);      // keeps the erf expansions from piling up in registers
+          }
+      }
+    };
+    auto store_tile = [&](bf16* out, int64_t ld) {      // LDS -> global, whole rows
+      const int p = lane & 31;
+      int n = n0 + p * 8;
+      bool n_ok = n < g.N;
+      if (GLU) { const int feat = n0 + (p & 15) * 8; n_ok = feat < glu_f; n = (p >> 4) ? glu_f + feat : feat; }
+#pragma unroll
+      for (int t = 0; t < BMV / WAVES / 2; ++t) {
+        const int r = wave * (BMV / WAVES) + 2 * t + (lane >> 5), m = m0 + r;
+        const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4));
+        if (m < g.M && n_ok) *reinterpret_cast<u32x4*>(out + (int64_t)m * ld + n) = v;   // N % 8 == 0
+      }
+    };
+    stage_tile([](float v) { return v; });
+    __syncthreads();
+    store_tile((bf16*)g.C, g.ldc);
+    if (EPI == EPI_STORE) return;
+    // the activation, from the fp32 accumulators
+    __syncthreads();                  // every wavefront has read the staged z tile back
+    if (EPI == EPI_GELU) {
+      stage_tile([](float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); });
+      __syncthreads();
+      store_tile((bf16*)g.C2, g.ldc2);
+    } else {
+      // a = silu(gate) * up: 128 features per row = 256 bytes; rows with bit 4 set use the upper half of their
+      // 512-byte LDS row so that rows r and r + 16 do not share banks
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = wm + i * 32 + row_l;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int p = (wn + j * 32 + q * 8) >> 3;
+          const int fp = (wn >> 6) * 4 + q;
           bf16x4 o;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[i][j][q * 4 + e];
-          *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4) + (lane >> 5) * 8) = o;
+          for (int e = 0; e < 4; ++e) {
+            const float gv = acc[i][0][q * 4 + e];
+            o[e] = (bf16)(gv * (1.f / (1.f + __expf(-gv))) * acc[i][TN - 1][q * 4 + e]);
+          }
+          *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * 512 + ((((r & 16) | fp) ^ (r & 15)) << 4) + (lane >> 5) * 8) = o;
         }
-    }
-    __syncthreads();
-    const int p = lane & 31, n = n0 + p * 8;
+      }
+      __syncthreads();
+      const int pc = lane & 15, feat = n0 + pc * 8;
 #pragma unroll
-    for (int t = 0; t < BMV / WAVES / 2; ++t) {
-      const int r = wave * (BMV / WAVES) + 2 * t + (lane >> 5), m = m0 + r;
-      const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4));
-      if (m < g.M && n < g.N) *reinterpret_cast<u32x4*>((bf16*)g.C + (int64_t)m * g.ldc + n) = v;   // N % 8 == 0
+      for (int t = 0; t < BMV / WAVES / 4; ++t) {
+        const int r = wave * (BMV / WAVES) + 4 * t + (lane >> 4), m = m0 + r;
+        const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(smem + r * 512 + ((((r & 16) | pc) ^ (r & 15)) << 4));
+        if (m < g.M && feat < glu_f) *reinterpret_cast<u32x4*>((bf16*)g.C2 + (int64_t)m * g.ldc2 + feat) = v;
+      }
     }
     return;
   }
@@ -418,7 +497,8 @@ __global__ __launch_bounds__(WR * 512 / TN) void gemm_mfma_kernel(GemmArgs g, in
   }
   int tile_m, tile_n;
   tile_of(first + (WR == 2 ? bid : bid >> 1), tiles_m, tiles_n, tile_m, tile_n);
-  gemm_tile<AKC, BKC, EPI, TN, WR>(g, tile_m * BM + (WR == 2 ? 0 : (bid & 1) * 128), tile_n * BN, (lds_char*)smem_raw);
+  gemm_tile<AKC, BKC, EPI, TN, WR>(g, tile_m * BM + (WR == 2 ? 0 : (bid & 1) * 128), tile_n * (EPI == EPI_SWIGLU ? GLU_BN : BN),
+                                   (lds_char*)smem_raw);
 }
 
 // Several weight-gradient products C_p += A_p^T . B_p in one launch of persistent workgroups.  Each workgroup
@@ -483,7 +563,8 @@ hipError_t launch_tiles(const GemmArgs& g, hipStream_t s, int tiles_m, int tiles
 // take about half as long each.  `shape`: 0 = this rule, 1 = full tiles only, 2 = half-height tiles only.
 template <bool AKC, bool BKC, int EPI>
 hipError_t launch(const GemmArgs& g, hipStream_t s, int shape) {
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN, total = tiles_m * tiles_n;
+  const int tiles_m = (g.M + BM - 1) / BM;
+  const int tiles_n = EPI == EPI_SWIGLU ? (g.N / 2 + GLU_BN - 1) / GLU_BN : (g.N + BN - 1) / BN, total = tiles_m * tiles_n;
   int n_half = 0;                         // full tiles at the end of the walk order that are split in two
   if constexpr (AKC) {
     const int n_cu = cu_count(), tail = total % n_cu;
@@ -511,6 +592,11 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   const int64_t a_rows = g.mode == GEMM_TN ? g.K : g.M, b_rows = g.mode == GEMM_NT ? g.N : g.K;
   if (a_rows * g.lda >= lim || b_rows * g.ldb >= lim) return false;
   if (g.acc_f32 && (int64_t)g.M * g.ldc >= lim / 2) return false;   // C is read through a 32-bit byte offset too
+  if (g.bias && (g.mode != GEMM_NN || ((uintptr_t)g.bias & 7))) return false;
+  if (g.act) {     // fused activation: forward FFN-in product only
+    if (g.mode != GEMM_NN || g.R || g.c_f32 || g.acc_f32 || (g.act != 1 && g.act != 2) || !g.C2 || !al16(g.C2) || g.ldc2 % 8) return false;
+    if (g.act == 2 && g.N % 16) return false;      // gate | up halves of whole 16-byte pieces
+  }
   switch (g.mode) {
     case GEMM_NN: return g.K % BK == 0 && !g.acc_f32;
     case GEMM_NT: return g.K % BK == 0 && !g.acc_f32 && !g.R && !g.c_f32;
@@ -521,7 +607,10 @@ bool gemm_mfma_supported(const GemmArgs& g) {
 
 hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s, int tile_shape) {
   switch (g.mode) {
-    case GEMM_NN: return (g.R || g.c_f32) ? launch<true, false, EPI_RESID>(g, s, tile_shape) : launch<true, false, EPI_STORE>(g, s, tile_shape);
+    case GEMM_NN:
+      if (g.act == 1) return launch<true, false, EPI_GELU>(g, s, tile_shape);
+      if (g.act == 2) return launch<true, false, EPI_SWIGLU>(g, s, tile_shape);
+      return (g.R || g.c_f32) ? launch<true, false, EPI_RESID>(g, s, tile_shape) : launch<true, false, EPI_STORE>(g, s, tile_shape);
     case GEMM_NT: return launch<true, true, EPI_STORE>(g, s, tile_shape);
     case GEMM_TN: return launch<false, false, EPI_ACC32>(g, s, tile_shape);
   }

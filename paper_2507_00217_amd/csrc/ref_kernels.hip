@@ -66,6 +66,7 @@ __global__ __launch_bounds__(256) void gemm_ref_kernel(GemmArgs g) {
         C[(int64_t)gm * g.ldc + gn] += acc[i][j];
       } else {
         float v = acc[i][j];
+        if (g.bias) v += to_f32(((const T*)g.bias)[gn]);
         if (g.R) v += g.r_f32 ? ((const float*)g.R)[(int64_t)gm * g.ldr + gn] : to_f32(((const T*)g.R)[(int64_t)gm * g.ldr + gn]);
         if (g.c_f32) ((float*)g.C)[(int64_t)gm * g.ldc + gn] = v;
         else ((T*)g.C)[(int64_t)gm * g.ldc + gn] = from_f32<T>(v);

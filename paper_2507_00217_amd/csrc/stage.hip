@@ -23,6 +23,7 @@ inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 struct Dims {
   int L, d, h, hkv, hd, da, dkv, dq, f, fin, s, b, T, n_mb, cap, n_sub;   // da = h*hd: width of the attention output
   int rope;              // rotary position embedding on
+  int bias;              // linear maps carry biases
   int recompute, hcap;   // layer-wise recomputation on; cap on microbatches holding a rebuilt stash (B started, W not finished)
   size_t es;  // bytes per element of the compute dtype
 };
@@ -46,6 +47,7 @@ bool make_dims(const stage_config_t* c, Dims* o) {
   if (c->n_sub < 0 || c->n_sub > 32 || (c->n_sub > 0 && c->n_layers % c->n_sub)) return false;
   if ((c->recompute != 0 && c->recompute != 1) || c->recompute_cap < 0 || c->recompute_cap > c->n_microbatches) return false;
   if (!c->recompute && c->recompute_cap) return false;
+  if (c->bias != 0 && c->bias != 1) return false;
   const size_t es = c->dtype == STAGE_DTYPE_FP32 ? 4 : 2;
   if (c->hidden > 256 * 4 * (int)(16 / es)) return false;  // one norm row must fit a workgroup's registers
   if ((int64_t)c->seq * c->mb_size > (1 << 20) || c->seq > 65536) return false;
@@ -56,6 +58,7 @@ bool make_dims(const stage_config_t* c, Dims* o) {
   o->cap = c->stash_cap ? c->stash_cap : c->n_microbatches;
   o->n_sub = c->n_sub > 0 ? c->n_sub : 1;
   o->rope = c->rope_theta > 0.f;
+  o->bias = c->bias;
   o->recompute = c->recompute;
   o->hcap = !c->recompute ? 0 : (c->recompute_cap ? c->recompute_cap : o->cap);
   if (o->hcap > o->cap) return false;   // a microbatch with a rebuilt stash is also live
@@ -74,6 +77,9 @@ void param_dims(const Dims& D, int norm, int pid, int64_t* rows, int64_t* cols) 
     case STAGE_P_WO: *rows = D.da; *cols = D.d; break;
     case STAGE_P_WIN: *rows = D.d; *cols = D.fin; break;
     case STAGE_P_WOUT: *rows = D.f; *cols = D.d; break;
+    case STAGE_P_BQKV: *rows = D.bias; *cols = D.bias ? D.dq : 0; break;
+    case STAGE_P_BO: case STAGE_P_BOUT: *rows = D.bias; *cols = D.bias ? D.d : 0; break;
+    case STAGE_P_BIN: *rows = D.bias; *cols = D.bias ? D.fin : 0; break;
     default: *rows = 0; *cols = 0;
   }
 }
@@ -131,7 +137,7 @@ size_t slot_bytes(const Dims& D) { return (D.recompute ? x_bytes(D) : rec_bytes(
 size_t big_slot_bytes(const Dims& D) { return D.recompute ? rec_bytes(D) * D.L : 0; }
 size_t stash_bytes(const Dims& D) { return slot_bytes(D) * D.cap + big_slot_bytes(D) * D.hcap; }
 
-struct WsOff { size_t da, dn, delta, partial, rec, dkvp, rope, end; };
+struct WsOff { size_t da, dn, delta, partial, rec, dkvp, rope, bpart, end; };
 WsOff ws_off(const Dims& D) {
   WsOff w; size_t p = 0;
   auto take = [&](size_t bytes) { size_t r = p; p += up(bytes); return r; };
@@ -142,6 +148,7 @@ WsOff ws_off(const Dims& D) {
   w.rec = take(D.recompute ? rec_bytes(D) : 0);       // the layer record F works in under recomputation
   w.dkvp = take(D.es == 2 ? attn_bwd_part_bytes(D.b, D.s, D.h, D.hkv, D.hd) : 0);   // grouped-query dK/dV partials
   w.rope = take(D.rope ? (size_t)D.s * (D.hd / 2) * 2 * sizeof(float) : 0);          // (cos, sin) per position and pair
+  w.bpart = take(D.bias ? bias_grad_partial_bytes(D.fin > D.dq ? (D.fin > D.d ? D.fin : D.d) : (D.dq > D.d ? D.dq : D.d)) : 0);
   w.end = p;
   return w;
 }
@@ -246,11 +253,11 @@ struct stage {
 
 namespace {
 
-struct LayerW { const char *g1, *b1, *wqkv, *wo, *g2, *b2, *win, *wout; float *G[STAGE_P_COUNT]; };
+struct LayerW { const char *g1, *b1, *wqkv, *wo, *g2, *b2, *win, *wout, *bqkv, *bo, *bin, *bout; float *G[STAGE_P_COUNT]; };
 
 LayerW layer_weights(const stage* st, int l) {
   LayerW w;
-  const char** slots[STAGE_P_COUNT] = {&w.g1, &w.b1, &w.wqkv, &w.wo, &w.g2, &w.b2, &w.win, &w.wout};
+  const char** slots[STAGE_P_COUNT] = {&w.g1, &w.b1, &w.wqkv, &w.wo, &w.g2, &w.b2, &w.win, &w.wout, &w.bqkv, &w.bo, &w.bin, &w.bout};
   for (int p = 0; p < STAGE_P_COUNT; ++p) {
     int64_t r, c; param_dims(st->D, st->cfg.norm, p, &r, &c);
     const size_t off = param_offset(st->D, st->cfg.norm, l, p);
@@ -286,12 +293,27 @@ double attn_flops(const stage* st, bool bwd) {
 }
 
 int do_gemm(stage* st, int mode, int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
-            void* C, int64_t ldc, const void* R, int64_t ldr, int acc, int r_f32 = 0, int c_f32 = 0) {
+            void* C, int64_t ldc, const void* R, int64_t ldr, int acc, int r_f32 = 0, int c_f32 = 0, const void* bias = nullptr) {
   GemmArgs g{mode, M, N, K, A, lda, B, ldb, C, ldc, R, ldr, acc, r_f32, c_f32};
+  g.bias = bias;
   ProfScope ps(st, STAGE_K_GEMM_NN + mode, 2.0 * M * N * K);
   if (st->kernel_set == 0 && st->dt == DT_BF16 && gemm_mfma_supported(g)) HIPCHK(gemm_mfma(g, st->stream));
   else HIPCHK(gemm_ref(st->dt, g, st->stream));
   return STAGE_OK;
+}
+
+// FFN-in product with the activation fused into its epilogue: z = A.W and a = act(z) from the fp32 accumulators, in
+// one kernel.  Returns false (nothing enqueued) when the tuned kernel does not take the shape or is switched off; the
+// caller then runs the product and the activation kernel one after the other.
+bool try_gemm_act(stage* st, int* rc, int M, int f, int K, const void* A, const void* W, const void* bias, void* z, void* a) {
+  const int fin = st->cfg.act == STAGE_ACT_SWIGLU ? 2 * f : f;
+  GemmArgs g{GEMM_NN, M, fin, K, A, (int64_t)K, W, (int64_t)fin, z, (int64_t)fin, nullptr, 0, 0, 0, 0};
+  g.act = st->cfg.act == STAGE_ACT_SWIGLU ? 2 : 1; g.C2 = a; g.ldc2 = f; g.bias = bias;
+  if (st->kernel_set != 0 || st->dt != DT_BF16 || !gemm_mfma_supported(g)) return false;
+  ProfScope ps(st, STAGE_K_GEMM_NN, 2.0 * M * fin * K);
+  *rc = STAGE_OK;
+  if (gemm_mfma(g, st->stream) != hipSuccess) { st->sticky = STAGE_E_HIP; *rc = STAGE_E_HIP; }
+  return true;
 }
 
 // Where one layer's tensors of one microbatch live.
@@ -340,7 +362,7 @@ int forward_layer(stage* st, int l, const LayerBuf& o, void* y_l, bool y_lp) {
   NormArgs n{}; n.kind = st->cfg.norm; n.rows = D.T; n.d = D.d; n.eps = st->cfg.norm_eps; n.x_f32 = 1;
   n.x = o.x; n.gamma = W.g1; n.beta = W.b1; n.out = o.n1; n.stats = o.st1;
   { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 1, 1)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
-  int rc = do_gemm(st, GEMM_NN, D.T, D.dq, D.d, o.n1, D.d, W.wqkv, D.dq, o.qkv, D.dq, nullptr, 0, 0);
+  int rc = do_gemm(st, GEMM_NN, D.T, D.dq, D.d, o.n1, D.d, W.wqkv, D.dq, o.qkv, D.dq, nullptr, 0, 0, 0, 0, W.bqkv);
   if (rc) return rc;
   if (D.rope) {      // q and k of the stash are the rotated ones: attention forward and backward both want those
     ProfScope ps(st, STAGE_K_ROPE, 2.0 * D.T * (D.da + D.dkv) * D.es);
@@ -352,16 +374,20 @@ int forward_layer(stage* st, int l, const LayerBuf& o, void* y_l, bool y_lp) {
     if (st->kernel_set == 0 && st->dt == DT_BF16 && attn_mfma_supported(a)) HIPCHK(attn_fwd_mfma(a, st->stream));
     else HIPCHK(attn_fwd_ref(st->dt, a, st->stream));
   }
-  rc = do_gemm(st, GEMM_NN, D.T, D.d, D.da, o.o, D.da, W.wo, D.d, o.x1, D.d, o.x, D.d, 0, 1, 1);
+  rc = do_gemm(st, GEMM_NN, D.T, D.d, D.da, o.o, D.da, W.wo, D.d, o.x1, D.d, o.x, D.d, 0, 1, 1, W.bo);
   if (rc) return rc;
   n.x = o.x1; n.gamma = W.g2; n.beta = W.b2; n.out = o.n2; n.stats = o.st2;
   { ProfScope ps(st, STAGE_K_NORM_FWD, norm_bytes(st, 1, 1)); HIPCHK(norm_fwd(st->dt, n, st->stream)); }
-  rc = do_gemm(st, GEMM_NN, D.T, D.fin, D.d, o.n2, D.d, W.win, D.fin, o.z, D.fin, nullptr, 0, 0);
-  if (rc) return rc;
-  ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = o.z; ac.a = o.a;
-  { ProfScope ps(st, STAGE_K_ACT_FWD, act_bytes_fwd(st)); HIPCHK(act_fwd(st->dt, ac, st->stream)); }
+  if (try_gemm_act(st, &rc, D.T, D.f, D.d, o.n2, W.win, W.bin, o.z, o.a)) {
+    if (rc) return rc;
+  } else {
+    rc = do_gemm(st, GEMM_NN, D.T, D.fin, D.d, o.n2, D.d, W.win, D.fin, o.z, D.fin, nullptr, 0, 0, 0, 0, W.bin);
+    if (rc) return rc;
+    ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = o.z; ac.a = o.a;
+    { ProfScope ps(st, STAGE_K_ACT_FWD, act_bytes_fwd(st)); HIPCHK(act_fwd(st->dt, ac, st->stream)); }
+  }
   if (!y_l) return STAGE_OK;
-  return do_gemm(st, GEMM_NN, D.T, D.d, D.f, o.a, D.f, W.wout, D.d, y_l, D.d, o.x1, D.d, 0, 1, y_lp ? 0 : 1);
+  return do_gemm(st, GEMM_NN, D.T, D.d, D.f, o.a, D.f, W.wout, D.d, y_l, D.d, o.x1, D.d, 0, 1, y_lp ? 0 : 1, W.bout);
 }
 
 // layers [l0, l1): x is read when l0 == 0, y is written when l1 == L
@@ -403,11 +429,21 @@ int exec_backward_input(stage* st, int mb, const void* dy, void* dx, int l0, int
     // term, which is the fp32 dx the layer above left in its x region (the caller's dY for the last layer)
     const void* dy_op = o.dyb;
     const void* dy_res = last ? dy_op : (const void*)layer_buf(st, mb, l + 1).x;
+    // bias gradients: column sums of the four dZ tensors, as each becomes available
+    float* bpart = (float*)(st->ws + w.bpart);
+    auto dbias = [&](const void* dz, int n, int pid) -> int {
+      if (!D.bias) return STAGE_OK;
+      ProfScope ps(st, STAGE_K_COPY, (double)D.T * n * D.es);
+      HIPCHK(bias_grad(st->dt, dz, n, D.T, n, bpart, W.G[pid], st->stream));
+      return STAGE_OK;
+    };
+    if ((rc = dbias(dy_op, D.d, STAGE_P_BOUT))) return rc;
     // FFN: da = dy.Wout^T ; dz = act'(z) * da (in place over z) ; dn2 = dz.Win^T
     rc = do_gemm(st, GEMM_NT, D.T, D.f, D.d, dy_op, D.d, W.wout, D.d, da, D.f, nullptr, 0, 0);
     if (rc) return rc;
     ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = o.z; ac.da = da;
     { ProfScope ps(st, STAGE_K_ACT_BWD, (double)D.T * (2.0 * D.fin + D.f) * D.es); HIPCHK(act_bwd(st->dt, ac, st->stream)); }
+    if ((rc = dbias(o.z, D.fin, STAGE_P_BIN))) return rc;
     rc = do_gemm(st, GEMM_NT, D.T, D.d, D.fin, o.z, D.fin, W.win, D.fin, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
     // dx1 = dy + norm2'(dn2): fp32 in place over x1, plus a compute-dtype copy for the two GEMMs that read it
@@ -417,6 +453,7 @@ int exec_backward_input(stage* st, int mb, const void* dy, void* dx, int l0, int
     n.dgamma = W.G[STAGE_P_NORM2_GAMMA]; n.dbeta = W.G[STAGE_P_NORM2_BETA]; n.partial = (float*)(st->ws + w.partial);
     { ProfScope ps(st, STAGE_K_NORM_BWD, norm_bytes(st, last ? 2 : 3, last ? 3 : 2)); HIPCHK(norm_bwd(st->dt, n, st->stream)); }
     // attention: do = dx1.Wo^T ; (dq,dk,dv) ; dn1 = dqkv.Wqkv^T
+    if ((rc = dbias(o.dx1b, D.d, STAGE_P_BO))) return rc;
     rc = do_gemm(st, GEMM_NT, D.T, D.da, D.d, o.dx1b, D.d, W.wo, D.d, dn, D.da, nullptr, 0, 0);
     if (rc) return rc;
     AttnArgs a = attn_args(st, o, dn, w);
@@ -429,6 +466,7 @@ int exec_backward_input(stage* st, int mb, const void* dy, void* dx, int l0, int
       ProfScope ps(st, STAGE_K_ROPE, 2.0 * D.T * (D.da + D.dkv) * D.es);
       HIPCHK(rope_apply(st->dt, o.dqkv, D.dq, D.T, D.s, D.h + D.hkv, D.hd, (const float*)(st->ws + w.rope), 1, st->stream));
     }
+    if ((rc = dbias(o.dqkv, D.dq, STAGE_P_BQKV))) return rc;
     rc = do_gemm(st, GEMM_NT, D.T, D.d, D.dq, o.dqkv, D.dq, W.wqkv, D.dq, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
     // dx = dx1 + norm1'(dn1): layer 0 hands it to the caller; otherwise fp32 in place over x (the residual term of
@@ -632,6 +670,12 @@ int init_stage(const stage_config_t* cfg, void* weights_dev, void* grads_dev, vo
     const Dims& S = share_with->D;
     if (slot_bytes(D) != slot_bytes(S) || big_slot_bytes(D) != big_slot_bytes(S) || D.cap != S.cap || D.hcap != S.hcap ||
         D.recompute != S.recompute)
+      return STAGE_E_INVAL;
+    // A workspace may be common to the chunks only if this chunk fits into it and finds the same rotary table there
+    // (it is written at init): same offsets, same table.  A chunk of another shape brings its own workspace.
+    if (workspace_dev == (void*)share_with->ws &&
+        (ws_off(D).end > ws_off(S).end || ws_off(D).rope != ws_off(S).rope || D.rope != S.rope || D.s != S.s || D.hd != S.hd ||
+         cfg->rope_theta != share_with->cfg.rope_theta))
       return STAGE_E_INVAL;
   }
   stage* st = new (std::nothrow) stage();
@@ -914,6 +958,25 @@ int stage_kernel_gemm(int dtype, int mode, int M, int N, int K, const void* A, i
   return hip_rc(gemm_ref((DType)dtype, g, (hipStream_t)hip_stream));
 }
 
+int stage_kernel_gemm_act(int dtype, int act, int M, int f, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
+                          void* Z, int64_t ldz, void* Aout, int64_t lda_out, int kernel_set, void* hip_stream) {
+  if (!dtype_ok(dtype) || (act != STAGE_ACT_GELU && act != STAGE_ACT_SWIGLU) || M <= 0 || f <= 0 || K <= 0 || !A || !B || !Z || !Aout)
+    return STAGE_E_INVAL;
+  const int fin = act == STAGE_ACT_SWIGLU ? 2 * f : f;
+  if (lda < K || ldb < fin || ldz < fin || lda_out < f) return STAGE_E_INVAL;
+  GemmArgs g{GEMM_NN, M, fin, K, A, lda, B, ldb, Z, ldz, nullptr, 0, 0, 0, 0};
+  g.act = act == STAGE_ACT_SWIGLU ? 2 : 1; g.C2 = Aout; g.ldc2 = lda_out;
+  if (kernel_set != 1 && dtype == STAGE_DTYPE_BF16 && gemm_mfma_supported(g))
+    return hip_rc(gemm_mfma(g, (hipStream_t)hip_stream, kernel_set == 2 ? 1 : kernel_set == 3 ? 2 : 0));
+  // plain kernels: the product, then the activation from the stored z (needs dense rows)
+  if (ldz != fin || lda_out != f) return STAGE_E_INVAL;
+  g.act = 0; g.C2 = nullptr;
+  const hipError_t e = gemm_ref((DType)dtype, g, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_rc(e);
+  ActArgs ac{}; ac.kind = act; ac.rows = M; ac.f = f; ac.z = Z; ac.a = Aout;
+  return hip_rc(act_fwd((DType)dtype, ac, (hipStream_t)hip_stream));
+}
+
 int stage_kernel_wgrad_group(int dtype, int n, const int* M, const int* N, const int* K, const void* const* A,
                              const int64_t* lda, const void* const* B, const int64_t* ldb, float* const* C,
                              const int64_t* ldc, int kernel_set, void* hip_stream) {
@@ -998,6 +1061,13 @@ int stage_kernel_norm_bwd(int dtype, int norm, int rows, int d, const void* x, c
   NormArgs n{}; n.kind = norm; n.rows = rows; n.d = d; n.x = x; n.stats = (float*)stats; n.gamma = gamma; n.dout = dout;
   n.resid = resid; n.out = dx; n.dgamma = dgamma; n.dbeta = dbeta; n.partial = partial;
   return hip_rc(norm_bwd((DType)dtype, n, (hipStream_t)hip_stream));
+}
+
+size_t stage_kernel_bias_grad_scratch_bytes(int n) { return bias_grad_partial_bytes(n); }
+
+int stage_kernel_bias_grad(int dtype, int rows, int n, const void* dz, int64_t ld, float* dbias, float* scratch, void* hip_stream) {
+  if (!dtype_ok(dtype) || rows <= 0 || n <= 0 || !dz || ld < n || !dbias || !scratch) return STAGE_E_INVAL;
+  return hip_rc(bias_grad((DType)dtype, dz, ld, rows, n, scratch, dbias, (hipStream_t)hip_stream));
 }
 
 size_t stage_kernel_norm_partial_bytes(int d) { return d > 0 ? (size_t)norm_partial_rows() * 2 * d * sizeof(float) : 0; }

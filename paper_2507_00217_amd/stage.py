@@ -20,7 +20,8 @@ F, B, W = 0, 1, 2
 NORM = {"layernorm": 0, "rmsnorm": 1}
 ACT = {"gelu": 0, "swiglu": 1}
 DTYPE = {"fp32": 0, "bf16": 1}
-PARAM_IDS = {"g1": 0, "b1": 1, "wqkv": 2, "wo": 3, "g2": 4, "b2": 5, "win": 6, "wout": 7}
+PARAM_IDS = {"g1": 0, "b1": 1, "wqkv": 2, "wo": 3, "g2": 4, "b2": 5, "win": 6, "wout": 7,
+             "bqkv": 8, "bo": 9, "bin": 10, "bout": 11}
 KERNEL_CLASSES = ("gemm_nn", "gemm_nt", "gemm_tn", "attn_fwd", "attn_bwd", "norm_fwd", "norm_bwd", "act_fwd", "act_bwd", "copy", "rope")
 OK, E_INVAL, E_ORDER, E_STASH_FULL, E_HIP = 0, -1, -2, -3, -4
 
@@ -28,7 +29,7 @@ OK, E_INVAL, E_ORDER, E_STASH_FULL, E_HIP = 0, -1, -2, -3, -4
 class StageConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_heads", "n_kv_heads", "ffn", "seq", "mb_size", "n_microbatches",
-        "norm", "act", "causal", "dtype", "stash_cap", "enforce_mb_order")] + [("norm_eps", C.c_float), ("n_sub", C.c_int32), ("recompute", C.c_int32), ("recompute_cap", C.c_int32), ("head_dim", C.c_int32), ("rope_theta", C.c_float)]
+        "norm", "act", "causal", "dtype", "stash_cap", "enforce_mb_order")] + [("norm_eps", C.c_float), ("n_sub", C.c_int32), ("recompute", C.c_int32), ("recompute_cap", C.c_int32), ("head_dim", C.c_int32), ("rope_theta", C.c_float), ("bias", C.c_int32)]
 
 
 class StageSubOp(C.Structure):
@@ -128,7 +129,8 @@ def make_config(cfg: dict) -> StageConfig:
         stash_cap=cfg.get("stash_cap", 0), enforce_mb_order=int(cfg.get("enforce_mb_order", 0)),
         norm_eps=cfg.get("norm_eps", 1e-5), n_sub=cfg.get("n_sub", 0),
         recompute=int(cfg.get("recompute", 0)), recompute_cap=cfg.get("recompute_cap", 0),
-        head_dim=cfg.get("head_dim", 0) or 0, rope_theta=float(cfg.get("rope_theta", 0.0) or 0.0))
+        head_dim=cfg.get("head_dim", 0) or 0, rope_theta=float(cfg.get("rope_theta", 0.0) or 0.0),
+        bias=int(cfg.get("bias", 0) or 0))
 
 
 def make_ops(ops: Sequence[Tuple[int, int]]):
@@ -227,7 +229,8 @@ class Stage:
                                       self._stash.data_ptr(), self._ws.data_ptr(), self.stream.cuda_stream, C.byref(h))
             else:
                 self.stream = share_with.stream
-                self._stash, self._ws = share_with._stash, share_with._ws      # keeps them alive; one stream orders all uses
+                self._stash = share_with._stash                                  # keeps it alive
+                self._ws = torch.empty(sz["workspace"], dtype=torch.uint8, device=self.device)    # the chunk's own
                 rc = lib().stage_init_chunk(C.byref(self.ccfg), self._weights.data_ptr(), self._grads.data_ptr(),
                                             self._ws.data_ptr(), share_with.h, C.byref(h))
         if rc:

@@ -21,6 +21,7 @@ def L():
     if not hasattr(lib, "_ksig"):
         vp, i, i64, fl = C.c_void_p, C.c_int, C.c_int64, C.c_float
         lib.stage_kernel_gemm.argtypes = [i, i, i, i, i, vp, i64, vp, i64, vp, i64, vp, i64, i, i, vp]
+        lib.stage_kernel_gemm_act.argtypes = [i, i, i, i, i, vp, i64, vp, i64, vp, i64, vp, i64, i, vp]
         lib.stage_kernel_wgrad_group.argtypes = [i, i] + [vp] * 9 + [i, vp]
         lib.stage_kernel_rope_table.argtypes = [i, i, fl, vp, vp]
         lib.stage_kernel_rope.argtypes = [i, i, i, i, i, i, vp, i64, vp, vp]
@@ -32,6 +33,9 @@ def L():
         lib.stage_kernel_norm_fwd.argtypes = [i, i, i, i, fl, vp, vp, vp, vp, vp, vp]
         lib.stage_kernel_norm_bwd.argtypes = [i, i, i, i] + [vp] * 10
         lib.stage_kernel_norm_partial_bytes.restype = C.c_size_t
+        lib.stage_kernel_bias_grad.argtypes = [i, i, i, vp, i64, vp, vp, vp]
+        lib.stage_kernel_bias_grad_scratch_bytes.argtypes = [i]
+        lib.stage_kernel_bias_grad_scratch_bytes.restype = C.c_size_t
         lib.stage_kernel_act_fwd.argtypes = [i, i, i, i, vp, vp, vp]
         lib.stage_kernel_act_bwd.argtypes = [i, i, i, i, vp, vp, vp]
         lib._ksig = True
@@ -93,6 +97,37 @@ def test_gemm_tile_shapes_agree_bitwise(mode, M, N, K):
         outs.append(Cd)
     torch.cuda.synchronize()
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+@pytest.mark.parametrize("dtype,kernel_set", [("fp32", 0), ("bf16", 0), ("bf16", 1), ("bf16", 2), ("bf16", 3)])
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+@pytest.mark.parametrize("M,f,K", [(128, 256, 128), (200, 192, 192), (328, 1088, 512), (257, 1408, 64), (512, 64, 256), (1024, 704, 320)])
+def test_gemm_with_fused_activation(dtype, kernel_set, act, M, f, K):
+    """The forward FFN-in product and its activation in one call: Z against the product's definition, Aout against the
+    oracle's activation of the exact product (the tuned kernel forms it from fp32 accumulators; the plain kernels from
+    the stored Z).  Ragged tiles in every dimension; kernel_set 2 / 3 force full / half-height tiles."""
+    import torch
+    kind = {"gelu": 0, "swiglu": 1}[act]
+    fin = 2 * f if act == "swiglu" else f
+    A = rnd(synth.normal(7, 1, (M, K)), dtype); Bm = rnd(synth.normal(7, 2, (K, fin), std=1.5 / math.sqrt(K)), dtype)
+    Ad, Bd = to_dev(A, dtype), to_dev(Bm, dtype)
+    z_ref = A.astype(np.float64) @ Bm.astype(np.float64)
+    sh = so.Shape(1, 64, 1, 1, f, 1, 1, act=act)
+    a_ref = so.gelu(z_ref) if act == "gelu" else z_ref[:, :f] * so.sigmoid(z_ref[:, :f]) * z_ref[:, f:]
+    tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+    Zd = torch.full((M, fin), float("nan"), dtype=tdt, device="cuda:0")
+    Aout = torch.full((M, f), float("nan"), dtype=tdt, device="cuda:0")
+    rc = L().stage_kernel_gemm_act(DT[dtype], kind, M, f, K, P(Ad), K, P(Bd), fin, P(Zd), fin, P(Aout), f, kernel_set, None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert so.max_rel_err(to_np(Zd), z_ref) <= KTOL[dtype]
+    assert so.max_rel_err(to_np(Aout), a_ref) <= KTOL[dtype]
+    if dtype == "bf16" and kernel_set != 1:
+        # one rounding only: the fused activation is the rounded activation of the (fp32) product, not of the rounded Z
+        a_once = synth.round_bf16(a_ref.astype(np.float32)).astype(np.float64)
+        assert np.mean(to_np(Aout) == a_once) > 0.97
+    assert L().stage_kernel_gemm_act(DT[dtype], 5, M, f, K, P(Ad), K, P(Bd), fin, P(Zd), fin, P(Aout), f, kernel_set, None) == -1
+    assert L().stage_kernel_gemm_act(DT[dtype], kind, M, f, K, P(Ad), K, P(Bd), fin, None, fin, P(Aout), f, kernel_set, None) == -1
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
@@ -302,6 +337,29 @@ def test_activation(dtype, act, rows, f):
     torch.cuda.synchronize()
     assert so.max_rel_err(to_np(ad), a_ref) <= KTOL[dtype]
     assert so.max_rel_err(to_np(zd), dz_ref) <= KTOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("rows,n,ld", [(128, 256, 256), (333, 1088, 1088), (1000, 64, 192), (5, 2816, 2816), (4096, 520, 1040)])
+def test_bias_gradient(dtype, rows, n, ld):
+    """dbias += column sums of dZ (the oracle's _bias_grads), strided rows, two calls accumulate, same bits each time."""
+    import torch
+    dz = rnd(synth.normal(8, 1, (rows, ld)), dtype)
+    d0 = synth.normal(8, 2, (n,))
+    ref = so._bias_grads({"bo": 0}, {"wo": dz[:, :n].astype(np.float64)})["bo"]
+    dzd = to_dev(dz, dtype)
+    scr = torch.zeros(L().stage_kernel_bias_grad_scratch_bytes(n) // 4, dtype=torch.float32, device="cuda:0")
+    outs = []
+    for _ in range(2):
+        db = to_dev(d0, "fp32")
+        assert L().stage_kernel_bias_grad(DT[dtype], rows, n, P(dzd), ld, P(db), P(scr), None) == 0
+        assert L().stage_kernel_bias_grad(DT[dtype], rows, n, P(dzd), ld, P(db), P(scr), None) == 0
+        torch.cuda.synchronize()
+        outs.append(db.clone())
+    assert torch.equal(outs[0], outs[1])
+    assert so.max_rel_err(to_np(outs[0]) - d0, 2 * ref) <= 1e-5
+    assert L().stage_kernel_bias_grad(DT[dtype], rows, n, None, ld, P(db), P(scr), None) == -1
+    assert L().stage_kernel_bias_grad(DT[dtype], rows, n, P(dzd), n - 8, P(db), P(scr), None) == -1
 
 
 def test_mfma_ceiling_probe():

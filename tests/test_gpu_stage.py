@@ -70,6 +70,40 @@ def test_small_variants_bf16(name, kernel_set):
     compare(cfg, run_gpu(cfg, params, X, G, ops, kernel_set), run_oracle(cfg, params, X, G, ops), TOL["bf16"])
 
 
+@pytest.mark.parametrize("variant", ["cfg1_fp32", "cfg2s", "cfg3s", "cfg5s_recompute", "cfg4s_sub"])
+@pytest.mark.parametrize("kernel_set", [0, 1])
+def test_linear_biases(variant, kernel_set):
+    """GPT-style layers: every linear map carries a bias (added in the product's epilogue, before the residual / the
+    activation); the bias gradients, column sums of the dZ tensors, are accumulated by B.  Also under recomputation and
+    with sub-block ops."""
+    if variant == "cfg1_fp32":
+        cfg = dict(synth.CONFIGS["cfg1"], bias=1)
+    elif variant == "cfg5s_recompute":
+        cfg = dict(SMALL["cfg5s"], bias=1, recompute=1)
+    elif variant == "cfg4s_sub":
+        cfg = dict(SMALL["cfg4s"], bias=1, n_sub=2)
+    else:
+        cfg = dict(SMALL[variant], bias=1)
+    params, X, G = inputs(cfg, 2900 + len(variant))
+    assert set(synth.BIAS_NAMES) <= set(params[0])
+    ops = synth.make_schedule(cfg)
+    cfg["stash_cap"] = synth.peak_live(ops)
+    got = run_gpu(cfg, params, X, G, ops, kernel_set)
+    ref = so.OracleStage(shape_of(cfg), params, recompute=bool(cfg.get("recompute")))
+    Yr, dXr, peak = ref.run_schedule(ops, X.astype(np.float64), G.astype(np.float64))
+    errs = compare(cfg, got, (Yr, dXr, ref.grads, peak), TOL[cfg["dtype"]])
+    assert all(f"L0.{b}" in errs for b in synth.BIAS_NAMES)
+    # the biases matter on these inputs, and schedule order does not (bitwise, microbatch-ordered ops)
+    nob = [{k: v for k, v in lp.items() if k not in synth.BIAS_NAMES} for lp in params]
+    assert so.max_rel_err(run_oracle(dict(cfg, bias=0), nob, X, G, ops)[0], Yr) > 1e-3
+    if variant == "cfg2s":
+        n = cfg["n_microbatches"]
+        alt = run_gpu(cfg, params, X, G, synth.schedule_w_deferred(n, 2, 2), kernel_set)
+        for la, lb in zip(got[2], alt[2]):
+            for k in la:
+                assert np.array_equal(la[k], lb[k]), k
+
+
 @pytest.mark.parametrize("kernel_set", [0, 1])
 @pytest.mark.parametrize("heads,kv,hidden", [(2, 1, 512), (6, 2, 512), (3, 3, 256)])
 def test_head_width_independent_of_hidden(heads, kv, hidden, kernel_set):
@@ -401,7 +435,19 @@ def test_two_chunks_share_one_stash(defer_w):
                                   (B, 0, -1, 0), (W, 0, -1, 0), (B, 1, -1, 0), (W, 1, -1, 0)], Xd, Gd, Y, dX)
     torch.cuda.synchronize()
     assert (c0.stats()["live"], c1.stats()["live"]) == (0, 0)
-    c1.close(); c0.close()
+    # a chunk that needs another workspace than the first one's (here: a rotary table, which the first has none of) may not
+    # be given the first one's buffer; with a workspace of its own it is accepted
+    import ctypes as C
+    rcfg = dict(cfg, rope_theta=10000.0)
+    assert S.stage_query_sizes(rcfg)["stash"] == S.stage_query_sizes(cfg)["stash"]
+    h = C.c_void_p()
+    wts = torch.zeros(S.stage_query_sizes(rcfg)["weights"], dtype=torch.uint8, device="cuda:0")
+    grd = torch.zeros(S.stage_query_sizes(rcfg)["grads"], dtype=torch.uint8, device="cuda:0")
+    rc = S.lib().stage_init_chunk(C.byref(S.make_config(rcfg)), wts.data_ptr(), grd.data_ptr(), c0._ws.data_ptr(), c0.h, C.byref(h))
+    assert rc == S.E_INVAL and not h.value
+    c2 = S.Stage(rcfg, share_with=c0)
+    assert c2._ws.data_ptr() != c0._ws.data_ptr()
+    c2.close(); c1.close(); c0.close()
 
 
 @pytest.mark.parametrize("name", ["cfg3s", "cfg5s"])
