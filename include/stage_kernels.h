@@ -83,6 +83,17 @@ int stage_kernel_norm_bwd(int dtype, int norm, int rows, int d, const void* x, c
                           const void* dout, const void* resid, void* dx, float* dgamma, float* dbeta, float* partial,
                           void* hip_stream);
 size_t stage_kernel_norm_partial_bytes(int d);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): stage_kernel_norm_bwd without the `partial` argument.  The partial sums live in a fixed 32 MiB
+ * device array inside the library (one copy per GPU, held until the process ends), which limits it to d <= 8192:
+ * a wider row returns STAGE_E_INVAL with nothing enqueued.  The call allocates and frees nothing.  It acts on the
+ * current device, which must be the one hip_stream and the data pointers belong to.  All calls on one GPU share the
+ * array: calls that overlap on one GPU (different streams) race; calls on one stream are ordered and need no clearing
+ * in between.  Same kernels, same results, bit for bit, as stage_kernel_norm_bwd. */
+int stage_kernel_norm_bwd_noalloc(int dtype, int norm, int rows, int d, const void* x, const float* stats, const void* gamma,
+                                  const void* dout, const void* resid, void* dx, float* dgamma, float* dbeta,
+                                  void* hip_stream);
+
 /* Gradient of a linear map's bias (layers with biases): dbias[j] += sum over rows of dz[row * ld + j], j < n, fp32, in a
  * fixed summation order.  n and ld multiples of 16 bytes' worth of elements; scratch: stage_kernel_bias_grad_scratch_bytes(n). */
 size_t stage_kernel_bias_grad_scratch_bytes(int n);

@@ -6,6 +6,8 @@
 // on scheduling.
 #include "common.h"
 
+#include <mutex>
+
 namespace stg {
 
 template <typename T> struct Vec {
@@ -250,6 +252,43 @@ hipError_t norm_fwd(DType dt, const NormArgs& n, hipStream_t s) {
 }
 hipError_t norm_bwd(DType dt, const NormArgs& n, hipStream_t s) {
   return dt == DT_F32 ? norm_bwd_t<float>(n, s) : norm_bwd_t<bf16>(n, s);
+}
+
+// Norm backward for callers that cannot allocate device memory: the per-workgroup partial sums of dgamma / dbeta go to
+// a fixed array in the library's own device image instead of a caller-provided buffer.  Every GPU the library runs on
+// holds its own copy of the array, at its own address, until the process ends; `scratch` in host code is only a handle
+// to the symbol, so the device address is looked up once per device and that pointer is what the kernels are given.
+// The kernels write every partial they later read, so nothing has to be cleared between calls; two calls that
+// overlap on one GPU (different streams) would race on the array.
+constexpr int NOALLOC_MAX_D = 8192;
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static __device__ __align__(256) float scratch[(size_t)NORM_PARTIAL_ROWS * 2 * NOALLOC_MAX_D];   // 32 MiB
+
+int norm_bwd_noalloc_max_d() { return NOALLOC_MAX_D; }
+
+hipError_t norm_bwd_noalloc(DType dt, const NormArgs& n, hipStream_t s) {
+  static std::mutex mu;
+  static float* scratch_of[NOALLOC_MAX_DEVICES] = {};
+  if (n.d < 1 || n.d > NOALLOC_MAX_D) return hipErrorInvalidValue;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return hipErrorInvalidDevice;
+  float* ptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!scratch_of[dev]) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));     // the current device's copy
+      if (e != hipSuccess) return e;
+      if (!p) return hipErrorInvalidSymbol;
+      scratch_of[dev] = (float*)p;
+    }
+    ptr = scratch_of[dev];
+  }
+  NormArgs m = n;
+  m.partial = ptr;
+  return norm_bwd(dt, m, s);
 }
 
 // ---------------------------------------------------------------------------

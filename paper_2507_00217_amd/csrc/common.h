@@ -89,6 +89,9 @@ hipError_t attn_bwd_ref(DType dt, const AttnArgs& a, hipStream_t s);
 // bandwidth-bound kernels (wavefront reductions, 16-byte accesses)
 hipError_t norm_fwd(DType dt, const NormArgs& n, hipStream_t s);
 hipError_t norm_bwd(DType dt, const NormArgs& n, hipStream_t s);
+// the same with the partial sums in a fixed device array of the library (n.partial ignored); d <= norm_bwd_noalloc_max_d()
+hipError_t norm_bwd_noalloc(DType dt, const NormArgs& n, hipStream_t s);
+int norm_bwd_noalloc_max_d();
 hipError_t act_fwd(DType dt, const ActArgs& a, hipStream_t s);
 hipError_t act_bwd(DType dt, const ActArgs& a, hipStream_t s);
 // dbias[n] += sum over rows of dz[row, n] (fp32, fixed summation order); partial: bias_grad_partial_bytes(n) bytes

@@ -1063,6 +1063,17 @@ int stage_kernel_norm_bwd(int dtype, int norm, int rows, int d, const void* x, c
   return hip_rc(norm_bwd((DType)dtype, n, (hipStream_t)hip_stream));
 }
 
+int stage_kernel_norm_bwd_noalloc(int dtype, int norm, int rows, int d, const void* x, const float* stats, const void* gamma,
+                                  const void* dout, const void* resid, void* dx, float* dgamma, float* dbeta, void* hip_stream) {
+  if (!dtype_ok(dtype) || (norm != 0 && norm != 1) || rows <= 0 || d <= 0 || !x || !stats || !gamma || !dout || !dx || !dgamma ||
+      (norm == 0 && !dbeta))
+    return STAGE_E_INVAL;
+  if (d > norm_bwd_noalloc_max_d()) return STAGE_E_INVAL;      // wider rows than the fixed scratch holds partials for
+  NormArgs n{}; n.kind = norm; n.rows = rows; n.d = d; n.x = x; n.stats = (float*)stats; n.gamma = gamma; n.dout = dout;
+  n.resid = resid; n.out = dx; n.dgamma = dgamma; n.dbeta = dbeta;
+  return hip_rc(norm_bwd_noalloc((DType)dtype, n, (hipStream_t)hip_stream));
+}
+
 size_t stage_kernel_bias_grad_scratch_bytes(int n) { return bias_grad_partial_bytes(n); }
 
 int stage_kernel_bias_grad(int dtype, int rows, int n, const void* dz, int64_t ld, float* dbias, float* scratch, void* hip_stream) {
