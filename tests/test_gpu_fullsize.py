@@ -32,6 +32,19 @@ FULL_SEED = {"cfg2": 3020, "cfg3": 3000, "cfg4": 3040, "cfg5": 3050}
 INTRINSIC_FACTOR = 1.5
 
 
+def row_rel_err(got, ref):
+    """Largest row-wise relative error: max over rows r of max_i |got - ref|[r, i] / max_i |ref|[r, i].  The tolerance's
+    metric normalises by the largest element of the whole tensor, so a row of small values could be far off and pass; a
+    wrong or missing row (a token, an input feature) shows here as an error of order one."""
+    got = np.asarray(got, dtype=np.float64).reshape(-1, np.shape(ref)[-1])
+    ref = np.asarray(ref, dtype=np.float64).reshape(got.shape)
+    den = np.abs(ref).max(axis=1)
+    return float((np.abs(got - ref).max(axis=1) / np.where(den > 0, den, 1.0)).max())
+
+
+ROW_TOL = 0.25      # an order of magnitude above what bf16 rounding produces on a row, far below a structural error
+
+
 def oracle_run(cfg, params, X, G, operand_bits, tag):
     ref = so.OracleStage(shape_of(cfg, operand_bits), params)
     Yr = ref.forward(0, X[0].astype(np.float64))
@@ -79,6 +92,10 @@ def test_full_depth_one_microbatch(name, mb):
     print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     worst = max(errs, key=errs.get)
     print(f"{name} mb {mb}: worst {worst} {errs[worst]:.3e} (tol {TOL['bf16']:g})", flush=True)
+    rows = {k: row_rel_err(got[k], exact[k]) for k in exact if np.ndim(exact[k]) >= 2}
+    wr = max(rows, key=rows.get)
+    print(f"{name} mb {mb}: worst row-wise relative error {wr} {rows[wr]:.3e} (bound {ROW_TOL:g})", flush=True)
+    assert rows[wr] <= ROW_TOL, (wr, rows[wr])
     over = [k for k, v in errs.items() if v > TOL["bf16"]]
     if over:
         rounded = oracle_run(cfg, params, X, G, 8, "bf16-compute")
