@@ -138,7 +138,7 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(NormArgs n) {
     const int64_t roff = (int64_t)row * n.d;
     const T* dout = (const T*)n.dout + roff;
     const float mean = n.stats[2 * row], rstd = n.stats[2 * row + 1];
-    float xh[NORM_MAXCH][V], dxh[NORM_MAXCH][V];
+    float xh[NORM_MAXCH][V], dxh[NORM_MAXCH][V], res[NORM_MAXCH][V];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int c = 0; c < NORM_MAXCH; ++c) {
@@ -147,6 +147,7 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(NormArgs n) {
         float tx[V];
         ld_row<T>(tx, n.x, roff + vi * V, n.x_f32);
         Vec<T> td = ldv(dout + vi * V);
+        if (n.resid) ld_row<T>(res[c], n.resid, roff + vi * V, n.resid_f32);     // in flight during the row reductions
 #pragma unroll
         for (int e = 0; e < V; ++e) {
           const float xhat = (tx[e] - mean) * rstd;
@@ -167,12 +168,11 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(NormArgs n) {
     for (int c = 0; c < NORM_MAXCH; ++c) {
       const int vi = threadIdx.x + c * NORM_THREADS;
       if (vi < nvec) {
-        float r[V], o[V];
-        if (n.resid) ld_row<T>(r, n.resid, roff + vi * V, n.resid_f32);
+        float o[V];
 #pragma unroll
         for (int e = 0; e < V; ++e) {
           float v = (dxh[c][e] - m1 - xh[c][e] * m2) * rstd;
-          if (n.resid) v += r[e];
+          if (n.resid) v += res[c][e];
           o[e] = v;
         }
         st_row<T>(n.out, roff + vi * V, o, n.out_f32);
