@@ -12,7 +12,7 @@ bandwidth occupancy model (section 4.2.3), the alpha-beta communication model
 (section 2.2) and the performance model of section 3.5 (start of a block =
 max(end of the previous block on its stage, end of the block it depends on +
 communication delay)).  The paper states the heuristic in prose only; the
-readings taken here (also listed in the design doc):
+readings taken here:
 
   * unidirectional pipeline, one model chunk per stage, stage == device;
     F(s,m) depends on F(s-1,m); D(s,m) on D(s+1,m) (on F(s,m) for the last
