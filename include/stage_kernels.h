@@ -43,6 +43,14 @@ int stage_kernel_gemm(int dtype, int mode, int M, int N, int K, const void* A, i
 int stage_kernel_gemm_act(int dtype, int act, int M, int f, int K, const void* A, int64_t lda, const void* B, int64_t ldb,
                           void* Z, int64_t ldz, void* Aout, int64_t lda_out, int kernel_set, void* hip_stream);
 
+/* The input-gradient product of the FFN-out map with the activation backward (part of a chunk's B block): da = dY.W^T with
+ * W [f, K] (the map's weight, [in, out]), then Z [M, f] (GELU) or [M, 2f] (SwiGLU, gate | up) is overwritten by
+ * dZ = da * gelu'(Z), or dgate = da * up * silu'(gate), dup = da * silu(gate).  The tuned kernel does this in the
+ * product's epilogue on the fp32 accumulators (da is never stored; da_scratch may be NULL); the plain kernels (kernel_set
+ * 1, or fp32) store da [M, f] in da_scratch and run the activation kernel, which needs ldz = f or 2f. */
+int stage_kernel_gemm_act_bwd(int dtype, int act, int M, int f, int K, const void* dY, int64_t ldy, const void* W, int64_t ldw,
+                              void* Z, int64_t ldz, void* da_scratch, int kernel_set, void* hip_stream);
+
 /* n weight-gradient products (mode 2 above) in one call: C_p[M_p,N_p] += A_p^T . B_p for p = 0..n-1, the separately
  * schedulable W block of the paper's Appendix B for several linear maps at once.  All array arguments are HOST arrays of
  * length n (the pointers in A, B, C are device pointers); the C_p must not overlap.  Results are bit-identical to n calls

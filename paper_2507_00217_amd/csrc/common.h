@@ -31,6 +31,11 @@ struct GemmArgs {
   void* C2; int64_t ldc2;        // [M, f] in the compute dtype
   const void* bias;              // optional bias vector [N] in the compute dtype, added to every row of the product
                                  // (before the residual / activation); forward products only
+  // Fused activation backward (input-gradient product of the FFN-out map only, mode GEMM_NT): the product da = dY.Wout^T
+  // [M, N = f] is not stored; the kernel turns Z [M, f or 2f] (the stashed pre-activation) into dZ in place,
+  // dZ = da * gelu'(z), or (SwiGLU) dgate = da * up * silu'(gate), dup = da * silu(gate).  C is unused.
+  int act_bwd;                   // 0 none; 1 GELU; 2 SwiGLU
+  void* Z; int64_t ldz;
 };
 
 struct AttnArgs {

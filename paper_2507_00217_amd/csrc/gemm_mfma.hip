@@ -43,7 +43,7 @@ constexpr int TILE_SLOTS = TILE_BYTES / 16;                  // 16-byte pieces: 
 constexpr size_t LDS_BYTES = (size_t)4 * TILE_BYTES;         // A,B x 2 buffers = 128 KiB
 static_assert(BM == BN, "both operand tiles share one geometry");
 
-enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_ACC32 = 2, EPI_GELU = 3, EPI_SWIGLU = 4 };
+enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_ACC32 = 2, EPI_GELU = 3, EPI_SWIGLU = 4, EPI_DGELU = 5, EPI_DSWIGLU = 6 };
 // EPI_SWIGLU: a tile covers GLU_BN features j and holds, side by side in 32-column blocks, the gate columns j and
 // the up columns f + j of the product (even blocks gate, odd blocks up), so that a lane's two accumulator blocks are
 // the gate and the up value of the same 32 features and silu(gate) * up is formed in registers.
@@ -355,6 +355,79 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
         }
       }
   }
+  if (EPI == EPI_DGELU || EPI == EPI_DSWIGLU) {
+    // Activation backward on the fp32 accumulators (da), in place over the stashed z: 128 rows of the tile at a time,
+    // their z columns (gate, and for SwiGLU up) come global -> LDS directly, whole rows, into the layout of the bf16
+    // staging above (row r's piece p at r*512 + ((p ^ (r & 31)) << 4), the up half 64 KiB further on); the wavefronts
+    // that hold those rows' accumulators rewrite their elements in LDS; everybody stores the rows back.
+    constexpr int NOP = EPI == EPI_DSWIGLU ? 2 : 1;              // z operands per row: gate (| up)
+    constexpr int HALF_B = 128 * 512;                            // one operand, 128 rows
+    constexpr int NLD = (128 * 32) / (WAVES * 64);               // 16-byte pieces per thread, operand and half
+    const int f = g.N;
+    const rsrc_words rsZ = raw_rsrc(g.Z, (unsigned)((((int64_t)(g.M - 1) * g.ldz) + NOP * f) * 2));
+    typedef __attribute__((address_space(3))) bf16x4* lds_b4;
+    for (int h = 0; h < WR; ++h) {
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();                 // main loop's last fragment reads / previous half's stores are done
+#pragma unroll
+      for (int o = 0; o < NOP; ++o)
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+          const int s = (j * WAVES + wave) * 64 + lane, r = s >> 5, p = (s & 31) ^ (r & 31);
+          const int row = m0 + h * 128 + r, col = n0 + p * 8;
+          const unsigned off = (row < g.M && col < f) ? (unsigned)(((int64_t)row * g.ldz + o * f + col) * 2) : OOB;
+          load_to_lds_b128(rsZ, (unsigned)(size_t)(smem + o * HALF_B + (j * WAVES + wave) * 1024), off);
+        }
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      if (wm == h * 128) {             // wave-uniform: this wavefront's rows are the ones in LDS
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = i * 32 + row_l;
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int p = (wn + j * 32 + q * 8) >> 3;
+              lds_char* at = smem + r * 512 + ((p ^ (r & 31)) << 4) + (lane >> 5) * 8;
+              if (EPI == EPI_DGELU) {
+                bf16x4 u = *(lds_b4)at, o4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const float uv = (float)u[e];
+                  const float dgl = 0.5f * (1.f + erff(uv * 0.70710678118654752f)) + uv * 0.39894228040143268f * __expf(-0.5f * uv * uv);
+                  o4[e] = (bf16)(acc[i][j][q * 4 + e] * dgl);
+                }
+                *(lds_b4)at = o4;
+                __builtin_amdgcn_sched_barrier(0);
+              } else {
+                bf16x4 gt = *(lds_b4)at, up = *(lds_b4)(at + HALF_B), og, ou;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const float gv = (float)gt[e], uv = (float)up[e], d = acc[i][j][q * 4 + e];
+                  const float sg = 1.f / (1.f + __expf(-gv));
+                  og[e] = (bf16)(d * uv * (sg + gv * sg * (1.f - sg)));
+                  ou[e] = (bf16)(d * gv * sg);
+                }
+                *(lds_b4)at = og;
+                *(lds_b4)(at + HALF_B) = ou;
+              }
+            }
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int o = 0; o < NOP; ++o)
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+          const int s = (j * WAVES + wave) * 64 + lane, r = s >> 5, p = s & 31;      // lane order = column order: whole rows
+          const int row = m0 + h * 128 + r, col = n0 + p * 8;
+          const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(smem + o * HALF_B + r * 512 + ((p ^ (r & 31)) << 4));
+          if (row < g.M && col < f) *reinterpret_cast<u32x4*>((bf16*)g.Z + (int64_t)row * g.ldz + o * f + col) = v;
+        }
+    }
+    return;
+  }
   if (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_SWIGLU) {
     // bf16 output: the 256 x 256 tile goes through LDS (exactly the 128 KiB the operand buffers held) so that the
     // global stores are whole 512-byte rows, 16 bytes per lane, instead of 16-byte fragments of 32 rows.  Row r's
@@ -550,7 +623,10 @@ int cu_count() {
 
 template <bool AKC, bool BKC, int EPI, int WR>
 hipError_t launch_tiles(const GemmArgs& g, hipStream_t s, int tiles_m, int tiles_n, int first, int n_wg) {
-  constexpr size_t LDS = (size_t)2 * (WR * 128 * BK * 2 + TILE_BYTES);
+  // two buffers of (A tile, B tile); the activation-backward epilogue stages 128 rows of z per operand (64 KiB each)
+  constexpr size_t LDS_MAIN = (size_t)2 * (WR * 128 * BK * 2 + TILE_BYTES);
+  constexpr size_t LDS_EPI = EPI == EPI_DSWIGLU ? 2 * 65536 : EPI == EPI_DGELU ? 65536 : 0;
+  constexpr size_t LDS = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
   auto kern = gemm_mfma_kernel<AKC, BKC, EPI, WAVE_COLS, WR>;
   static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
   if (attr != hipSuccess) return attr;
@@ -585,7 +661,7 @@ hipError_t launch(const GemmArgs& g, hipStream_t s, int shape) {
 bool gemm_mfma_supported(const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return false;
   auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
-  if (!al16(g.A) || !al16(g.B) || !al16(g.C) || (g.R && !al16(g.R))) return false;
+  if (!al16(g.A) || !al16(g.B) || (!g.act_bwd && !al16(g.C)) || (g.R && !al16(g.R))) return false;
   if (g.lda % 8 || g.ldb % 8 || g.ldc % 4 || (g.R && g.ldr % 4) || g.N % 8) return false;
   if (!g.acc_f32 && !g.c_f32 && g.ldc % 8) return false;   // bf16 C is stored 16 bytes at a time
   const int64_t lim = (int64_t)1 << 30;   // operand byte offsets are 32-bit buffer offsets below 2 GiB
@@ -593,6 +669,11 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   if (a_rows * g.lda >= lim || b_rows * g.ldb >= lim) return false;
   if (g.acc_f32 && (int64_t)g.M * g.ldc >= lim / 2) return false;   // C is read through a 32-bit byte offset too
   if (g.bias && (g.mode != GEMM_NN || ((uintptr_t)g.bias & 7))) return false;
+  if (g.act_bwd) {  // fused activation backward: input-gradient product of the FFN-out map only
+    if (g.mode != GEMM_NT || g.act || g.bias || g.R || g.c_f32 || g.acc_f32 || (g.act_bwd != 1 && g.act_bwd != 2) || !g.Z || !al16(g.Z) ||
+        g.ldz % 8 || g.ldz < (int64_t)g.act_bwd * g.N || (int64_t)g.M * g.ldz >= lim)
+      return false;
+  }
   if (g.act) {     // fused activation: forward FFN-in product only
     if (g.mode != GEMM_NN || g.R || g.c_f32 || g.acc_f32 || (g.act != 1 && g.act != 2) || !g.C2 || !al16(g.C2) || g.ldc2 % 8) return false;
     if (g.act == 2 && g.N % 16) return false;      // gate | up halves of whole 16-byte pieces
@@ -611,7 +692,10 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t s, int tile_shape) {
       if (g.act == 1) return launch<true, false, EPI_GELU>(g, s, tile_shape);
       if (g.act == 2) return launch<true, false, EPI_SWIGLU>(g, s, tile_shape);
       return (g.R || g.c_f32) ? launch<true, false, EPI_RESID>(g, s, tile_shape) : launch<true, false, EPI_STORE>(g, s, tile_shape);
-    case GEMM_NT: return launch<true, true, EPI_STORE>(g, s, tile_shape);
+    case GEMM_NT:
+      if (g.act_bwd == 1) return launch<true, true, EPI_DGELU>(g, s, tile_shape);
+      if (g.act_bwd == 2) return launch<true, true, EPI_DSWIGLU>(g, s, tile_shape);
+      return launch<true, true, EPI_STORE>(g, s, tile_shape);
     case GEMM_TN: return launch<false, false, EPI_ACC32>(g, s, tile_shape);
   }
   return hipErrorInvalidValue;

@@ -316,6 +316,19 @@ bool try_gemm_act(stage* st, int* rc, int M, int f, int K, const void* A, const 
   return true;
 }
 
+// The FFN-out map's input-gradient product with the activation backward fused into its epilogue: z becomes dz in place
+// and da = dy.Wout^T never reaches memory.  False (nothing enqueued) when the tuned kernel does not apply.
+bool try_gemm_act_bwd(stage* st, int* rc, int M, int f, int K, const void* dy, const void* W, void* z) {
+  const int nop = st->cfg.act == STAGE_ACT_SWIGLU ? 2 : 1;
+  GemmArgs g{GEMM_NT, M, f, K, dy, (int64_t)K, W, (int64_t)K, nullptr, (int64_t)f, nullptr, 0, 0, 0, 0};
+  g.act_bwd = nop; g.Z = z; g.ldz = (int64_t)nop * f;
+  if (st->kernel_set != 0 || st->dt != DT_BF16 || !gemm_mfma_supported(g)) return false;
+  ProfScope ps(st, STAGE_K_GEMM_NT, 2.0 * M * f * K);
+  *rc = STAGE_OK;
+  if (gemm_mfma(g, st->stream) != hipSuccess) { st->sticky = STAGE_E_HIP; *rc = STAGE_E_HIP; }
+  return true;
+}
+
 // Where one layer's tensors of one microbatch live.
 struct LayerBuf { char *x, *n1, *qkv, *dqkv, *o, *x1, *n2, *z, *a, *dyb, *dx1b; float *st1, *st2, *lse; };
 
@@ -439,10 +452,14 @@ int exec_backward_input(stage* st, int mb, const void* dy, void* dx, int l0, int
     };
     if ((rc = dbias(dy_op, D.d, STAGE_P_BOUT))) return rc;
     // FFN: da = dy.Wout^T ; dz = act'(z) * da (in place over z) ; dn2 = dz.Win^T
-    rc = do_gemm(st, GEMM_NT, D.T, D.f, D.d, dy_op, D.d, W.wout, D.d, da, D.f, nullptr, 0, 0);
-    if (rc) return rc;
-    ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = o.z; ac.da = da;
-    { ProfScope ps(st, STAGE_K_ACT_BWD, (double)D.T * (2.0 * D.fin + D.f) * D.es); HIPCHK(act_bwd(st->dt, ac, st->stream)); }
+    if (try_gemm_act_bwd(st, &rc, D.T, D.f, D.d, dy_op, W.wout, o.z)) {
+      if (rc) return rc;
+    } else {
+      rc = do_gemm(st, GEMM_NT, D.T, D.f, D.d, dy_op, D.d, W.wout, D.d, da, D.f, nullptr, 0, 0);
+      if (rc) return rc;
+      ActArgs ac{}; ac.kind = st->cfg.act; ac.rows = D.T; ac.f = D.f; ac.z = o.z; ac.da = da;
+      { ProfScope ps(st, STAGE_K_ACT_BWD, (double)D.T * (2.0 * D.fin + D.f) * D.es); HIPCHK(act_bwd(st->dt, ac, st->stream)); }
+    }
     if ((rc = dbias(o.z, D.fin, STAGE_P_BIN))) return rc;
     rc = do_gemm(st, GEMM_NT, D.T, D.d, D.fin, o.z, D.fin, W.win, D.fin, dn, D.d, nullptr, 0, 0);
     if (rc) return rc;
@@ -975,6 +992,25 @@ int stage_kernel_gemm_act(int dtype, int act, int M, int f, int K, const void* A
   if (e != hipSuccess) return hip_rc(e);
   ActArgs ac{}; ac.kind = act; ac.rows = M; ac.f = f; ac.z = Z; ac.a = Aout;
   return hip_rc(act_fwd((DType)dtype, ac, (hipStream_t)hip_stream));
+}
+
+int stage_kernel_gemm_act_bwd(int dtype, int act, int M, int f, int K, const void* dY, int64_t ldy, const void* W, int64_t ldw,
+                              void* Z, int64_t ldz, void* da_scratch, int kernel_set, void* hip_stream) {
+  if (!dtype_ok(dtype) || (act != STAGE_ACT_GELU && act != STAGE_ACT_SWIGLU) || M <= 0 || f <= 0 || K <= 0 || !dY || !W || !Z)
+    return STAGE_E_INVAL;
+  const int nop = act == STAGE_ACT_SWIGLU ? 2 : 1;
+  if (ldy < K || ldw < K || ldz < (int64_t)nop * f) return STAGE_E_INVAL;
+  GemmArgs g{GEMM_NT, M, f, K, dY, ldy, W, ldw, nullptr, (int64_t)f, nullptr, 0, 0, 0, 0};
+  g.act_bwd = nop; g.Z = Z; g.ldz = ldz;
+  if (kernel_set != 1 && dtype == STAGE_DTYPE_BF16 && gemm_mfma_supported(g))
+    return hip_rc(gemm_mfma(g, (hipStream_t)hip_stream, kernel_set == 2 ? 1 : kernel_set == 3 ? 2 : 0));
+  // plain kernels: the product into the scratch, then the activation backward kernel (dense z rows)
+  if (!da_scratch || ldz != (int64_t)nop * f) return STAGE_E_INVAL;
+  g.act_bwd = 0; g.Z = nullptr; g.C = da_scratch;
+  const hipError_t e = gemm_ref((DType)dtype, g, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_rc(e);
+  ActArgs ac{}; ac.kind = act; ac.rows = M; ac.f = f; ac.z = Z; ac.da = da_scratch;
+  return hip_rc(act_bwd((DType)dtype, ac, (hipStream_t)hip_stream));
 }
 
 int stage_kernel_wgrad_group(int dtype, int n, const int* M, const int* N, const int* K, const void* const* A,

@@ -22,6 +22,7 @@ def L():
         vp, i, i64, fl = C.c_void_p, C.c_int, C.c_int64, C.c_float
         lib.stage_kernel_gemm.argtypes = [i, i, i, i, i, vp, i64, vp, i64, vp, i64, vp, i64, i, i, vp]
         lib.stage_kernel_gemm_act.argtypes = [i, i, i, i, i, vp, i64, vp, i64, vp, i64, vp, i64, i, vp]
+        lib.stage_kernel_gemm_act_bwd.argtypes = [i, i, i, i, i, vp, i64, vp, i64, vp, i64, vp, i, vp]
         lib.stage_kernel_wgrad_group.argtypes = [i, i] + [vp] * 9 + [i, vp]
         lib.stage_kernel_rope_table.argtypes = [i, i, fl, vp, vp]
         lib.stage_kernel_rope.argtypes = [i, i, i, i, i, i, vp, i64, vp, vp]
@@ -128,6 +129,35 @@ def test_gemm_with_fused_activation(dtype, kernel_set, act, M, f, K):
         assert np.mean(to_np(Aout) == a_once) > 0.97
     assert L().stage_kernel_gemm_act(DT[dtype], 5, M, f, K, P(Ad), K, P(Bd), fin, P(Zd), fin, P(Aout), f, kernel_set, None) == -1
     assert L().stage_kernel_gemm_act(DT[dtype], kind, M, f, K, P(Ad), K, P(Bd), fin, None, fin, P(Aout), f, kernel_set, None) == -1
+
+
+@pytest.mark.parametrize("dtype,kernel_set", [("fp32", 0), ("bf16", 0), ("bf16", 1), ("bf16", 2), ("bf16", 3)])
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+@pytest.mark.parametrize("M,f,K", [(128, 256, 128), (200, 192, 192), (328, 1088, 512), (257, 1408, 64), (512, 64, 256), (1024, 704, 320)])
+def test_gemm_with_fused_activation_backward(dtype, kernel_set, act, M, f, K):
+    """The FFN-out map's input-gradient product and the activation backward in one call: Z becomes dZ in place, against
+    the oracle's act_backward of the exact product.  Ragged tiles in every dimension; both tile shapes."""
+    import torch
+    kind = {"gelu": 0, "swiglu": 1}[act]
+    fin = 2 * f if act == "swiglu" else f
+    dY = rnd(synth.normal(9, 1, (M, K)), dtype); Wm = rnd(synth.normal(9, 2, (f, K), std=1.5 / math.sqrt(K)), dtype)
+    Z = rnd(synth.normal(9, 3, (M, fin), std=1.5), dtype)
+    sh = so.Shape(1, 64, 1, 1, f, 1, 1, act=act)
+    da_ref = dY.astype(np.float64) @ Wm.astype(np.float64).T
+    dz_ref = so.act_backward(sh, Z.astype(np.float64), da_ref)
+    tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+    Zd, dYd, Wd = to_dev(Z, dtype), to_dev(dY, dtype), to_dev(Wm, dtype)
+    guard = torch.full((M, f), 7.0, dtype=tdt, device="cuda:0")
+    rc = L().stage_kernel_gemm_act_bwd(DT[dtype], kind, M, f, K, P(dYd), K, P(Wd), K, P(Zd), fin, P(guard), kernel_set, None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert so.max_rel_err(to_np(Zd), dz_ref) <= KTOL[dtype]
+    if dtype == "bf16" and kernel_set != 1:
+        assert bool((guard == 7.0).all())                  # the tuned kernel stores no da
+        dz_once = synth.round_bf16(dz_ref.astype(np.float32)).astype(np.float64)
+        assert np.mean(to_np(Zd) == dz_once) > 0.97        # one rounding: from the fp32 product, not from a rounded da
+    assert L().stage_kernel_gemm_act_bwd(DT[dtype], 3, M, f, K, P(Zd), K, P(Zd), K, P(Zd), fin, P(guard), kernel_set, None) == -1
+    assert L().stage_kernel_gemm_act_bwd(DT[dtype], kind, M, f, K, P(Zd), K, P(Zd), K, None, fin, P(guard), kernel_set, None) == -1
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
@@ -311,8 +341,9 @@ def test_norm(dtype, norm, rows, d):
     dgd, dbd = to_dev(dg0, "fp32"), to_dev(db0, "fp32")
     part = torch.zeros(L().stage_kernel_norm_partial_bytes(d) // 4, dtype=torch.float32, device="cuda:0")
     dxd = xd.clone()     # in place over x, as the stage uses it
-    assert L().stage_kernel_norm_bwd(DT[dtype], kind, rows, d, P(dxd), P(st), P(gd), P(to_dev(dout, dtype)),
-                                     P(to_dev(resid, dtype)), P(dxd), P(dgd), P(dbd), P(part), None) == 0
+    doutd, residd = to_dev(dout, dtype), to_dev(resid, dtype)      # named: the buffers must outlive the launch
+    assert L().stage_kernel_norm_bwd(DT[dtype], kind, rows, d, P(dxd), P(st), P(gd), P(doutd),
+                                     P(residd), P(dxd), P(dgd), P(dbd), P(part), None) == 0
     torch.cuda.synchronize()
     assert so.max_rel_err(to_np(dxd), dx_ref + resid) <= KTOL[dtype]
     assert so.max_rel_err(to_np(dgd) - dg0, dg_ref) <= (1e-5 if dtype == "fp32" else 2e-3)
@@ -336,7 +367,8 @@ def test_activation(dtype, act, rows, f):
     dz_ref = so.act_backward(sh, z64, da.astype(np.float64))
     zd = to_dev(z, dtype); ad = torch.zeros((rows, f), dtype=zd.dtype, device="cuda:0")
     assert L().stage_kernel_act_fwd(DT[dtype], kind, rows, f, P(zd), P(ad), None) == 0
-    assert L().stage_kernel_act_bwd(DT[dtype], kind, rows, f, P(zd), P(to_dev(da, dtype)), None) == 0
+    dad = to_dev(da, dtype)
+    assert L().stage_kernel_act_bwd(DT[dtype], kind, rows, f, P(zd), P(dad), None) == 0
     torch.cuda.synchronize()
     assert so.max_rel_err(to_np(ad), a_ref) <= KTOL[dtype]
     assert so.max_rel_err(to_np(zd), dz_ref) <= KTOL[dtype]
