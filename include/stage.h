@@ -32,10 +32,9 @@
  *   - Row-major everywhere.  A boundary tensor of one microbatch is
  *     [mb_size, seq, hidden] contiguous in the compute dtype (fp32 or bf16).
  *   - Threads: calls that use the same stage_t (or stages sharing one stash) must not
- *     overlap.  Different stages may be driven from different threads once each
- *     kind of kernel has been launched once in the process: the one-time
+ *     overlap.  Different stages may be driven from different threads; the one-time
  *     per-kernel set-up (raising a kernel's LDS limit, reading the CU count) is
- *     not synchronised.  One process drives one GPU.
+ *     done once, thread-safely.  One process drives one GPU.
  *   - Return value: 0 on success, a negative STAGE_E_* code otherwise.  A call
  *     that returns STAGE_E_INVAL / _ORDER / _STASH_FULL has enqueued nothing
  *     and changed no state.  STAGE_E_HIP (a failed launch) is sticky.

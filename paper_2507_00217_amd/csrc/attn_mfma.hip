@@ -840,20 +840,18 @@ hipError_t allow_lds(K kern, size_t bytes) {
 // 4-wavefront workgroups when 8-wavefront ones would number fewer than two per CU
 static bool fwd_narrow(const AttnArgs& a) {
   if (a.width) return a.width == 2;
-  static int n_cu = 0;
-  if (!n_cu) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
-      n_cu = 256;
-  }
+  static const int n_cu = [] {        // function-local statics: initialised once, thread-safely
+    int dev = 0, n = 0;
+    return (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+  }();
   const int64_t wide = (int64_t)a.b * a.h * ((a.s + fwd_bq(FWD_WIDE) - 1) / fwd_bq(FWD_WIDE));
   return wide < 2 * (int64_t)n_cu;
 }
 
 template <int HD, int NT>
 hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
-  static bool ready = false;
-  if (!ready) { hipError_t e = allow_lds(attn_fwd_kernel<HD, NT>, fwd_lds<HD>()); if (e != hipSuccess) return e; ready = true; }
+  static const hipError_t ready = allow_lds(attn_fwd_kernel<HD, NT>, fwd_lds<HD>());
+  if (ready != hipSuccess) return ready;
   const int nqt = (a.s + fwd_bq(NT) - 1) / fwd_bq(NT);
   hipLaunchKernelGGL((attn_fwd_kernel<HD, NT>), dim3(a.h, nqt, a.b), dim3(NT), fwd_lds<HD>(), s, a);
   return hipGetLastError();
@@ -865,20 +863,16 @@ hipError_t fwd_t(const AttnArgs& a, hipStream_t s) {
 
 template <int HD, int NT>
 hipError_t dq_launch(const AttnArgs& a, hipStream_t s) {
-  static bool ready = false;
-  if (!ready) { hipError_t e = allow_lds(attn_dq_kernel<HD, NT>, fwd_lds<HD>()); if (e != hipSuccess) return e; ready = true; }
+  static const hipError_t ready = allow_lds(attn_dq_kernel<HD, NT>, fwd_lds<HD>());
+  if (ready != hipSuccess) return ready;
   hipLaunchKernelGGL((attn_dq_kernel<HD, NT>), dim3(a.h, (a.s + fwd_bq(NT) - 1) / fwd_bq(NT), a.b), dim3(NT), fwd_lds<HD>(), s, a);
   return hipGetLastError();
 }
 
 template <int HD>
 hipError_t bwd_t(const AttnArgs& a, hipStream_t s) {
-  static bool ready = false;
-  if (!ready) {
-    hipError_t e = allow_lds(attn_dkv_kernel<HD>, dkv_lds<HD>());
-    if (e != hipSuccess) return e;
-    ready = true;
-  }
+  static const hipError_t ready = allow_lds(attn_dkv_kernel<HD>, dkv_lds<HD>());
+  if (ready != hipSuccess) return ready;
   {      // dQ first: it also leaves delta = rowsum(dO * O) in a.delta for the dK/dV pass
     const hipError_t e = fwd_narrow(a) ? dq_launch<HD, FWD_NARROW>(a, s) : dq_launch<HD, FWD_WIDE>(a, s);
     if (e != hipSuccess) return e;
