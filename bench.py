@@ -302,12 +302,12 @@ def main():
         # what the matrix cores alone sustain on this GPU (no memory or LDS traffic): with random operands the shader
         # clock settles well below its nominal value, so a kernel on real data cannot reach the published peak
         torch.cuda.synchronize()
-        rnd, rnd_mhz = S.probe_mfma_ceiling(True, 400000)      # ~0.25 s: long enough for the clock to settle
-        cst, cst_mhz = S.probe_mfma_ceiling(False, 100000)
+        rnd, rnd_mhz = S.probe_mfma_ceiling(True, 200000)      # ~0.25 s: long enough for the clock to settle
+        cst, cst_mhz = S.probe_mfma_ceiling(False, 50000)
         out["mfma_ceiling"] = {"random_operands": {"tflops": round(rnd, 1), "shader_mhz": round(rnd_mhz)},
                                "constant_operands": {"tflops": round(cst, 1), "shader_mhz": round(cst_mhz)},
                                "roofline_achieved_over_random_ceiling": round(achieved / rnd, 4),
-                               "note": "back-to-back v_mfma_f32_32x32x16_bf16 on every CU, 2 wavefronts per SIMD, operands in "
+                               "note": "back-to-back v_mfma_f32_16x16x32_bf16 (the GEMM's instruction) on every CU, 2 wavefronts per SIMD, operands in "
                                        "registers; measured after the timed region"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)

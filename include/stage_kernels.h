@@ -112,7 +112,7 @@ int stage_kernel_act_fwd(int dtype, int act, int rows, int f, const void* z, voi
 int stage_kernel_act_bwd(int dtype, int act, int rows, int f, void* z, const void* da, void* hip_stream);
 
 /* Measurement aid (not an operation of the paper): runs nothing but back-to-back bf16 MFMAs on every compute unit for
- * `iters` (1 .. 2^22) rounds of 16 per wavefront and reports the rate reached and the shader clock held meanwhile.
+ * `iters` (1 .. 2^22) rounds of 32 v_mfma_f32_16x16x32_bf16 per wavefront and reports the rate reached and the shader clock held meanwhile.
  * random_operands = 0 uses the constant 1.0, != 0 uniform values in [-1, 1): the clock, and with it the rate a kernel
  * can approach on real data, depends on the operands.  scratch_dev: device memory of at least 16 + 2048 * (number of
  * compute units) bytes, 16-byte aligned (1 MiB covers any gfx950 part); its contents afterwards are meaningless.

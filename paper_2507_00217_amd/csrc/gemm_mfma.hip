@@ -6,26 +6,31 @@
 //   TN  C[M,N] += A[K,M]^T . B[K,N]   (fp32)   wgrad,    A^T.dZ
 //
 // Design: 256x256x64 macro tile per workgroup, 8 wavefronts (2x4, two per SIMD),
-// each owning a 128x64 sub-tile as 4x2 v_mfma_f32_32x32x16_bf16 accumulators
-// (128 fp32 registers per lane).  Operand tiles travel global -> LDS directly
+// each owning a 128x64 sub-tile as 8x4 v_mfma_f32_16x16x32_bf16 accumulators
+// (128 fp32 registers per lane; on random data this MFMA shape sustains a higher
+// rate than 32x32x16 -- the chip is power-limited there and it moves half as many
+// accumulator registers per flop).  Operand tiles travel global -> LDS directly
 // (buffer loads with the LDS bit: no staging registers, no ds_write instructions,
-// hardware range check gives the zero fill at the edges), two LDS buffers, one
-// barrier per K tile, the next-but-one tile in flight; fragments are
-// double-buffered in registers and the loop body is an explicit 4-stage software
-// pipeline.  Such a load writes each wavefront's 64 x 16 bytes to consecutive
-// LDS addresses, so the tiles are unpadded and bank conflicts are avoided by
-// choosing WHICH 16-byte piece each lane fetches (an XOR swizzle of the piece
-// index).  An operand whose reduction index is contiguous in memory sits in LDS
-// as [row][k] and is read with 16-byte loads; an operand whose reduction index is
-// the slow one sits as [k][row] and is read with ds_read_b64_tr_b16, the LDS
-// transpose load, so no layout needs a transposing copy.  The MFMA is issued with
-// the operands swapped (computes the transposed 32x32 block), which leaves every
-// lane with 4 consecutive columns of one row: 8-byte bf16 / 16-byte fp32 epilogue
-// accesses.  Workgroup ids are remapped so that each XCD (own L2) works on a
-// compact band of tiles.  A 128x256 half-height tile (4 wavefronts) takes over
-// where full tiles would keep at most half of the CUs busy: the last round of a
-// product, or a product with few tiles.
+// hardware range check gives the zero fill at the edges) into a ring of five
+// 32 KiB slots that the A and B tiles of the reduction take in turn: one barrier
+// per K tile, loads issued at an even rate of one operand tile per k-step, a few
+// MFMAs apart, each with at least half a K tile's time to land; fragments are
+// double-buffered in registers and the loop body is an explicit two-stage
+// software pipeline without branches.  Such a load writes each wavefront's
+// 64 x 16 bytes to consecutive LDS addresses, so the tiles are unpadded and bank
+// conflicts are avoided by choosing WHICH 16-byte piece each lane fetches (an XOR
+// swizzle of the piece index).  An operand whose reduction index is contiguous in
+// memory sits in LDS as [row][k] and is read with 16-byte loads; an operand whose
+// reduction index is the slow one sits as [k][row] and is read with
+// ds_read_b64_tr_b16, the LDS transpose load, so no layout needs a transposing
+// copy.  The MFMA is issued with the operands swapped (computes the transposed
+// 16x16 block), which leaves every lane with 4 consecutive columns of one row:
+// 8-byte bf16 / 16-byte fp32 epilogue accesses.  Workgroup ids are remapped so
+// that each XCD (own L2) works on a compact band of tiles.  A 128x256 half-height
+// tile (4 wavefronts) takes over where full tiles would keep at most half of the
+// CUs busy: the last round of a product, or a product with few tiles.
 #include "common.h"
+#include <type_traits>
 
 namespace stg {
 
@@ -40,7 +45,8 @@ namespace {
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int TILE_BYTES = BM * BK * 2;                      // one operand tile, either layout: 32 KiB
 constexpr int TILE_SLOTS = TILE_BYTES / 16;                  // 16-byte pieces: 2048
-constexpr size_t LDS_BYTES = (size_t)4 * TILE_BYTES;         // A,B x 2 buffers = 128 KiB
+constexpr int SLOT = TILE_BYTES, NSLOT = 5;                  // ring of operand tiles in LDS
+constexpr size_t LDS_BYTES = (size_t)NSLOT * SLOT;           // 160 KiB
 static_assert(BM == BN, "both operand tiles share one geometry");
 
 enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_ACC32 = 2, EPI_GELU = 3, EPI_SWIGLU = 4, EPI_DGELU = 5, EPI_DSWIGLU = 6 };
@@ -60,10 +66,12 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, un
 
 // LDS placement of a tile's 16-byte pieces ("slots", slot s at byte 16*s):
 //   [row][k] layout (KC, reduction index contiguous in memory): row r = 8 pieces; piece c (8 k's) of row r sits in
-//     slot 8*r + (c ^ ((r >> 1) & 7)).  A fragment read takes piece c of 32 consecutive rows per half-wave: 16
-//     consecutive rows hit 16 different 16-byte bank groups.
-//   [k][row] layout: reduction row k = 32 pieces of 8 rows; piece p sits in slot 32*k + (p ^ ((k & 3) << 2)).  A
-//     transpose read takes 64 bytes from each of 4 consecutive k rows, which land in 4 different 64-byte bank groups.
+//     slot 8*r + (c ^ ((r >> 1) & 7)).  A fragment read takes piece c of 16 consecutive rows per quarter-wave, which
+//     hit 16 different 16-byte bank groups.
+//   [k][row] layout: reduction row k = 32 pieces of 8 rows; piece p sits in slot 32*k + (p ^ swz(k)),
+//     swz(k) = ((k & 3) << 2) | (((k >> 3) & 1) << 1).  A transpose read by 16 lanes takes 32 bytes from each of 4
+//     consecutive k rows, which land in 4 different 64-byte bank groups; the next 16 lanes read 8 rows further on,
+//     which the second term moves to the other 32 bytes of those groups.
 // Per-thread global byte offsets at k = 0 of the pieces it fetches: load j of wavefront w fills slots
 // (j*8 + w)*64 .. +63, lane l the l-th of them.  Rows past the end of the matrix fall outside the buffer's range
 // by themselves or are redirected to OOB, which stores zeros.
@@ -81,7 +89,7 @@ __device__ __forceinline__ void tile_offsets(unsigned (&off)[CH], int64_t ld, in
       const int r = s >> 3, c = (s & 7) ^ ((r >> 1) & 7);
       off[j] = row0 + r < rows ? (unsigned)(((int64_t)(row0 + r) * ld + c * 8) * 2) : OOB;
     } else {
-      const int k = s >> 5, p = (s & 31) ^ ((k & 3) << 2);
+      const int k = s >> 5, p = (s & 31) ^ (((k & 3) << 2) | (((k >> 3) & 1) << 1));
       int row = row0 + p * 8;
       bool ok = row < rows;
       if (glu_f) {
@@ -124,38 +132,39 @@ __device__ __forceinline__ void g2s(lds_char* tile, rsrc_words rsrc, const unsig
   for (int j = 0; j < CH; ++j) g2s_one<KC, WAVES, CH>(tile, rsrc, off, ld, k0, wave, j);
 }
 
-// Per-lane LDS byte offsets (inside one operand tile) from which the fragments of a 32-row block are read.
-// Fragment = 32(row) x 16(k): lane l holds row l%32, k = (l/32)*8 .. +7.
-//   KC:  ad[ks], ks = k-step 0..3; block b of 32 rows adds 4096 bytes (the swizzle repeats every 16 rows)
-//   else ad[b & 3], b = 32-row block index inside the tile; k-step ks adds 16 reduction rows = 8192 bytes; the
+// Per-lane LDS byte offsets (inside one operand tile) from which the fragments of a 16-row block are read.
+// Fragment = 16(row) x 32(k): lane l holds row l%16, k = (l/16)*8 .. +7.
+//   KC:  ad[ks], ks = k-step 0..1; block b of 16 rows adds 2048 bytes (the swizzle repeats every 16 rows)
+//   else ad[b], b = 16-row block index counted from row0; k-step ks adds 32 reduction rows = 16384 bytes; the
 //        transpose load: in a 16-lane group, lane i addresses row (i/4) of a 4(k) x 16(row) block at column 4*(i%4)
-//        and receives column i of the block, i.e. 4 consecutive k for its own row
-template <bool KC>
-__device__ __forceinline__ void frag_offsets(unsigned (&ad)[4], int row0, int lane) {
+//        and receives column i of the block, i.e. 4 consecutive k for its own row; the four groups of a wavefront
+//        take the reduction rows g*8 .. g*8+3 (and, in a second load, 4 rows further on)
+template <bool KC, int NB>
+__device__ __forceinline__ void frag_offsets(unsigned (&ad)[NB], int row0, int lane) {
   if (KC) {
-    const int r = row0 + (lane & 31), sw = (r >> 1) & 7, h = lane >> 5;
+    const int r = row0 + (lane & 15), sw = (r >> 1) & 7, h = lane >> 4;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) ad[ks] = (unsigned)((r * 8 + ((2 * ks + h) ^ sw)) * 16);
+    for (int ks = 0; ks < 2; ++ks) ad[ks] = (unsigned)((r * 8 + ((4 * ks + h) ^ sw)) * 16);
   } else {
     const int g = lane >> 4, li = lane & 15;
-    const int krow = (g >> 1) * 8 + (li >> 2), swv = (li >> 2) & 3;           // krow & 3 == swv
-    const int piece_lo = (g & 1) * 2 + ((li & 3) >> 1);                        // 16-byte piece inside the 32-row block
+    const int krow = g * 8 + (li >> 2);
+    const int sw = ((krow & 3) << 2) | (((krow >> 3) & 1) << 1);
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int blk = (row0 >> 5) + b;                                        // 32-row block index; row0 % 128 == 0 or b < 2
-      ad[b] = (unsigned)(krow * 512 + ((((blk & ~3) | ((blk ^ swv) & 3)) << 2) + piece_lo) * 16 + (li & 1) * 8);
+    for (int b = 0; b < NB; ++b) {
+      const int p = ((row0 >> 4) + b) * 2 + ((li & 3) >> 1);                   // 16-byte piece of the reduction row
+      ad[b] = (unsigned)(krow * 512 + (p ^ sw) * 16 + (li & 1) * 8);
     }
   }
 }
 
 // `pt`: the tile's LDS address plus the offsets above
-template <bool KC>
-__device__ __forceinline__ bf16x8 frag(lds_char* const (&pt)[4], int b, int ks) {
+template <bool KC, int NB>
+__device__ __forceinline__ bf16x8 frag(lds_char* const (&pt)[NB], int b, int ks) {
   if (KC) {
-    return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(pt[ks] + b * 4096);
+    return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(pt[ks] + b * 2048);
   } else {
     typedef s16x4 __attribute__((address_space(3))) * lds_p;
-    lds_char* p = pt[b] + ks * 8192;
+    lds_char* p = pt[b] + ks * 16384;
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
     s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * 512));
     union { struct { s16x4 a, b; } s; bf16x8 v; } u;
@@ -164,8 +173,8 @@ __device__ __forceinline__ bf16x8 frag(lds_char* const (&pt)[4], int b, int ks) 
   }
 }
 
-// TN = 32-column accumulator blocks per wavefront: 2 -> 8 wavefronts of 128x64 (two per SIMD, 128 accumulator
-// registers each), 4 -> 4 wavefronts of 128x128 (one per SIMD, 256 accumulator registers, a third less LDS read traffic)
+// TN = 32-column groups per wavefront: 2 -> 8 wavefronts of 128x64 (two per SIMD, 128 accumulator registers each),
+// 4 -> 4 wavefronts of 128x128 (one per SIMD, 256 accumulator registers, a third less LDS read traffic)
 // K segments: the reduction may run over `nseg` operand pairs of equal shape, pair s being (A, B) moved by
 // seg_delta[s] bytes (seg_delta[0] == 0): C (+)= sum_s A_s . B_s with the K tiles taken in order s = 0, 1, ...  One
 // pass over K then does the work of nseg launches with a single read-modify-write of C, and -- fp32 accumulators
@@ -178,10 +187,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
                                           const int64_t* seg_delta = nullptr) {
   static_assert(WR == 2 || (WR == 1 && AKC), "the half-height tile takes a [row][k] A operand");
   constexpr bool GLU = EPI == EPI_SWIGLU;
-  static_assert(!GLU || (TN == 2 && !BKC), "gate and up blocks are a wavefront's two accumulator columns");
+  static_assert(!GLU || (TN == 2 && !BKC), "gate and up blocks are the two halves of a wavefront's columns");
   constexpr int WGN = 8 / TN, WAVES = WR * WGN;
   constexpr int BMV = WR * 128, A_BYTES = BMV * BK * 2;                            // A tile: BMV rows
   constexpr int CHA = (A_BYTES / 16) / (WAVES * 64), CHB = TILE_SLOTS / (WAVES * 64); // loads per thread and K tile
+  constexpr int NI = 8, NJ = 2 * TN;                                               // 16 x 16 accumulator blocks per wavefront
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / WGN) * 128, wn = (wave % WGN) * (TN * 32);
@@ -190,175 +200,172 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   const unsigned bytesA = (unsigned)(((int64_t)((AKC ? g.M : g.K) - 1) * g.lda + (AKC ? g.K : g.M)) * 2);
   const unsigned bytesB = (unsigned)(((int64_t)((BKC ? g.N : g.K) - 1) * g.ldb + (BKC ? g.K : g.N)) * 2);
   rsrc_words rsA = raw_rsrc(g.A, bytesA), rsB = raw_rsrc(g.B, bytesB);
-  // where the next K tile to fetch lies: segment and reduction offset inside it (all wave-uniform)
-  int ld_seg = 0, ld_k = 0;
-  auto advance = [&]() {
-    ld_k += BK;
-    if (ld_k >= g.K && ld_seg + 1 < nseg) {
-      ld_k = 0;
-      ++ld_seg;
-      rsA = raw_rsrc((const char*)g.A + seg_delta[ld_seg], bytesA);
-      rsB = raw_rsrc((const char*)g.B + seg_delta[ld_seg], bytesB);
-    }
-  };
   unsigned offa[CHA], offb[CHB];
   tile_offsets<AKC, WAVES, CHA>(offa, g.lda, m0, g.M, wave, lane);
   tile_offsets<BKC, WAVES, CHB>(offb, g.ldb, n0, g.N, wave, lane, GLU ? g.N / 2 : 0);
 
-  // LDS map: buffer u at byte u * BUF_BYTES, A tile first, then B tile
-  constexpr int BUF_BYTES = A_BYTES + TILE_BYTES;
+  // LDS map: a ring of NSLOT slots of one operand tile each; the operand tiles of the reduction take the slots in the
+  // order A0 B0 A1 B1 A2 ..., tile number i (A_t = 2t, B_t = 2t + 1) sitting in slot i % NSLOT.
   const int nk = ((g.K + BK - 1) / BK) * nseg;
-  g2s<AKC, WAVES, CHA>(smem, rsA, offa, g.lda, 0, wave);
-  g2s<BKC, WAVES, CHB>(smem + A_BYTES, rsB, offb, g.ldb, 0, wave);
-  advance();
+  // where the next tile of each operand to fetch lies: segment and reduction offset inside it (all wave-uniform)
+  int segA = 0, kA = 0, segB = 0, kB = 0;
+  auto advanceA = [&]() {
+    kA += BK;
+    if (EPI == EPI_ACC32 && kA >= g.K && segA + 1 < nseg) { kA = 0; ++segA; rsA = raw_rsrc((const char*)g.A + seg_delta[segA], bytesA); }
+  };
+  auto advanceB = [&]() {
+    kB += BK;
+    if (EPI == EPI_ACC32 && kB >= g.K && segB + 1 < nseg) { kB = 0; ++segB; rsB = raw_rsrc((const char*)g.B + seg_delta[segB], bytesB); }
+  };
+  // start-up: A0 B0 A1 B1, as far as they exist
+  g2s<AKC, WAVES, CHA>(smem, rsA, offa, g.lda, kA, wave);
+  advanceA();
+  g2s<BKC, WAVES, CHB>(smem + SLOT, rsB, offb, g.ldb, kB, wave);
+  advanceB();
   if (nk > 1) {
-    g2s<AKC, WAVES, CHA>(smem + BUF_BYTES, rsA, offa, g.lda, ld_k, wave);
-    g2s<BKC, WAVES, CHB>(smem + BUF_BYTES + A_BYTES, rsB, offb, g.ldb, ld_k, wave);
-    advance();
+    g2s<AKC, WAVES, CHA>(smem + 2 * SLOT, rsA, offa, g.lda, kA, wave);
+    advanceA();
+    g2s<BKC, WAVES, CHB>(smem + 3 * SLOT, rsB, offb, g.ldb, kB, wave);
+    advanceB();
   }
 
+  // acc[i][j][e] = C[m0 + wm + i*16 + lane%16][n0 + wn + j*16 + (lane/16)*4 + e]: the MFMA is issued with the operands
+  // swapped, which leaves every lane with 4 consecutive columns of one row.
   // Accumulators start at zero, or -- weight gradients, C += A^T.B -- at the current value of C: the read half of
   // the read-modify-write then travels together with the first operand tiles instead of stalling the epilogue.
-  f32x16 acc[4][TN];
+  const int row_l = lane & 15, col_l = (lane >> 4) * 4;
+  f32x4 acc[NI][NJ];
   if (EPI == EPI_ACC32) {
     const __amdgpu_buffer_rsrc_t rsC = make_rsrc(g.C, (unsigned)(((int64_t)(g.M - 1) * g.ldc + g.N) * 4));
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = m0 + wm + i * 32 + (lane & 31);
+    for (int i = 0; i < NI; ++i) {
+      const int m = m0 + wm + i * 16 + row_l;
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + wn + j * 32 + q * 8 + (lane >> 5) * 4;
-          const unsigned off = (m < g.M && n < g.N) ? (unsigned)(((int64_t)m * g.ldc + n) * 4) : OOB;
-          const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsC, (int)off, 0, 0));
-          acc[i][j][q * 4] = v[0]; acc[i][j][q * 4 + 1] = v[1]; acc[i][j][q * 4 + 2] = v[2]; acc[i][j][q * 4 + 3] = v[3];
-        }
+      for (int j = 0; j < NJ; ++j) {
+        const int n = n0 + wn + j * 16 + col_l;
+        const unsigned off = (m < g.M && n < g.N) ? (unsigned)(((int64_t)m * g.ldc + n) * 4) : OOB;
+        acc[i][j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsC, (int)off, 0, 0));
+      }
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // fragment addresses in the buffer being read, and where the next loads go; both hop between the two buffers
-  lds_char *pa[4], *pb[4];
+  // fragment addresses in the slots being read
+  constexpr int NPA = AKC ? 2 : NI, NPB = BKC ? 2 : NJ;
+  lds_char *pa[NPA], *pb[NPB];
   {
-    unsigned ada[4], adb[4];
-    frag_offsets<AKC>(ada, wm, lane);
-    frag_offsets<BKC>(adb, wn, lane);
+    unsigned ada[NPA], adb[NPB];
+    frag_offsets<AKC, NPA>(ada, wm, lane);
+    frag_offsets<BKC, NPB>(adb, wn, lane);
 #pragma unroll
-    for (int x = 0; x < 4; ++x) { pa[x] = smem + ada[x]; pb[x] = smem + A_BYTES + adb[x]; }
+    for (int x = 0; x < NPA; ++x) pa[x] = smem + ada[x];
+#pragma unroll
+    for (int x = 0; x < NPB; ++x) pb[x] = smem + SLOT + adb[x];
   }
-  lds_char* fill = smem;      // buffer that the loads issued in this trip fill (wave-uniform)
-  int hop = BUF_BYTES;
+  int slotA = 0;               // slot of the A tile being read; its B tile sits in the next slot of the ring
 
-  // Software pipeline, one K tile (4 k-steps of 16) per trip, fragments double-buffered in registers:
-  //   S0  read frags k1 | MFMA k0            S2  read frags k3 | MFMA k2
-  //   S1  read frags k2 | MFMA k1            -- wait for tile t+1 to have landed; barrier --
-  //                                          S3  MFMA k3, and after each MFMA one fragment of k0 of tile t+1 and one
-  //                                              load of tile t+2 into the buffer just vacated
-  // At the barrier only tile t+1's loads are outstanding, hence vmcnt(0).
-  constexpr int NREADS = (AKC ? 4 : 8) + (BKC ? TN : 2 * TN);   // LDS read instructions per k-step
-  constexpr int NMFMA = 4 * TN;                                 // MFMAs per k-step
-  bf16x8 fa[2][4], fb[2][TN];
-#define LOAD_FRAGS(buf, ks_)                                                        \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) fa[buf][i] = frag<AKC>(pa, i, ks_); \
-  _Pragma("unroll") for (int j = 0; j < TN; ++j) fb[buf][j] = frag<BKC>(pb, j, ks_);
-#define MFMA_STEP(buf)                                                               \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
-  _Pragma("unroll") for (int j = 0; j < TN; ++j)                                     \
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
-  // scheduling hint: `n` instructions of class `mask`, spread evenly over the NMFMA MFMAs of a stage
-#define SPREAD(mask, n)                                                                              \
-  __builtin_amdgcn_sched_group_barrier(mask, (n) / 4, 0);                                            \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 4, 0);                                         \
-  __builtin_amdgcn_sched_group_barrier(mask, (2 * (n)) / 4 - (n) / 4, 0);                            \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 4, 0);                                         \
-  __builtin_amdgcn_sched_group_barrier(mask, (3 * (n)) / 4 - (2 * (n)) / 4, 0);                      \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 4, 0);                                         \
-  __builtin_amdgcn_sched_group_barrier(mask, (n) - (3 * (n)) / 4, 0);                                \
-  __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / 4, 0);
+  // Software pipeline, one K tile (2 k-steps of 32) per trip t, fragments double-buffered in registers:
+  //   S0  MFMA k0 | read frags k1 | A(t+2)'s loads
+  //   -- wait for A(t+1), B(t+1); barrier --
+  //   S1  MFMA k1 | frags k0 of tile t+1 | B(t+2)'s loads
+  // The barrier frees the two slots just read: B(t+2) goes into A(t)'s, A(t+3) -- half a trip later -- into B(t)'s.
+  // With five slots the loads are issued at an even rate, one operand tile per k-step and a few MFMAs apart, instead of
+  // all at once after the barrier (the CU's vector-memory path takes about half a trip to move a trip's 64 KiB, and a
+  // wavefront whose load does not fit the queue stands still, MFMAs included), and every load has half a trip or more
+  // to land.  Away from the end of the reduction the loop body has no branches.
+  constexpr int NMFMA = NI * NJ;                                // MFMAs per k-step
+  constexpr int NFRAG = NI + NJ;                                // fragments per k-step
+  static_assert(NMFMA % CHA == 0 && NMFMA % CHB == 0 && NMFMA >= 2 * NFRAG, "placement of loads and fragment reads");
+  bf16x8 fa[2][NI], fb[2][NJ];
+  // one k-step: the MFMAs on fragment set `cur`; after every second MFMA one fragment of `ks_next` into the other set
+  // (B's first: the first MFMAs of the next k-step need all of them); and the loads of operand tile `op` (0 = A, 1 = B)
+  // spread between the MFMAs
+  auto kstep = [&](auto cur_c, auto ks_c, auto op_c, auto tail_c, bool exists, lds_char* dst) __attribute__((always_inline)) {
+    constexpr int cur = decltype(cur_c)::value, ks_next = decltype(ks_c)::value, op = decltype(op_c)::value;
+    constexpr int NL = op ? CHB : CHA, GAP = NMFMA / NL;
+    const bool do_load = !decltype(tail_c)::value || exists;      // away from the end of the reduction every load exists: no branch
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        const int n = i * NJ + j;
+        if (n % 2 == 0 && n / 2 < NFRAG) {
+          const int f = n / 2;
+          if (f < NJ) fb[cur ^ 1][f] = frag<BKC, NPB>(pb, f, ks_next);
+          else fa[cur ^ 1][f - NJ] = frag<AKC, NPA>(pa, f - NJ, ks_next);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (n % GAP == GAP - 1 && do_load) {
+          const int l = n / GAP;
+          if (op == 0) g2s_one<AKC, WAVES, CHA>(dst, rsA, offa, g.lda, kA, wave, l);
+          else g2s_one<BKC, WAVES, CHB>(dst, rsB, offb, g.ldb, kB, wave, l);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+  };
+  std::integral_constant<int, 0> c0; std::integral_constant<int, 1> c1;
 
-  __builtin_amdgcn_s_waitcnt(0);   // tile 0 (and 1, and C for weight gradients) landed
+  __builtin_amdgcn_s_waitcnt(0);   // the start-up tiles (and C for weight gradients) landed
   __syncthreads();
-  LOAD_FRAGS(0, 0)
-  for (int kt = 0; kt < nk; ++kt) {
-    LOAD_FRAGS(1, 1)
-    MFMA_STEP(0)
-    SPREAD(0x100, NREADS)
-    __builtin_amdgcn_sched_barrier(0);
-    LOAD_FRAGS(0, 2)
-    MFMA_STEP(1)
-    SPREAD(0x100, NREADS)
-    __builtin_amdgcn_sched_barrier(0);
-    LOAD_FRAGS(1, 3)
-    MFMA_STEP(0)
-    SPREAD(0x100, NREADS)
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0);         // vmcnt(0) lgkmcnt(0): tile kt+1 has landed, own LDS reads are done
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) fb[0][j] = frag<BKC, NPB>(pb, j, 0);
+#pragma unroll
+  for (int i = 0; i < NI; ++i) fa[0][i] = frag<AKC, NPA>(pa, i, 0);
+  int kt = 0;
+  auto trip = [&](auto tail_c) __attribute__((always_inline)) {
+    // ring position (wave-uniform) of tile 2kt + 4 = A(kt+2); tile 2kt + 5 = B(kt+2) takes A(kt)'s slot
+    const int s4 = slotA + 4 >= NSLOT ? slotA + 4 - NSLOT : slotA + 4;
+    const bool more = kt + 2 < nk;
+    kstep(c0, c1, c0, tail_c, more, smem + s4 * SLOT);
+    if (!decltype(tail_c)::value || more) advanceA();
+    // A(kt+1), B(kt+1) have landed once nothing older than A(kt+2)'s loads is outstanding; own LDS reads are done
+    if (!decltype(tail_c)::value || more) __builtin_amdgcn_s_waitcnt(0x0070 | (CHA & 15) | ((CHA >> 4) << 14));
+    else __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
+    {
+      const int dA = (slotA >= NSLOT - 2 ? 2 - NSLOT : 2) * SLOT;
+      const int sB = slotA + 1 >= NSLOT ? slotA + 1 - NSLOT : slotA + 1;
+      const int dB = (sB >= NSLOT - 2 ? 2 - NSLOT : 2) * SLOT;
 #pragma unroll
-    for (int x = 0; x < 4; ++x) { pa[x] += hop; pb[x] += hop; }
-    // after every MFMA of this stage: one fragment of the next tile's first k-step (while there are any) and one
-    // tile load; the fences pin the order.  Right after the barrier every wavefront wants the LDS at once: with all
-    // of a wavefront's fragment reads ahead of its MFMAs the matrix core waits for the LDS queue.  Nothing is
-    // fetched past the last K tile.
-    const bool more = kt + 2 < nk;      // wave-uniform: a scalar branch around each load, none around an MFMA
+      for (int x = 0; x < NPA; ++x) pa[x] += dA;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        const int n = i * TN + j;         // 4*TN MFMAs, 4 + TN fragments, CHA + CHB <= 8*TN loads
-        if (n < 4) fa[0][n] = frag<AKC>(pa, n, 0);
-        else if (n < 4 + TN) fb[0][n - 4] = frag<BKC>(pb, n - 4, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (more) {
-#pragma unroll
-          for (int l = n; l < CHA + CHB; l += 4 * TN) {
-            if (l < CHA) g2s_one<AKC, WAVES, CHA>(fill, rsA, offa, g.lda, ld_k, wave, l);
-            else g2s_one<BKC, WAVES, CHB>(fill + A_BYTES, rsB, offb, g.ldb, ld_k, wave, l - CHA);
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    advance();
-    fill += hop;
-    hop = -hop;
-  }
-#undef LOAD_FRAGS
-#undef MFMA_STEP
-#undef SPREAD
+      for (int x = 0; x < NPB; ++x) pb[x] += dB;
+    }
+    kstep(c1, c0, c1, tail_c, more, smem + slotA * SLOT);     // (fragments past the last tile are read and not used)
+    if (!decltype(tail_c)::value || more) advanceB();
+    slotA = slotA + 2 >= NSLOT ? slotA + 2 - NSLOT : slotA + 2;
+  };
+  for (; kt + 2 < nk; ++kt) trip(std::false_type{});
+  for (; kt < nk; ++kt) trip(std::true_type{});
 
-  // epilogue: acc[i][j][e] = C[m][n],  m = m0+wm+i*32 + lane%32,  n = n0+wn+j*32 + (e/4)*8 + (lane/32)*4 + e%4
-  const int row_l = lane & 31, col_l = (lane >> 5) * 4;
+  // epilogue
   if (EPI != EPI_ACC32 && g.bias) {       // wave-uniform; the bias of a column goes to every row of it
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+    for (int j = 0; j < NJ; ++j) {
+      int n = n0 + wn + j * 16 + col_l;
+      bool ok = n < g.N;
+      if (GLU) { const int feat = n0 + (wn >> 6) * 32 + (j & 1) * 16 + col_l; ok = feat < g.N / 2; n = (j >> 1) ? g.N / 2 + feat : feat; }
+      if (ok) {
+        const bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16*)g.bias + n);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        int n = n0 + wn + j * 32 + q * 8 + col_l;
-        bool ok = n < g.N;
-        if (GLU) { const int feat = n0 + (wn >> 6) * 32 + q * 8 + col_l; ok = feat < g.N / 2; n = j ? g.N / 2 + feat : feat; }
-        if (ok) {
-          const bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16*)g.bias + n);
+        for (int i = 0; i < NI; ++i)
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[i][j][q * 4 + e] += (float)b[e];
-        }
+          for (int e = 0; e < 4; ++e) acc[i][j][e] += (float)b[e];
       }
+    }
   }
+  const int sub_b = (col_l & 4) * 2;      // byte inside a 16-byte piece at which this lane's 4 columns start
   if (EPI == EPI_DGELU || EPI == EPI_DSWIGLU) {
     // Activation backward on the fp32 accumulators (da), in place over the stashed z: 128 rows of the tile at a time,
     // their z columns (gate, and for SwiGLU up) come global -> LDS directly, whole rows, into the layout of the bf16
-    // staging above (row r's piece p at r*512 + ((p ^ (r & 31)) << 4), the up half 64 KiB further on); the wavefronts
+    // staging below (row r's piece p at r*512 + ((p ^ (r & 31)) << 4), the up half 64 KiB further on); the wavefronts
     // that hold those rows' accumulators rewrite their elements in LDS; everybody stores the rows back.
     constexpr int NOP = EPI == EPI_DSWIGLU ? 2 : 1;              // z operands per row: gate (| up)
     constexpr int HALF_B = 128 * 512;                            // one operand, 128 rows
@@ -382,37 +389,35 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
       __syncthreads();
       if (wm == h * 128) {             // wave-uniform: this wavefront's rows are the ones in LDS
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int r = i * 32 + row_l;
+        for (int i = 0; i < NI; ++i) {
+          const int r = i * 16 + row_l;
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
+          for (int j = 0; j < NJ; ++j) {
+            const int p = (wn + j * 16 + col_l) >> 3;
+            lds_char* at = smem + r * 512 + ((p ^ (r & 31)) << 4) + sub_b;
+            if (EPI == EPI_DGELU) {
+              bf16x4 u = *(lds_b4)at, o4;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int p = (wn + j * 32 + q * 8) >> 3;
-              lds_char* at = smem + r * 512 + ((p ^ (r & 31)) << 4) + (lane >> 5) * 8;
-              if (EPI == EPI_DGELU) {
-                bf16x4 u = *(lds_b4)at, o4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const float uv = (float)u[e];
-                  const float dgl = 0.5f * (1.f + erff(uv * 0.70710678118654752f)) + uv * 0.39894228040143268f * __expf(-0.5f * uv * uv);
-                  o4[e] = (bf16)(acc[i][j][q * 4 + e] * dgl);
-                }
-                *(lds_b4)at = o4;
-                __builtin_amdgcn_sched_barrier(0);
-              } else {
-                bf16x4 gt = *(lds_b4)at, up = *(lds_b4)(at + HALF_B), og, ou;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const float gv = (float)gt[e], uv = (float)up[e], d = acc[i][j][q * 4 + e];
-                  const float sg = 1.f / (1.f + __expf(-gv));
-                  og[e] = (bf16)(d * uv * (sg + gv * sg * (1.f - sg)));
-                  ou[e] = (bf16)(d * gv * sg);
-                }
-                *(lds_b4)at = og;
-                *(lds_b4)(at + HALF_B) = ou;
+              for (int e = 0; e < 4; ++e) {
+                const float uv = (float)u[e];
+                const float dgl = 0.5f * (1.f + erff(uv * 0.70710678118654752f)) + uv * 0.39894228040143268f * __expf(-0.5f * uv * uv);
+                o4[e] = (bf16)(acc[i][j][e] * dgl);
               }
+              *(lds_b4)at = o4;
+              __builtin_amdgcn_sched_barrier(0);
+            } else {
+              bf16x4 gt = *(lds_b4)at, up = *(lds_b4)(at + HALF_B), og, ou;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const float gv = (float)gt[e], uv = (float)up[e], d = acc[i][j][e];
+                const float sg = 1.f / (1.f + __expf(-gv));
+                og[e] = (bf16)(d * uv * (sg + gv * sg * (1.f - sg)));
+                ou[e] = (bf16)(d * gv * sg);
+              }
+              *(lds_b4)at = og;
+              *(lds_b4)(at + HALF_B) = ou;
             }
+          }
         }
       }
       __syncthreads();
@@ -429,11 +434,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     return;
   }
   if (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_SWIGLU) {
-    // bf16 output: the 256 x 256 tile goes through LDS (exactly the 128 KiB the operand buffers held) so that the
-    // global stores are whole 512-byte rows, 16 bytes per lane, instead of 16-byte fragments of 32 rows.  Row r's
-    // 16-byte piece p sits at r*512 + ((p ^ (r & 31)) << 4): the fragment writes of 32 rows spread over all banks
-    // and a row is read back as a permutation of itself.  No loads are in flight here (none is issued past the
-    // last K tile); the barrier waits for the other wavefronts' last fragment reads.
+    // bf16 output: the tile goes through LDS (128 KiB of what the operand ring held) so that the global stores are
+    // whole 512-byte rows, 16 bytes per lane, instead of 8-byte fragments of 16 rows.  Row r's 16-byte piece p sits at
+    // r*512 + ((p ^ (r & 31)) << 4): the fragment writes of 16 rows spread over all banks and a row is read back as a
+    // permutation of itself.  No loads are in flight here (none is issued past the last K tile); the barrier waits
+    // for the other wavefronts' last fragment reads.
     // EPI_SWIGLU: pieces 0..15 of a staged row are the tile's 128 gate columns, pieces 16..31 its 128 up columns (two
     // 256-byte runs of the output row).
     const int glu_f = g.N / 2;
@@ -441,19 +446,17 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     __syncthreads();
     auto stage_tile = [&](auto fn) {         // fn(acc) -> LDS as bf16, in the layout above
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int r = wm + i * 32 + row_l;
+      for (int i = 0; i < NI; ++i) {
+        const int r = wm + i * 16 + row_l;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < NJ; ++j) {
+          const int p = GLU ? (j >> 1) * 16 + (wn >> 6) * 4 + (j & 1) * 2 + (col_l >> 3) : (wn + j * 16 + col_l) >> 3;
+          bf16x4 o;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int p = GLU ? j * 16 + (wn >> 6) * 4 + q : (wn + j * 32 + q * 8) >> 3;
-            bf16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (bf16)fn(acc[i][j][q * 4 + e]);
-            *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4) + (lane >> 5) * 8) = o;
-            if (EPI == EPI_GELU) __builtin_amdgcn_sched_barrier(0);      // keeps the erf expansions from piling up in registers
-          }
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)fn(acc[i][j][e]);
+          *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4) + sub_b) = o;
+          if (EPI == EPI_GELU) __builtin_amdgcn_sched_barrier(0);      // keeps the erf expansions from piling up in registers
+        }
       }
     };
     auto store_tile = [&](bf16* out, int64_t ld) {      // LDS -> global, whole rows
@@ -482,18 +485,18 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
       // a = silu(gate) * up: 128 features per row = 256 bytes; rows with bit 4 set use the upper half of their
       // 512-byte LDS row so that rows r and r + 16 do not share banks
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int r = wm + i * 32 + row_l;
+      for (int i = 0; i < NI; ++i) {
+        const int r = wm + i * 16 + row_l;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int fp = (wn >> 6) * 4 + q;
+        for (int jj = 0; jj < NJ / 2; ++jj) {
+          const int fp = (wn >> 6) * 4 + jj * 2 + (col_l >> 3);
           bf16x4 o;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float gv = acc[i][0][q * 4 + e];
-            o[e] = (bf16)(gv * (1.f / (1.f + __expf(-gv))) * acc[i][TN - 1][q * 4 + e]);
+            const float gv = acc[i][jj][e];
+            o[e] = (bf16)(gv * (1.f / (1.f + __expf(-gv))) * acc[i][jj + NJ / 2][e]);
           }
-          *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * 512 + ((((r & 16) | fp) ^ (r & 15)) << 4) + (lane >> 5) * 8) = o;
+          *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * 512 + ((((r & 16) | fp) ^ (r & 15)) << 4) + sub_b) = o;
         }
       }
       __syncthreads();
@@ -508,36 +511,33 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     return;
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = m0 + wm + i * 32 + row_l;
+  for (int i = 0; i < NI; ++i) {
+    const int m = m0 + wm + i * 16 + row_l;
     if (m >= g.M) continue;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn + j * 32 + q * 8 + col_l;
-        if (n >= g.N) continue;          // N % 8 == 0 and n % 4 == 0: the 4 columns are in or out together
-        f32x4 v = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-        if (EPI == EPI_ACC32) {
-          *reinterpret_cast<f32x4*>((float*)g.C + (int64_t)m * g.ldc + n) = v;   // acc already holds C + A^T.B
-        } else {
-          if (EPI == EPI_RESID && g.R) {
-            if (g.r_f32) {
-              v += *reinterpret_cast<const f32x4*>((const float*)g.R + (int64_t)m * g.ldr + n);
-            } else {
-              bf16x4 r = *reinterpret_cast<const bf16x4*>((const bf16*)g.R + (int64_t)m * g.ldr + n);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
-            }
-          }
-          if (EPI == EPI_RESID && g.c_f32) {
-            *reinterpret_cast<f32x4*>((float*)g.C + (int64_t)m * g.ldc + n) = v;
+    for (int j = 0; j < NJ; ++j) {
+      const int n = n0 + wn + j * 16 + col_l;
+      if (n >= g.N) continue;          // N % 8 == 0 and n % 4 == 0: the 4 columns are in or out together
+      f32x4 v = acc[i][j];
+      if (EPI == EPI_ACC32) {
+        *reinterpret_cast<f32x4*>((float*)g.C + (int64_t)m * g.ldc + n) = v;   // acc already holds C + A^T.B
+      } else {
+        if (EPI == EPI_RESID && g.R) {
+          if (g.r_f32) {
+            v += *reinterpret_cast<const f32x4*>((const float*)g.R + (int64_t)m * g.ldr + n);
           } else {
-            bf16x4 o;
+            bf16x4 r = *reinterpret_cast<const bf16x4*>((const bf16*)g.R + (int64_t)m * g.ldr + n);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-            *reinterpret_cast<bf16x4*>((bf16*)g.C + (int64_t)m * g.ldc + n) = o;
+            for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
           }
+        }
+        if (EPI == EPI_RESID && g.c_f32) {
+          *reinterpret_cast<f32x4*>((float*)g.C + (int64_t)m * g.ldc + n) = v;
+        } else {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+          *reinterpret_cast<bf16x4*>((bf16*)g.C + (int64_t)m * g.ldc + n) = o;
         }
       }
     }
@@ -607,7 +607,7 @@ __global__ __launch_bounds__(1024 / TN) void gemm_wgrad_group_kernel(GemmGroup g
 }
 
 // Eight wavefronts of 128x64 and four of 128x128 measure within a few percent of each other on the stage's shapes
-// (the narrower ones ahead on forward and input-gradient products, the wider ones on some weight-gradient ones).
+// (the wider ones ahead on the longest reductions only); the fused SwiGLU epilogue needs the narrower ones.
 constexpr int WAVE_COLS = 2;
 
 // One-time set-up (CU count, a kernel's LDS limit) sits in function-local statics, whose initialisation the language
@@ -623,10 +623,8 @@ int cu_count() {
 
 template <bool AKC, bool BKC, int EPI, int WR>
 hipError_t launch_tiles(const GemmArgs& g, hipStream_t s, int tiles_m, int tiles_n, int first, int n_wg) {
-  // two buffers of (A tile, B tile); the activation-backward epilogue stages 128 rows of z per operand (64 KiB each)
-  constexpr size_t LDS_MAIN = (size_t)2 * (WR * 128 * BK * 2 + TILE_BYTES);
-  constexpr size_t LDS_EPI = EPI == EPI_DSWIGLU ? 2 * 65536 : EPI == EPI_DGELU ? 65536 : 0;
-  constexpr size_t LDS = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
+  // the ring of operand tiles; every epilogue's staging (at most 128 KiB) fits inside it
+  constexpr size_t LDS = LDS_BYTES;
   auto kern = gemm_mfma_kernel<AKC, BKC, EPI, WAVE_COLS, WR>;
   static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
   if (attr != hipSuccess) return attr;

@@ -1,5 +1,5 @@
 // Measurement aid, not part of the stage's path: the rate this GPU sustains on nothing but back-to-back
-// v_mfma_f32_32x32x16_bf16 (two wavefronts per SIMD, four independent accumulator chains each, operands in registers,
+// v_mfma_f32_16x16x32_bf16, the GEMM's instruction (two wavefronts per SIMD, eight independent accumulator chains each, operands in registers,
 // no memory or LDS traffic), and the shader clock it holds meanwhile.  With constant operands the clock stays at its
 // nominal value and the rate is the published peak; with random operands the clock settles much lower (the matrix
 // cores' power depends on how many bits toggle), and that lower rate -- not the published one -- is what a kernel
@@ -12,14 +12,14 @@ namespace stg {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int CEIL_THREADS = 512, CEIL_MFMA_PER_ITER = 16;
+constexpr int CEIL_THREADS = 512, CEIL_MFMA_PER_ITER = 32;
 
 __global__ __launch_bounds__(CEIL_THREADS) void mfma_ceiling_kernel(float* out, unsigned long long* clocks, int iters, int random_operands) {
-  f32x16 acc[4];
-  for (int i = 0; i < 4; ++i)
-    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  f32x4 acc[8];
+  for (int i = 0; i < 8; ++i)
+    for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
   bf16x8 a[4], b[4];
   unsigned h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;       // a small LCG per lane
   for (int i = 0; i < 4; ++i)
@@ -34,13 +34,13 @@ __global__ __launch_bounds__(CEIL_THREADS) void mfma_ceiling_kernel(float* out, 
   const unsigned long long c0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int r = 0; r < CEIL_MFMA_PER_ITER / 4; ++r)
+    for (int r = 0; r < CEIL_MFMA_PER_ITER / 8; ++r)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(i + r) & 3], b[i], acc[i], 0, 0, 0);
+      for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[(i + r) & 3], b[i & 3], acc[i], 0, 0, 0);
   }
   float s = 0.f;
-  for (int i = 0; i < 4; ++i)
-    for (int e = 0; e < 16; ++e) s += acc[i][e];
+  for (int i = 0; i < 8; ++i)
+    for (int e = 0; e < 4; ++e) s += acc[i][e];
   const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
   out[(size_t)blockIdx.x * CEIL_THREADS + threadIdx.x] = s;
   // the youngest wavefront of a SIMD gets the matrix core last, so its span is the workgroup's
@@ -73,7 +73,7 @@ extern "C" int stage_probe_mfma_ceiling(int random_operands, int iters, void* sc
   if (hipGetLastError() != hipSuccess || hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) goto done;
   if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess || ms <= 0.f) goto done;
   if (hipMemcpy(h, clocks, sizeof h, hipMemcpyDeviceToHost) != hipSuccess || h[1] == 0) goto done;
-  *tflops = (double)cus * (CEIL_THREADS / 64) * CEIL_MFMA_PER_ITER * (double)iters * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
+  *tflops = (double)cus * (CEIL_THREADS / 64) * CEIL_MFMA_PER_ITER * (double)iters * (2.0 * 16 * 16 * 32) / (ms * 1e-3) / 1e12;
   *shader_mhz = (double)h[0] / ((double)h[1] / 100.0);       // the reference counter runs at 100 MHz
   rc = STAGE_OK;
 done:

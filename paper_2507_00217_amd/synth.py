@@ -37,6 +37,9 @@ CONFIGS: Dict[str, dict] = {
                  n_microbatches=12, norm="layernorm", act="gelu", dtype="bf16", stash_cap=6, schedule="w_lag1", warmup=4),
     "cfg5": dict(n_layers=2, hidden=8192, n_heads=64, n_kv_heads=8, ffn=28672, seq=4096, mb_size=1,
                  n_microbatches=32, norm="rmsnorm", act="swiglu", dtype="bf16", stash_cap=8, schedule="greedy", warmup=4),
+    # the GPT-style stage with linear biases (GPT-style layers carry them; the paper's Llama-style ones do not)
+    "cfg2_bias": dict(n_layers=6, hidden=2048, n_heads=16, n_kv_heads=16, ffn=8192, seq=2048, mb_size=1, bias=1,
+                      n_microbatches=8, norm="layernorm", act="gelu", dtype="bf16", stash_cap=0, schedule="1f1b", warmup=3),
     # further shapes of the paper's models (section 7): the M8 layer, and the share of an M70 / M8 layer that one GPU
     # holds under 4-way tensor parallelism (a quarter of the heads and of the ffn against the full hidden width); these
     # are Llama-style layers, so they carry the rotary position embedding

@@ -106,7 +106,7 @@ def test_full_depth_one_microbatch(name, mb):
             assert errs[k] <= INTRINSIC_FACTOR * dev[k], (k, errs[k], dev[k])
 
 
-@pytest.mark.parametrize("name", ["m8", "m70_tp4", "m8_tp4"])
+@pytest.mark.parametrize("name", ["m8", "m70_tp4", "m8_tp4", "cfg2_bias"])
 def test_one_layer_one_microbatch_full_shapes(name):
     import torch
     from paper_2507_00217_amd import stage as S

@@ -398,8 +398,8 @@ def test_bias_gradient(dtype, rows, n, ld):
 
 
 def test_mfma_ceiling_probe():
-    """The measurement aid returns sane figures: the rate and the clock it reports agree (16 MFMAs of 32 cycles per
-    round on each SIMD), random operands do not beat constant ones, and bad arguments are refused."""
+    """The measurement aid returns sane figures: the rate and the clock it reports agree (an MFMA of 16384 flops every 16
+    cycles on each SIMD), random operands do not beat constant ones, and bad arguments are refused."""
     import torch
     from paper_2507_00217_amd import stage as S
     cus = torch.cuda.get_device_properties(0).multi_processor_count
