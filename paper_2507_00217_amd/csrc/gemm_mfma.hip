@@ -606,9 +606,13 @@ __global__ __launch_bounds__(1024 / TN) void gemm_wgrad_group_kernel(GemmGroup g
   }
 }
 
-// Eight wavefronts of 128x64 and four of 128x128 measure within a few percent of each other on the stage's shapes
-// (the wider ones ahead on the longest reductions only); the fused SwiGLU epilogue needs the narrower ones.
-constexpr int WAVE_COLS = 2;
+// Eight wavefronts of 128x64 or four of 128x128 per tile: the wider ones read a third less from LDS and are ahead on
+// weight gradients (+2..4 %) and on input gradients with a long reduction (+7 % at K = 22016), the narrower ones on
+// short reductions (an epilogue without spills, two wavefronts per SIMD to cover it); the fused SwiGLU epilogue and the
+// half-height tile need the narrower ones.  Both give the same bits: every output element sums the same products in the
+// same order.
+constexpr int WAVE_COLS = 2, WAVE_COLS_WGRAD = 4;
+constexpr int WIDE_MIN_K = 8192;       // input gradients: four wavefronts from this reduction length on
 
 // One-time set-up (CU count, a kernel's LDS limit) sits in function-local statics, whose initialisation the language
 // makes thread-safe: concurrent first calls from several threads run it once.
@@ -621,14 +625,14 @@ int cu_count() {
   return n_cu;
 }
 
-template <bool AKC, bool BKC, int EPI, int WR>
+template <bool AKC, bool BKC, int EPI, int WR, int TN = WAVE_COLS>
 hipError_t launch_tiles(const GemmArgs& g, hipStream_t s, int tiles_m, int tiles_n, int first, int n_wg) {
   // the ring of operand tiles; every epilogue's staging (at most 128 KiB) fits inside it
   constexpr size_t LDS = LDS_BYTES;
-  auto kern = gemm_mfma_kernel<AKC, BKC, EPI, WAVE_COLS, WR>;
+  auto kern = gemm_mfma_kernel<AKC, BKC, EPI, TN, WR>;
   static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL(kern, dim3(n_wg), dim3(WR * 512 / WAVE_COLS), LDS, s, g, tiles_m, tiles_n, first);
+  hipLaunchKernelGGL(kern, dim3(n_wg), dim3(WR * 512 / TN), LDS, s, g, tiles_m, tiles_n, first);
   return hipGetLastError();
 }
 
@@ -645,7 +649,12 @@ hipError_t launch(const GemmArgs& g, hipStream_t s, int shape) {
     n_half = shape == 2 ? total : shape == 1 ? 0 : (2 * tail <= n_cu ? tail : 0);
   }
   if (total > n_half) {
-    hipError_t e = launch_tiles<AKC, BKC, EPI, 2>(g, s, tiles_m, tiles_n, 0, total - n_half);
+    hipError_t e;
+    if constexpr (AKC && BKC && EPI == EPI_STORE)
+      e = g.K >= WIDE_MIN_K ? launch_tiles<AKC, BKC, EPI, 2, 4>(g, s, tiles_m, tiles_n, 0, total - n_half)
+                            : launch_tiles<AKC, BKC, EPI, 2>(g, s, tiles_m, tiles_n, 0, total - n_half);
+    else
+      e = launch_tiles<AKC, BKC, EPI, 2>(g, s, tiles_m, tiles_n, 0, total - n_half);
     if (e != hipSuccess) return e;
   }
   if constexpr (AKC) {
@@ -709,7 +718,7 @@ bool gemm_mfma_wgrad_group_supported(const GemmArgs* list, int n, int nseg, cons
 }
 
 hipError_t gemm_mfma_wgrad_group(const GemmArgs* list, int n, int nseg, const int64_t* seg_delta, hipStream_t s) {
-  auto kern = gemm_wgrad_group_kernel<WAVE_COLS>;
+  auto kern = gemm_wgrad_group_kernel<WAVE_COLS_WGRAD>;
   static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
   if (attr != hipSuccess) return attr;
   const int n_cu = cu_count();
@@ -727,7 +736,7 @@ hipError_t gemm_mfma_wgrad_group(const GemmArgs* list, int n, int nseg, const in
     for (int i = gg.n; i <= GROUP_MAX; ++i) gg.first_tile[i] = total;
     gg.total_tiles = total;
     const int grid = total < n_cu ? total : n_cu;       // one workgroup per CU (128 KiB of LDS each)
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(1024 / WAVE_COLS), LDS_BYTES, s, gg);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(1024 / WAVE_COLS_WGRAD), LDS_BYTES, s, gg);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
