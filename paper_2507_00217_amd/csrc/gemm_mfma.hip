@@ -292,7 +292,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+        const int js = (TN == 2 && (i & 1)) ? NJ - 1 - j : j;     // boustrophedon: consecutive MFMAs always share one operand
+                                                                  // (with four column groups the register allocator spills on it)
+        acc[i][js] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[cur][js], fa[cur][i], acc[i][js], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         const int n = i * NJ + j;
         if (n % 2 == 0 && n / 2 < NFRAG) {
