@@ -13,7 +13,8 @@
  * the shape, 1 = plain reference HIP kernels.  stage_kernel_gemm and the
  * attention entries also take 2 and 3: the tuned kernels with a choice they
  * normally make from the shape fixed, so that tests reach both variants on any
- * shape -- GEMM: 2 = full 256 x 256 tiles only, 3 = half-height tiles only;
+ * shape -- GEMM: 2 = full 256 x 256 tiles only, 3 = half-height tiles only, 4 (stage_kernel_gemm, forward and
+ * input-gradient layouts) = 128 x 128 tiles only;
  * attention: 2 / 3 = forward and dQ workgroups of 8 / 4 wavefronts.
  * Return: 0, or STAGE_E_INVAL for
  * a shape the kernel does not take, STAGE_E_HIP for a failed launch.

@@ -44,7 +44,6 @@ namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int TILE_BYTES = BM * BK * 2;                      // one operand tile, either layout: 32 KiB
-constexpr int TILE_SLOTS = TILE_BYTES / 16;                  // 16-byte pieces: 2048
 constexpr int SLOT = TILE_BYTES, NSLOT = 5;                  // ring of operand tiles in LDS
 constexpr size_t LDS_BYTES = (size_t)NSLOT * SLOT;           // 160 KiB
 static_assert(BM == BN, "both operand tiles share one geometry");
@@ -75,13 +74,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, un
 // Per-thread global byte offsets at k = 0 of the pieces it fetches: load j of wavefront w fills slots
 // (j*8 + w)*64 .. +63, lane l the l-th of them.  Rows past the end of the matrix fall outside the buffer's range
 // by themselves or are redirected to OOB, which stores zeros.
-// (a [row][k] tile may have any multiple of 8 rows: WAVES * 64 * CH pieces; a [k][row] tile always has 256 rows)
+// (a [row][k] tile may have any multiple of 8 rows: WAVES * 64 * CH pieces; a [k][row] tile has PCS pieces = 8 * PCS rows
+// per reduction row, 32 or 16, and the same formulas with 32 replaced by PCS)
 // glu_f > 0 (a [k][row] B tile of EPI_SWIGLU): row0 is the tile's first feature and piece p = 8 columns of block p / 4
 // fetches columns (odd block ? glu_f : 0) + row0 + (p / 8) * 32 + (p % 4) * 8 ..
-template <bool KC, int WAVES, int CH>
+template <bool KC, int WAVES, int CH, int PCS = 32>
 __device__ __forceinline__ void tile_offsets(unsigned (&off)[CH], int64_t ld, int row0, int rows, int wave, int lane,
                                              int glu_f = 0) {
-  static_assert(KC || WAVES * 64 * CH == TILE_SLOTS, "every 16-byte piece of the tile has one owner");
+  static_assert(KC || WAVES * 64 * CH == BK * PCS, "every 16-byte piece of the tile has one owner");
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
     const int s = (j * WAVES + wave) * 64 + lane;
@@ -89,7 +89,7 @@ __device__ __forceinline__ void tile_offsets(unsigned (&off)[CH], int64_t ld, in
       const int r = s >> 3, c = (s & 7) ^ ((r >> 1) & 7);
       off[j] = row0 + r < rows ? (unsigned)(((int64_t)(row0 + r) * ld + c * 8) * 2) : OOB;
     } else {
-      const int k = s >> 5, p = (s & 31) ^ (((k & 3) << 2) | (((k >> 3) & 1) << 1));
+      const int k = s / PCS, p = (s % PCS) ^ (((k & 3) << 2) | (((k >> 3) & 1) << 1));
       int row = row0 + p * 8;
       bool ok = row < rows;
       if (glu_f) {
@@ -135,11 +135,11 @@ __device__ __forceinline__ void g2s(lds_char* tile, rsrc_words rsrc, const unsig
 // Per-lane LDS byte offsets (inside one operand tile) from which the fragments of a 16-row block are read.
 // Fragment = 16(row) x 32(k): lane l holds row l%16, k = (l/16)*8 .. +7.
 //   KC:  ad[ks], ks = k-step 0..1; block b of 16 rows adds 2048 bytes (the swizzle repeats every 16 rows)
-//   else ad[b], b = 16-row block index counted from row0; k-step ks adds 32 reduction rows = 16384 bytes; the
+//   else ad[b], b = 16-row block index counted from row0; k-step ks adds 32 reduction rows of PCS * 16 bytes; the
 //        transpose load: in a 16-lane group, lane i addresses row (i/4) of a 4(k) x 16(row) block at column 4*(i%4)
 //        and receives column i of the block, i.e. 4 consecutive k for its own row; the four groups of a wavefront
 //        take the reduction rows g*8 .. g*8+3 (and, in a second load, 4 rows further on)
-template <bool KC, int NB>
+template <bool KC, int NB, int PCS = 32>
 __device__ __forceinline__ void frag_offsets(unsigned (&ad)[NB], int row0, int lane) {
   if (KC) {
     const int r = row0 + (lane & 15), sw = (r >> 1) & 7, h = lane >> 4;
@@ -152,21 +152,21 @@ __device__ __forceinline__ void frag_offsets(unsigned (&ad)[NB], int row0, int l
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       const int p = ((row0 >> 4) + b) * 2 + ((li & 3) >> 1);                   // 16-byte piece of the reduction row
-      ad[b] = (unsigned)(krow * 512 + (p ^ sw) * 16 + (li & 1) * 8);
+      ad[b] = (unsigned)(krow * (PCS * 16) + (p ^ sw) * 16 + (li & 1) * 8);
     }
   }
 }
 
 // `pt`: the tile's LDS address plus the offsets above
-template <bool KC, int NB>
+template <bool KC, int NB, int PCS = 32>
 __device__ __forceinline__ bf16x8 frag(lds_char* const (&pt)[NB], int b, int ks) {
   if (KC) {
     return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(pt[ks] + b * 2048);
   } else {
     typedef s16x4 __attribute__((address_space(3))) * lds_p;
-    lds_char* p = pt[b] + ks * 16384;
+    lds_char* p = pt[b] + ks * (32 * PCS * 16);
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * 512));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * PCS * 16));
     union { struct { s16x4 a, b; } s; bf16x8 v; } u;
     u.s.a = lo; u.s.b = hi;
     return u.v;
@@ -179,22 +179,27 @@ __device__ __forceinline__ bf16x8 frag(lds_char* const (&pt)[NB], int b, int ks)
 // seg_delta[s] bytes (seg_delta[0] == 0): C (+)= sum_s A_s . B_s with the K tiles taken in order s = 0, 1, ...  One
 // pass over K then does the work of nseg launches with a single read-modify-write of C, and -- fp32 accumulators
 // written to and read back from fp32 memory unchanged -- gives the same bits as those launches one after another.
-// WR = rows of 128 in the tile: 2 -> 256 x 256 (wave grid 2 x WGN), 1 -> 128 x 256 (wave grid 1 x WGN, half the
-// wavefronts; A must be a [row][k] operand).  The half-height tile exists for the work a grid of full tiles would
-// leave to a fraction of the CUs: the last, partly filled round of a product, and products with few tiles.
-template <bool AKC, bool BKC, int EPI, int TN, int WR = 2>
+// WR, WC = rows and columns of 128 in the tile: (2, 2) -> 256 x 256 (wave grid 2 x WGN); (1, 2) -> 128 x 256 (wave grid
+// 1 x WGN, half the wavefronts); (1, 1) -> 128 x 128 (four wavefronts of 64 x 64); A must be a [row][k] operand unless
+// the tile is a full one.  The smaller tiles exist for the work a grid of full tiles would leave to a fraction of the
+// CUs: the last, partly filled round of a product, and products with few tiles.
+template <bool AKC, bool BKC, int EPI, int TN, int WR = 2, int WC = 2>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds_char* smem, int nseg = 1,
                                           const int64_t* seg_delta = nullptr) {
-  static_assert(WR == 2 || (WR == 1 && AKC), "the half-height tile takes a [row][k] A operand");
+  static_assert(WR == 2 || (WR == 1 && AKC), "the smaller tiles take a [row][k] A operand");
+  static_assert(WC == 2 || (WR == 1 && TN == 2 && (EPI == EPI_STORE || EPI == EPI_RESID)), "the 128 x 128 tile: plain epilogues only");
   constexpr bool GLU = EPI == EPI_SWIGLU;
   static_assert(!GLU || (TN == 2 && !BKC), "gate and up blocks are the two halves of a wavefront's columns");
-  constexpr int WGN = 8 / TN, WAVES = WR * WGN;
-  constexpr int BMV = WR * 128, A_BYTES = BMV * BK * 2;                            // A tile: BMV rows
-  constexpr int CHA = (A_BYTES / 16) / (WAVES * 64), CHB = TILE_SLOTS / (WAVES * 64); // loads per thread and K tile
-  constexpr int NI = 8, NJ = 2 * TN;                                               // 16 x 16 accumulator blocks per wavefront
+  constexpr int BMV = WR * 128, BNV = WC * 128;                                    // tile: BMV rows, BNV columns
+  constexpr int RW = WC == 1 ? 64 : 128;                                           // rows of a wavefront's sub-tile
+  constexpr int WGN = BNV / (TN * 32), WAVES = (BMV / RW) * WGN;
+  constexpr int A_BYTES = BMV * BK * 2, B_BYTES = BNV * BK * 2;
+  constexpr int PCS = BNV / 8;                                                     // 16-byte pieces per row of C / per reduction row of a [k][row] B tile
+  constexpr int CHA = (A_BYTES / 16) / (WAVES * 64), CHB = (B_BYTES / 16) / (WAVES * 64); // loads per thread and K tile
+  constexpr int NI = RW / 16, NJ = 2 * TN;                                         // 16 x 16 accumulator blocks per wavefront
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = (wave / WGN) * 128, wn = (wave % WGN) * (TN * 32);
+  const int wm = (wave / WGN) * RW, wn = (wave % WGN) * (TN * 32);
 
   // buffer descriptors cover exactly the rows that exist: KC operand = [rows, ld], other = [K, ld]
   const unsigned bytesA = (unsigned)(((int64_t)((AKC ? g.M : g.K) - 1) * g.lda + (AKC ? g.K : g.M)) * 2);
@@ -202,7 +207,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   rsrc_words rsA = raw_rsrc(g.A, bytesA), rsB = raw_rsrc(g.B, bytesB);
   unsigned offa[CHA], offb[CHB];
   tile_offsets<AKC, WAVES, CHA>(offa, g.lda, m0, g.M, wave, lane);
-  tile_offsets<BKC, WAVES, CHB>(offb, g.ldb, n0, g.N, wave, lane, GLU ? g.N / 2 : 0);
+  tile_offsets<BKC, WAVES, CHB, PCS>(offb, g.ldb, n0, g.N, wave, lane, GLU ? g.N / 2 : 0);
 
   // LDS map: a ring of NSLOT slots of one operand tile each; the operand tiles of the reduction take the slots in the
   // order A0 B0 A1 B1 A2 ..., tile number i (A_t = 2t, B_t = 2t + 1) sitting in slot i % NSLOT.
@@ -260,7 +265,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   {
     unsigned ada[NPA], adb[NPB];
     frag_offsets<AKC, NPA>(ada, wm, lane);
-    frag_offsets<BKC, NPB>(adb, wn, lane);
+    frag_offsets<BKC, NPB, PCS>(adb, wn, lane);
 #pragma unroll
     for (int x = 0; x < NPA; ++x) pa[x] = smem + ada[x];
 #pragma unroll
@@ -299,7 +304,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
         const int n = i * NJ + j;
         if (n % 2 == 0 && n / 2 < NFRAG) {
           const int f = n / 2;
-          if (f < NJ) fb[cur ^ 1][f] = frag<BKC, NPB>(pb, f, ks_next);
+          if (f < NJ) fb[cur ^ 1][f] = frag<BKC, NPB, PCS>(pb, f, ks_next);
           else fa[cur ^ 1][f - NJ] = frag<AKC, NPA>(pa, f - NJ, ks_next);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -316,7 +321,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   __builtin_amdgcn_s_waitcnt(0);   // the start-up tiles (and C for weight gradients) landed
   __syncthreads();
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) fb[0][j] = frag<BKC, NPB>(pb, j, 0);
+  for (int j = 0; j < NJ; ++j) fb[0][j] = frag<BKC, NPB, PCS>(pb, j, 0);
 #pragma unroll
   for (int i = 0; i < NI; ++i) fa[0][i] = frag<AKC, NPA>(pa, i, 0);
   int kt = 0;
@@ -437,9 +442,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   }
   if (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_SWIGLU) {
     // bf16 output: the tile goes through LDS (128 KiB of what the operand ring held) so that the global stores are
-    // whole 512-byte rows, 16 bytes per lane, instead of 8-byte fragments of 16 rows.  Row r's 16-byte piece p sits at
-    // r*512 + ((p ^ (r & 31)) << 4): the fragment writes of 16 rows spread over all banks and a row is read back as a
-    // permutation of itself.  No loads are in flight here (none is issued past the last K tile); the barrier waits
+    // whole rows of the tile (512 bytes; 256 for the 128-column tile), 16 bytes per lane, instead of 8-byte fragments of
+    // 16 rows.  Row r's 16-byte piece p (of PCS) sits at r*PCS*16 + ((p ^ (r % PCS)) << 4): the fragment writes of 16
+    // rows spread over all banks and a row is read back as a permutation of itself.  No loads are in flight here (none is issued past the last K tile); the barrier waits
     // for the other wavefronts' last fragment reads.
     // EPI_SWIGLU: pieces 0..15 of a staged row are the tile's 128 gate columns, pieces 16..31 its 128 up columns (two
     // 256-byte runs of the output row).
@@ -456,20 +461,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
           bf16x4 o;
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] = (bf16)fn(acc[i][j][e]);
-          *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4) + sub_b) = o;
+          *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * (PCS * 16) + ((p ^ (r & (PCS - 1))) << 4) + sub_b) = o;
           if (EPI == EPI_GELU) __builtin_amdgcn_sched_barrier(0);      // keeps the erf expansions from piling up in registers
         }
       }
     };
     auto store_tile = [&](bf16* out, int64_t ld) {      // LDS -> global, whole rows
-      const int p = lane & 31;
+      constexpr int RPI = 64 / PCS;                      // rows per instruction
+      const int p = lane & (PCS - 1);
       int n = n0 + p * 8;
       bool n_ok = n < g.N;
       if (GLU) { const int feat = n0 + (p & 15) * 8; n_ok = feat < glu_f; n = (p >> 4) ? glu_f + feat : feat; }
 #pragma unroll
-      for (int t = 0; t < BMV / WAVES / 2; ++t) {
-        const int r = wave * (BMV / WAVES) + 2 * t + (lane >> 5), m = m0 + r;
-        const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(smem + r * 512 + ((p ^ (r & 31)) << 4));
+      for (int t = 0; t < BMV / WAVES / RPI; ++t) {
+        const int r = wave * (BMV / WAVES) + RPI * t + lane / PCS, m = m0 + r;
+        const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(smem + r * (PCS * 16) + ((p ^ (r & (PCS - 1))) << 4));
         if (m < g.M && n_ok) *reinterpret_cast<u32x4*>(out + (int64_t)m * ld + n) = v;   // N % 8 == 0
       }
     };
@@ -576,6 +582,20 @@ __global__ __launch_bounds__(WR * 512 / TN) void gemm_mfma_kernel(GemmArgs g, in
                                    (lds_char*)smem_raw);
 }
 
+// one workgroup per 128 x 128 tile (four wavefronts of 64 x 64), tiles counted in units of 128
+template <bool AKC, bool BKC, int EPI>
+__global__ __launch_bounds__(256) void gemm_quarter_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  int bid = blockIdx.x;
+  {
+    const int per = (int)gridDim.x >> 3, main = per << 3;
+    if (bid < main) bid = (bid & 7) * per + (bid >> 3);
+  }
+  int tile_m, tile_n;
+  tile_of(bid, tiles_m, tiles_n, tile_m, tile_n);
+  gemm_tile<AKC, BKC, EPI, 2, 1, 1>(g, tile_m * 128, tile_n * 128, (lds_char*)smem_raw);
+}
+
 // Several weight-gradient products C_p += A_p^T . B_p in one launch of persistent workgroups.  Each workgroup
 // takes the tiles  r * gridDim.x + (its slot)  of the concatenated tile list, r = 0, 1, ...: after it has issued a
 // tile's stores it goes straight on to the next tile's C and operand loads, so the read-modify-write of the fp32
@@ -640,9 +660,22 @@ hipError_t launch_tiles(const GemmArgs& g, hipStream_t s, int tiles_m, int tiles
 
 // Full tiles for every complete round of one tile per CU; what is left over -- a last round that would keep at most
 // half of the CUs busy, or a whole product with that few tiles -- goes out as twice as many half-height tiles, which
-// take about half as long each.  `shape`: 0 = this rule, 1 = full tiles only, 2 = half-height tiles only.
+// take about half as long each; a product with so few tiles that even those would leave half of the CUs idle goes out
+// as 128 x 128 tiles (plain epilogues only).  `shape`: 0 = this rule, 1 = full tiles only, 2 = half-height tiles only,
+// 3 = 128 x 128 tiles only (where there are none: the rule).
 template <bool AKC, bool BKC, int EPI>
 hipError_t launch(const GemmArgs& g, hipStream_t s, int shape) {
+  if constexpr (AKC && (EPI == EPI_STORE || EPI == EPI_RESID)) {
+    const int full = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+    if (shape == 3 || (shape == 0 && 4 * full <= cu_count())) {
+      const int qm = (g.M + 127) / 128, qn = (g.N + 127) / 128;
+      auto kern = gemm_quarter_kernel<AKC, BKC, EPI>;
+      static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+      if (attr != hipSuccess) return attr;
+      hipLaunchKernelGGL(kern, dim3(qm * qn), dim3(256), LDS_BYTES, s, g, qm, qn);
+      return hipGetLastError();
+    }
+  }
   const int tiles_m = (g.M + BM - 1) / BM;
   const int tiles_n = EPI == EPI_SWIGLU ? (g.N / 2 + GLU_BN - 1) / GLU_BN : (g.N + BN - 1) / BN, total = tiles_m * tiles_n;
   int n_half = 0;                         // full tiles at the end of the walk order that are split in two

@@ -971,7 +971,7 @@ int stage_kernel_gemm(int dtype, int mode, int M, int N, int K, const void* A, i
   if ((mode == GEMM_TN) != (acc_f32 != 0) || (acc_f32 && R)) return STAGE_E_INVAL;
   GemmArgs g{mode, M, N, K, A, lda, B, ldb, C, ldc, R, ldr, acc_f32};
   if (kernel_set != 1 && dtype == STAGE_DTYPE_BF16 && gemm_mfma_supported(g))
-    return hip_rc(gemm_mfma(g, (hipStream_t)hip_stream, kernel_set == 2 ? 1 : kernel_set == 3 ? 2 : 0));
+    return hip_rc(gemm_mfma(g, (hipStream_t)hip_stream, kernel_set == 2 ? 1 : kernel_set == 3 ? 2 : kernel_set == 4 ? 3 : 0));
   return hip_rc(gemm_ref((DType)dtype, g, (hipStream_t)hip_stream));
 }
 

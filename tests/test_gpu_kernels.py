@@ -50,11 +50,12 @@ def P(t):
 GEMM_SHAPES = [(128, 256, 768), (200, 192, 136), (328, 1088, 512), (512, 512, 2048), (257, 320, 72), (1024, 768, 264)]
 
 
-@pytest.mark.parametrize("dtype,kernel_set", [("fp32", 0), ("fp32", 1), ("bf16", 0), ("bf16", 1), ("bf16", 2), ("bf16", 3)])
+@pytest.mark.parametrize("dtype,kernel_set", [("fp32", 0), ("fp32", 1), ("bf16", 0), ("bf16", 1), ("bf16", 2), ("bf16", 3), ("bf16", 4)])
 @pytest.mark.parametrize("mode", [0, 1, 2])
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
 def test_gemm(dtype, mode, kernel_set, M, N, K):
-    """kernel_set 2 / 3: the tuned kernel with full 256 x 256 tiles only / half-height tiles only (0 mixes them by shape)."""
+    """kernel_set 2 / 3 / 4: the tuned kernel with full 256 x 256 tiles only / half-height tiles only / 128 x 128 tiles only
+    (0 picks by shape; weight gradients have full tiles only)."""
     import torch
     a_shape = (K, M) if mode == 2 else (M, K)
     b_shape = (N, K) if mode == 1 else (K, N)
@@ -82,22 +83,22 @@ def test_gemm(dtype, mode, kernel_set, M, N, K):
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("M,N,K", [(1160, 2304, 320), (520, 1088, 512), (1280, 5376, 192)])
 def test_gemm_tile_shapes_agree_bitwise(mode, M, N, K):
-    """Full tiles, half-height tiles and the mix chosen from the shape give the same bits: every output element is the
-    same sequence of MFMAs over K whichever tile it falls in.  (The last shape has 105 full tiles... and the first 45:
+    """Full tiles, half-height tiles, 128 x 128 tiles and the mix chosen from the shape give the same bits: every output
+    element is the same sequence of MFMAs over K whichever tile it falls in.  (The last shape has 105 full tiles... and the first 45:
     with forced shapes both kernels see ragged edges in M and N.)"""
     import torch
     A = rnd(synth.normal(11, 1, (M, K)), "bf16"); Bm = rnd(synth.normal(11, 2, (N, K) if mode == 1 else (K, N)), "bf16")
     R = rnd(synth.normal(11, 3, (M, N)), "bf16")
     Ad, Bd, Rd = to_dev(A, "bf16"), to_dev(Bm, "bf16"), to_dev(R, "bf16")
     outs = []
-    for ks in (2, 3, 0):
+    for ks in (2, 3, 4, 0):
         Cd = torch.zeros((M, N), dtype=Ad.dtype, device="cuda:0")
         rc = L().stage_kernel_gemm(DT["bf16"], mode, M, N, K, P(Ad), K, P(Bd), K if mode == 1 else N, P(Cd), N,
                                    P(Rd) if mode == 0 else None, N, 0, ks, None)
         assert rc == 0
         outs.append(Cd)
     torch.cuda.synchronize()
-    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert all(torch.equal(outs[0], o) for o in outs[1:])
 
 
 @pytest.mark.parametrize("dtype,kernel_set", [("fp32", 0), ("bf16", 0), ("bf16", 1), ("bf16", 2), ("bf16", 3)])
