@@ -47,7 +47,8 @@ def P(t):
     return None if t is None else t.data_ptr()
 
 
-GEMM_SHAPES = [(128, 256, 768), (200, 192, 136), (328, 1088, 512), (512, 512, 2048), (257, 320, 72), (1024, 768, 264)]
+GEMM_SHAPES = [(128, 256, 768), (200, 192, 136), (328, 1088, 512), (512, 512, 2048), (257, 320, 72), (1024, 768, 264),
+               (136, 72, 64), (72, 136, 128), (264, 136, 192)]      # the last three: one, two and three K tiles (the pipeline's start-up and tail alone)
 
 
 @pytest.mark.parametrize("dtype,kernel_set", [("fp32", 0), ("fp32", 1), ("bf16", 0), ("bf16", 1), ("bf16", 2), ("bf16", 3), ("bf16", 4)])
