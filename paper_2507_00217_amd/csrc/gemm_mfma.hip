@@ -369,61 +369,70 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     }
   }
   const int sub_b = (col_l & 4) * 2;      // byte inside a 16-byte piece at which this lane's 4 columns start
-  if (EPI == EPI_DGELU || EPI == EPI_DSWIGLU) {
-    // Activation backward on the fp32 accumulators (da), in place over the stashed z: 128 rows of the tile at a time,
-    // their z columns (gate, and for SwiGLU up) come global -> LDS directly, whole rows, into the layout of the bf16
-    // staging below (row r's piece p at r*512 + ((p ^ (r & 31)) << 4), the up half 64 KiB further on); the wavefronts
-    // that hold those rows' accumulators rewrite their elements in LDS; everybody stores the rows back.
+  if constexpr (EPI == EPI_DGELU || EPI == EPI_DSWIGLU) {
+    // Activation backward on the fp32 accumulators (da), in place over the stashed z, in four quarters of the tile: a
+    // quarter takes 32 rows from each 128-row half, so that every wavefront owns two of its accumulator block rows in
+    // it.  The quarter's z columns (gate, and for SwiGLU up) come global -> LDS directly, whole rows (row r's piece p at
+    // r*512 + ((p ^ (r & 31)) << 4), the up rows after the gate rows); the wavefronts rewrite their elements in LDS
+    // (each element has one owner); everybody stores the rows back.  Two quarter buffers: the next quarter's loads are
+    // in flight during this quarter's arithmetic and stores.
     constexpr int NOP = EPI == EPI_DSWIGLU ? 2 : 1;              // z operands per row: gate (| up)
-    constexpr int HALF_B = 128 * 512;                            // one operand, 128 rows
-    constexpr int NLD = (128 * 32) / (WAVES * 64);               // 16-byte pieces per thread, operand and half
+    constexpr int QROWS = WR * 32;                               // staged rows per quarter
+    constexpr int OPB = QROWS * 512, QBUF = NOP * OPB;           // bytes per operand and per quarter
+    constexpr int NLD = (QROWS * 32) / (WAVES * 64);             // 16-byte pieces per thread, operand and quarter
+    static_assert(NI == 8 && 2 * QBUF <= (int)LDS_BYTES, "quarters of two block rows per wavefront");
     const int f = g.N;
     const rsrc_words rsZ = raw_rsrc(g.Z, (unsigned)((((int64_t)(g.M - 1) * g.ldz) + NOP * f) * 2));
     typedef __attribute__((address_space(3))) bf16x4* lds_b4;
-    for (int h = 0; h < WR; ++h) {
-      __builtin_amdgcn_s_waitcnt(0);
-      __syncthreads();                 // main loop's last fragment reads / previous half's stores are done
+    auto quarter_loads = [&](int q, lds_char* buf) __attribute__((always_inline)) {
 #pragma unroll
       for (int o = 0; o < NOP; ++o)
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
-          const int s = (j * WAVES + wave) * 64 + lane, r = s >> 5, p = (s & 31) ^ (r & 31);
-          const int row = m0 + h * 128 + r, col = n0 + p * 8;
+          const int s = (j * WAVES + wave) * 64 + lane, sr = s >> 5, p = (s & 31) ^ (sr & 31);
+          const int row = m0 + (sr >> 5) * 128 + q * 32 + (sr & 31), col = n0 + p * 8;
           const unsigned off = (row < g.M && col < f) ? (unsigned)(((int64_t)row * g.ldz + o * f + col) * 2) : OOB;
-          load_to_lds_b128(rsZ, (unsigned)(size_t)(smem + o * HALF_B + (j * WAVES + wave) * 1024), off);
+          load_to_lds_b128(rsZ, (unsigned)(size_t)(buf + o * OPB + (j * WAVES + wave) * 1024), off);
         }
-      __builtin_amdgcn_s_waitcnt(0);
+    };
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();                   // the main loop's last fragment reads are done: the ring is free
+    quarter_loads(0, smem);
+    quarter_loads(1, smem + QBUF);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      lds_char* buf = smem + (q & 1) * QBUF;
+      __builtin_amdgcn_s_waitcnt(0);   // this quarter's rows (issued a quarter ago) and the previous quarter's stores
       __syncthreads();
-      if (wm == h * 128) {             // wave-uniform: this wavefront's rows are the ones in LDS
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-          const int r = i * 16 + row_l;
+      for (int ii = 0; ii < 2; ++ii) {
+        const int i = 2 * q + ii;
+        const int sr = (wm >> 7) * 32 + ii * 16 + row_l;
 #pragma unroll
-          for (int j = 0; j < NJ; ++j) {
-            const int p = (wn + j * 16 + col_l) >> 3;
-            lds_char* at = smem + r * 512 + ((p ^ (r & 31)) << 4) + sub_b;
-            if (EPI == EPI_DGELU) {
-              bf16x4 u = *(lds_b4)at, o4;
+        for (int j = 0; j < NJ; ++j) {
+          const int p = (wn + j * 16 + col_l) >> 3;
+          lds_char* at = buf + sr * 512 + ((p ^ (sr & 31)) << 4) + sub_b;
+          if (EPI == EPI_DGELU) {
+            bf16x4 u = *(lds_b4)at, o4;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const float uv = (float)u[e];
-                const float dgl = 0.5f * (1.f + erff(uv * 0.70710678118654752f)) + uv * 0.39894228040143268f * __expf(-0.5f * uv * uv);
-                o4[e] = (bf16)(acc[i][j][e] * dgl);
-              }
-              *(lds_b4)at = o4;
-              __builtin_amdgcn_sched_barrier(0);
-            } else {
-              bf16x4 gt = *(lds_b4)at, up = *(lds_b4)(at + HALF_B), og, ou;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const float gv = (float)gt[e], uv = (float)up[e], d = acc[i][j][e];
-                const float sg = 1.f / (1.f + __expf(-gv));
-                og[e] = (bf16)(d * uv * (sg + gv * sg * (1.f - sg)));
-                ou[e] = (bf16)(d * gv * sg);
-              }
-              *(lds_b4)at = og;
-              *(lds_b4)(at + HALF_B) = ou;
+            for (int e = 0; e < 4; ++e) {
+              const float uv = (float)u[e];
+              const float dgl = 0.5f * (1.f + erff(uv * 0.70710678118654752f)) + uv * 0.39894228040143268f * __expf(-0.5f * uv * uv);
+              o4[e] = (bf16)(acc[i][j][e] * dgl);
             }
+            *(lds_b4)at = o4;
+            __builtin_amdgcn_sched_barrier(0);
+          } else {
+            bf16x4 gt = *(lds_b4)at, up = *(lds_b4)(at + OPB), og, ou;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float gv = (float)gt[e], uv = (float)up[e], d = acc[i][j][e];
+              const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-gv));
+              og[e] = (bf16)(d * uv * (sg + gv * sg * (1.f - sg)));
+              ou[e] = (bf16)(d * gv * sg);
+            }
+            *(lds_b4)at = og;
+            *(lds_b4)(at + OPB) = ou;
           }
         }
       }
@@ -432,11 +441,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
       for (int o = 0; o < NOP; ++o)
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
-          const int s = (j * WAVES + wave) * 64 + lane, r = s >> 5, p = s & 31;      // lane order = column order: whole rows
-          const int row = m0 + h * 128 + r, col = n0 + p * 8;
-          const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(smem + o * HALF_B + r * 512 + ((p ^ (r & 31)) << 4));
+          const int s = (j * WAVES + wave) * 64 + lane, sr = s >> 5, p = s & 31;      // lane order = column order: whole rows
+          const int row = m0 + (sr >> 5) * 128 + q * 32 + (sr & 31), col = n0 + p * 8;
+          const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(buf + o * OPB + sr * 512 + ((p ^ (sr & 31)) << 4));
           if (row < g.M && col < f) *reinterpret_cast<u32x4*>((bf16*)g.Z + (int64_t)row * g.ldz + o * f + col) = v;
         }
+      if (q + 2 < 4) {
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): own reads of the buffer are done
+        __syncthreads();                       // ... and everybody else's
+        quarter_loads(q + 2, buf);
+      }
     }
     return;
   }
@@ -502,7 +516,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float gv = acc[i][jj][e];
-            o[e] = (bf16)(gv * (1.f / (1.f + __expf(-gv))) * acc[i][jj + NJ / 2][e]);
+            o[e] = (bf16)(gv * __builtin_amdgcn_rcpf(1.f + __expf(-gv)) * acc[i][jj + NJ / 2][e]);
           }
           *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(smem + r * 512 + ((((r & 16) | fp) ^ (r & 15)) << 4) + sub_b) = o;
         }
