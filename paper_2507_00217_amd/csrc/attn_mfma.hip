@@ -552,8 +552,11 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a) {
 // dK/dV: one workgroup = 128 keys of one (sequence, kv head) = 4 key blocks of 32, each worked on by TWO wavefronts
 // that share a SIMD (wavefronts w and w+4):
 //   the dV wavefront:  S = Q.K^T, P = exp(S - lse),                       dV^T += dO^T.P      16 MFMAs per 32 queries
-//   the dK wavefront:  S = Q.K^T, dP = dO.V^T, P, dS = P (dP - delta),    dK^T += Q^T.dS      24 MFMAs per 32 queries
-// S is computed twice, a quarter more MFMAs than one wavefront doing both.  What it buys: each role fits the
+//   the dK wavefront:  dP = dO.V^T, dS = P (dP - delta),                  dK^T += Q^T.dS      16 MFMAs per 32 queries
+// P is computed once: the dV wavefront leaves each 32 x 32 block of it (fp32, its own accumulator layout, which is the dK
+// wavefront's too) in a 4 KiB LDS slot of the pair and the dK wavefront picks it up -- a one-slot queue between two
+// wavefronts of the same workgroup, a produced and a consumed count in LDS; the waits are bounded spins on those counts
+// (the producer never waits for anything but the slot to be free, so they end).  What the split buys: each role fits the
 // 256-register budget of two wavefronts per SIMD with every accumulator in ordinary registers, and the vector
 // arithmetic of one role runs under the MFMAs of the other -- a single wavefront cannot overlap the two.
 // The workgroup walks the query heads of its group and their 128-query tiles (Q, dO, lse, delta of a tile go global ->
@@ -632,7 +635,7 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
   lds_char* lds = (lds_char*)smem_raw;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int role = 1 - (wave >> 2), kw = wave & 3;       // role 0: dV, role 1: dK (the longer one, on the older wavefront); kw and kw+4 share a SIMD
+  const int role = wave >> 2, kw = wave & 3;             // role 0: dV and the producer of P (on the older wavefront), role 1: dK; kw and kw+4 share a SIMD
   const int kt = blockIdx.y;                              // slow grid index: early key tiles see the most queries, first
   // grid.x = KV heads x splits: this workgroup takes `grp` of the query heads of KV head g, starting at head j0
   const int g = blockIdx.x / nsplit, sp = blockIdx.x % nsplit, ib = blockIdx.z;
@@ -689,6 +692,16 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
   lds_char* ldp = lds + LT + hf * 16;                 // this lane's lse values of the current buffer; delta follows TQ*4 later
   int hopb = BUFB;
   typedef __attribute__((address_space(3))) const f32x4* lds_f4;
+  // the pair's P slot ([e4][lane] f32x4) and its counts: produced = blocks written, consumed = blocks read
+  lds_char* pslot = lds + 2 * BUFB + kw * 4096 + lane * 16;
+  volatile __attribute__((address_space(3))) int* produced = (volatile __attribute__((address_space(3))) int*)(lds + 2 * BUFB + 4 * 4096) + kw;
+  volatile __attribute__((address_space(3))) int* consumed = produced + 4;
+  if (tid < 8) ((volatile __attribute__((address_space(3))) int*)(lds + 2 * BUFB + 4 * 4096))[tid] = 0;   // published by the barrier below
+  auto wait_for = [&](volatile __attribute__((address_space(3))) int* count, int value) {
+    for (int guard = 0; *count != value && guard < (1 << 20); ++guard) __builtin_amdgcn_s_sleep(1);
+    asm volatile("" ::: "memory");                       // nothing of what follows is read or written ahead of the wait
+  };
+  int nblk = 0;                                          // 32 x 32 blocks of P handled so far
 
   // end of an iteration: the next tiles have landed and every wavefront is done with this buffer; refill it
   auto turn = [&](int it) {
@@ -744,6 +757,14 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
           for (int e = 0; e < 4; ++e) p[e4 * 4 + e] = pv[e];
         }
         const bf16x8 pf[2] = {pack8(&p[0]), pack8(&p[8])};
+        wait_for(consumed, nblk);                      // the slot is free
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4)
+          *(__attribute__((address_space(3))) f32x4*)(pslot + e4 * 1024) = f32x4{p[e4 * 4], p[e4 * 4 + 1], p[e4 * 4 + 2], p[e4 * 4 + 3]};
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): the block is in LDS
+        asm volatile("" ::: "memory");
+        *produced = ++nblk;
         SCHED_FENCE;
         dkv_tr_product<HD, OT>(lds, fo, qc * 32, tf, pf, acc);          // dV^T += dO^T . P
       }
@@ -756,24 +777,27 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     for (int it = 0; it < niter; ++it) {
-      const int q0 = (t_first + it % per_head) * TQ;
-      const bool diag = a.causal && it % per_head == 0;
-      const int lim0 = key - q0 - hf * 4;
 #pragma unroll
       for (int qc = 0; qc < NB; ++qc) {
-        f32x16 sacc, pacc;
-        dkv_rows_product2<HD, QT, OT>(lds, fo, qc * 32, kf, vf, sacc, pacc);      // S = Q.K^T, dP = dO.V^T
+        f32x16 pacc;
+        dkv_rows_product<HD, OT>(lds, fo, qc * 32, vf, pacc);                     // dP = dO.V^T
         bf16x8 tf[4];
         dkv_tr_read<HD, QT>(lds, fo, qc * 32, tf);
         SCHED_FENCE;
+        wait_for(produced, nblk + 1);                  // the partner has left this block's P (masked where causal) in the slot
+        f32x4 pv[4];
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) pv[e4] = *(__attribute__((address_space(3))) const f32x4*)(pslot + e4 * 1024);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): the block is in registers
+        asm volatile("" ::: "memory");
+        *consumed = ++nblk;
         float ds[16];
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
-          float pv[4];
-          probs4(sacc, qc, e4, diag, lim0, pv);
           const f32x4 d4 = *reinterpret_cast<lds_f4>(ldp + (DT - LT) + (qc * 32 + e4 * 8) * 4);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) ds[e4 * 4 + e] = pv[e] * (pacc[e4 * 4 + e] - d4[e]);
+          for (int e = 0; e < 4; ++e) ds[e4 * 4 + e] = pv[e4][e] * (pacc[e4 * 4 + e] - d4[e]);
         }
         const bf16x8 df[2] = {pack8(&ds[0]), pack8(&ds[8])};
         SCHED_FENCE;
@@ -830,7 +854,7 @@ __global__ __launch_bounds__(256) void attn_dkv_reduce_kernel(AttnArgs a, int ns
 
 // dynamic LDS of the kernels above
 template <int HD> constexpr size_t fwd_lds() { return (size_t)4 * Geo<HD>::TILEB; }
-template <int HD> constexpr size_t dkv_lds() { return (size_t)2 * (2 * DKV_TQ * Geo<HD>::ROWB + 2 * DKV_TQ * 4); }
+template <int HD> constexpr size_t dkv_lds() { return (size_t)2 * (2 * DKV_TQ * Geo<HD>::ROWB + 2 * DKV_TQ * 4) + 4 * 4096 + 64; }   // + P slots and counts
 
 template <typename K>
 hipError_t allow_lds(K kern, size_t bytes) {
