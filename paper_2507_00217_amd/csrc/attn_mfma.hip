@@ -715,8 +715,9 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
   };
   // P of elements e4*4 .. +3 of query block qc (element e is query q0 + qc*32 + e4*8 + hf*4 + e).  Only the diagonal
   // tile needs the causal mask: an element is masked when its query is before the lane's key, i.e. e < lim.
-  auto probs4 = [&](const f32x16& sacc, int qc, int e4, bool diag, int lim0, float (&pv)[4]) {
-    const f32x4 l4 = *reinterpret_cast<lds_f4>(ldp + (qc * 32 + e4 * 8) * 4);
+  // (l4: the lse values of those queries, read from LDS ahead of the product that makes sacc -- read where they are
+  // used, each of the four loads would cost the wavefront a full LDS round trip)
+  auto probs4 = [&](const f32x16& sacc, const f32x4& l4, int qc, int e4, bool diag, int lim0, float (&pv)[4]) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) pv[e] = fast_exp2(fmaf(sacc[e4 * 4 + e], sl2, -LOG2E * l4[e]));
     if (diag) {
@@ -743,6 +744,9 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
       const int lim0 = key - q0 - hf * 4;
 #pragma unroll
       for (int qc = 0; qc < NB; ++qc) {
+        f32x4 l4[4];
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) l4[e4] = *reinterpret_cast<lds_f4>(ldp + (qc * 32 + e4 * 8) * 4);
         f32x16 sacc;
         dkv_rows_product<HD, QT>(lds, fo, qc * 32, kf, sacc);
         bf16x8 tf[4];
@@ -752,7 +756,7 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
           float pv[4];
-          probs4(sacc, qc, e4, diag, lim0, pv);
+          probs4(sacc, l4[e4], qc, e4, diag, lim0, pv);
 #pragma unroll
           for (int e = 0; e < 4; ++e) p[e4 * 4 + e] = pv[e];
         }
@@ -779,6 +783,9 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
     for (int it = 0; it < niter; ++it) {
 #pragma unroll
       for (int qc = 0; qc < NB; ++qc) {
+        f32x4 d4[4];                                    // delta of the block's queries, ahead of the product (see probs4)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) d4[e4] = *reinterpret_cast<lds_f4>(ldp + (DT - LT) + (qc * 32 + e4 * 8) * 4);
         f32x16 pacc;
         dkv_rows_product<HD, OT>(lds, fo, qc * 32, vf, pacc);                     // dP = dO.V^T
         bf16x8 tf[4];
@@ -795,9 +802,8 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
         float ds[16];
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
-          const f32x4 d4 = *reinterpret_cast<lds_f4>(ldp + (DT - LT) + (qc * 32 + e4 * 8) * 4);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) ds[e4 * 4 + e] = pv[e4][e] * (pacc[e4 * 4 + e] - d4[e]);
+          for (int e = 0; e < 4; ++e) ds[e4 * 4 + e] = pv[e4][e] * (pacc[e4 * 4 + e] - d4[e4][e]);
         }
         const bf16x8 df[2] = {pack8(&ds[0]), pack8(&ds[8])};
         SCHED_FENCE;
