@@ -555,8 +555,9 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a) {
 //   the dK wavefront:  dP = dO.V^T, dS = P (dP - delta),                  dK^T += Q^T.dS      16 MFMAs per 32 queries
 // P is computed once: the dV wavefront leaves each 32 x 32 block of it (fp32, its own accumulator layout, which is the dK
 // wavefront's too) in a 4 KiB LDS slot of the pair and the dK wavefront picks it up -- a one-slot queue between two
-// wavefronts of the same workgroup, a produced and a consumed count in LDS; the waits are bounded spins on those counts
-// (the producer never waits for anything but the slot to be free, so they end).  What the split buys: each role fits the
+// wavefronts of the same workgroup, a produced and a consumed count in LDS (written right behind the block's writes or
+// reads: the LDS executes a wavefront's instructions in order); the waits are bounded spins on those counts (the
+// producer never waits for anything but the slot to be free, so they end).  What the split buys: each role fits the
 // 256-register budget of two wavefronts per SIMD with every accumulator in ordinary registers, and the vector
 // arithmetic of one role runs under the MFMAs of the other -- a single wavefront cannot overlap the two.
 // The workgroup walks the query heads of its group and their 128-query tiles (Q, dO, lse, delta of a tile go global ->
@@ -760,15 +761,14 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
 #pragma unroll
           for (int e = 0; e < 4; ++e) p[e4 * 4 + e] = pv[e];
         }
-        const bf16x8 pf[2] = {pack8(&p[0]), pack8(&p[8])};
         wait_for(consumed, nblk);                      // the slot is free
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4)
           *(__attribute__((address_space(3))) f32x4*)(pslot + e4 * 1024) = f32x4{p[e4 * 4], p[e4 * 4 + 1], p[e4 * 4 + 2], p[e4 * 4 + 3]};
+        asm volatile("" ::: "memory");                 // the LDS executes a wavefront's instructions in order: the count
+        *produced = ++nblk;                            // is written after the block, no wait in between
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): the block is in LDS
-        asm volatile("" ::: "memory");
-        *produced = ++nblk;
+        const bf16x8 pf[2] = {pack8(&p[0]), pack8(&p[8])};
         SCHED_FENCE;
         dkv_tr_product<HD, OT>(lds, fo, qc * 32, tf, pf, acc);          // dV^T += dO^T . P
       }
@@ -795,10 +795,9 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
         f32x4 pv[4];
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) pv[e4] = *(__attribute__((address_space(3))) const f32x4*)(pslot + e4 * 1024);
+        asm volatile("" ::: "memory");                 // in-order LDS: the slot has been read by the time the count is
+        *consumed = ++nblk;                            // written, whenever the data reaches the registers
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): the block is in registers
-        asm volatile("" ::: "memory");
-        *consumed = ++nblk;
         float ds[16];
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
