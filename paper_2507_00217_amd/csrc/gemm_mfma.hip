@@ -596,9 +596,10 @@ __global__ __launch_bounds__(WR * 512 / TN) void gemm_mfma_kernel(GemmArgs g, in
                                    (lds_char*)smem_raw);
 }
 
-// one workgroup per 128 x 128 tile (four wavefronts of 64 x 64), tiles counted in units of 128
+// one workgroup per 128 x 128 tile (four wavefronts of 64 x 64): workgroup `bid` takes quadrant bid % 4 of the full
+// tile number first + bid / 4 of the walk order; a quadrant that lies outside the matrix has nothing to do
 template <bool AKC, bool BKC, int EPI>
-__global__ __launch_bounds__(256) void gemm_quarter_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(256) void gemm_quarter_kernel(GemmArgs g, int tiles_m, int tiles_n, int first) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   int bid = blockIdx.x;
   {
@@ -606,8 +607,10 @@ __global__ __launch_bounds__(256) void gemm_quarter_kernel(GemmArgs g, int tiles
     if (bid < main) bid = (bid & 7) * per + (bid >> 3);
   }
   int tile_m, tile_n;
-  tile_of(bid, tiles_m, tiles_n, tile_m, tile_n);
-  gemm_tile<AKC, BKC, EPI, 2, 1, 1>(g, tile_m * 128, tile_n * 128, (lds_char*)smem_raw);
+  tile_of(first + (bid >> 2), tiles_m, tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM + (bid & 1) * 128, n0 = tile_n * BN + ((bid >> 1) & 1) * 128;
+  if (m0 >= g.M || n0 >= g.N) return;                  // the same for the whole workgroup
+  gemm_tile<AKC, BKC, EPI, 2, 1, 1>(g, m0, n0, (lds_char*)smem_raw);
 }
 
 // Several weight-gradient products C_p += A_p^T . B_p in one launch of persistent workgroups.  Each workgroup
@@ -674,40 +677,41 @@ hipError_t launch_tiles(const GemmArgs& g, hipStream_t s, int tiles_m, int tiles
 
 // Full tiles for every complete round of one tile per CU; what is left over -- a last round that would keep at most
 // half of the CUs busy, or a whole product with that few tiles -- goes out as twice as many half-height tiles, which
-// take about half as long each; a product with so few tiles that even those would leave half of the CUs idle goes out
-// as 128 x 128 tiles (plain epilogues only).  `shape`: 0 = this rule, 1 = full tiles only, 2 = half-height tiles only,
-// 3 = 128 x 128 tiles only (where there are none: the rule).
+// take about two thirds as long each, or, if that would still leave half of the CUs idle and the epilogue is a plain
+// one, as four times as many 128 x 128 tiles (two fifths as long each).  `shape`: 0 = this rule, 1 = full tiles only,
+// 2 = half-height tiles only, 3 = 128 x 128 tiles only (where there are none: the rule).
 template <bool AKC, bool BKC, int EPI>
 hipError_t launch(const GemmArgs& g, hipStream_t s, int shape) {
-  if constexpr (AKC && (EPI == EPI_STORE || EPI == EPI_RESID)) {
-    const int full = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-    if (shape == 3 || (shape == 0 && 4 * full <= cu_count())) {
-      const int qm = (g.M + 127) / 128, qn = (g.N + 127) / 128;
-      auto kern = gemm_quarter_kernel<AKC, BKC, EPI>;
-      static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
-      if (attr != hipSuccess) return attr;
-      hipLaunchKernelGGL(kern, dim3(qm * qn), dim3(256), LDS_BYTES, s, g, qm, qn);
-      return hipGetLastError();
-    }
-  }
   const int tiles_m = (g.M + BM - 1) / BM;
   const int tiles_n = EPI == EPI_SWIGLU ? (g.N / 2 + GLU_BN - 1) / GLU_BN : (g.N + BN - 1) / BN, total = tiles_m * tiles_n;
-  int n_half = 0;                         // full tiles at the end of the walk order that are split in two
+  constexpr bool QUARTERS = AKC && (EPI == EPI_STORE || EPI == EPI_RESID);
+  int n_half = 0, n_quarter = 0;          // full tiles at the end of the walk order that are split in two / in four
   if constexpr (AKC) {
     const int n_cu = cu_count(), tail = total % n_cu;
-    n_half = shape == 2 ? total : shape == 1 ? 0 : (2 * tail <= n_cu ? tail : 0);
+    if (QUARTERS && (shape == 3 || (shape == 0 && 4 * tail <= n_cu))) n_quarter = shape == 3 ? total : tail;
+    else n_half = shape == 2 ? total : shape == 1 ? 0 : (2 * tail <= n_cu ? tail : 0);
   }
-  if (total > n_half) {
+  const int n_small = n_half + n_quarter;
+  if (total > n_small) {
     hipError_t e;
     if constexpr (AKC && BKC && EPI == EPI_STORE)
-      e = g.K >= WIDE_MIN_K ? launch_tiles<AKC, BKC, EPI, 2, 4>(g, s, tiles_m, tiles_n, 0, total - n_half)
-                            : launch_tiles<AKC, BKC, EPI, 2>(g, s, tiles_m, tiles_n, 0, total - n_half);
+      e = g.K >= WIDE_MIN_K ? launch_tiles<AKC, BKC, EPI, 2, 4>(g, s, tiles_m, tiles_n, 0, total - n_small)
+                            : launch_tiles<AKC, BKC, EPI, 2>(g, s, tiles_m, tiles_n, 0, total - n_small);
     else
-      e = launch_tiles<AKC, BKC, EPI, 2>(g, s, tiles_m, tiles_n, 0, total - n_half);
+      e = launch_tiles<AKC, BKC, EPI, 2>(g, s, tiles_m, tiles_n, 0, total - n_small);
     if (e != hipSuccess) return e;
   }
   if constexpr (AKC) {
     if (n_half) return launch_tiles<AKC, BKC, EPI, 1>(g, s, tiles_m, tiles_n, total - n_half, 2 * n_half);
+  }
+  if constexpr (QUARTERS) {
+    if (n_quarter) {
+      auto kern = gemm_quarter_kernel<AKC, BKC, EPI>;
+      static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+      if (attr != hipSuccess) return attr;
+      hipLaunchKernelGGL(kern, dim3(4 * n_quarter), dim3(256), LDS_BYTES, s, g, tiles_m, tiles_n, total - n_quarter);
+      return hipGetLastError();
+    }
   }
   return hipSuccess;
 }

@@ -82,11 +82,12 @@ def test_gemm(dtype, mode, kernel_set, M, N, K):
 
 
 @pytest.mark.parametrize("mode", [0, 1])
-@pytest.mark.parametrize("M,N,K", [(1160, 2304, 320), (520, 1088, 512), (1280, 5376, 192)])
+@pytest.mark.parametrize("M,N,K", [(1160, 2304, 320), (520, 1088, 512), (1280, 5376, 192), (4352, 4104, 128)])
 def test_gemm_tile_shapes_agree_bitwise(mode, M, N, K):
     """Full tiles, half-height tiles, 128 x 128 tiles and the mix chosen from the shape give the same bits: every output
-    element is the same sequence of MFMAs over K whichever tile it falls in.  (The last shape has 105 full tiles... and the first 45:
-    with forced shapes both kernels see ragged edges in M and N.)"""
+    element is the same sequence of MFMAs over K whichever tile it falls in.  (The third shape has 105 full tiles and the first 45:
+    with forced shapes both kernels see ragged edges in M and N; the last one has 17 x 17 = 289 full tiles on 256 CUs, so the
+    rule gives its last 33 tiles to the 128 x 128 kernel.)"""
     import torch
     A = rnd(synth.normal(11, 1, (M, K)), "bf16"); Bm = rnd(synth.normal(11, 2, (N, K) if mode == 1 else (K, N)), "bf16")
     R = rnd(synth.normal(11, 3, (M, N)), "bf16")
