@@ -15,7 +15,8 @@
  * normally make from the shape fixed, so that tests reach both variants on any
  * shape -- GEMM: 2 = full 256 x 256 tiles only, 3 = half-height tiles only, 4 (stage_kernel_gemm, forward and
  * input-gradient layouts) = 128 x 128 tiles only;
- * attention: 2 / 3 = forward and dQ workgroups of 8 / 4 wavefronts.
+ * attention: 2 / 3 = forward and dQ workgroups of 8 / 4 wavefronts (dK/dV workgroups of 128 keys), 4 = forward and dQ
+ * workgroups of 64 queries whose two wavefronts per query block each take half of the keys, dK/dV workgroups of 64 keys.
  * Return: 0, or STAGE_E_INVAL for
  * a shape the kernel does not take, STAGE_E_HIP for a failed launch.
  */

@@ -38,6 +38,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -206,7 +207,17 @@ __device__ __forceinline__ int acc_row(int e, int hf) { return (e >> 2) * 8 + hf
 // a CU, so either way two wavefronts sit on each SIMD; 8 read every K/V tile once for twice the queries and are faster
 // when there is plenty of work, 4 give twice as many workgroups and win when 8 would leave CUs idle.
 constexpr int FWD_WIDE = 512, FWD_NARROW = 256;
-constexpr int fwd_bq(int nthr) { return (nthr / 64) * 32; }
+constexpr int fwd_bq(int nthr, int ks = 1) { return (nthr / 64) * 32 / ks; }
+
+// Which query tile (forward, dQ: the later, the more keys it sees) the workgroup of dispatch rank `rank` takes.
+// Plain order is heaviest first.  `fold`: the heavier half first, heaviest first, then the lighter half, lightest
+// first -- for grids that are resident all at once with two workgroups per CU, so that a CU's second workgroup is as
+// light as its first is heavy (ranks r and r + nh add up to the same work) instead of the chip waiting for the CUs that
+// drew two heavy ones.
+__device__ __forceinline__ int tile_of_rank(int rank, int n, int fold) {
+  const int nh = (n + 1) >> 1;
+  return (!fold || rank < nh) ? n - 1 - rank : rank - nh;
+}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; -inf -> 0
 
@@ -214,26 +225,28 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // One key tile of the forward for one wavefront (32 queries x 64 keys).  LDS fragment reads run ahead of the MFMAs
 // that consume them (K fragments three k-steps ahead; the first V^T fragments are fetched before the softmax
 // arithmetic and land while it runs), so a wavefront does not sit out one LDS round trip per MFMA.
-template <int HD, int BUF>
+template <int HD, int BUF, int NC = 2>
 __device__ __forceinline__ void fwd_tile(lds_char* lds, const FragOff<HD>& fo, const bf16x8 (&qf)[HD / 16], f32x16 (&o)[HD / 32],
                                          float& m, float& l, int kv0, int q, int hf, int s, int causal, float sl2, bool need_mask) {
   using G = Geo<HD>;
-  constexpr int KT = BUF, VT = BUF + G::TILEB, AHEAD = 3, NPV = G::NHB * 4, VA = 4;
-  // S^T[key][query] for two 32-key blocks
-  bf16x8 kf[AHEAD + 1][2];
+  constexpr int KT = BUF, VT = BUF + G::TILEB, AHEAD = 3, NPV = G::NHB * 2 * NC, VA = 4;
+  // S^T[key][query] for NC 32-key blocks
+  bf16x8 kf[AHEAD + 1][NC];
 #pragma unroll
-  for (int kk = 0; kk < AHEAD; ++kk) { kf[kk][0] = frag_rows<HD>(lds, fo, KT, 0, kk); kf[kk][1] = frag_rows<HD>(lds, fo, KT, 32, kk); }
-  f32x16 sacc[2];
+  for (int kk = 0; kk < AHEAD; ++kk)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) kf[kk][c] = frag_rows<HD>(lds, fo, KT, c * 32, kk);
+  f32x16 sacc[NC];
 #pragma unroll
   for (int kk = 0; kk < G::NKK; ++kk) {
     if (kk + AHEAD < G::NKK) {
-      kf[(kk + AHEAD) % (AHEAD + 1)][0] = frag_rows<HD>(lds, fo, KT, 0, kk + AHEAD);
-      kf[(kk + AHEAD) % (AHEAD + 1)][1] = frag_rows<HD>(lds, fo, KT, 32, kk + AHEAD);
+#pragma unroll
+      for (int c = 0; c < NC; ++c) kf[(kk + AHEAD) % (AHEAD + 1)][c] = frag_rows<HD>(lds, fo, KT, c * 32, kk + AHEAD);
     }
-    if (kk == 0) { sacc[0] = mfma0(kf[0][0], qf[0]); sacc[1] = mfma0(kf[0][1], qf[0]); }
-    else {
-      sacc[0] = MFMA(kf[kk % (AHEAD + 1)][0], qf[kk], sacc[0]);
-      sacc[1] = MFMA(kf[kk % (AHEAD + 1)][1], qf[kk], sacc[1]);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      if (kk == 0) sacc[c] = mfma0(kf[0][c], qf[0]);
+      else sacc[c] = MFMA(kf[kk % (AHEAD + 1)][c], qf[kk], sacc[c]);
     }
     SCHED_FENCE;
   }
@@ -247,22 +260,22 @@ __device__ __forceinline__ void fwd_tile(lds_char* lds, const FragOff<HD>& fo, c
   if (need_mask) {
     const int bound = min(causal ? q - kv0 : 0x7fffffff, s - 1 - kv0) - hf * 4;
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < NC; ++c)
 #pragma unroll
       for (int e = 0; e < 16; ++e)
         if (c * 32 + acc_row(e, 0) > bound) sacc[c][e] = -INFINITY;
   }
   float mx = -INFINITY;                           // raw scores; sl2 > 0, so the max can be taken before scaling
 #pragma unroll
-  for (int c = 0; c < 2; ++c)
+  for (int c = 0; c < NC; ++c)
 #pragma unroll
     for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[c][e]);
-  float p[2][16];
+  float p[NC][16];
   mx = fmaxf(mx, xhalf(mx));
   const float mn = fmaxf(m, mx * sl2);
   float sum = 0.f;
 #pragma unroll
-  for (int c = 0; c < 2; ++c)
+  for (int c = 0; c < NC; ++c)
 #pragma unroll
     for (int e = 0; e < 16; ++e) p[c][e] = fast_exp2(fmaf(sacc[c][e], sl2, -mn));
   if (__any(mn != m)) {                          // the running max moved for some query of the wavefront
@@ -273,13 +286,13 @@ __device__ __forceinline__ void fwd_tile(lds_char* lds, const FragOff<HD>& fo, c
 #pragma unroll
       for (int e = 0; e < 16; ++e) o[hb][e] *= alpha;
   }
-  bf16x8 pf[2][2];
+  bf16x8 pf[NC][2];
 #pragma unroll
-  for (int c = 0; c < 2; ++c) { pf[c][0] = pack8(&p[c][0]); pf[c][1] = pack8(&p[c][8]); }
+  for (int c = 0; c < NC; ++c) { pf[c][0] = pack8(&p[c][0]); pf[c][1] = pack8(&p[c][8]); }
   // row sum of the probabilities as rounded for the P.V product (so the weights applied to V sum to one exactly),
   // two per instruction
 #pragma unroll
-  for (int c = 0; c < 2; ++c)
+  for (int c = 0; c < NC; ++c)
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) sum = dot_ones(pf[c][t2], sum);
   sum += xhalf(sum);
@@ -299,24 +312,28 @@ __device__ __forceinline__ void fwd_tile(lds_char* lds, const FragOff<HD>& fo, c
   }
 }
 
-template <int HD, int FWD_THREADS>
-__global__ __launch_bounds__(FWD_THREADS, 2) void attn_fwd_kernel(AttnArgs a) {
+// KS = 2 (small grids): two wavefronts per 32 queries, each taking one 32-key half of every key tile, so that a
+// workgroup of 4 wavefronts covers only 64 queries and there are twice as many workgroups (and still two wavefronts on
+// every SIMD); the halves' (O, m, l) are merged through LDS at the end.
+template <int HD, int FWD_THREADS, int KS>
+__global__ __launch_bounds__(FWD_THREADS, 2) void attn_fwd_kernel(AttnArgs a, int fold) {
   using G = Geo<HD>;
   constexpr int KT = 0, VT = G::TILEB, BUFB = 2 * G::TILEB;   // two buffers of (K tile, V tile)
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char* lds = (lds_char*)smem_raw;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  constexpr int BQ = fwd_bq(FWD_THREADS);
+  constexpr int BQ = fwd_bq(FWD_THREADS, KS), KW = TK / KS;
+  const int qb = KS == 2 ? wave >> 1 : wave, kh = KS == 2 ? wave & 1 : 0;   // query block, key half
   const int nqt = (a.s + BQ - 1) / BQ;
-  const int qt = nqt - 1 - blockIdx.y;              // slow grid index: heaviest (latest) query tiles are dispatched first
-  const int j = blockIdx.x, ib = blockIdx.z;
+  const int qt = tile_of_rank(blockIdx.y / a.b, nqt, fold);   // slow grid index: heavy (late) query tiles are dispatched first
+  const int j = blockIdx.x, ib = blockIdx.y % a.b;
   const int d = a.h * HD, dkv = a.hkv * HD, g = j / (a.h / a.hkv);
   const bf16* base = (const bf16*)a.qkv + (int64_t)ib * a.s * a.ld;
   const bf16* qp = base + j * HD;
   const rsrc_words rsK = head_rsrc(base + d + g * HD, a.ld, a.s, HD);
   const rsrc_words rsV = head_rsrc(base + d + dkv + g * HD, a.ld, a.s, HD);
-  const int q0b = qt * BQ, q0w = q0b + wave * 32;
+  const int q0b = qt * BQ, q0w = q0b + qb * 32;
   const int q = q0w + (lane & 31);
   const float sl2 = rsqrtf((float)HD) * LOG2E;
 
@@ -342,6 +359,7 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_fwd_kernel(AttnArgs a) {
 
   FragOff<HD> fo;
   fo.init(lane, lds);
+  if (KS == 2) fo.hop(kh * 32 * G::ROWB);           // this wavefront's half of every tile
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
@@ -350,11 +368,11 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_fwd_kernel(AttnArgs a) {
   // covers two tiles so that the buffer is a compile-time part of every LDS address.
   auto step = [&](int t, auto buf) {
     constexpr int BUF = decltype(buf)::value;
-    const int kv0 = t * TK;
-    const bool active = !a.causal || kv0 <= min(q0w + 32, a.s) - 1;
+    const int kv0 = t * TK, kvw = kv0 + kh * 32;     // first key of the tile, of the wavefront's part of it
+    const bool active = kvw < a.s && (!a.causal || kvw <= min(q0w + 32, a.s) - 1);
     if (active && q0w < a.s) {
-      const bool need_mask = (a.causal && kv0 + TK - 1 > q0w) || kv0 + TK > a.s;
-      fwd_tile<HD, BUF>(lds, fo, qf, o, m, l, kv0, q, hf, a.s, a.causal, sl2, need_mask);
+      const bool need_mask = (a.causal && kvw + KW - 1 > q0w) || kvw + KW > a.s;
+      fwd_tile<HD, BUF, 2 / KS>(lds, fo, qf, o, m, l, kvw, q, hf, a.s, a.causal, sl2, need_mask);
     }
     __builtin_amdgcn_s_waitcnt(0);                  // tile t+1 has landed (issued a whole tile ago), own LDS reads done
     __syncthreads();
@@ -368,6 +386,38 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_fwd_kernel(AttnArgs a) {
     if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, BUFB>{});
   }
 
+  if constexpr (KS == 2) {
+    // The loop's last barrier has passed: nobody reads the tiles any more and no load is in flight.  The second half's
+    // wavefront leaves its (O, m, l) in LDS ([piece][lane] of 16 bytes), the first half's folds them into its own.
+    constexpr int OB = G::NHB * 4 * 1024;            // bytes of one wavefront's O: NHB * 4 pieces of 16 bytes per lane
+    static_assert(2 * (OB + 512) <= 4 * G::TILEB, "the merge area fits the tile buffers");
+    lds_char* mo = lds + qb * (OB + 512) + lane * 16;
+    lds_char* ml = lds + qb * (OB + 512) + OB + lane * 8;
+    if (kh == 1) {
+#pragma unroll
+      for (int hb = 0; hb < G::NHB; ++hb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          *(__attribute__((address_space(3))) f32x4*)(mo + (hb * 4 + q4) * 1024) =
+              f32x4{o[hb][q4 * 4], o[hb][q4 * 4 + 1], o[hb][q4 * 4 + 2], o[hb][q4 * 4 + 3]};
+      *(__attribute__((address_space(3))) f32x2*)ml = f32x2{m, l};
+    }
+    __syncthreads();
+    if (kh == 1) return;
+    const f32x2 other = *(__attribute__((address_space(3))) const f32x2*)ml;
+    const float mn = fmaxf(m, other.x);
+    const float a0 = fast_exp2(m - mn), a1 = fast_exp2(other.x - mn);   // a half that saw no key has m = -1e30, l = 0, O = 0
+    l = l * a0 + other.y * a1;
+#pragma unroll
+    for (int hb = 0; hb < G::NHB; ++hb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 v = *(__attribute__((address_space(3))) const f32x4*)(mo + (hb * 4 + q4) * 1024);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[hb][q4 * 4 + e] = o[hb][q4 * 4 + e] * a0 + v[e] * a1;
+      }
+    m = mn;
+  }
   if (q < a.s) {
     const float inv = 1.f / l;
     bf16* orow = (bf16*)a.o + ((int64_t)ib * a.s + q) * d + j * HD;
@@ -443,25 +493,26 @@ __device__ __forceinline__ void dq_block(lds_char* lds, const FragOff<HD>& fo, c
 // dQ: one workgroup = 8 wavefronts x 32 queries of one (sequence, head); two wavefronts per SIMD so that one
 // wavefront's exp / dS arithmetic overlaps the other's MFMAs
 // ---------------------------------------------------------------------------
-template <int HD, int FWD_THREADS>
-__global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a) {
+template <int HD, int FWD_THREADS, int KS>
+__global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a, int fold) {
   using G = Geo<HD>;
   constexpr int KT = 0, VT = G::TILEB, BUFB = 2 * G::TILEB;   // two buffers of (K tile, V tile)
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char* lds = (lds_char*)smem_raw;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  constexpr int BQ = fwd_bq(FWD_THREADS);
+  constexpr int BQ = fwd_bq(FWD_THREADS, KS);
+  const int qb = KS == 2 ? wave >> 1 : wave, kh = KS == 2 ? wave & 1 : 0;   // query block, key half (as in the forward)
   const int nqt = (a.s + BQ - 1) / BQ;
-  const int qt = nqt - 1 - blockIdx.y;              // slow grid index: heaviest query tiles first
-  const int j = blockIdx.x, ib = blockIdx.z;
+  const int qt = tile_of_rank(blockIdx.y / a.b, nqt, fold);   // slow grid index: heavy query tiles first
+  const int j = blockIdx.x, ib = blockIdx.y % a.b;
   const int d = a.h * HD, dkv = a.hkv * HD, g = j / (a.h / a.hkv);
   const bf16* base = (const bf16*)a.qkv + (int64_t)ib * a.s * a.ld;
   const bf16* qp = base + j * HD;
   const rsrc_words rsK = head_rsrc(base + d + g * HD, a.ld, a.s, HD);
   const rsrc_words rsV = head_rsrc(base + d + dkv + g * HD, a.ld, a.s, HD);
   const bf16* dop = (const bf16*)a.dout + (int64_t)ib * a.s * d + j * HD;
-  const int q0b = qt * BQ, q0w = q0b + wave * 32;
+  const int q0b = qt * BQ, q0w = q0b + qb * 32;
   const float scale = rsqrtf((float)HD), sl2 = scale * LOG2E;
   const int q = q0w + (lane & 31);
 
@@ -498,7 +549,7 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a) {
   }
   if (q < a.s) {
     lse2 = a.lse[((int64_t)ib * a.h + j) * a.s + q] * LOG2E;
-    if (hf == 0) a.delta[((int64_t)ib * a.h + j) * a.s + q] = dl;
+    if (hf == 0 && kh == 0) a.delta[((int64_t)ib * a.h + j) * a.s + q] = dl;
   }
   f32x16 dq[G::NHB];
 #pragma unroll
@@ -506,6 +557,7 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a) {
 
   FragOff<HD> fo;
   fo.init(lane, lds);
+  if (KS == 2) fo.hop(kh * 32 * G::ROWB);           // this wavefront's half of every tile
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
@@ -513,13 +565,19 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a) {
   auto step = [&](int t, auto buf) {
     constexpr int BUF = decltype(buf)::value;
     const int kv0 = t * TK;
-    const bool active = !a.causal || kv0 <= min(q0w + 32, a.s) - 1;
+    const int kvw = kv0 + kh * 32;                    // first key of the wavefront's part of the tile
+    const bool active = kvw < a.s && (!a.causal || kvw <= min(q0w + 32, a.s) - 1);
     if (active && q0w < a.s) {
-      const bool need_mask = (a.causal && kv0 + TK - 1 > q0w) || kv0 + TK > a.s;
+      if constexpr (KS == 2) {
+        const bool need_mask = (a.causal && kvw + 31 > q0w) || kvw + 32 > a.s;
+        dq_block<HD, BUF>(lds, fo, qf, dof, dq, 0, kvw, q, hf, a.s, a.causal, sl2, lse2, dl, need_mask);
+      } else {
+        const bool need_mask = (a.causal && kv0 + TK - 1 > q0w) || kv0 + TK > a.s;
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        if (a.causal && kv0 + c * 32 > q0w + 31) continue;          // the whole 32-key block is in the future
-        dq_block<HD, BUF>(lds, fo, qf, dof, dq, c, kv0, q, hf, a.s, a.causal, sl2, lse2, dl, need_mask);
+        for (int c = 0; c < 2; ++c) {
+          if (a.causal && kv0 + c * 32 > q0w + 31) continue;          // the whole 32-key block is in the future
+          dq_block<HD, BUF>(lds, fo, qf, dof, dq, c, kv0, q, hf, a.s, a.causal, sl2, lse2, dl, need_mask);
+        }
       }
     }
     __builtin_amdgcn_s_waitcnt(0);
@@ -534,6 +592,28 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a) {
     if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, BUFB>{});
   }
 
+  if constexpr (KS == 2) {      // add the second key half's dQ to the first's, through LDS (the tiles are no longer read)
+    static_assert(2 * G::NHB * 4 * 1024 <= 4 * G::TILEB, "the merge area fits the tile buffers");
+    lds_char* mo = lds + qb * (G::NHB * 4 * 1024) + lane * 16;
+    if (kh == 1) {
+#pragma unroll
+      for (int hb = 0; hb < G::NHB; ++hb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          *(__attribute__((address_space(3))) f32x4*)(mo + (hb * 4 + q4) * 1024) =
+              f32x4{dq[hb][q4 * 4], dq[hb][q4 * 4 + 1], dq[hb][q4 * 4 + 2], dq[hb][q4 * 4 + 3]};
+    }
+    __syncthreads();
+    if (kh == 1) return;
+#pragma unroll
+    for (int hb = 0; hb < G::NHB; ++hb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 v = *(__attribute__((address_space(3))) const f32x4*)(mo + (hb * 4 + q4) * 1024);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dq[hb][q4 * 4 + e] += v[e];
+      }
+  }
   if (q < a.s) {
     bf16* row = (bf16*)a.dqkv + ((int64_t)ib * a.s + q) * a.ld + j * HD;
 #pragma unroll
@@ -563,7 +643,12 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a) {
 // The workgroup walks the query heads of its group and their 128-query tiles (Q, dO, lse, delta of a tile go global ->
 // LDS directly, two buffers, one barrier per tile).
 // ---------------------------------------------------------------------------
-constexpr int DKV_THREADS = 512, DKV_TQ = 128, DKV_BKEY = 4 * 32;
+// TQ = keys per workgroup = queries per tile: 128 (8 wavefronts, one workgroup per CU) or, for small grids, 64
+// (4 wavefronts, two workgroups per CU: twice as many workgroups for the same number of resident wavefronts)
+constexpr int DKV_TQ = 128, DKV_TQ_SMALL = 64;
+// early key tiles see the most queries: plain order is kt = rank; folded (see tile_of_rank) the heavy half first, then
+// the light half, lightest first
+__device__ __forceinline__ int key_tile_of_rank(int rank, int n, int fold) { return n - 1 - tile_of_rank(rank, n, fold); }
 
 // acc = sum over head_dim of rows(tile `TILE`, rows rb..rb+31) x bfr (the wavefront's K or V fragments); fragment
 // reads run three k-steps ahead
@@ -626,33 +711,32 @@ __device__ __forceinline__ void dkv_tr_product(lds_char* lds, const FragOff<HD>&
   }
 }
 
-template <int HD>
-__global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int nsplit) {
+template <int HD, int TQ>
+__global__ __launch_bounds__(TQ * 4, 2) void attn_dkv_kernel(AttnArgs a, int nsplit, int fold) {
   using G = Geo<HD>;
-  constexpr int NTHR = DKV_THREADS, TQ = DKV_TQ, NB = TQ / 32, TILEB = TQ * G::ROWB;
+  constexpr int NTHR = TQ * 4, NB = TQ / 32, NKW = TQ / 32, TILEB = TQ * G::ROWB;   // NKW key blocks, two wavefronts each
   // two buffers of (Q tile, dO tile, lse of the tile's queries, delta of the tile's queries)
   constexpr int QT = 0, OT = TILEB, LT = 2 * TILEB, DT = LT + TQ * 4, BUFB = DT + TQ * 4;
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char* lds = (lds_char*)smem_raw;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int role = wave >> 2, kw = wave & 3;             // role 0: dV and the producer of P (on the older wavefront), role 1: dK; kw and kw+4 share a SIMD
-  const int kt = blockIdx.y;                              // slow grid index: early key tiles see the most queries, first
+  const int role = wave / NKW, kw = wave % NKW;          // role 0: dV and the producer of P (on the older wavefront), role 1: dK; with 8 wavefronts kw and kw+4 share a SIMD
+  const int nkt = (a.s + TQ - 1) / TQ;
+  const int kt = key_tile_of_rank(blockIdx.y / a.b, nkt, fold);   // slow grid index: heavy (early) key tiles first
   // grid.x = KV heads x splits: this workgroup takes `grp` of the query heads of KV head g, starting at head j0
-  const int g = blockIdx.x / nsplit, sp = blockIdx.x % nsplit, ib = blockIdx.z;
+  const int g = blockIdx.x / nsplit, sp = blockIdx.x % nsplit, ib = blockIdx.y % a.b;
   const int d = a.h * HD, dkv = a.hkv * HD, grp = a.h / a.hkv / nsplit, j0 = g * (a.h / a.hkv) + sp * grp;
   const bf16* base = (const bf16*)a.qkv + (int64_t)ib * a.s * a.ld;
   const bf16* dobase = (const bf16*)a.dout + (int64_t)ib * a.s * d;
   const bf16* kp = base + d + g * HD;
   const bf16* vp = base + d + dkv + g * HD;
-  const int k0b = kt * DKV_BKEY, k0w = k0b + kw * 32;
+  const int k0b = kt * TQ, k0w = k0b + kw * 32;
   const int key = k0w + (lane & 31);
   const float scale = rsqrtf((float)HD), sl2 = scale * LOG2E;
 
-  static_assert(DKV_BKEY == DKV_TQ, "the diagonal query tile of a key tile has the same index");
-  const int t_first = a.causal ? kt : 0;
-  const int nqt = (a.s + TQ - 1) / TQ;
-  const int per_head = nqt - t_first;
+  const int t_first = a.causal ? kt : 0;              // keys per workgroup = queries per tile: the diagonal query tile has the key tile's index
+  const int per_head = nkt - t_first;
   const int niter = per_head * grp;
   // Per-thread offsets of the pieces it fetches: load j covers rows j*SWEEP + (its wavefront's and lane's row inside
   // a sweep); SWEEP is a multiple of 16, so the swizzle -- and with it the column -- is the same for every j and
@@ -695,9 +779,9 @@ __global__ __launch_bounds__(DKV_THREADS) void attn_dkv_kernel(AttnArgs a, int n
   typedef __attribute__((address_space(3))) const f32x4* lds_f4;
   // the pair's P slot ([e4][lane] f32x4) and its counts: produced = blocks written, consumed = blocks read
   lds_char* pslot = lds + 2 * BUFB + kw * 4096 + lane * 16;
-  volatile __attribute__((address_space(3))) int* produced = (volatile __attribute__((address_space(3))) int*)(lds + 2 * BUFB + 4 * 4096) + kw;
-  volatile __attribute__((address_space(3))) int* consumed = produced + 4;
-  if (tid < 8) ((volatile __attribute__((address_space(3))) int*)(lds + 2 * BUFB + 4 * 4096))[tid] = 0;   // published by the barrier below
+  volatile __attribute__((address_space(3))) int* produced = (volatile __attribute__((address_space(3))) int*)(lds + 2 * BUFB + NKW * 4096) + kw;
+  volatile __attribute__((address_space(3))) int* consumed = produced + NKW;
+  if (tid < 2 * NKW) ((volatile __attribute__((address_space(3))) int*)(lds + 2 * BUFB + NKW * 4096))[tid] = 0;   // published by the barrier below
   auto wait_for = [&](volatile __attribute__((address_space(3))) int* count, int value) {
     for (int guard = 0; *count != value && guard < (1 << 20); ++guard) __builtin_amdgcn_s_sleep(1);
     asm volatile("" ::: "memory");                       // nothing of what follows is read or written ahead of the wait
@@ -859,56 +943,86 @@ __global__ __launch_bounds__(256) void attn_dkv_reduce_kernel(AttnArgs a, int ns
 
 // dynamic LDS of the kernels above
 template <int HD> constexpr size_t fwd_lds() { return (size_t)4 * Geo<HD>::TILEB; }
-template <int HD> constexpr size_t dkv_lds() { return (size_t)2 * (2 * DKV_TQ * Geo<HD>::ROWB + 2 * DKV_TQ * 4) + 4 * 4096 + 64; }   // + P slots and counts
+template <int HD, int TQ> constexpr size_t dkv_lds() { return (size_t)2 * (2 * TQ * Geo<HD>::ROWB + 2 * TQ * 4) + (TQ / 32) * 4096 + 64; }   // + P slots and counts
 
 template <typename K>
 hipError_t allow_lds(K kern, size_t bytes) {
   return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-// 4-wavefront workgroups when 8-wavefront ones would number fewer than two per CU
-static bool fwd_narrow(const AttnArgs& a) {
-  if (a.width) return a.width == 2;
-  static const int n_cu = [] {        // function-local statics: initialised once, thread-safely
-    int dev = 0, n = 0;
-    return (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
-  }();
-  const int64_t wide = (int64_t)a.b * a.h * ((a.s + fwd_bq(FWD_WIDE) - 1) / fwd_bq(FWD_WIDE));
-  return wide < 2 * (int64_t)n_cu;
+// The dispatch rules below count workgroups against the CUs of a 256-CU chip (two resident workgroups per CU for
+// forward, dQ and the small dK/dV tile); the scratch size of the backward depends on them, so they use the constant
+// rather than the device's count.
+constexpr int64_t RESIDENT = 2 * 256;
+
+// Forward / dQ workgroup shape: 4 wavefronts x 32 queries when that gives two workgroups per CU; else 64 queries with
+// the key range of each query block split over two wavefronts.  (8 wavefronts x 32 queries read every K/V tile once for
+// twice the queries, but measured 3-4 % slower than 4 on every shape of the workloads here, the finer grains filling the
+// end of the launch better; they stay available as a forced choice.)
+enum FwdShape { SHAPE_WIDE = 1, SHAPE_NARROW = 2, SHAPE_SPLIT = 3 };
+static int64_t fwd_count(const AttnArgs& a, int bq) { return (int64_t)a.b * a.h * ((a.s + bq - 1) / bq); }
+static FwdShape fwd_shape(const AttnArgs& a) {
+  if (a.width >= 1 && a.width <= 3) return (FwdShape)a.width;
+  return fwd_count(a, fwd_bq(FWD_NARROW)) >= RESIDENT ? SHAPE_NARROW : SHAPE_SPLIT;
 }
 
-template <int HD, int NT>
+template <int HD, int NT, int KS>
 hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
-  static const hipError_t ready = allow_lds(attn_fwd_kernel<HD, NT>, fwd_lds<HD>());
+  static const hipError_t ready = allow_lds(attn_fwd_kernel<HD, NT, KS>, fwd_lds<HD>());
   if (ready != hipSuccess) return ready;
-  const int nqt = (a.s + fwd_bq(NT) - 1) / fwd_bq(NT);
-  hipLaunchKernelGGL((attn_fwd_kernel<HD, NT>), dim3(a.h, nqt, a.b), dim3(NT), fwd_lds<HD>(), s, a);
+  const int nqt = (a.s + fwd_bq(NT, KS) - 1) / fwd_bq(NT, KS);
+  const int fold = a.causal && (int64_t)a.b * a.h * nqt <= RESIDENT;      // everything resident at once: pair heavy with light
+  hipLaunchKernelGGL((attn_fwd_kernel<HD, NT, KS>), dim3(a.h, nqt * a.b), dim3(NT), fwd_lds<HD>(), s, a, fold);
   return hipGetLastError();
 }
 template <int HD>
 hipError_t fwd_t(const AttnArgs& a, hipStream_t s) {
-  return fwd_narrow(a) ? fwd_launch<HD, FWD_NARROW>(a, s) : fwd_launch<HD, FWD_WIDE>(a, s);
+  switch (fwd_shape(a)) {
+    case SHAPE_WIDE: return fwd_launch<HD, FWD_WIDE, 1>(a, s);
+    case SHAPE_NARROW: return fwd_launch<HD, FWD_NARROW, 1>(a, s);
+    default: return fwd_launch<HD, FWD_NARROW, 2>(a, s);
+  }
 }
 
-template <int HD, int NT>
+template <int HD, int NT, int KS>
 hipError_t dq_launch(const AttnArgs& a, hipStream_t s) {
-  static const hipError_t ready = allow_lds(attn_dq_kernel<HD, NT>, fwd_lds<HD>());
+  static const hipError_t ready = allow_lds(attn_dq_kernel<HD, NT, KS>, fwd_lds<HD>());
   if (ready != hipSuccess) return ready;
-  hipLaunchKernelGGL((attn_dq_kernel<HD, NT>), dim3(a.h, (a.s + fwd_bq(NT) - 1) / fwd_bq(NT), a.b), dim3(NT), fwd_lds<HD>(), s, a);
+  const int nqt = (a.s + fwd_bq(NT, KS) - 1) / fwd_bq(NT, KS);
+  const int fold = a.causal && (int64_t)a.b * a.h * nqt <= RESIDENT;
+  hipLaunchKernelGGL((attn_dq_kernel<HD, NT, KS>), dim3(a.h, nqt * a.b), dim3(NT), fwd_lds<HD>(), s, a, fold);
   return hipGetLastError();
 }
 
-template <int HD>
-hipError_t bwd_t(const AttnArgs& a, hipStream_t s) {
-  static const hipError_t ready = allow_lds(attn_dkv_kernel<HD>, dkv_lds<HD>());
-  if (ready != hipSuccess) return ready;
-  {      // dQ first: it also leaves delta = rowsum(dO * O) in a.delta for the dK/dV pass
-    const hipError_t e = fwd_narrow(a) ? dq_launch<HD, FWD_NARROW>(a, s) : dq_launch<HD, FWD_WIDE>(a, s);
-    if (e != hipSuccess) return e;
+// Split a KV head's query heads over workgroups until the dK/dV grid has two workgroups per CU (or every query head
+// has its own workgroup); the count must divide the group size.
+static int dkv_splits(int b, int s, int h, int hkv, int tq) {
+  const int grp = h / hkv;
+  const int64_t wgs = (int64_t)b * hkv * ((s + tq - 1) / tq);
+  int ns = 1;
+  while (ns < grp && wgs * ns < RESIDENT) {
+    int nx = ns + 1;
+    while (grp % nx) ++nx;
+    ns = nx;
   }
-  const int nsplit = a.dkv_part ? attn_bwd_splits(a.b, a.s, a.h, a.hkv) : 1;
-  hipLaunchKernelGGL((attn_dkv_kernel<HD>), dim3(a.hkv * nsplit, (a.s + DKV_BKEY - 1) / DKV_BKEY, a.b), dim3(DKV_THREADS),
-                     dkv_lds<HD>(), s, a, nsplit);
+  return ns;
+}
+// 64-key workgroups when 128-key ones, split as far as they go, still number fewer than two per CU
+static bool dkv_small(int b, int s, int h, int hkv, int width) {
+  if (width) return width == 3;
+  return (int64_t)b * hkv * ((s + DKV_TQ - 1) / DKV_TQ) * dkv_splits(b, s, h, hkv, DKV_TQ) < RESIDENT;
+}
+
+template <int HD, int TQ>
+hipError_t dkv_launch(const AttnArgs& a, hipStream_t s) {
+  constexpr size_t lds_bytes = dkv_lds<HD, TQ>();
+  static const hipError_t ready = allow_lds(attn_dkv_kernel<HD, TQ>, lds_bytes);
+  if (ready != hipSuccess) return ready;
+  const int nsplit = a.dkv_part ? dkv_splits(a.b, a.s, a.h, a.hkv, TQ) : 1;
+  const int nkt = (a.s + TQ - 1) / TQ;
+  // two 64-key workgroups share a CU: when all are resident at once, pair heavy key tiles with light ones
+  const int fold = TQ == DKV_TQ_SMALL && a.causal && (int64_t)a.b * a.hkv * nsplit * nkt <= RESIDENT;
+  hipLaunchKernelGGL((attn_dkv_kernel<HD, TQ>), dim3(a.hkv * nsplit, nkt * a.b), dim3(TQ * 4), lds_bytes, s, a, nsplit, fold);
   if (nsplit > 1) {
     const int64_t pieces = (int64_t)a.b * a.s * (2 * a.hkv * HD / 4);
     hipLaunchKernelGGL(attn_dkv_reduce_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, a, nsplit, a.h * HD, a.hkv * HD);
@@ -916,20 +1030,25 @@ hipError_t bwd_t(const AttnArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int HD>
+hipError_t bwd_t(const AttnArgs& a, hipStream_t s) {
+  hipError_t e;      // dQ first: it also leaves delta = rowsum(dO * O) in a.delta for the dK/dV pass
+  switch (fwd_shape(a)) {
+    case SHAPE_WIDE: e = dq_launch<HD, FWD_WIDE, 1>(a, s); break;
+    case SHAPE_NARROW: e = dq_launch<HD, FWD_NARROW, 1>(a, s); break;
+    default: e = dq_launch<HD, FWD_NARROW, 2>(a, s); break;
+  }
+  if (e != hipSuccess) return e;
+  return dkv_small(a.b, a.s, a.h, a.hkv, a.width) ? dkv_launch<HD, DKV_TQ_SMALL>(a, s) : dkv_launch<HD, DKV_TQ>(a, s);
+}
+
 }  // namespace
 
-// Split a KV head's query heads over workgroups until the dK/dV grid has two workgroups per CU of a 256-CU chip
-// (or every query head has its own workgroup); the count must divide the group size.
+// Scratch of the backward: the fp32 partial dK | dV of every split.  Sized for either tile of the dK/dV kernel (the
+// tile is chosen from the shape, or forced by AttnArgs::width).
 int attn_bwd_splits(int b, int s, int h, int hkv) {
-  const int grp = h / hkv;
-  const int64_t wgs = (int64_t)b * hkv * ((s + DKV_BKEY - 1) / DKV_BKEY);
-  int ns = 1;
-  while (ns < grp && wgs * ns < 512) {
-    int nx = ns + 1;
-    while (grp % nx) ++nx;
-    ns = nx;
-  }
-  return ns;
+  const int n128 = dkv_splits(b, s, h, hkv, DKV_TQ), n64 = dkv_splits(b, s, h, hkv, DKV_TQ_SMALL);
+  return n128 > n64 ? n128 : n64;
 }
 size_t attn_bwd_part_bytes(int b, int s, int h, int hkv, int hd) {
   const int ns = attn_bwd_splits(b, s, h, hkv);

@@ -47,11 +47,12 @@ struct AttnArgs {
   const void* dout;              // [b*s, d]
   void* dqkv;                    // [b*s, d + 2*dkv]
   float* delta;                  // [b, h, s] scratch: rowsum(dout * o)
-  int width;                     // forward / dQ workgroups: 0 = chosen from the shape, 1 = 8 wavefronts, 2 = 4 wavefronts
+  int width;                     // workgroup shapes: 0 = chosen from the shape; forward / dQ 1 = 8 wavefronts, 2 = 4 wavefronts,
+                                 // 3 = 4 wavefronts with the keys split in two; dK/dV 128 keys per workgroup for 1 and 2, 64 for 3
   float* dkv_part;               // scratch for grouped-query attention, attn_bwd_part_bytes() bytes, or null: fp32 partial
                                  // dK | dV of each split of a KV head's query heads, [nsplit][b*s][2*dkv]
 };
-// Into how many workgroups the query heads of one KV head are split in the dK/dV kernel (1 = not at all), and the
+// Into how many workgroups at most the query heads of one KV head are split in the dK/dV kernel (1 = not at all), and the
 // scratch that needs.  Depends on the shape only.
 int attn_bwd_splits(int b, int s, int h, int hkv);
 size_t attn_bwd_part_bytes(int b, int s, int h, int hkv, int hd);

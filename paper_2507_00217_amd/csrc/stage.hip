@@ -1037,7 +1037,7 @@ int stage_kernel_attention_fwd(int dtype, int b, int s, int h, int hkv, int hd, 
   if (!attn_shape(dtype, b, s, h, hkv, hd, causal) || !qkv || !o || !lse) return STAGE_E_INVAL;
   AttnArgs a{}; a.b = b; a.s = s; a.h = h; a.hkv = hkv; a.hd = hd; a.causal = causal;
   a.qkv = qkv; a.ld = (int64_t)(h + 2 * hkv) * hd; a.o = o; a.lse = lse;
-  a.width = kernel_set == 2 ? 1 : kernel_set == 3 ? 2 : 0;
+  a.width = kernel_set == 2 ? 1 : kernel_set == 3 ? 2 : kernel_set == 4 ? 3 : 0;
   if (kernel_set != 1 && dtype == STAGE_DTYPE_BF16 && attn_mfma_supported(a)) return hip_rc(attn_fwd_mfma(a, (hipStream_t)hip_stream));
   return hip_rc(attn_fwd_ref((DType)dtype, a, (hipStream_t)hip_stream));
 }
@@ -1075,7 +1075,7 @@ int stage_kernel_attention_bwd_ws(int dtype, int b, int s, int h, int hkv, int h
   a.qkv = qkv; a.ld = (int64_t)(h + 2 * hkv) * hd; a.o = (void*)o; a.lse = (float*)lse;
   a.dout = dout; a.dqkv = dqkv; a.delta = delta;
   a.dkv_part = attn_bwd_part_bytes(b, s, h, hkv, hd) ? (float*)scratch : nullptr;
-  a.width = kernel_set == 2 ? 1 : kernel_set == 3 ? 2 : 0;
+  a.width = kernel_set == 2 ? 1 : kernel_set == 3 ? 2 : kernel_set == 4 ? 3 : 0;
   if (kernel_set != 1 && dtype == STAGE_DTYPE_BF16 && attn_mfma_supported(a)) return hip_rc(attn_bwd_mfma(a, (hipStream_t)hip_stream));
   return hip_rc(attn_bwd_ref((DType)dtype, a, (hipStream_t)hip_stream));
 }

@@ -206,14 +206,17 @@ def test_gemm_rejects_bad_arguments():
     assert L().stage_kernel_gemm(7, 0, 64, 64, 64, P(t), 64, P(t), 64, P(t), 64, None, 0, 0, 0, None) == -1
 
 
-ATT_SHAPES = [(1, 128, 4, 4, 64), (2, 200, 5, 5, 128), (1, 392, 8, 1, 128), (1, 448, 4, 2, 128), (1, 1, 2, 1, 64), (1, 640, 2, 2, 64)]
+ATT_SHAPES = [(1, 128, 4, 4, 64), (2, 200, 5, 5, 128), (1, 392, 8, 1, 128), (1, 448, 4, 2, 128), (1, 1, 2, 1, 64), (1, 640, 2, 2, 64),
+              (3, 300, 2, 1, 128)]
 
 
-@pytest.mark.parametrize("dtype,kernel_set", [("fp32", 0), ("fp32", 1), ("bf16", 0), ("bf16", 1), ("bf16", 2), ("bf16", 3)])
+@pytest.mark.parametrize("dtype,kernel_set", [("fp32", 0), ("fp32", 1), ("bf16", 0), ("bf16", 1), ("bf16", 2), ("bf16", 3), ("bf16", 4)])
 @pytest.mark.parametrize("causal", [1, 0])
 @pytest.mark.parametrize("b,s,h,hkv,hd", ATT_SHAPES)
 def test_attention(dtype, kernel_set, causal, b, s, h, hkv, hd):
-    """kernel_set 2 / 3: the tuned kernels with 8- / 4-wavefront forward and dQ workgroups forced (0 picks by shape)."""
+    """kernel_set 2 / 3 / 4: the tuned kernels with one workgroup shape forced (0 picks by shape): forward and dQ with 8
+    wavefronts, with 4, or with 4 that split each query block's keys in two; dK/dV with 128 keys per workgroup (2, 3) or
+    64 (4)."""
     import torch
     d, dkv = h * hd, hkv * hd
     qkv = rnd(synth.normal(2, 1, (b, s, d + 2 * dkv)), dtype)
@@ -278,12 +281,13 @@ def test_rope(dtype, b, s, h, hkv, hd, theta):
     assert L().stage_kernel_rope_table(s, 96, theta, P(table), None) == -1
 
 
+@pytest.mark.parametrize("kernel_set", [0, 3, 4])
 @pytest.mark.parametrize("causal", [1, 0])
 @pytest.mark.parametrize("b,s,h,hkv,hd", [(1, 392, 8, 1, 128), (2, 300, 12, 2, 64), (1, 448, 4, 2, 128)])
-def test_attention_bwd_with_split_query_heads(causal, b, s, h, hkv, hd):
+def test_attention_bwd_with_split_query_heads(kernel_set, causal, b, s, h, hkv, hd):
     """Grouped-query dK/dV with each KV head's query heads split over several workgroups (fp32 partials in caller
     scratch, summed in a fixed order): against the oracle, and equal to the unsplit pass up to the one extra bf16
-    rounding order."""
+    rounding order.  kernel_set 3 / 4: 128 / 64 keys per workgroup (0 picks by shape)."""
     import torch
     d, dkv = h * hd, hkv * hd
     qkv = rnd(synth.normal(6, 1, (b, s, d + 2 * dkv)), "bf16")
@@ -304,7 +308,7 @@ def test_attention_bwd_with_split_query_heads(causal, b, s, h, hkv, hd):
     for use in (True, False):
         dqkv = torch.zeros_like(qd)
         rc = L().stage_kernel_attention_bwd_ws(1, b, s, h, hkv, hd, causal, P(qd), P(od), P(lse), P(dod), P(dqkv), P(delta),
-                                               P(scratch) if use else None, nbytes if use else 0, 0, None)
+                                               P(scratch) if use else None, nbytes if use else 0, kernel_set, None)
         assert rc == 0
         torch.cuda.synchronize()
         outs.append(to_np(dqkv))
