@@ -44,8 +44,7 @@ namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int TILE_BYTES = BM * BK * 2;                      // one operand tile, either layout: 32 KiB
-constexpr int SLOT = TILE_BYTES, NSLOT = 5;                  // ring of operand tiles in LDS
-constexpr size_t LDS_BYTES = (size_t)NSLOT * SLOT;           // 160 KiB
+constexpr size_t LDS_BYTES = (size_t)5 * TILE_BYTES;         // 160 KiB: the ring of operand tiles (five full-size slots)
 static_assert(BM == BN, "both operand tiles share one geometry");
 
 enum Epi { EPI_STORE = 0, EPI_RESID = 1, EPI_ACC32 = 2, EPI_GELU = 3, EPI_SWIGLU = 4, EPI_DGELU = 5, EPI_DSWIGLU = 6 };
@@ -197,6 +196,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   constexpr int PCS = BNV / 8;                                                     // 16-byte pieces per row of C / per reduction row of a [k][row] B tile
   constexpr int CHA = (A_BYTES / 16) / (WAVES * 64), CHB = (B_BYTES / 16) / (WAVES * 64); // loads per thread and K tile
   constexpr int NI = RW / 16, NJ = 2 * TN;                                         // 16 x 16 accumulator blocks per wavefront
+  // The ring of operand tiles (see below): DEPTH K tiles ahead of the one being multiplied, 2 * DEPTH + 1 slots.  The
+  // 128 x 128 tile's operand tiles are half the size and its K tile takes a quarter of the MFMA time, so the same LDS
+  // holds -- and the same lead in time needs -- twice the depth: with a lead of two K tiles (about 1 us here) operands
+  // that come from HBM rather than from a cache arrive late, and products of this tile ran a quarter to a third slower
+  // on cold operands than on warm ones.
+  constexpr bool SMALL = WR == 1 && WC == 1;
+  constexpr int SLOT = SMALL ? TILE_BYTES / 2 : TILE_BYTES, DEPTH = SMALL ? 4 : 2, NSLOT = 2 * DEPTH + 1;
+  static_assert(A_BYTES <= SLOT && B_BYTES <= SLOT && (size_t)NSLOT * SLOT <= LDS_BYTES, "ring fits");
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / WGN) * RW, wn = (wave % WGN) * (TN * 32);
@@ -222,17 +229,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     kB += BK;
     if (EPI == EPI_ACC32 && kB >= g.K && segB + 1 < nseg) { kB = 0; ++segB; rsB = raw_rsrc((const char*)g.B + seg_delta[segB], bytesB); }
   };
-  // start-up: A0 B0 A1 B1, as far as they exist
-  g2s<AKC, WAVES, CHA>(smem, rsA, offa, g.lda, kA, wave);
-  advanceA();
-  g2s<BKC, WAVES, CHB>(smem + SLOT, rsB, offb, g.ldb, kB, wave);
-  advanceB();
-  if (nk > 1) {
-    g2s<AKC, WAVES, CHA>(smem + 2 * SLOT, rsA, offa, g.lda, kA, wave);
-    advanceA();
-    g2s<BKC, WAVES, CHB>(smem + 3 * SLOT, rsB, offb, g.ldb, kB, wave);
-    advanceB();
-  }
+  // start-up: A0 B0 A1 B1 ... of the first DEPTH K tiles, as far as they exist
+#pragma unroll
+  for (int t = 0; t < DEPTH; ++t)
+    if (t == 0 || nk > t) {
+      g2s<AKC, WAVES, CHA>(smem + 2 * t * SLOT, rsA, offa, g.lda, kA, wave);
+      advanceA();
+      g2s<BKC, WAVES, CHB>(smem + (2 * t + 1) * SLOT, rsB, offb, g.ldb, kB, wave);
+      advanceB();
+    }
 
   // acc[i][j][e] = C[m0 + wm + i*16 + lane%16][n0 + wn + j*16 + (lane/16)*4 + e]: the MFMA is issued with the operands
   // swapped, which leaves every lane with 4 consecutive columns of one row.
@@ -326,13 +331,17 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   for (int i = 0; i < NI; ++i) fa[0][i] = frag<AKC, NPA>(pa, i, 0);
   int kt = 0;
   auto trip = [&](auto tail_c) __attribute__((always_inline)) {
-    // ring position (wave-uniform) of tile 2kt + 4 = A(kt+2); tile 2kt + 5 = B(kt+2) takes A(kt)'s slot
-    const int s4 = slotA + 4 >= NSLOT ? slotA + 4 - NSLOT : slotA + 4;
-    const bool more = kt + 2 < nk;
+    // ring position (wave-uniform) of tile 2(kt + DEPTH) = A(kt+DEPTH): the slot before A(kt)'s, which B(kt-1) has left;
+    // tile 2(kt + DEPTH) + 1 = B(kt+DEPTH) takes A(kt)'s slot
+    const int s4 = slotA == 0 ? NSLOT - 1 : slotA - 1;
+    const bool more = kt + DEPTH < nk;
     kstep(c0, c1, c0, tail_c, more, smem + s4 * SLOT);
     if (!decltype(tail_c)::value || more) advanceA();
-    // A(kt+1), B(kt+1) have landed once nothing older than A(kt+2)'s loads is outstanding; own LDS reads are done
-    if (!decltype(tail_c)::value || more) __builtin_amdgcn_s_waitcnt(0x0070 | (CHA & 15) | ((CHA >> 4) << 14));
+    // A(kt+1), B(kt+1) have landed once nothing older than the loads of A(kt+2) ... A(kt+DEPTH) is outstanding; own
+    // LDS reads are done
+    constexpr int VM = (DEPTH - 1) * CHA + (DEPTH - 2) * CHB;
+    static_assert(VM < 64, "vmcnt is a 6-bit count");
+    if (!decltype(tail_c)::value || more) __builtin_amdgcn_s_waitcnt(0x0070 | (VM & 15) | ((VM >> 4) << 14));
     else __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
@@ -349,7 +358,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     if (!decltype(tail_c)::value || more) advanceB();
     slotA = slotA + 2 >= NSLOT ? slotA + 2 - NSLOT : slotA + 2;
   };
-  for (; kt + 2 < nk; ++kt) trip(std::false_type{});
+  for (; kt + DEPTH < nk; ++kt) trip(std::false_type{});
   for (; kt < nk; ++kt) trip(std::true_type{});
 
   // epilogue
@@ -580,7 +589,11 @@ __device__ __forceinline__ void tile_of(int idx, int tiles_m, int tiles_n, int& 
 // one workgroup per tile: workgroup `bid` takes the full tile number first + bid of the walk order (WR == 2), or the
 // upper (even bid) / lower (odd bid) 128 rows of full tile number first + bid / 2 (WR == 1)
 template <bool AKC, bool BKC, int EPI, int TN, int WR>
-__global__ __launch_bounds__(WR * 512 / TN) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n, int first) {
+// The second launch bound (wavefronts per SIMD the register budget must allow) is 2 for the half-height tile: its four
+// wavefronts of 128 x 64 then get the 256 registers the full tile's eight have, all of them ordinary VGPRs.  Left at
+// one per SIMD (512 registers), the compiler kept the accumulators in AGPRs, gave the MFMAs a destination other than
+// their C operand and moved 128-190 registers between the two files on every trip of the main loop.
+__global__ __launch_bounds__(WR * 512 / TN, WR == 1 ? 2 : 1) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n, int first) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give XCD x the
   // x-th contiguous band of the tile sequence.
@@ -599,7 +612,8 @@ __global__ __launch_bounds__(WR * 512 / TN) void gemm_mfma_kernel(GemmArgs g, in
 // one workgroup per 128 x 128 tile (four wavefronts of 64 x 64): workgroup `bid` takes quadrant bid % 4 of the full
 // tile number first + bid / 4 of the walk order; a quadrant that lies outside the matrix has nothing to do
 template <bool AKC, bool BKC, int EPI>
-__global__ __launch_bounds__(256) void gemm_quarter_kernel(GemmArgs g, int tiles_m, int tiles_n, int first) {
+__global__ __launch_bounds__(256, 2) void gemm_quarter_kernel(   // (register budget: as for the half-height tile)
+    GemmArgs g, int tiles_m, int tiles_n, int first) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   int bid = blockIdx.x;
   {
