@@ -294,10 +294,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   // one k-step: the MFMAs on fragment set `cur`; after every second MFMA one fragment of `ks_next` into the other set
   // (B's first: the first MFMAs of the next k-step need all of them); and the loads of operand tile `op` (0 = A, 1 = B)
   // spread between the MFMAs
-  auto kstep = [&](auto cur_c, auto ks_c, auto op_c, auto tail_c, bool exists, lds_char* dst) __attribute__((always_inline)) {
+  auto kstep = [&](auto cur_c, auto ks_c, auto op_c, auto tail_c, lds_char* dst) __attribute__((always_inline)) {
     constexpr int cur = decltype(cur_c)::value, ks_next = decltype(ks_c)::value, op = decltype(op_c)::value;
     constexpr int NL = op ? CHB : CHA, GAP = NMFMA / NL;
-    const bool do_load = !decltype(tail_c)::value || exists;      // away from the end of the reduction every load exists: no branch
+    constexpr bool do_load = !decltype(tail_c)::value;            // the last DEPTH trips have nothing left to fetch
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
@@ -313,7 +313,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
           else fa[cur ^ 1][f - NJ] = frag<AKC, NPA>(pa, f - NJ, ks_next);
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (n % GAP == GAP - 1 && do_load) {
+        if constexpr (do_load) if (n % GAP == GAP - 1) {
           const int l = n / GAP;
           if (op == 0) g2s_one<AKC, WAVES, CHA>(dst, rsA, offa, g.lda, kA, wave, l);
           else g2s_one<BKC, WAVES, CHB>(dst, rsB, offb, g.ldb, kB, wave, l);
@@ -331,17 +331,20 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   for (int i = 0; i < NI; ++i) fa[0][i] = frag<AKC, NPA>(pa, i, 0);
   int kt = 0;
   auto trip = [&](auto tail_c) __attribute__((always_inline)) {
+    constexpr bool tail = decltype(tail_c)::value;
     // ring position (wave-uniform) of tile 2(kt + DEPTH) = A(kt+DEPTH): the slot before A(kt)'s, which B(kt-1) has left;
     // tile 2(kt + DEPTH) + 1 = B(kt+DEPTH) takes A(kt)'s slot
     const int s4 = slotA == 0 ? NSLOT - 1 : slotA - 1;
-    const bool more = kt + DEPTH < nk;
-    kstep(c0, c1, c0, tail_c, more, smem + s4 * SLOT);
-    if (!decltype(tail_c)::value || more) advanceA();
-    // A(kt+1), B(kt+1) have landed once nothing older than the loads of A(kt+2) ... A(kt+DEPTH) is outstanding; own
-    // LDS reads are done
+    kstep(c0, c1, c0, tail_c, smem + s4 * SLOT);
+    if (!tail) advanceA();
+    // A(kt+1), B(kt+1) have landed once nothing older than the loads of A(kt+2) ... A(kt+DEPTH) is outstanding (in the
+    // last trips: of the tiles that are left beyond kt+1); own LDS reads are done
     constexpr int VM = (DEPTH - 1) * CHA + (DEPTH - 2) * CHB;
     static_assert(VM < 64, "vmcnt is a 6-bit count");
-    if (!decltype(tail_c)::value || more) __builtin_amdgcn_s_waitcnt(0x0070 | (VM & 15) | ((VM >> 4) << 14));
+    auto wait_vm = [](auto n_c) { constexpr int n = decltype(n_c)::value; __builtin_amdgcn_s_waitcnt(0x0070 | (n & 15) | ((n >> 4) << 14)); };
+    if (!tail) wait_vm(std::integral_constant<int, VM>{});
+    else if (DEPTH == 4 && nk - kt == 4) wait_vm(std::integral_constant<int, DEPTH == 4 ? 2 * (CHA + CHB) : 0>{});
+    else if (DEPTH == 4 && nk - kt == 3) wait_vm(std::integral_constant<int, DEPTH == 4 ? CHA + CHB : 0>{});
     else __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
@@ -354,8 +357,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
 #pragma unroll
       for (int x = 0; x < NPB; ++x) pb[x] += dB;
     }
-    kstep(c1, c0, c1, tail_c, more, smem + slotA * SLOT);     // (fragments past the last tile are read and not used)
-    if (!decltype(tail_c)::value || more) advanceB();
+    kstep(c1, c0, c1, tail_c, smem + slotA * SLOT);           // (fragments past the last tile are read and not used)
+    if (!tail) advanceB();
     slotA = slotA + 2 >= NSLOT ? slotA + 2 - NSLOT : slotA + 2;
   };
   for (; kt + DEPTH < nk; ++kt) trip(std::false_type{});
