@@ -221,13 +221,24 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
   const int nk = ((g.K + BK - 1) / BK) * nseg;
   // where the next tile of each operand to fetch lies: segment and reduction offset inside it (all wave-uniform)
   int segA = 0, kA = 0, segB = 0, kB = 0;
+  // reduction offset at which an operand moves on to its next segment (never, in the last one): one compare per K tile,
+  // its branch laid out as not taken -- a taken branch costs the single wavefront of a SIMD, and with it the SIMD's MFMA
+  // pipe, some twenty cycles
+  constexpr int NEVER = 0x7fffffff;
+  int endA = (EPI == EPI_ACC32 && nseg > 1) ? g.K : NEVER, endB = endA;
   auto advanceA = [&]() {
     kA += BK;
-    if (EPI == EPI_ACC32 && kA >= g.K && segA + 1 < nseg) { kA = 0; ++segA; rsA = raw_rsrc((const char*)g.A + seg_delta[segA], bytesA); }
+    if (EPI == EPI_ACC32 && __builtin_expect(kA >= endA, 0)) {
+      kA = 0; ++segA; rsA = raw_rsrc((const char*)g.A + seg_delta[segA], bytesA);
+      if (segA + 1 >= nseg) endA = NEVER;
+    }
   };
   auto advanceB = [&]() {
     kB += BK;
-    if (EPI == EPI_ACC32 && kB >= g.K && segB + 1 < nseg) { kB = 0; ++segB; rsB = raw_rsrc((const char*)g.B + seg_delta[segB], bytesB); }
+    if (EPI == EPI_ACC32 && __builtin_expect(kB >= endB, 0)) {
+      kB = 0; ++segB; rsB = raw_rsrc((const char*)g.B + seg_delta[segB], bytesB);
+      if (segB + 1 >= nseg) endB = NEVER;
+    }
   };
   // start-up: A0 B0 A1 B1 ... of the first DEPTH K tiles, as far as they exist
 #pragma unroll
