@@ -555,6 +555,28 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
     }
     return;
   }
+  if constexpr (EPI == EPI_ACC32) {
+    // acc already holds C + A^T.B.  Buffer stores like the loads that fetched C: one 32-bit offset per row block and
+    // column block, elements outside the matrix redirected out of range and dropped -- no branch per store, which with
+    // one wavefront per SIMD would hold up everything behind it
+    const __amdgpu_buffer_rsrc_t rsC = make_rsrc(g.C, (unsigned)(((int64_t)(g.M - 1) * g.ldc + g.N) * 4));
+    unsigned col_b[NJ];                // byte offset of the lane's columns inside a row; N % 8 == 0 and n % 4 == 0: the 4
+                                       // columns are in or out together
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) col_b[j] = (unsigned)(n0 + wn + j * 16 + col_l) * 4u;
+    const unsigned row_b = (unsigned)((int64_t)(m0 + wm + row_l) * g.ldc * 4), step_b = (unsigned)g.ldc * 64u;   // 16 rows on
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const bool row_ok = m0 + wm + i * 16 + row_l < g.M;
+      const unsigned base = row_b + (unsigned)i * step_b;       // (wraps only for rows that are not there)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const bool ok = row_ok && n0 + wn + j * 16 + col_l < g.N;
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[i][j]), rsC, (int)(ok ? base + col_b[j] : OOB), 0, 0);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const int m = m0 + wm + i * 16 + row_l;
@@ -564,9 +586,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int m0, int n0, lds
       const int n = n0 + wn + j * 16 + col_l;
       if (n >= g.N) continue;          // N % 8 == 0 and n % 4 == 0: the 4 columns are in or out together
       f32x4 v = acc[i][j];
-      if (EPI == EPI_ACC32) {
-        *reinterpret_cast<f32x4*>((float*)g.C + (int64_t)m * g.ldc + n) = v;   // acc already holds C + A^T.B
-      } else {
+      {
         if (EPI == EPI_RESID && g.R) {
           if (g.r_f32) {
             v += *reinterpret_cast<const f32x4*>((const float*)g.R + (int64_t)m * g.ldr + n);
