@@ -950,20 +950,21 @@ hipError_t allow_lds(K kern, size_t bytes) {
   return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-// The dispatch rules below count workgroups against the CUs of a 256-CU chip (two resident workgroups per CU for
-// forward, dQ and the small dK/dV tile); the scratch size of the backward depends on them, so they use the constant
-// rather than the device's count.
+// The dispatch rules below count workgroups against the CUs of a 256-CU chip (two resident 4-wavefront workgroups per
+// CU for forward, dQ and the small dK/dV tile; the 8-wavefront ones sit one to a CU); the scratch size of the backward
+// depends on them, so they use the constant rather than the device's count.
 constexpr int64_t RESIDENT = 2 * 256;
 
-// Forward / dQ workgroup shape: 4 wavefronts x 32 queries when that gives two workgroups per CU; else 64 queries with
-// the key range of each query block split over two wavefronts.  (8 wavefronts x 32 queries read every K/V tile once for
-// twice the queries, but measured 3-4 % slower than 4 on every shape of the workloads here, the finer grains filling the
-// end of the launch better; they stay available as a forced choice.)
+// Forward / dQ workgroup shape: 8 wavefronts x 32 queries when that gives two workgroups per CU (they read every K/V
+// tile once for twice the queries); else 4 x 32 queries; else (still under two per CU) 64 queries with the key range of
+// each query block split over two wavefronts.
 enum FwdShape { SHAPE_WIDE = 1, SHAPE_NARROW = 2, SHAPE_SPLIT = 3 };
 static int64_t fwd_count(const AttnArgs& a, int bq) { return (int64_t)a.b * a.h * ((a.s + bq - 1) / bq); }
 static FwdShape fwd_shape(const AttnArgs& a) {
   if (a.width >= 1 && a.width <= 3) return (FwdShape)a.width;
-  return fwd_count(a, fwd_bq(FWD_NARROW)) >= RESIDENT ? SHAPE_NARROW : SHAPE_SPLIT;
+  if (fwd_count(a, fwd_bq(FWD_WIDE)) >= RESIDENT) return SHAPE_WIDE;
+  if (fwd_count(a, fwd_bq(FWD_NARROW)) >= RESIDENT) return SHAPE_NARROW;
+  return SHAPE_SPLIT;
 }
 
 template <int HD, int NT, int KS>
@@ -971,7 +972,9 @@ hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
   static const hipError_t ready = allow_lds(attn_fwd_kernel<HD, NT, KS>, fwd_lds<HD>());
   if (ready != hipSuccess) return ready;
   const int nqt = (a.s + fwd_bq(NT, KS) - 1) / fwd_bq(NT, KS);
-  const int fold = a.causal && (int64_t)a.b * a.h * nqt <= RESIDENT;      // everything resident at once: pair heavy with light
+  // 4-wavefront workgroups sit two to a CU: when the whole grid is resident at once, pair heavy with light.  (8-wavefront
+  // ones sit one to a CU and come in two rounds or more: heaviest first, and the light ones fill in behind.)
+  const int fold = NT == FWD_NARROW && a.causal && (int64_t)a.b * a.h * nqt <= RESIDENT;
   hipLaunchKernelGGL((attn_fwd_kernel<HD, NT, KS>), dim3(a.h, nqt * a.b), dim3(NT), fwd_lds<HD>(), s, a, fold);
   return hipGetLastError();
 }
@@ -989,7 +992,7 @@ hipError_t dq_launch(const AttnArgs& a, hipStream_t s) {
   static const hipError_t ready = allow_lds(attn_dq_kernel<HD, NT, KS>, fwd_lds<HD>());
   if (ready != hipSuccess) return ready;
   const int nqt = (a.s + fwd_bq(NT, KS) - 1) / fwd_bq(NT, KS);
-  const int fold = a.causal && (int64_t)a.b * a.h * nqt <= RESIDENT;
+  const int fold = NT == FWD_NARROW && a.causal && (int64_t)a.b * a.h * nqt <= RESIDENT;      // as in the forward
   hipLaunchKernelGGL((attn_dq_kernel<HD, NT, KS>), dim3(a.h, nqt * a.b), dim3(NT), fwd_lds<HD>(), s, a, fold);
   return hipGetLastError();
 }
