@@ -194,27 +194,40 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(NormArgs n) {
   }
 }
 
-// grads += sum over workgroup partials, in a fixed order: 64 columns per workgroup, 4 wavefronts each summing a
-// quarter of the partial rows (coalesced 256-byte reads), then wavefront 0 adds the four quarter-sums in order
+// grads += sum over workgroup partials, in a fixed order: 64 columns per workgroup, FIN_WAVES wavefronts each summing
+// an equal share of the partial rows (coalesced 256-byte reads, all of a wavefront's loads in flight at once: the kernel
+// is a few microseconds of memory latency, not bandwidth), then wavefront 0 adds the shares in order
+constexpr int FIN_WAVES = 16;
+static_assert(NORM_PARTIAL_ROWS % FIN_WAVES == 0, "equal shares");
 template <int KIND>
-__global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(NormArgs n, int nparts) {
-  __shared__ float sg[4][64], sb[4][64];
+__global__ __launch_bounds__(FIN_WAVES * 64) void norm_bwd_finalize_kernel(NormArgs n, int nparts) {
+  __shared__ float sg[FIN_WAVES][64], sb[FIN_WAVES][64];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int col = blockIdx.x * 64 + lane;
   float g = 0.f, b = 0.f;
   if (col < n.d) {
-    const int per = nparts / 4;
-#pragma unroll 8
-    for (int p = w * per; p < (w + 1) * per; ++p) {
-      g += n.partial[(int64_t)p * 2 * n.d + col];
-      if (KIND == 0) b += n.partial[(int64_t)p * 2 * n.d + n.d + col];
+    constexpr int PER = NORM_PARTIAL_ROWS / FIN_WAVES;
+    const float* p0 = n.partial + (int64_t)w * PER * 2 * n.d + col;
+    float vg[PER], vb[PER];
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      vg[p] = p0[(int64_t)p * 2 * n.d];
+      if (KIND == 0) vb[p] = p0[(int64_t)p * 2 * n.d + n.d];
+    }
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      g += vg[p];
+      if (KIND == 0) b += vb[p];
     }
   }
   sg[w][lane] = g; sb[w][lane] = b;
   __syncthreads();
   if (w == 0 && col < n.d) {
-    n.dgamma[col] += ((sg[0][lane] + sg[1][lane]) + sg[2][lane]) + sg[3][lane];
-    if (KIND == 0) n.dbeta[col] += ((sb[0][lane] + sb[1][lane]) + sb[2][lane]) + sb[3][lane];
+    float tg = sg[0][lane], tb = sb[0][lane];
+#pragma unroll
+    for (int k = 1; k < FIN_WAVES; ++k) { tg += sg[k][lane]; tb += sb[k][lane]; }
+    n.dgamma[col] += tg;
+    if (KIND == 0) n.dbeta[col] += tb;
   }
 }
 
@@ -239,10 +252,10 @@ static hipError_t norm_bwd_t(const NormArgs& n, hipStream_t s) {
   const int fb = (n.d + 63) / 64;
   if (n.kind == 0) {
     hipLaunchKernelGGL((norm_bwd_kernel<T, 0>), dim3(parts), dim3(NORM_THREADS), 0, s, n);
-    hipLaunchKernelGGL((norm_bwd_finalize_kernel<0>), dim3(fb), dim3(256), 0, s, n, parts);
+    hipLaunchKernelGGL((norm_bwd_finalize_kernel<0>), dim3(fb), dim3(FIN_WAVES * 64), 0, s, n, parts);
   } else {
     hipLaunchKernelGGL((norm_bwd_kernel<T, 1>), dim3(parts), dim3(NORM_THREADS), 0, s, n);
-    hipLaunchKernelGGL((norm_bwd_finalize_kernel<1>), dim3(fb), dim3(256), 0, s, n, parts);
+    hipLaunchKernelGGL((norm_bwd_finalize_kernel<1>), dim3(fb), dim3(FIN_WAVES * 64), 0, s, n, parts);
   }
   return hipGetLastError();
 }
