@@ -205,7 +205,9 @@ __device__ __forceinline__ int acc_row(int e, int hf) { return (e >> 2) * 8 + hf
 // ---------------------------------------------------------------------------
 // Forward and dQ come with 8 wavefronts (256 queries) or 4 (128 queries) per workgroup.  Two workgroups of 4 share
 // a CU, so either way two wavefronts sit on each SIMD; 8 read every K/V tile once for twice the queries and are faster
-// when there is plenty of work, 4 give twice as many workgroups and win when 8 would leave CUs idle.
+// when there is plenty of work, 4 give twice as many workgroups and win when 8 would leave CUs idle.  A third shape
+// for grids smaller still: 4 wavefronts on 64 queries, two per 32-query block, each taking one 32-key half of every
+// K/V tile (template parameter KS = 2); what the two halves hold is merged through LDS after the last tile.
 constexpr int FWD_WIDE = 512, FWD_NARROW = 256;
 constexpr int fwd_bq(int nthr, int ks = 1) { return (nthr / 64) * 32 / ks; }
 
