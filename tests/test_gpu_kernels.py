@@ -48,7 +48,8 @@ def P(t):
 
 
 GEMM_SHAPES = [(128, 256, 768), (200, 192, 136), (328, 1088, 512), (512, 512, 2048), (257, 320, 72), (1024, 768, 264),
-               (136, 72, 64), (72, 136, 128), (264, 136, 192)]      # the last three: one, two and three K tiles (the pipeline's start-up and tail alone)
+               (136, 72, 64), (72, 136, 128), (264, 136, 192),      # one, two and three K tiles (the pipeline's start-up and tail alone)
+               (200, 136, 256), (136, 264, 320)]                    # four and five: the 128 x 128 tile's ring is four K tiles deep
 
 
 @pytest.mark.parametrize("dtype,kernel_set", [("fp32", 0), ("fp32", 1), ("bf16", 0), ("bf16", 1), ("bf16", 2), ("bf16", 3), ("bf16", 4)])
