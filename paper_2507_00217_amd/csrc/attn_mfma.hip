@@ -171,7 +171,20 @@ __device__ __forceinline__ bf16x8 pack8(const float* v) {
   for (int e = 0; e < 8; ++e) r[e] = (bf16)v[e];
   return r;
 }
-__device__ __forceinline__ float xhalf(float v) { return __shfl_xor(v, 32, 64); }
+// The value held by the lane 32 further on (or back): v_permlane32_swap exchanges the upper half of one register with
+// the lower half of another, one vector instruction instead of a round trip through the LDS crossbar.  Given v twice, the
+// first result holds the partner's value in lanes 32-63 and the second in lanes 0-31.  (The second copy is made opaque
+// and the two results are only ever selected between, never combined with each other: the compiler folded a sum of the
+// two results into twice the first.)
+__device__ __forceinline__ float xhalf(float v, int hf) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  unsigned w = u;
+  asm volatile("" : "+v"(w));
+  const auto r = __builtin_amdgcn_permlane32_swap(u, w, false, false);
+  return __builtin_bit_cast(float, hf ? r[0] : r[1]);
+}
+__device__ __forceinline__ float half_max(float v, int hf) { return fmaxf(v, xhalf(v, hf)); }
+__device__ __forceinline__ float half_sum(float v, int hf) { return v + xhalf(v, hf); }
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // acc + sum of the 8 elements of v (v_dot2c_f32_bf16 against (1, 1): exact products, fp32 accumulation)
 __device__ __forceinline__ float dot_ones(bf16x8 v, float acc) {
@@ -273,7 +286,7 @@ __device__ __forceinline__ void fwd_tile(lds_char* lds, const FragOff<HD>& fo, c
 #pragma unroll
     for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[c][e]);
   float p[NC][16];
-  mx = fmaxf(mx, xhalf(mx));
+  mx = half_max(mx, hf);
   const float mn = fmaxf(m, mx * sl2);
   float sum = 0.f;
 #pragma unroll
@@ -297,7 +310,7 @@ __device__ __forceinline__ void fwd_tile(lds_char* lds, const FragOff<HD>& fo, c
   for (int c = 0; c < NC; ++c)
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) sum = dot_ones(pf[c][t2], sum);
-  sum += xhalf(sum);
+  sum = half_sum(sum, hf);
   l += sum;
   m = mn;
   SCHED_FENCE;
@@ -547,7 +560,7 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void attn_dq_kernel(AttnArgs a, int
 #pragma unroll
       for (int e = 0; e < 8; ++e) part = fmaf((float)dof[kk][e], (float)of[e], part);
     }
-    dl = part + xhalf(part);
+    dl = half_sum(part, hf);
   }
   if (q < a.s) {
     lse2 = a.lse[((int64_t)ib * a.h + j) * a.s + q] * LOG2E;
