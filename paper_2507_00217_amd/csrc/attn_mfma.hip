@@ -1078,6 +1078,7 @@ bool attn_mfma_supported(const AttnArgs& a) {
   if (a.ld % 8 || ((uintptr_t)a.qkv & 15) || ((uintptr_t)a.o & 15)) return false;
   if (a.dout && (((uintptr_t)a.dout & 15) || ((uintptr_t)a.dqkv & 15))) return false;
   if ((int64_t)a.s * a.ld * 2 >= ((int64_t)1 << 31)) return false;   // tile loads use 32-bit byte offsets inside a sequence
+  if ((int64_t)a.b * ((a.s + 63) / 64) > 65535) return false;        // grid.y = tiles of a sequence x sequences, smallest tile
   return a.b > 0 && a.s > 0 && a.h > 0 && a.hkv > 0 && a.h % a.hkv == 0;
 }
 
